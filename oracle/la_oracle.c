@@ -1,0 +1,433 @@
+/*
+ * la_oracle.c: plain fp64 CPU oracle for kernelised linear attention with the
+ * feature map phi(x) = elu(x) + 1 (paper eq. 7).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, obviously-correct checker
+ * that the GPU library is compared against.  It shares no code, header, table
+ * or helper with the HIP path, and nothing on the product path may call it.
+ * Only the tests, the smoke check and the benchmark's cpu_baseline leg use it.
+ *
+ * Every function is a direct transcription of a definition or of the steps of
+ * an algorithm in the paper, in the paper's order and notation, with no
+ * blocking, fusion or reordering:
+ *
+ *   phi / dphi                       eq. 7 (elu with alpha = 1, plus one)
+ *   causal_fwd_quadratic             eq. 8 with sim(q,k) = phi(q)^T phi(k)      (definition)
+ *   causal_weights                   the row-normalised weights inside eq. 8    (definition)
+ *   causal_fwd_prefix                eq. 10, 11, 12 (running sums S_i, Z_i)
+ *   recurrent_step                   eq. 16-20 (s_i, z_i update, then read-out)
+ *   global_fwd_quadratic             eq. 3 with the same sim                    (definition)
+ *   global_fwd_linear                eq. 5 / eq. 6
+ *   causal_numerator_fwd / _bwd      Algorithm 1, forward and backward, as printed
+ *                                    (takes already-mapped phi(Q), phi(K))
+ *   causal_bwd_quadratic             gradient of eq. 8 by brute force           (definition)
+ *   causal_bwd_linear                Algorithm 1 backward applied to values
+ *                                    augmented with a column of ones, then the
+ *                                    chain rule through phi (the paper leaves the
+ *                                    denominator and the fraction to autograd,
+ *                                    supplementary section A; this is that part
+ *                                    written out)
+ *
+ * Readings of the paper that this file fixes (the paper is silent on each):
+ *   - eps: den_i = phi(Q_i)^T Z_i + eps, added once after the dot product.
+ *   - elu has alpha = 1; the branch is x > 0 (strict), so phi(0) = exp(0) = 1.
+ *   - the causal sum is inclusive (j <= i); the recurrent step updates first,
+ *     then reads.
+ *   - gradients are with respect to the raw Q, K (through phi) and V.
+ *
+ * Layout: every tensor is row-major [BH, N, feature]; the BH slabs (one per
+ * batch element and head) are independent problems.  OpenMP runs over slabs
+ * only; inside a slab all sums run in ascending token order (descending for
+ * the reverse loop of Algorithm 1).
+ *
+ * Pins (tests/test_oracle_*.py): prefix == quadratic == stepwise; linear
+ * backward == brute-force backward == central finite differences == autograd
+ * of the quadratic form; closed forms (Q = K = 0 gives a running mean, constant
+ * V gives a constant output, N = 1); rational hand-worked case in tests/golden.
+ */
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* eq. 7: phi(x) = elu(x) + 1 = x + 1 for x > 0, exp(x) otherwise. */
+double la_oracle_phi(double x) { return x > 0.0 ? x + 1.0 : exp(x); }
+
+/* derivative of eq. 7: 1 for x > 0, exp(x) otherwise. */
+double la_oracle_dphi(double x) { return x > 0.0 ? 1.0 : exp(x); }
+
+int la_oracle_max_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+void la_oracle_set_threads(int n) {
+#ifdef _OPENMP
+    if (n > 0) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
+static double dot(const double *a, const double *b, int n) {
+    double s = 0.0;
+    for (int t = 0; t < n; ++t) s += a[t] * b[t];
+    return s;
+}
+
+static double *map_rows(const double *X, long rows, int D, double (*f)(double)) {
+    double *Y = (double *)malloc(sizeof(double) * (size_t)rows * (size_t)D);
+    for (long t = 0; t < rows * D; ++t) Y[t] = f(X[t]);
+    return Y;
+}
+
+/* ------------------------------------------------------------------------ */
+/* eq. 8: V'_i = sum_{j<=i} sim(Q_i,K_j) V_j / sum_{j<=i} sim(Q_i,K_j),      */
+/* sim(q,k) = phi(q)^T phi(k).  O(N^2).  den (may be NULL) gets the          */
+/* denominator including eps.                                                */
+void la_oracle_causal_fwd_quadratic(const double *Q, const double *K, const double *V,
+                                    double *O, double *den,
+                                    int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M;
+        double *Os = O + (size_t)s * N * M;
+        double *fq = map_rows(Qs, N, D, la_oracle_phi);
+        double *fk = map_rows(Ks, N, D, la_oracle_phi);
+        double *num = (double *)malloc(sizeof(double) * (size_t)M);
+        for (int i = 0; i < N; ++i) {
+            double d = 0.0;
+            for (int e = 0; e < M; ++e) num[e] = 0.0;
+            for (int j = 0; j <= i; ++j) {
+                double a = dot(fq + (size_t)i * D, fk + (size_t)j * D, D);
+                for (int e = 0; e < M; ++e) num[e] += a * Vs[(size_t)j * M + e];
+                d += a;
+            }
+            d += eps;
+            for (int e = 0; e < M; ++e) Os[(size_t)i * M + e] = num[e] / d;
+            if (den) den[(size_t)s * N + i] = d;
+        }
+        free(num); free(fq); free(fk);
+    }
+}
+
+/* The normalised weights of eq. 8 for one slab: W[i][j] = sim(Q_i,K_j)/den_i  */
+/* for j <= i, 0 for j > i.  W is [N, N].                                      */
+void la_oracle_causal_weights(const double *Q, const double *K, double *W,
+                              int N, int D, double eps) {
+    double *fq = map_rows(Q, N, D, la_oracle_phi);
+    double *fk = map_rows(K, N, D, la_oracle_phi);
+    for (int i = 0; i < N; ++i) {
+        double d = 0.0;
+        for (int j = 0; j < N; ++j) {
+            double a = j <= i ? dot(fq + (size_t)i * D, fk + (size_t)j * D, D) : 0.0;
+            W[(size_t)i * N + j] = a;
+            d += a;
+        }
+        d += eps;
+        for (int j = 0; j < N; ++j) W[(size_t)i * N + j] /= d;
+    }
+    free(fq); free(fk);
+}
+
+/* ------------------------------------------------------------------------ */
+/* eq. 16-20 for one token per slab: s <- s + phi(k) v^T, z <- z + phi(k),    */
+/* out = phi(q)^T s / (phi(q)^T z + eps).  S is [BH, D, M], z is [BH, D].     */
+void la_oracle_recurrent_step(const double *q, const double *k, const double *v,
+                              double *S, double *z, double *out, double *den,
+                              int BH, int D, int M, double eps) {
+#pragma omp parallel for schedule(static)
+    for (int s = 0; s < BH; ++s) {
+        const double *qs = q + (size_t)s * D, *ks = k + (size_t)s * D, *vs = v + (size_t)s * M;
+        double *Ss = S + (size_t)s * D * M, *zs = z + (size_t)s * D, *os = out + (size_t)s * M;
+        for (int d = 0; d < D; ++d) {
+            double fk = la_oracle_phi(ks[d]);
+            for (int e = 0; e < M; ++e) Ss[(size_t)d * M + e] += fk * vs[e];   /* eq. 18 */
+            zs[d] += fk;                                                        /* eq. 19 */
+        }
+        double dn = 0.0;
+        for (int e = 0; e < M; ++e) os[e] = 0.0;
+        for (int d = 0; d < D; ++d) {
+            double fq = la_oracle_phi(qs[d]);
+            for (int e = 0; e < M; ++e) os[e] += fq * Ss[(size_t)d * M + e];
+            dn += fq * zs[d];
+        }
+        dn += eps;
+        for (int e = 0; e < M; ++e) os[e] /= dn;                                /* eq. 20 */
+        if (den) den[s] = dn;
+    }
+}
+
+/* eq. 10-12: S_i = S_{i-1} + phi(K_i) V_i^T, Z_i = Z_{i-1} + phi(K_i),       */
+/* V'_i = phi(Q_i)^T S_i / (phi(Q_i)^T Z_i + eps).  O(N D M).                 */
+void la_oracle_causal_fwd_prefix(const double *Q, const double *K, const double *V,
+                                 double *O, double *den,
+                                 int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M;
+        double *Os = O + (size_t)s * N * M;
+        double *S = (double *)calloc((size_t)D * M, sizeof(double));
+        double *Z = (double *)calloc((size_t)D, sizeof(double));
+        double *fq = (double *)malloc(sizeof(double) * (size_t)D);
+        for (int i = 0; i < N; ++i) {
+            for (int d = 0; d < D; ++d) {
+                double fk = la_oracle_phi(Ks[(size_t)i * D + d]);
+                for (int e = 0; e < M; ++e) S[(size_t)d * M + e] += fk * Vs[(size_t)i * M + e];
+                Z[d] += fk;
+            }
+            for (int d = 0; d < D; ++d) fq[d] = la_oracle_phi(Qs[(size_t)i * D + d]);
+            double dn = dot(fq, Z, D) + eps;
+            for (int e = 0; e < M; ++e) {
+                double a = 0.0;
+                for (int d = 0; d < D; ++d) a += fq[d] * S[(size_t)d * M + e];
+                Os[(size_t)i * M + e] = a / dn;
+            }
+            if (den) den[(size_t)s * N + i] = dn;
+        }
+        free(S); free(Z); free(fq);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* eq. 3 with sim = phi^T phi: every query attends to every key.  O(N^2).    */
+void la_oracle_global_fwd_quadratic(const double *Q, const double *K, const double *V,
+                                    double *O, int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M;
+        double *Os = O + (size_t)s * N * M;
+        double *fq = map_rows(Qs, N, D, la_oracle_phi);
+        double *fk = map_rows(Ks, N, D, la_oracle_phi);
+        double *num = (double *)malloc(sizeof(double) * (size_t)M);
+        for (int i = 0; i < N; ++i) {
+            double d = 0.0;
+            for (int e = 0; e < M; ++e) num[e] = 0.0;
+            for (int j = 0; j < N; ++j) {
+                double a = dot(fq + (size_t)i * D, fk + (size_t)j * D, D);
+                for (int e = 0; e < M; ++e) num[e] += a * Vs[(size_t)j * M + e];
+                d += a;
+            }
+            d += eps;
+            for (int e = 0; e < M; ++e) Os[(size_t)i * M + e] = num[e] / d;
+        }
+        free(num); free(fq); free(fk);
+    }
+}
+
+/* eq. 5-6: sum_j phi(K_j) V_j^T and sum_j phi(K_j) computed once, reused for */
+/* every query.  O(N D M).                                                    */
+void la_oracle_global_fwd_linear(const double *Q, const double *K, const double *V,
+                                 double *O, int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M;
+        double *Os = O + (size_t)s * N * M;
+        double *S = (double *)calloc((size_t)D * M, sizeof(double));
+        double *Z = (double *)calloc((size_t)D, sizeof(double));
+        double *fq = (double *)malloc(sizeof(double) * (size_t)D);
+        for (int j = 0; j < N; ++j)
+            for (int d = 0; d < D; ++d) {
+                double fk = la_oracle_phi(Ks[(size_t)j * D + d]);
+                for (int e = 0; e < M; ++e) S[(size_t)d * M + e] += fk * Vs[(size_t)j * M + e];
+                Z[d] += fk;
+            }
+        for (int i = 0; i < N; ++i) {
+            for (int d = 0; d < D; ++d) fq[d] = la_oracle_phi(Qs[(size_t)i * D + d]);
+            double dn = dot(fq, Z, D) + eps;
+            for (int e = 0; e < M; ++e) {
+                double a = 0.0;
+                for (int d = 0; d < D; ++d) a += fq[d] * S[(size_t)d * M + e];
+                Os[(size_t)i * M + e] = a / dn;
+            }
+        }
+        free(S); free(Z); free(fq);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Algorithm 1, forward: S <- S + phi(K_i) V_i^T ; Vbar_i <- phi(Q_i) S.      */
+/* Inputs are already mapped (fQ = phi(Q), fK = phi(K)); one slab.            */
+static void numerator_fwd_slab(const double *fQ, const double *fK, const double *V,
+                               double *Vbar, int N, int C, int M) {
+    double *S = (double *)calloc((size_t)C * M, sizeof(double));
+    for (int i = 0; i < N; ++i) {
+        for (int d = 0; d < C; ++d)
+            for (int e = 0; e < M; ++e)
+                S[(size_t)d * M + e] += fK[(size_t)i * C + d] * V[(size_t)i * M + e];
+        for (int e = 0; e < M; ++e) {
+            double a = 0.0;
+            for (int d = 0; d < C; ++d) a += fQ[(size_t)i * C + d] * S[(size_t)d * M + e];
+            Vbar[(size_t)i * M + e] = a;
+        }
+    }
+    free(S);
+}
+
+/* Algorithm 1, backward.  First loop, i = 1..N: rebuild S, emit the gradient */
+/* for phi(Q_i) = G_i S^T (eq. 13).  Second loop, i = N..1: S <- S + phi(Q_i) */
+/* G_i^T, then emit grad V_i = S^T phi(K_i) (eq. 15) and grad phi(K_i) = S V_i */
+/* (eq. 14); the update comes first because both sums start at j = i.         */
+static void numerator_bwd_slab(const double *fQ, const double *fK, const double *V,
+                               const double *G, double *gQ, double *gK, double *gV,
+                               int N, int C, int M) {
+    double *S = (double *)calloc((size_t)C * M, sizeof(double));
+    for (int i = 0; i < N; ++i) {
+        for (int d = 0; d < C; ++d)
+            for (int e = 0; e < M; ++e)
+                S[(size_t)d * M + e] += fK[(size_t)i * C + d] * V[(size_t)i * M + e];
+        for (int d = 0; d < C; ++d) {
+            double a = 0.0;
+            for (int e = 0; e < M; ++e) a += G[(size_t)i * M + e] * S[(size_t)d * M + e];
+            gQ[(size_t)i * C + d] = a;
+        }
+    }
+    memset(S, 0, sizeof(double) * (size_t)C * M);
+    for (int i = N - 1; i >= 0; --i) {
+        for (int d = 0; d < C; ++d)
+            for (int e = 0; e < M; ++e)
+                S[(size_t)d * M + e] += fQ[(size_t)i * C + d] * G[(size_t)i * M + e];
+        for (int e = 0; e < M; ++e) {
+            double a = 0.0;
+            for (int d = 0; d < C; ++d) a += S[(size_t)d * M + e] * fK[(size_t)i * C + d];
+            gV[(size_t)i * M + e] = a;
+        }
+        for (int d = 0; d < C; ++d) {
+            double a = 0.0;
+            for (int e = 0; e < M; ++e) a += S[(size_t)d * M + e] * V[(size_t)i * M + e];
+            gK[(size_t)i * C + d] = a;
+        }
+    }
+    free(S);
+}
+
+void la_oracle_causal_numerator_fwd(const double *fQ, const double *fK, const double *V,
+                                    double *Vbar, int BH, int N, int C, int M) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s)
+        numerator_fwd_slab(fQ + (size_t)s * N * C, fK + (size_t)s * N * C, V + (size_t)s * N * M,
+                           Vbar + (size_t)s * N * M, N, C, M);
+}
+
+void la_oracle_causal_numerator_bwd(const double *fQ, const double *fK, const double *V,
+                                    const double *G, double *gQ, double *gK, double *gV,
+                                    int BH, int N, int C, int M) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s)
+        numerator_bwd_slab(fQ + (size_t)s * N * C, fK + (size_t)s * N * C, V + (size_t)s * N * M,
+                           G + (size_t)s * N * M, gQ + (size_t)s * N * C, gK + (size_t)s * N * C,
+                           gV + (size_t)s * N * M, N, C, M);
+}
+
+/* ------------------------------------------------------------------------ */
+/* Gradient of eq. 8 by brute force.  With A_ij = phi(Q_i)^T phi(K_j) (j<=i), */
+/* den_i = sum_j A_ij + eps and O_i = sum_j A_ij V_j / den_i:                  */
+/*   dL/dV_j  = sum_{i>=j} (A_ij/den_i) G_i                                    */
+/*   dL/dA_ij = G_i^T (V_j - O_i) / den_i                                      */
+/*   dL/dphi(Q_i) = sum_{j<=i} dL/dA_ij phi(K_j),                              */
+/*   dL/dphi(K_j) = sum_{i>=j} dL/dA_ij phi(Q_i), then times phi'.             */
+void la_oracle_causal_bwd_quadratic(const double *Q, const double *K, const double *V,
+                                    const double *G, double *dQ, double *dK, double *dV,
+                                    int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M, *Gs = G + (size_t)s * N * M;
+        double *dQs = dQ + (size_t)s * N * D, *dKs = dK + (size_t)s * N * D;
+        double *dVs = dV + (size_t)s * N * M;
+        double *fq = map_rows(Qs, N, D, la_oracle_phi);
+        double *fk = map_rows(Ks, N, D, la_oracle_phi);
+        double *A = (double *)malloc(sizeof(double) * (size_t)N);
+        double *Oi = (double *)malloc(sizeof(double) * (size_t)M);
+        memset(dQs, 0, sizeof(double) * (size_t)N * D);
+        memset(dKs, 0, sizeof(double) * (size_t)N * D);
+        memset(dVs, 0, sizeof(double) * (size_t)N * M);
+        for (int i = 0; i < N; ++i) {
+            double dn = 0.0;
+            for (int e = 0; e < M; ++e) Oi[e] = 0.0;
+            for (int j = 0; j <= i; ++j) {
+                A[j] = dot(fq + (size_t)i * D, fk + (size_t)j * D, D);
+                dn += A[j];
+                for (int e = 0; e < M; ++e) Oi[e] += A[j] * Vs[(size_t)j * M + e];
+            }
+            dn += eps;
+            for (int e = 0; e < M; ++e) Oi[e] /= dn;
+            for (int j = 0; j <= i; ++j) {
+                double dA = 0.0;
+                for (int e = 0; e < M; ++e) {
+                    dVs[(size_t)j * M + e] += (A[j] / dn) * Gs[(size_t)i * M + e];
+                    dA += Gs[(size_t)i * M + e] * (Vs[(size_t)j * M + e] - Oi[e]);
+                }
+                dA /= dn;
+                for (int d = 0; d < D; ++d) {
+                    dQs[(size_t)i * D + d] += dA * fk[(size_t)j * D + d];
+                    dKs[(size_t)j * D + d] += dA * fq[(size_t)i * D + d];
+                }
+            }
+        }
+        for (long t = 0; t < (long)N * D; ++t) {
+            dQs[t] *= la_oracle_dphi(Qs[t]);
+            dKs[t] *= la_oracle_dphi(Ks[t]);
+        }
+        free(A); free(Oi); free(fq); free(fk);
+    }
+}
+
+/* Linear-time gradient.  Write the fraction as num_i / den_i with            */
+/*   [num_i, den_i - eps] = phi(Q_i)^T sum_{j<=i} phi(K_j) [V_j, 1]^T,         */
+/* i.e. the numerator of Algorithm 1 on values augmented with a ones column.  */
+/* Its upstream gradient is Gt_i = [G_i / den_i, -(G_i . O_i) / den_i]         */
+/* (quotient rule).  Algorithm 1 backward on (phi(Q), phi(K), [V,1], Gt) then  */
+/* gives the gradients for phi(Q), phi(K) and the augmented values; the ones  */
+/* column's own gradient is dropped, and the chain rule through phi finishes. */
+void la_oracle_causal_bwd_linear(const double *Q, const double *K, const double *V,
+                                 const double *G, double *dQ, double *dK, double *dV,
+                                 int BH, int N, int D, int M, double eps) {
+    const int Ma = M + 1;
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M, *Gs = G + (size_t)s * N * M;
+        double *dQs = dQ + (size_t)s * N * D, *dKs = dK + (size_t)s * N * D;
+        double *dVs = dV + (size_t)s * N * M;
+        double *fq = map_rows(Qs, N, D, la_oracle_phi);
+        double *fk = map_rows(Ks, N, D, la_oracle_phi);
+        double *Va = (double *)malloc(sizeof(double) * (size_t)N * Ma);
+        double *Nu = (double *)malloc(sizeof(double) * (size_t)N * Ma);
+        double *Gt = (double *)malloc(sizeof(double) * (size_t)N * Ma);
+        double *gVa = (double *)malloc(sizeof(double) * (size_t)N * Ma);
+        for (int i = 0; i < N; ++i) {
+            for (int e = 0; e < M; ++e) Va[(size_t)i * Ma + e] = Vs[(size_t)i * M + e];
+            Va[(size_t)i * Ma + M] = 1.0;
+        }
+        numerator_fwd_slab(fq, fk, Va, Nu, N, D, Ma);
+        for (int i = 0; i < N; ++i) {
+            double dn = Nu[(size_t)i * Ma + M] + eps;
+            double go = 0.0;
+            for (int e = 0; e < M; ++e) {
+                double o = Nu[(size_t)i * Ma + e] / dn;
+                Gt[(size_t)i * Ma + e] = Gs[(size_t)i * M + e] / dn;
+                go += Gs[(size_t)i * M + e] * o;
+            }
+            Gt[(size_t)i * Ma + M] = -go / dn;
+        }
+        numerator_bwd_slab(fq, fk, Va, Gt, dQs, dKs, gVa, N, D, Ma);
+        for (int i = 0; i < N; ++i)
+            for (int e = 0; e < M; ++e) dVs[(size_t)i * M + e] = gVa[(size_t)i * Ma + e];
+        for (long t = 0; t < (long)N * D; ++t) {
+            dQs[t] *= la_oracle_dphi(Qs[t]);
+            dKs[t] *= la_oracle_dphi(Ks[t]);
+        }
+        free(fq); free(fk); free(Va); free(Nu); free(Gt); free(gVa);
+    }
+}
