@@ -1,0 +1,279 @@
+#!/usr/bin/env python3
+"""Benchmark of the linear-attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+One "step" is one pass of the whole training hot path over one batch of synthetic
+input: la_causal_fwd followed by la_causal_bwd (every kernel they launch) on the
+metric's workload: B=2, H=8, N=65536, D=M=64, fp32, Q/K/V/dO i.i.d. N(0,1) from
+a fixed seed, already resident in HBM when the clock starts.  Prints ONE JSON line:
+throughput in Mtokens/s (a token = all 8 heads), the roofline fraction of the
+dominant kernel (HIP events around its launches inside the timed region) and the
+fp64 CPU oracle timed on this machine's host cores on a bounded sample.
+
+`--table` additionally times the other workloads (sequence-length sweep, the
+MNIST/CIFAR-shaped configs, bf16, the global forward and the decode loop) and writes
+gpurun_out/bench_table.json; it is a reporting aid and prints no extra stdout line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
+MFMA_F32_PEAK_TFLOPS = 157.3     # MI355X dense fp32 matrix, published
+
+
+def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
+    """Algorithmic HBM bytes per token-head of one launch of `name`: the tensors it must
+    read and write once (e = bytes per element of the N-sized tensors; den, 1/den and
+    delta are fp32 scalars per token-head)."""
+    return {
+        "causal_pass_fwd": e * (2 * D + 2 * M) + 4,     # Q K V -> O, den
+        "causal_pass_dq": e * (3 * D + 2 * M) + 8,      # dO V K Q, 1/den, delta -> dQ
+        "causal_pass_dv": e * (2 * D + 2 * M) + 4,      # K Q dO, 1/den -> dV
+        "causal_pass_dk": e * (3 * D + 2 * M) + 8,      # V dO Q K, 1/den, delta -> dK
+        "segment_state_kv": e * (D + M),                # K V
+        "segment_state_qg": e * (D + M) + 8,            # Q dO, 1/den, delta
+        "bwd_prep": e * 2 * M + 12,                     # dO O den -> 1/den, delta
+        "global_readout": e * (D + M),                  # Q -> O
+    }.get(name, 0.0)
+
+
+def kernel_flops(name: str, D: int, M: int) -> float:
+    """Algorithmic flops per token-head: the state update and the state read-out
+    (2*D*(M+1) each, ones column included) that the pass performs."""
+    full = 4.0 * D * (M + 1)
+    return {"causal_pass_fwd": full, "causal_pass_dq": full, "causal_pass_dv": full,
+            "causal_pass_dk": full, "segment_state_kv": full / 2, "segment_state_qg": full / 2,
+            "global_readout": full / 2}.get(name, 0.0)
+
+
+class FwdBwd:
+    """Device buffers and the step function for one workload."""
+
+    def __init__(self, w, bf16=False):
+        import torch
+
+        import paper_2006_16236_amd as la
+        import workloads as wl
+        self.la, self.torch, self.w, self.bf16 = la, torch, w, bf16
+        dev = "cuda:0"
+        host = wl.qkvg(w)
+        if bf16:
+            host = [wl.round_to_bf16(x) for x in host]
+        self.host = host
+        dt = torch.bfloat16 if bf16 else torch.float32
+        self.Q, self.K, self.V, self.G = (torch.from_numpy(x).to(dev).to(dt) for x in host)
+        self.O = torch.empty_like(self.V)
+        self.den = torch.empty(w.B, w.H, w.N, dtype=torch.float32, device=dev)
+        self.dQ, self.dK, self.dV = (torch.empty_like(x) for x in (self.Q, self.K, self.V))
+        code = la.LA_BF16 if bf16 else la.LA_F32
+        nf = la.la_causal_fwd_workspace(w.B, w.H, w.N, w.D, w.M, code)
+        nb = la.la_causal_bwd_workspace(w.B, w.H, w.N, w.D, w.M, code)
+        self.ws_f = torch.empty(max(nf, 16), dtype=torch.uint8, device=dev)
+        self.ws_b = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
+
+    def step(self):
+        la, w = self.la, self.w
+        la.la_causal_fwd(self.Q, self.K, self.V, self.O, self.den, w.eps, ws=self.ws_f)
+        la.la_causal_bwd(self.Q, self.K, self.V, self.O, self.den, self.G, self.dQ, self.dK,
+                         self.dV, w.eps, ws=self.ws_b)
+
+    def fwd_only(self):
+        self.la.la_causal_fwd(self.Q, self.K, self.V, self.O, self.den, self.w.eps, ws=self.ws_f)
+
+
+def time_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps
+
+
+def profile_kernels(la, fn, steps, torch, mask=None):
+    torch.cuda.synchronize()
+    la.la_profile_begin() if mask is None else la.la_profile_begin(mask)
+    for _ in range(steps):
+        fn()
+    prof = la.la_profile_end()
+    return {k: (ms / n, n // steps) for k, (ms, n) in prof.items()}   # avg ms per launch, launches/step
+
+
+def cpu_baseline(w, host, sample_tokens):
+    """The oracle as it stands (fp64, OpenMP over the (b, h) slabs), forward + backward, on
+    the first `sample_tokens` tokens of every slab of the same workload."""
+    import numpy as np
+
+    from oracle import la_oracle
+    Q, K, V, G = (np.ascontiguousarray(x[:, :, :sample_tokens], dtype=np.float64) for x in host)
+    threads = min(la_oracle.max_threads(), w.B * w.H)
+    t0 = time.perf_counter()
+    la_oracle.causal_fwd_prefix(Q, K, V, w.eps)
+    la_oracle.causal_bwd_linear(Q, K, V, G, w.eps)
+    dt = time.perf_counter() - t0
+    return {"value": w.B * sample_tokens / dt / 1e6, "unit": "Mtokens/s", "cores": threads,
+            "kind": "oracle",
+            "sample": f"fp64 oracle forward+backward on the first {sample_tokens} of {w.N} tokens of "
+                      f"all {w.B * w.H} (batch, head) sequences of the same inputs, one run, "
+                      f"{dt:.1f} s wall; OpenMP over sequences ({la_oracle.max_threads()} threads "
+                      f"available, {threads} busy)"}
+
+
+def run_headline(args):
+    import torch
+
+    import paper_2006_16236_amd as la
+    import workloads as wl
+
+    w = wl.HEADLINE
+    fb = FwdBwd(w)
+    for _ in range(args.warmup):
+        fb.step()
+    # untimed look at every kernel, to find the dominant one
+    prof_all = profile_kernels(la, fb.step, 3, torch)
+    per_step = {k: ms * n for k, (ms, n) in prof_all.items()}
+    dominant = max(per_step, key=per_step.get)
+    kid = [la.la_kernel_name(i) for i in range(10)].index(dominant)
+
+    # the timed region: exactly `steps` steps, events only around the dominant kernel
+    torch.cuda.synchronize()
+    la.la_profile_begin(1 << kid)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fb.step()
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t0) / args.steps
+    dom_ms, dom_n = la.la_profile_end()[dominant]
+    dom_ms /= dom_n
+
+    tokens = w.B * w.N
+    th = tokens * w.H
+    value = tokens / sec / 1e6
+    ach_gbs = kernel_bytes(dominant, w.D, w.M, 4) * th / (dom_ms * 1e-3) / 1e9
+    ach_tf = kernel_flops(dominant, w.D, w.M) * th / (dom_ms * 1e-3) / 1e12
+    hbm_ceiling = HBM_PEAK_GBS * 1e9 / (w.H * 4 * (6 * w.D + 6 * w.M)) / 1e6
+    out = {
+        "metric": "causal linear-attn fwd+bwd Mtokens/s (H=8,D=M=64,N=2^16)",
+        "value": round(value, 3), "unit": "Mtokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(sec * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "D": w.D, "M": w.M,
+                   "eps": w.eps, "step": "la_causal_fwd + la_causal_bwd", "seed": w.seed},
+        "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(ach_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": None, "avg_kernel_ms": round(dom_ms, 4),
+                     "mfma_f32_tflops_algorithmic": round(ach_tf, 2),
+                     "mfma_f32_frac": round(ach_tf / MFMA_F32_PEAK_TFLOPS, 4)},
+        "path_frac_of_hbm_roofline": round(value / hbm_ceiling, 4),
+        "path_hbm_ceiling_mtok_s": round(hbm_ceiling, 1),
+        "kernels_ms_per_step": {k: round(v, 4) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, fb.host, args.cpu_sample_tokens)
+    return out, fb
+
+
+def run_table(args):
+    """Everything else worth a number; written to gpurun_out/bench_table.json."""
+    import torch
+
+    import paper_2006_16236_amd as la
+    import workloads as wl
+    rows = []
+
+    def fwdbwd_row(w, bf16=False, steps=10):
+        fb = FwdBwd(w, bf16)
+        sec = time_steps(fb.step, steps, 3, torch)
+        secf = time_steps(fb.fwd_only, steps, 2, torch)
+        prof = profile_kernels(la, fb.step, 3, torch)
+        e = 2 if bf16 else 4
+        ceiling = HBM_PEAK_GBS * 1e9 / (w.H * e * (6 * w.D + 6 * w.M)) / 1e6
+        rows.append({"workload": w.name + ("_bf16" if bf16 else ""), "tokens": w.B * w.N,
+                     "fwd_bwd_ms": sec * 1e3, "fwd_ms": secf * 1e3,
+                     "fwd_bwd_mtok_s": w.B * w.N / sec / 1e6, "fwd_mtok_s": w.B * w.N / secf / 1e6,
+                     "hbm_ceiling_mtok_s": ceiling, "frac": w.B * w.N / sec / 1e6 / ceiling,
+                     "kernels_ms": {k: round(ms * n, 4) for k, (ms, n) in prof.items()}})
+        print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
+        return fb
+
+    for w in (wl.CFG2, wl.CFG3):
+        fwdbwd_row(w)
+    fwdbwd_row(wl.CFG3, bf16=True)
+    for n in range(9, 17):
+        w = wl.sweep_point(n)
+        fb = fwdbwd_row(w, steps=5)
+        # the non-causal forward on the same tensors
+        ws = torch.empty(la.la_global_fwd_workspace(w.B, w.H, w.N, w.D, w.M), dtype=torch.uint8,
+                         device="cuda:0")
+        sec = time_steps(lambda: la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws), 5, 2, torch)
+        rows.append({"workload": w.name + "_global_fwd", "tokens": w.B * w.N, "fwd_ms": sec * 1e3,
+                     "fwd_mtok_s": w.B * w.N / sec / 1e6,
+                     "hbm_ceiling_mtok_s": HBM_PEAK_GBS * 1e9 / (w.H * 4 * (2 * w.D + 2 * w.M)) / 1e6})
+        print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
+        del fb, ws
+    # recurrent decode: 3072 sequential steps, one token per head per step
+    for B in (wl.CFG5.B, 4096):
+        d = wl.CFG5
+        T = d.T if B == d.B else 64
+        q = torch.randn(8, B, d.H, d.D, device="cuda:0")
+        k = torch.randn(8, B, d.H, d.D, device="cuda:0")
+        v = torch.randn(8, B, d.H, d.M, device="cuda:0")
+        S = torch.zeros(B, d.H, d.D, d.M, device="cuda:0")
+        z = torch.zeros(B, d.H, d.D, device="cuda:0")
+        out = torch.empty(B, d.H, d.M, device="cuda:0")
+        for t in range(8):
+            la.la_recurrent_step(q[t % 8], k[t % 8], v[t % 8], S, z, out, d.eps)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(T):
+            la.la_recurrent_step(q[t % 8], k[t % 8], v[t % 8], S, z, out, d.eps)
+        torch.cuda.synchronize()
+        sec = (time.perf_counter() - t0) / T
+        bytes_step = B * d.H * (2 * 4 * d.D * (d.M + 1) + 4 * (2 * d.D + 2 * d.M))
+        rows.append({"workload": f"decode_B{B}_H8_D64", "steps": T, "us_per_step": sec * 1e6,
+                     "tokens_per_s": B / sec, "achieved_GBs": bytes_step / sec / 1e9,
+                     "frac_hbm": bytes_step / sec / 1e9 / HBM_PEAK_GBS})
+        print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+    with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
+        json.dump(rows, f, indent=1)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
+    ap.add_argument("--table", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    out, fb = run_headline(args)
+    del fb
+    if args.table:
+        run_table(args)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

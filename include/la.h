@@ -1,0 +1,165 @@
+/*
+ * la.h: C ABI of the MI355X (gfx950) linear-attention library.
+ *
+ * Kernelised attention with the feature map phi(x) = elu(x) + 1 (paper eq. 7):
+ * causal forward (eq. 9-12), its constant-memory backward (eq. 13-15,
+ * Algorithm 1), the non-causal forward (eq. 4-6) and the recurrent decode step
+ * (eq. 16-20).
+ *
+ * Conventions shared by every entry point
+ *   Pointers   All tensor pointers are DEVICE pointers (HBM) valid on the
+ *              current HIP device.  The library never allocates, frees or keeps
+ *              them; the caller owns every buffer including the workspace.
+ *   Layout     Dense row-major [B, H, N, D] (Q, K and their gradients) and
+ *              [B, H, N, M] (V, O and their gradients): each (batch, head) pair
+ *              is one contiguous N x D slab and an independent problem.
+ *   dtype      `t` is the element type of the N-sized tensors only (Q, K, V, O,
+ *              dO, dQ, dK, dV; q, k, v, out in the step).  den, the workspace,
+ *              the decode state S, z and all accumulation are always fp32.
+ *              LA_BF16 tensors hold raw bfloat16 bit patterns (uint16).
+ *   Sizes      B, H, N >= 1.  N needs no alignment.  D and M must each be 32 or
+ *              64 (LA_ERR_UNSUPPORTED otherwise).  B*H*N*max(D,M) < 2^40.
+ *   eps        den_i = phi(Q_i) . Z_i + eps, added once to the finished dot
+ *              product; eps >= 0 (0 is legal: phi > 0 keeps den positive).
+ *   Stream     `stream` is a hipStream_t passed as void*; NULL is the default
+ *              stream.  Every call only enqueues work and returns without
+ *              synchronising.
+ *   Alignment  Tensor pointers must be 16-byte aligned (LA_ERR_ALIGN).
+ *   Errors     Return value: LA_OK (0) or a negative la_status.  Argument
+ *              errors are detected on the host before anything is launched;
+ *              a failed launch returns LA_ERR_HIP.  No exceptions, no abort.
+ *   Aliasing   Outputs must not overlap inputs or each other (undefined).
+ *   Determinism No floating-point atomics: the same call on the same inputs
+ *              gives bit-identical results.
+ *   Threads    No global mutable state apart from the optional profiling hook
+ *              at the end of this file; calls from several host threads are
+ *              safe as long as they do not share output or workspace buffers.
+ *   Tuning     Two environment variables, read at every call, override the
+ *              segment schedule (for tests and experiments): LA_TARGET_WAVES
+ *              (default 2048: wavefronts wanted in flight) and
+ *              LA_MIN_SEG_CHUNKS (default 4: shortest segment, in 16-token
+ *              chunks).  The workspace query and the call must see the same
+ *              values.
+ */
+#ifndef LA_H_
+#define LA_H_
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
+
+typedef enum {
+    LA_OK = 0,
+    LA_ERR_NULL = -1,         /* a required pointer is NULL                         */
+    LA_ERR_SHAPE = -2,        /* B, H or N < 1, eps < 0 or not finite, size overflow */
+    LA_ERR_UNSUPPORTED = -3,  /* D or M not in {32, 64}, unknown dtype              */
+    LA_ERR_WORKSPACE = -4,    /* ws is NULL or ws_bytes is smaller than the query   */
+    LA_ERR_HIP = -5,          /* a HIP call or kernel launch failed                 */
+    LA_ERR_ALIGN = -6         /* a tensor pointer is not 16-byte aligned            */
+} la_status;
+
+/* Static, NUL-terminated description of a status code. */
+const char *la_status_string(int status);
+
+/* Library version, major * 10000 + minor * 100 + patch. */
+int la_version(void);
+
+/*
+ * Workspace queries.  Host-only, no GPU call.  Return the number of bytes the
+ * matching entry point needs for these sizes on the current device (0 is
+ * possible: then ws may be NULL), or 0 for invalid sizes (the entry point
+ * itself reports the error).  The workspace holds per-segment partial states
+ * (the running sums of eq. 10-11 cut at segment borders, so that one long
+ * sequence can occupy many compute units) and, for the backward, two fp32
+ * scalars per token.
+ */
+size_t la_causal_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
+size_t la_causal_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
+size_t la_global_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
+
+/*
+ * Causal linear attention, forward (eq. 9 in its prefix-sum form eq. 10-12):
+ *   S_i = sum_{j<=i} phi(K_j) V_j^T,  Z_i = sum_{j<=i} phi(K_j),
+ *   den_i = phi(Q_i) . Z_i + eps,     O_i = phi(Q_i)^T S_i / den_i.
+ * Q, K [B,H,N,D] in; V [B,H,N,M] in; O [B,H,N,M] out; den [B,H,N] fp32 out or
+ * NULL (pass it if la_causal_bwd will follow).  ws: la_causal_fwd_workspace()
+ * bytes of scratch, contents undefined before and after.
+ */
+int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Causal linear attention, backward (eq. 13-15 / Algorithm 1 applied to the
+ * numerator and to the denominator together, then the chain rule through phi):
+ * given dO = dL/dO it writes dQ, dK (with respect to the RAW Q, K, i.e.
+ * through phi) and dV.  One forward and one reverse cumulative sum; memory is
+ * O(N max(D,M)), no per-position state is stored.
+ * O [B,H,N,M] and den [B,H,N] are the results of la_causal_fwd on the same
+ * Q, K, V, eps; if either is NULL both are recomputed into the workspace.
+ * dQ, dK [B,H,N,D] out; dV [B,H,N,M] out.  ws as above
+ * (la_causal_bwd_workspace()).
+ */
+int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                  const void *dO, void *dQ, void *dK, void *dV,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Non-causal linear attention, forward (eq. 5-6): the sums over all N keys are
+ * formed once and reused for every query,
+ *   O_i = phi(Q_i)^T (sum_j phi(K_j) V_j^T) / (phi(Q_i) . sum_j phi(K_j) + eps).
+ * Arguments as la_causal_fwd without den.  ws: la_global_fwd_workspace() bytes
+ * (never 0).
+ */
+int la_global_fwd(const void *Q, const void *K, const void *V, void *O,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * One recurrent decode step for B*H heads (eq. 16-20): update, then read.
+ *   S <- S + phi(k) v^T,  z <- z + phi(k),  out = phi(q)^T S / (phi(q) . z + eps).
+ * q, k [B,H,D] in; v [B,H,M] in; S [B,H,D,M] fp32 and z [B,H,D] fp32 in/out
+ * (the caller zero-fills them before the first step, eq. 16-17, and may copy
+ * them out and back to suspend and resume a sequence); out [B,H,M] out.
+ * Successive steps on one stream are ordered by the stream.
+ */
+int la_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z, void *out,
+                      int B, int H, int D, int M, float eps, la_dtype t, void *stream);
+
+/*
+ * Optional profiling hook (measurement aid, not part of the method).  Between
+ * la_profile_begin(mask) and la_profile_end() every launch of a kernel whose
+ * bit (1u << la_kernel_id) is set in `mask` is bracketed by two HIP events on
+ * the stream it is launched on.  la_profile_end waits for those events, adds
+ * the elapsed milliseconds per kernel into ms_total[LA_K_COUNT] and the number
+ * of launches into launches[LA_K_COUNT] (either may be NULL), and switches the
+ * hook off.  Process-wide, guarded by a mutex; at most 8192 launches are
+ * recorded per window.  Both return LA_OK or LA_ERR_HIP.
+ */
+typedef enum {
+    LA_K_SEG_KV = 0,   /* per-segment sums of phi(K)^T V and phi(K)            */
+    LA_K_SEG_QG = 1,   /* per-segment sums of phi(Q)^T dO/den and delta phi(Q) */
+    LA_K_SCAN = 2,     /* scan over the segment sums                           */
+    LA_K_FWD = 3,      /* causal forward pass                                  */
+    LA_K_GLOBAL = 4,   /* non-causal read-out                                  */
+    LA_K_PREP = 5,     /* 1/den and delta per token                            */
+    LA_K_DQ = 6,       /* gradient for Q (forward direction)                   */
+    LA_K_DV = 7,       /* gradient for V (reverse direction)                   */
+    LA_K_DK = 8,       /* gradient for K (reverse direction)                   */
+    LA_K_STEP = 9,     /* recurrent decode step                                */
+    LA_K_COUNT = 10
+} la_kernel_id;
+
+const char *la_kernel_name(int kernel_id);
+int la_profile_begin(unsigned mask);
+int la_profile_end(float *ms_total, int *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LA_H_ */

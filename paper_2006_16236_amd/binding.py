@@ -1,0 +1,186 @@
+"""Thin ctypes binding of the C ABI in include/la.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+libla_hip.so.  PyTorch supplies device memory (tensors) and streams, nothing
+else.  There is no CPU fallback: if the library is missing the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libla_hip.so")
+
+LA_F32, LA_BF16 = 0, 1
+LA_OK, LA_ERR_NULL, LA_ERR_SHAPE, LA_ERR_UNSUPPORTED = 0, -1, -2, -3
+LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN = -4, -5, -6
+
+EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
+           "la_global_fwd_workspace", "la_causal_fwd", "la_causal_bwd", "la_global_fwd",
+           "la_recurrent_step", "la_kernel_name", "la_profile_begin", "la_profile_end")
+LA_K_COUNT = 10
+
+
+class LaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2006_16236_amd.build "
+            "or __graft_entry__.build()); this package has no fallback path")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.la_status_string.restype = ctypes.c_char_p
+    lib.la_status_string.argtypes = [i]
+    lib.la_version.restype = i
+    for name in ("la_causal_fwd_workspace", "la_causal_bwd_workspace", "la_global_fwd_workspace"):
+        fn = getattr(lib, name)
+        fn.restype = sz
+        fn.argtypes = [i, i, i, i, i, i]
+    lib.la_causal_fwd.restype = i
+    lib.la_causal_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_causal_bwd.restype = i
+    lib.la_causal_bwd.argtypes = [vp] * 9 + [i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_global_fwd.restype = i
+    lib.la_global_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_recurrent_step.restype = i
+    lib.la_recurrent_step.argtypes = [vp] * 6 + [i, i, i, i, f, i, vp]
+    lib.la_kernel_name.restype = ctypes.c_char_p
+    lib.la_kernel_name.argtypes = [i]
+    lib.la_profile_begin.restype = i
+    lib.la_profile_begin.argtypes = [ctypes.c_uint]
+    lib.la_profile_end.restype = i
+    lib.la_profile_end.argtypes = [ctypes.POINTER(f), ctypes.POINTER(i)]
+    return lib
+
+
+_lib = _load()
+
+
+def status_string(status: int) -> str:
+    return _lib.la_status_string(int(status)).decode()
+
+
+def la_version() -> int:
+    return int(_lib.la_version())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return LA_F32
+    if t.dtype == torch.bfloat16:
+        return LA_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16")
+
+
+def _ptr(t) -> int | None:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("tensors must be contiguous device tensors")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int | None:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    h = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return h or None
+
+
+def _ws(ws, need: int, device):
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=device)
+    return ws, ws.data_ptr(), ws.numel() * ws.element_size()
+
+
+def _check(status: int, where: str) -> None:
+    if status != LA_OK:
+        raise LaError(status, where)
+
+
+def la_causal_fwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
+    return int(_lib.la_causal_fwd_workspace(B, H, N, D, M, dtype_code))
+
+
+def la_causal_bwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
+    return int(_lib.la_causal_bwd_workspace(B, H, N, D, M, dtype_code))
+
+
+def la_global_fwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
+    return int(_lib.la_global_fwd_workspace(B, H, N, D, M, dtype_code))
+
+
+def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None):
+    """O [B,H,N,M] <- causal linear attention of Q, K [B,H,N,D], V [B,H,N,M]; den [B,H,N] fp32
+    (optional) receives the denominators.  Enqueues on `stream` (default: torch's current)."""
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q)
+    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_causal_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
+                              float(eps), t, wp, wb, _stream(stream)), "la_causal_fwd")
+    return ws
+
+
+def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None):
+    """dQ, dK, dV <- gradients of causal linear attention for upstream dO; O and den are the
+    forward results (either may be None: both are then recomputed)."""
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q)
+    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(dO), _ptr(dQ),
+                              _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t, wp, wb,
+                              _stream(stream)), "la_causal_bwd")
+    return ws
+
+
+def la_global_fwd(Q, K, V, O, eps=1e-6, ws=None, stream=None):
+    """O <- non-causal linear attention (every query sees every key)."""
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q)
+    ws, wp, wb = _ws(ws, la_global_fwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_global_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), B, H, N, D, M, float(eps), t,
+                              wp, wb, _stream(stream)), "la_global_fwd")
+    return ws
+
+
+def la_recurrent_step(q, k, v, S, z, out, eps=1e-6, stream=None):
+    """One decode step for q, k [B,H,D], v [B,H,M]: S [B,H,D,M], z [B,H,D] (fp32) are updated
+    in place, out [B,H,M] receives the attention output of the new token."""
+    B, H, D = q.shape
+    M = v.shape[-1]
+    _check(_lib.la_recurrent_step(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(z), _ptr(out), B, H, D,
+                                  M, float(eps), _dtype_code(q), _stream(stream)),
+           "la_recurrent_step")
+
+
+def la_kernel_name(kernel_id: int) -> str:
+    return _lib.la_kernel_name(int(kernel_id)).decode()
+
+
+def la_profile_begin(mask: int = (1 << LA_K_COUNT) - 1) -> None:
+    """Bracket every launch of the kernels selected by `mask` with HIP events."""
+    _check(_lib.la_profile_begin(int(mask)), "la_profile_begin")
+
+
+def la_profile_end() -> dict:
+    """Wait for the recorded events; {kernel name: (total ms, launches)} for kernels that ran."""
+    ms = (ctypes.c_float * LA_K_COUNT)()
+    n = (ctypes.c_int * LA_K_COUNT)()
+    _check(_lib.la_profile_end(ms, n), "la_profile_end")
+    return {la_kernel_name(k): (float(ms[k]), int(n[k])) for k in range(LA_K_COUNT) if n[k] > 0}
+
+
+def raw():
+    """The ctypes library handle, for tests of the raw C ABI (error paths)."""
+    return _lib

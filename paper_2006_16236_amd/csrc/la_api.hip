@@ -1,0 +1,354 @@
+// The C ABI of include/la.h: argument checks, the segment schedule, workspace
+// carving and kernel launches.  No allocation, no synchronisation, no retained
+// pointers.
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include <atomic>
+#include <mutex>
+#include <vector>
+
+#include "../../include/la.h"
+#include "la_launch.h"
+
+namespace {
+
+constexpr int kVersion = 100;   // 0.1.0
+
+// ---- schedule ---------------------------------------------------------------------------------
+// One wavefront walks one segment of one sequence.  MI355X holds 256 CUs x 4 SIMDs x 2
+// such waves; a sequence is cut into segments only as far as needed to reach that
+// many waves, and never into segments shorter than a few chunks.
+struct Plan {
+    int nchunks, nseg, cps;
+};
+
+int env_int(const char *name, int dflt) {
+    const char *s = getenv(name);
+    if (s == nullptr || *s == '\0') return dflt;
+    const long v = strtol(s, nullptr, 10);
+    return v > 0 && v < (1 << 24) ? (int)v : dflt;
+}
+
+Plan make_plan(long BH, int N) {
+    const int target_waves = env_int("LA_TARGET_WAVES", 2048);
+    const int min_chunks = env_int("LA_MIN_SEG_CHUNKS", 4);
+    Plan p;
+    p.nchunks = (N + la::kChunk - 1) / la::kChunk;
+    long want = (target_waves + BH - 1) / BH;
+    long maxseg = p.nchunks / min_chunks;
+    if (maxseg < 1) maxseg = 1;
+    long nseg = want < 1 ? 1 : (want > maxseg ? maxseg : want);
+    p.cps = (int)((p.nchunks + nseg - 1) / nseg);
+    p.nseg = (p.nchunks + p.cps - 1) / p.cps;
+    return p;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t esize(la_dtype t) { return t == LA_BF16 ? 2 : 4; }
+
+size_t states_bytes(long BH, const Plan &p, int D, int M) {
+    return align256((size_t)BH * p.nseg * la::state_stride(D, M) * sizeof(float));
+}
+
+int check_dims(int B, int H, int N, int D, int M, float eps, la_dtype t) {
+    if (t != LA_F32 && t != LA_BF16) return LA_ERR_UNSUPPORTED;
+    if (!((D == 32 || D == 64) && (M == 32 || M == 64))) return LA_ERR_UNSUPPORTED;
+    if (B < 1 || H < 1 || N < 1) return LA_ERR_SHAPE;
+    if (!(eps >= 0.0f) || !isfinite(eps)) return LA_ERR_SHAPE;
+    const double elems = (double)B * H * (double)N * (D > M ? D : M);
+    if (elems >= 1099511627776.0) return LA_ERR_SHAPE;                 // 2^40
+    if ((double)B * H >= 1048576.0) return LA_ERR_SHAPE;               // grid size stays in int
+    return LA_OK;
+}
+
+bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+struct Carver {
+    char *base;
+    size_t off;
+    void *take(size_t bytes) {
+        void *p = base + off;
+        off += align256(bytes);
+        return p;
+    }
+};
+
+int hip_status(hipError_t e) { return e == hipSuccess ? LA_OK : LA_ERR_HIP; }
+
+// ---- optional profiling hook: HIP events around selected launches ----------------------------
+struct ProfRec {
+    int kid;
+    hipEvent_t a, b;
+};
+std::atomic<unsigned> g_prof_mask{0};
+std::mutex g_prof_mu;
+std::vector<ProfRec> g_prof_recs;
+std::vector<hipEvent_t> g_prof_pool;
+constexpr size_t kProfMaxRecs = 8192;
+
+hipEvent_t prof_event() {          // caller holds g_prof_mu
+    if (!g_prof_pool.empty()) {
+        hipEvent_t e = g_prof_pool.back();
+        g_prof_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+// Brackets one launch when its kernel is selected; otherwise a single relaxed load.
+struct ProfScope {
+    hipEvent_t stop = nullptr;
+    hipStream_t s;
+    ProfScope(int kid, hipStream_t stream) : s(stream) {
+        if ((g_prof_mask.load(std::memory_order_relaxed) & (1u << kid)) == 0) return;
+        std::lock_guard<std::mutex> lk(g_prof_mu);
+        if (g_prof_recs.size() >= kProfMaxRecs) return;
+        hipEvent_t a = prof_event(), b = prof_event();
+        if (a == nullptr || b == nullptr) return;
+        if (hipEventRecord(a, s) != hipSuccess) return;
+        g_prof_recs.push_back({kid, a, b});
+        stop = b;
+    }
+    ~ProfScope() {
+        if (stop != nullptr) (void)hipEventRecord(stop, s);
+    }
+};
+
+#define LA_TRY(expr)                          \
+    do {                                      \
+        const int st_ = hip_status(expr);     \
+        if (st_ != LA_OK) return st_;         \
+    } while (0)
+
+// forward on already-validated arguments; `states` holds states_bytes() when p.nseg > 1
+int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den, long BH, int N,
+                   int D, int M, float eps, la_dtype t, const Plan &p, float *states,
+                   hipStream_t s) {
+    const int nblocks = (int)(BH * p.nseg);
+    if (p.nseg > 1) {
+        la::SegArgs sa{};
+        sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = states;
+        sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = p.nseg - 1;
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s)); }
+    }
+    la::PassArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.G = nullptr; a.rden = nullptr; a.delta = nullptr;
+    a.out = O; a.den = den; a.state = p.nseg > 1 ? states : nullptr;
+    a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
+    { ProfScope ps(LA_K_FWD, s); LA_TRY(la::launch_pass_fwd(false, D, M, (int)t, a, nblocks, s)); }
+    return LA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *la_status_string(int status) {
+    switch (status) {
+        case LA_OK: return "ok";
+        case LA_ERR_NULL: return "a required pointer is NULL";
+        case LA_ERR_SHAPE: return "invalid size (B, H, N must be >= 1, eps finite and >= 0, total size < 2^40)";
+        case LA_ERR_UNSUPPORTED: return "unsupported D, M (each must be 32 or 64) or dtype";
+        case LA_ERR_WORKSPACE: return "workspace is NULL or smaller than the workspace query";
+        case LA_ERR_HIP: return "a HIP call or kernel launch failed";
+        case LA_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+        default: return "unknown status";
+    }
+}
+
+int la_version(void) { return kVersion; }
+
+size_t la_causal_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
+    if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    return p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+}
+
+size_t la_causal_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
+    if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    const size_t rows = (size_t)BH * N;
+    size_t bytes = 2 * align256(rows * sizeof(float));                      // rden, delta
+    if (p.nseg > 1) bytes += 2 * states_bytes(BH, p, D, M);                 // S and R states
+    bytes += align256(rows * M * esize(t)) + align256(rows * sizeof(float)); // O, den if recomputed
+    return bytes;
+}
+
+size_t la_global_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
+    if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const long BH = (long)B * H;
+    return states_bytes(BH, make_plan(BH, N), D, M);
+}
+
+int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream) {
+    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
+    const int st = check_dims(B, H, N, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws))
+        return LA_ERR_ALIGN;
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return LA_ERR_WORKSPACE;
+    return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
+                          static_cast<hipStream_t>(stream));
+}
+
+int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                  const void *dO, void *dQ, void *dK, void *dV,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream) {
+    if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr ||
+        dK == nullptr || dV == nullptr)
+        return LA_ERR_NULL;
+    const int st = check_dims(B, H, N, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) ||
+        misaligned(dK) || misaligned(dV) || misaligned(O) || misaligned(den) || misaligned(ws))
+        return LA_ERR_ALIGN;
+    const size_t need = la_causal_bwd_workspace(B, H, N, D, M, t);
+    if (ws == nullptr || ws_bytes < need) return LA_ERR_WORKSPACE;
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    const size_t rows = (size_t)BH * N;
+    Carver cv{static_cast<char *>(ws), 0};
+    float *rden = static_cast<float *>(cv.take(rows * sizeof(float)));
+    float *delta = static_cast<float *>(cv.take(rows * sizeof(float)));
+    float *stS = nullptr, *stR = nullptr;
+    if (p.nseg > 1) {
+        stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
+        stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
+    }
+    if (O == nullptr || den == nullptr) {      // recompute the forward results
+        void *Otmp = cv.take(rows * M * esize(t));
+        float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
+        const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s);
+        if (fs != LA_OK) return fs;
+        O = Otmp;
+        den = dentmp;
+    }
+    { ProfScope ps(LA_K_PREP, s); LA_TRY(la::launch_bwd_prep(dO, O, den, rden, delta, rows, M, (int)t, s)); }
+
+    const int nblocks = (int)(BH * p.nseg);
+    if (p.nseg > 1) {
+        la::SegArgs sa{};
+        sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps;
+        sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = stS;
+        sa.skip_seg = p.nseg - 1;
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s)); }
+        sa.Y = Q; sa.Z = dO; sa.rden = rden; sa.delta = delta; sa.state = stR;
+        sa.skip_seg = 0;
+        { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(1, D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanReverse, s)); }
+    }
+    la::PassArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
+    a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
+    a.out = dQ; a.state = stS;
+    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(D, M, (int)t, a, nblocks, s)); }
+    a.out = dV; a.state = stR;
+    { ProfScope ps(LA_K_DV, s); LA_TRY(la::launch_pass_dv(D, M, (int)t, a, nblocks, s)); }
+    a.out = dK; a.state = stR;
+    { ProfScope ps(LA_K_DK, s); LA_TRY(la::launch_pass_dk(D, M, (int)t, a, nblocks, s)); }
+    return LA_OK;
+}
+
+int la_global_fwd(const void *Q, const void *K, const void *V, void *O,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream) {
+    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
+    const int st = check_dims(B, H, N, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws))
+        return LA_ERR_ALIGN;
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    if (ws == nullptr || ws_bytes < states_bytes(BH, p, D, M)) return LA_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float *states = static_cast<float *>(ws);
+    const int nblocks = (int)(BH * p.nseg);
+    la::SegArgs sa{};
+    sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = states;
+    sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
+    { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+    if (p.nseg > 1)
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+    la::PassArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.out = O; a.den = nullptr; a.state = states;
+    a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
+    { ProfScope ps(LA_K_GLOBAL, s); LA_TRY(la::launch_pass_fwd(true, D, M, (int)t, a, nblocks, s)); }
+    return LA_OK;
+}
+
+int la_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z, void *out,
+                      int B, int H, int D, int M, float eps, la_dtype t, void *stream) {
+    if (q == nullptr || k == nullptr || v == nullptr || S == nullptr || z == nullptr ||
+        out == nullptr)
+        return LA_ERR_NULL;
+    const int st = check_dims(B, H, 1, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(S) || misaligned(z) ||
+        misaligned(out))
+        return LA_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ProfScope ps(LA_K_STEP, s);
+    LA_TRY(la::launch_recurrent_step(q, k, v, S, z, out, (int)((long)B * H), D, M, eps, (int)t, s));
+    return LA_OK;
+}
+
+const char *la_kernel_name(int kernel_id) {
+    static const char *const names[LA_K_COUNT] = {"segment_state_kv", "segment_state_qg", "scan_states",
+                                                  "causal_pass_fwd", "global_readout", "bwd_prep",
+                                                  "causal_pass_dq", "causal_pass_dv", "causal_pass_dk",
+                                                  "recurrent_step"};
+    return kernel_id >= 0 && kernel_id < LA_K_COUNT ? names[kernel_id] : "unknown";
+}
+
+int la_profile_begin(unsigned mask) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    for (const ProfRec &r : g_prof_recs) {
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof_recs.clear();
+    g_prof_mask.store(mask & ((1u << LA_K_COUNT) - 1u), std::memory_order_relaxed);
+    return LA_OK;
+}
+
+int la_profile_end(float *ms_total, int *launches) {
+    std::lock_guard<std::mutex> lk(g_prof_mu);
+    g_prof_mask.store(0, std::memory_order_relaxed);
+    int status = LA_OK;
+    if (ms_total != nullptr)
+        for (int k = 0; k < LA_K_COUNT; ++k) ms_total[k] = 0.f;
+    if (launches != nullptr)
+        for (int k = 0; k < LA_K_COUNT; ++k) launches[k] = 0;
+    for (const ProfRec &r : g_prof_recs) {
+        float ms = 0.f;
+        if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) {
+            status = LA_ERR_HIP;
+        } else {
+            if (ms_total != nullptr) ms_total[r.kid] += ms;
+            if (launches != nullptr) launches[r.kid] += 1;
+        }
+        g_prof_pool.push_back(r.a);
+        g_prof_pool.push_back(r.b);
+    }
+    g_prof_recs.clear();
+    return status;
+}
+
+}  // extern "C"

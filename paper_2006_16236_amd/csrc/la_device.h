@@ -1,0 +1,120 @@
+// Device-side building blocks shared by the gfx950 linear-attention kernels:
+// feature map, element conversion, the two register layouts in which 16-token
+// tiles are fetched, and the fp32 16x16x4 MFMA wrapper.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace la {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kChunk = 16;       // tokens per chunk = MFMA tile edge
+constexpr int kWave = 64;
+
+// ---- feature map (paper eq. 7): phi(x) = elu(x) + 1 ------------------------------------
+// x > 0: x + 1; otherwise exp(x).  The exponential is only ever taken of a
+// non-positive argument (the untaken branch cannot overflow).
+__device__ __forceinline__ float phi(float x) {
+    const float e = __expf(fminf(x, 0.0f));
+    return x > 0.0f ? x + 1.0f : e;
+}
+// phi'(x) = 1 for x > 0, exp(x) otherwise.
+__device__ __forceinline__ float dphi(float x) {
+    const float e = __expf(fminf(x, 0.0f));
+    return x > 0.0f ? 1.0f : e;
+}
+
+// ---- element types ------------------------------------------------------------------------
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {      // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ void store_elem(T *p, float v);
+template <> __device__ __forceinline__ void store_elem<float>(float *p, float v) { *p = v; }
+template <> __device__ __forceinline__ void store_elem<bf16_t>(bf16_t *p, float v) {
+    p->bits = f32_to_bf16_bits(v);
+}
+
+// four consecutive elements, 16-byte (fp32) or 8-byte (bf16) aligned
+__device__ __forceinline__ f32x4 load4(const float *p) {
+    return *reinterpret_cast<const f32x4 *>(p);
+}
+__device__ __forceinline__ f32x4 load4(const bf16_t *p) {
+    const uint2 u = *reinterpret_cast<const uint2 *>(p);
+    f32x4 r;
+    r[0] = __uint_as_float(u.x << 16);
+    r[1] = __uint_as_float(u.x & 0xffff0000u);
+    r[2] = __uint_as_float(u.y << 16);
+    r[3] = __uint_as_float(u.y & 0xffff0000u);
+    return r;
+}
+
+// ---- wave-level helpers ---------------------------------------------------------------------
+// A wave is viewed as 4 groups (g = lane / 16) of 16 lanes (c = lane % 16).
+__device__ __forceinline__ float sum_over_groups(float v) {          // over g, result in all lanes
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    return v;
+}
+
+// D = A * B + C for one 16x16 tile, contraction depth 4.  Lane (c, g) supplies
+// A[c][g] and B[g][c]; register r of the accumulator holds C[4g + r][c].
+__device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
+}
+
+// ---- the two tile layouts -------------------------------------------------------------------
+// A tile is 16 consecutive tokens x F features of one [N, F] slab, F in {32, 64}.
+//
+// token-lane:   lane (c, g) holds token c, features 16*ft + 4g + r   -> x[ft][r]
+//               (the operand of an MFMA whose non-contracted index is the token;
+//               contraction step (ft, r) pairs feature 16*ft + 4g + r on both sides)
+// feature-lane: lane (c, g) holds feature 16*ft + c of tokens 4g + s -> x[ft][s]
+//               (the operand of an MFMA whose non-contracted index is the feature;
+//               contraction step s pairs token 4g + s on both sides)
+//
+// Rows at or beyond `nvalid` read as zero.  `base` points at token 0 of the tile.
+template <int F, typename T>
+__device__ __forceinline__ void load_token_lane(const T *base, int nvalid, int c, int g,
+                                                float (&x)[F / 16][4]) {
+    const bool ok = c < nvalid;
+    const T *p = base + (size_t)c * F + 4 * g;
+#pragma unroll
+    for (int ft = 0; ft < F / 16; ++ft) {
+        f32x4 v = {0.f, 0.f, 0.f, 0.f};
+        if (ok) v = load4(p + 16 * ft);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) x[ft][r] = v[r];
+    }
+}
+
+template <int F, typename T>
+__device__ __forceinline__ void load_feature_lane(const T *base, int nvalid, int c, int g,
+                                                  float (&x)[F / 16][4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const int row = 4 * g + s;
+        const bool ok = row < nvalid;
+        const T *p = base + (size_t)row * F + c;
+#pragma unroll
+        for (int ft = 0; ft < F / 16; ++ft) x[ft][s] = ok ? to_f32(p[16 * ft]) : 0.0f;
+    }
+}
+
+// four per-token scalars for tokens 4g + s (fp32 side arrays such as 1/den)
+__device__ __forceinline__ void load_rows4(const float *base, int nvalid, int g, float (&x)[4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) x[s] = (4 * g + s) < nvalid ? base[4 * g + s] : 0.0f;
+}
+
+}  // namespace la

@@ -1,0 +1,42 @@
+// Host-side launchers of the kernels, one per translation unit, used by the C ABI shell.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+#include "la_passes.h"
+
+namespace la {
+
+// dtype: 0 = fp32, 1 = bf16 (la_dtype of the public header)
+hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs &a, int nblocks,
+                           hipStream_t s);
+hipError_t launch_pass_dq(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
+hipError_t launch_pass_dv(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
+hipError_t launch_pass_dk(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
+hipError_t launch_segment_state(int kind, int D, int M, int dtype, const SegArgs &a, int nblocks,
+                                hipStream_t s);
+
+enum ScanMode { kScanForward = 0, kScanReverse = 1, kScanTotal = 2 };
+// In-place scan over the nseg slots of every sequence: exclusive prefix, exclusive
+// suffix, or the grand total written to slot 0.
+hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s);
+
+// rden_i = 1/den_i, delta_i = -(dO_i . O_i)/den_i for all rows.
+hipError_t launch_bwd_prep(const void *dO, const void *O, const float *den, float *rden,
+                           float *delta, size_t rows, int M, int dtype, hipStream_t s);
+
+hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z,
+                                 void *out, int BH, int D, int M, float eps, int dtype,
+                                 hipStream_t s);
+
+#define LA_DISPATCH_DM(D, M, ...)                                              \
+    do {                                                                       \
+        if ((D) == 32 && (M) == 32) { constexpr int kD = 32, kM = 32; __VA_ARGS__; }  \
+        else if ((D) == 32 && (M) == 64) { constexpr int kD = 32, kM = 64; __VA_ARGS__; } \
+        else if ((D) == 64 && (M) == 32) { constexpr int kD = 64, kM = 32; __VA_ARGS__; } \
+        else if ((D) == 64 && (M) == 64) { constexpr int kD = 64, kM = 64; __VA_ARGS__; } \
+        else return hipErrorInvalidValue;                                      \
+    } while (0)
+
+}  // namespace la

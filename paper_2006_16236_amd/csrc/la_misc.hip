@@ -1,0 +1,157 @@
+// Small bandwidth-bound kernels: the scan over segment states, the per-token
+// scalars of the backward, and the recurrent decode step (eq. 16-20).
+#include "la_launch.h"
+
+namespace la {
+
+// ---- scan over the segment states of each sequence ------------------------------------------
+// state: [BH, nseg, stride]; one thread per (sequence, element) walks the nseg slots.
+__global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg, int stride,
+                                                          int mode) {
+    const int e = blockIdx.x * 256 + threadIdx.x;
+    if (e >= stride) return;
+    float *p = state + (size_t)blockIdx.y * nseg * stride + e;
+    float acc = 0.f;
+    if (mode == kScanForward) {            // slot s <- sum of slots before s (the last total is unread)
+        for (int s = 0; s < nseg; ++s) {
+            const float t = (s + 1 < nseg) ? p[(size_t)s * stride] : 0.f;
+            p[(size_t)s * stride] = acc;
+            acc += t;
+        }
+    } else if (mode == kScanReverse) {     // slot s <- sum of slots after s (the first total is unread)
+        for (int s = nseg - 1; s >= 0; --s) {
+            const float t = (s > 0) ? p[(size_t)s * stride] : 0.f;
+            p[(size_t)s * stride] = acc;
+            acc += t;
+        }
+    } else {                               // slot 0 <- sum of all slots
+        for (int s = 0; s < nseg; ++s) acc += p[(size_t)s * stride];
+        p[0] = acc;
+    }
+}
+
+hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s) {
+    dim3 grid((stride + 255) / 256, BH);
+    scan_states_kernel<<<grid, 256, 0, s>>>(state, nseg, stride, mode);
+    return hipGetLastError();
+}
+
+// ---- per-token scalars of the backward -----------------------------------------------------
+// The fraction O = num/den sends dO/den to the numerator and -(dO . O)/den to the
+// denominator (quotient rule); both are needed by every backward pass.
+template <int M, typename T>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(const T *dO, const T *O, const float *den,
+                                                       float *rden, float *delta, size_t rows) {
+    constexpr int LPR = M / 4;                       // lanes that share one row
+    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t row = t / LPR;
+    const int col4 = (int)(t % LPR) * 4;
+    float p = 0.f;
+    if (row < rows) {
+        const f32x4 g4 = load4(dO + row * M + col4);
+        const f32x4 o4 = load4(O + row * M + col4);
+        p = (g4[0] * o4[0] + g4[1] * o4[1]) + (g4[2] * o4[2] + g4[3] * o4[3]);
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) p += __shfl_xor(p, off);
+    if (row < rows && col4 == 0) {
+        const float r = 1.0f / den[row];
+        rden[row] = r;
+        delta[row] = -p * r;
+    }
+}
+
+hipError_t launch_bwd_prep(const void *dO, const void *O, const float *den, float *rden,
+                           float *delta, size_t rows, int M, int dtype, hipStream_t s) {
+    const size_t threads = rows * (size_t)(M / 4);
+    const unsigned blocks = (unsigned)((threads + 255) / 256);
+    if (M == 64) {
+        if (dtype == 0) bwd_prep_kernel<64, float><<<blocks, 256, 0, s>>>((const float *)dO, (const float *)O, den, rden, delta, rows);
+        else bwd_prep_kernel<64, bf16_t><<<blocks, 256, 0, s>>>((const bf16_t *)dO, (const bf16_t *)O, den, rden, delta, rows);
+    } else if (M == 32) {
+        if (dtype == 0) bwd_prep_kernel<32, float><<<blocks, 256, 0, s>>>((const float *)dO, (const float *)O, den, rden, delta, rows);
+        else bwd_prep_kernel<32, bf16_t><<<blocks, 256, 0, s>>>((const bf16_t *)dO, (const bf16_t *)O, den, rden, delta, rows);
+    } else {
+        return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ---- recurrent decode step (eq. 16-20) -------------------------------------------------------
+// One workgroup of four waves per head.  Every lane owns four adjacent columns of
+// S; M/4 lanes cover a row, a wave covers 256/M rows per iteration.  The rank-1
+// update, the z update and the read-out run in one sweep over S (read once,
+// written once); the column sums are combined by wave shuffles, then across the
+// four waves through LDS.  Fixed order everywhere: bit-identical run to run.
+template <int D, int M, typename T>
+__global__ __launch_bounds__(256) void recurrent_step_kernel(const T *q, const T *k, const T *v,
+                                                             float *S, float *z, T *out,
+                                                             float eps) {
+    constexpr int LPR = M / 4;            // lanes per row of S
+    constexpr int RPW = kWave / LPR;      // rows per wave per iteration
+    constexpr int RPI = 4 * RPW;          // rows per workgroup per iteration
+    static_assert(D % RPI == 0, "D must be a multiple of the rows swept per iteration");
+    __shared__ float red[4][M];
+    __shared__ float dred[4];
+
+    const int bh = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col4 = (lane % LPR) * 4, rsub = lane / LPR;
+    const T *qh = q + (size_t)bh * D, *kh = k + (size_t)bh * D;
+    float *Sh = S + (size_t)bh * D * M, *zh = z + (size_t)bh * D;
+
+    const f32x4 v4 = load4(v + (size_t)bh * M + col4);
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    float dpart = 0.f;
+#pragma unroll
+    for (int it = 0; it < D / RPI; ++it) {
+        const int d = it * RPI + wave * RPW + rsub;
+        const float kd = phi(to_f32(kh[d]));
+        const float qd = phi(to_f32(qh[d]));
+        f32x4 s4 = *reinterpret_cast<f32x4 *>(Sh + (size_t)d * M + col4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s4[e] = fmaf(kd, v4[e], s4[e]);          // eq. 18
+            acc[e] = fmaf(qd, s4[e], acc[e]);
+        }
+        *reinterpret_cast<f32x4 *>(Sh + (size_t)d * M + col4) = s4;
+        if (col4 == 0) {
+            const float zn = zh[d] + kd;             // eq. 19
+            zh[d] = zn;
+            dpart = fmaf(qd, zn, dpart);
+        }
+    }
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], off);
+    }
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) dpart += __shfl_xor(dpart, off);
+    if (rsub == 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) red[wave][col4 + e] = acc[e];
+    }
+    if (lane == 0) dred[wave] = dpart;
+    __syncthreads();
+    if (tid < M) {
+        const float num = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+        const float den = ((dred[0] + dred[1]) + (dred[2] + dred[3])) + eps;
+        store_elem(out + (size_t)bh * M + tid, num / den);     // eq. 20 (the fraction)
+    }
+}
+
+hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z,
+                                 void *out, int BH, int D, int M, float eps, int dtype,
+                                 hipStream_t s) {
+    LA_DISPATCH_DM(D, M, {
+        if (dtype == 0)
+            recurrent_step_kernel<kD, kM, float><<<BH, 256, 0, s>>>(
+                (const float *)q, (const float *)k, (const float *)v, S, z, (float *)out, eps);
+        else
+            recurrent_step_kernel<kD, kM, bf16_t><<<BH, 256, 0, s>>>(
+                (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, S, z, (bf16_t *)out, eps);
+    });
+    return hipGetLastError();
+}
+
+}  // namespace la

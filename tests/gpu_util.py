@@ -1,0 +1,82 @@
+"""Helpers shared by the GPU parity tests: device upload/download, the error metric and
+schedule forcing.  Holds none of the method's arithmetic."""
+import contextlib
+import os
+
+import numpy as np
+import torch
+
+import workloads as wl
+
+DEV = "cuda:0"
+
+# Tolerances of the benchmark spec: max|gpu - ref| / max|ref| per output tensor.
+TOL_F32 = 1e-4          # fp32, N <= 4096
+TOL_F32_LONG = 1e-3     # fp32, N > 4096
+TOL_BF16 = 2e-2         # bf16 tensors, fp32 accumulation
+
+
+def tol_for(N, bf16=False):
+    if bf16:
+        return TOL_BF16
+    return TOL_F32 if N <= 4096 else TOL_F32_LONG
+
+
+def rel_err(got, ref, floor=0.0):
+    """max|got - ref| / max(max|ref|, floor).  `floor` matters only where the exact result
+    vanishes by cancellation (see grad_errs)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape
+    assert np.all(np.isfinite(got)), "non-finite values in the GPU result"
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), floor, 1e-300))
+
+
+def grad_errs(got, ref):
+    """Errors of (dQ, dK, dV).  Each tensor is scaled by its own max|ref|, but never by less
+    than 1e-3 of the largest of the three: for N = 1 (and for constant V) the exact dQ, dK
+    are zero up to eps, every term cancels, and a scale of their own would be meaningless."""
+    floor = 1e-3 * max(float(np.abs(r).max()) for r in ref)
+    return [rel_err(a, b, floor) for a, b in zip(got, ref)]
+
+
+def to_dev(x, bf16=False):
+    """float32 host array -> device tensor (bf16: the values must already be bf16-exact)."""
+    t = torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+    return t.to(torch.bfloat16) if bf16 else t
+
+
+def to_host(t):
+    return t.detach().to(torch.float32).cpu().numpy()
+
+
+@contextlib.contextmanager
+def schedule(target_waves=None, min_seg_chunks=None):
+    """Force the segment schedule of the library through its two environment knobs."""
+    keys = {"LA_TARGET_WAVES": target_waves, "LA_MIN_SEG_CHUNKS": min_seg_chunks}
+    old = {k: os.environ.get(k) for k in keys}
+    try:
+        for k, v in keys.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = str(v)
+        yield
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+SCHEDULES = {
+    "default": dict(),
+    "one_segment": dict(target_waves=1),
+    "many_segments": dict(target_waves=1 << 20, min_seg_chunks=1),
+    "three_chunk_segments": dict(target_waves=1 << 20, min_seg_chunks=3),
+}
+
+
+def maybe_bf16(arrs, bf16):
+    return [wl.round_to_bf16(a) for a in arrs] if bf16 else list(arrs)

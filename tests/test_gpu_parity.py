@@ -1,0 +1,228 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle, element by element,
+on the same seeded inputs.  Sizes span several 16-token chunks, several segments and ragged
+tails; every schedule of the segment scan is forced in turn."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import (DEV, SCHEDULES, grad_errs, maybe_bf16, rel_err, schedule, to_dev, to_host,
+                      tol_for)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def la():
+    import paper_2006_16236_amd as la_mod
+    assert torch.cuda.is_available()
+    return la_mod
+
+
+def run_fwd(la, Q, K, V, eps, bf16=False, want_den=True):
+    dq, dk, dv = (to_dev(x, bf16) for x in (Q, K, V))
+    O = torch.full_like(dv, float("nan"))
+    den = torch.full(Q.shape[:-1], float("nan"), dtype=torch.float32, device=DEV) if want_den else None
+    la.la_causal_fwd(dq, dk, dv, O, den, eps)
+    torch.cuda.synchronize()
+    return to_host(O), (den.cpu().numpy() if want_den else None)
+
+
+def run_bwd(la, Q, K, V, G, eps, bf16=False, reuse_fwd=True):
+    dq, dk, dv, dg = (to_dev(x, bf16) for x in (Q, K, V, G))
+    O = den = None
+    if reuse_fwd:
+        O = torch.empty_like(dv)
+        den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=DEV)
+        la.la_causal_fwd(dq, dk, dv, O, den, eps)
+    gq = torch.full_like(dq, float("nan"))
+    gk = torch.full_like(dk, float("nan"))
+    gv = torch.full_like(dv, float("nan"))
+    la.la_causal_bwd(dq, dk, dv, O, den, dg, gq, gk, gv, eps)
+    torch.cuda.synchronize()
+    return to_host(gq), to_host(gk), to_host(gv)
+
+
+EDGE_N = [1, 15, 16, 17, 63, 64, 65, 257, 784, 1000]
+
+
+@pytest.mark.parametrize("sched", list(SCHEDULES))
+@pytest.mark.parametrize("N", EDGE_N)
+def test_causal_fwd_edge_lengths(la, oracle, N, sched):
+    B, H, D, M = 2, 3, 64, 64
+    Q, K, V = wl.random_case(100 + N, B, H, N, D, M)[:3]
+    ref, dref = oracle.causal_fwd_prefix(Q, K, V, 1e-6, return_den=True)
+    with schedule(**SCHEDULES[sched]):
+        O, den = run_fwd(la, Q, K, V, 1e-6)
+    assert rel_err(O, ref) <= tol_for(N)
+    assert rel_err(den, dref) <= tol_for(N)
+
+
+@pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32), (64, 64)])
+@pytest.mark.parametrize("sched", ["default", "many_segments"])
+def test_causal_fwd_bwd_all_head_sizes(la, oracle, D, M, sched):
+    B, H, N = 2, 2, 203
+    Q, K, V, G = wl.random_case(200 + D + 2 * M, B, H, N, D, M)
+    eps = 1e-6
+    ref = oracle.causal_fwd_prefix(Q, K, V, eps)
+    gref = oracle.causal_bwd_linear(Q, K, V, G, eps)
+    with schedule(**SCHEDULES[sched]):
+        O, _ = run_fwd(la, Q, K, V, eps)
+        got = run_bwd(la, Q, K, V, G, eps)
+    assert rel_err(O, ref) <= tol_for(N)
+    for e, name in zip(grad_errs(got, gref), ("dQ", "dK", "dV")):
+        assert e <= tol_for(N), name
+
+
+@pytest.mark.parametrize("sched", list(SCHEDULES))
+@pytest.mark.parametrize("N", EDGE_N)
+def test_causal_bwd_edge_lengths(la, oracle, N, sched):
+    B, H, D, M = 1, 3, 64, 64
+    Q, K, V, G = wl.random_case(300 + N, B, H, N, D, M)
+    gref = oracle.causal_bwd_linear(Q, K, V, G, 1e-6)
+    with schedule(**SCHEDULES[sched]):
+        got = run_bwd(la, Q, K, V, G, 1e-6)
+    for e, name in zip(grad_errs(got, gref), ("dQ", "dK", "dV")):
+        assert e <= tol_for(N), name
+
+
+def test_causal_bwd_recomputes_forward_when_not_given(la, oracle):
+    B, H, N, D, M = 2, 2, 333, 64, 64
+    Q, K, V, G = wl.random_case(401, B, H, N, D, M)
+    gref = oracle.causal_bwd_linear(Q, K, V, G, 1e-6)
+    for sched in ("default", "many_segments"):
+        with schedule(**SCHEDULES[sched]):
+            a = run_bwd(la, Q, K, V, G, 1e-6, reuse_fwd=False)
+            b = run_bwd(la, Q, K, V, G, 1e-6, reuse_fwd=True)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+        assert max(grad_errs(a, gref)) <= tol_for(N)
+
+
+@pytest.mark.parametrize("eps", [0.0, 1e-6, 0.5])
+def test_eps_values(la, oracle, eps):
+    B, H, N, D, M = 1, 2, 100, 32, 32
+    Q, K, V, G = wl.random_case(402, B, H, N, D, M)
+    ref = oracle.causal_fwd_prefix(Q, K, V, eps)
+    gref = oracle.causal_bwd_linear(Q, K, V, G, eps)
+    O, _ = run_fwd(la, Q, K, V, eps)
+    assert rel_err(O, ref) <= tol_for(N)
+    assert max(grad_errs(run_bwd(la, Q, K, V, G, eps), gref)) <= tol_for(N)
+
+
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+@pytest.mark.parametrize("N", [1, 17, 64, 257, 1000])
+def test_global_fwd(la, oracle, N, sched):
+    B, H, D, M = 2, 2, 64, 64
+    Q, K, V = wl.random_case(500 + N, B, H, N, D, M)[:3]
+    ref = oracle.global_fwd_linear(Q, K, V, 1e-6)
+    dq, dk, dv = (to_dev(x) for x in (Q, K, V))
+    O = torch.full_like(dv, float("nan"))
+    with schedule(**SCHEDULES[sched]):
+        la.la_global_fwd(dq, dk, dv, O, 1e-6)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(O), ref) <= tol_for(N)
+
+
+@pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32), (64, 64)])
+def test_recurrent_steps_against_oracle_and_causal_fwd(la, oracle, D, M):
+    B, H, T = 3, 2, 40
+    w = wl.DecodeWorkload("t", B, H, D, M, T, 600 + D + 2 * M)
+    q, k, v = wl.decode_streams(w)
+    S = torch.zeros(B, H, D, M, device=DEV)
+    z = torch.zeros(B, H, D, device=DEV)
+    dq, dk, dv = (to_dev(x) for x in (q, k, v))
+    out = torch.empty(T, B, H, M, device=DEV)
+    for t in range(T):
+        la.la_recurrent_step(dq[t], dk[t], dv[t], S, z, out[t], 1e-6)
+    torch.cuda.synchronize()
+    So = np.zeros((B, H, D, M)); zo = np.zeros((B, H, D))
+    ref = np.stack([oracle.recurrent_step(q[t], k[t], v[t], So, zo, 1e-6) for t in range(T)])
+    assert rel_err(to_host(out), ref) <= 1e-4
+    assert rel_err(S.cpu().numpy(), So) <= 1e-4
+    assert rel_err(z.cpu().numpy(), zo) <= 1e-4
+    # the same tokens stacked as one sequence through the parallel kernel (eq. 12 == eq. 20)
+    Qs, Ks, Vs = (np.ascontiguousarray(np.moveaxis(x, 0, 2)) for x in (q, k, v))
+    O, _ = run_fwd(la, Qs, Ks, Vs, 1e-6)
+    assert rel_err(O, np.moveaxis(ref, 0, 2)) <= 1e-4
+
+
+@pytest.mark.parametrize("sched", ["default", "many_segments"])
+def test_bf16_tensors_fp32_state(la, oracle, sched):
+    B, H, N, D, M = 2, 2, 300, 64, 64
+    Q, K, V, G = maybe_bf16(wl.random_case(700, B, H, N, D, M, scale=0.125), True)
+    eps = 1e-6
+    ref = oracle.causal_fwd_prefix(Q, K, V, eps)
+    with schedule(**SCHEDULES[sched]):
+        O, _ = run_fwd(la, Q, K, V, eps, bf16=True)
+        got = run_bwd(la, Q, K, V, G, eps, bf16=True)
+    assert rel_err(O, ref) <= tol_for(N, True)
+    # the backward consumes the bf16-rounded O of the forward, as a training step would
+    gref = oracle.causal_bwd_linear(Q, K, V, G, eps)
+    for e, name in zip(grad_errs(got, gref), ("dQ", "dK", "dV")):
+        assert e <= tol_for(N, True), name
+
+
+def test_bitwise_determinism_and_slab_independence(la):
+    B, H, N, D, M = 2, 4, 500, 64, 64
+    Q, K, V, G = wl.random_case(800, B, H, N, D, M)
+    with schedule(**SCHEDULES["three_chunk_segments"]):
+        O1, d1 = run_fwd(la, Q, K, V, 1e-6)
+        O2, d2 = run_fwd(la, Q, K, V, 1e-6)
+        g1 = run_bwd(la, Q, K, V, G, 1e-6)
+        g2 = run_bwd(la, Q, K, V, G, 1e-6)
+        perm = [1, 0]
+        O3, _ = run_fwd(la, Q[perm], K[perm], V[perm], 1e-6)
+    assert np.array_equal(O1, O2) and np.array_equal(d1, d2)
+    assert all(np.array_equal(a, b) for a, b in zip(g1, g2))
+    assert np.array_equal(O3, O1[perm])
+
+
+def test_causality_huge_future_does_not_leak(la):
+    """Outputs before token t are bit-identical whatever finite values follow it: the mask
+    is a select on the scores, so even 1e30-sized future values contribute an exact zero.
+    (Non-finite inputs are outside the contract: 0 * inf inside a 16-token tile is NaN.)"""
+    B, H, N, D, M = 1, 2, 200, 64, 64
+    Q, K, V = wl.random_case(801, B, H, N, D, M)[:3]
+    t = 77                                     # inside a chunk: 77 = 4*16 + 13
+    O, _ = run_fwd(la, Q, K, V, 1e-6)
+    Q2, K2, V2 = Q.copy(), K.copy(), V.copy()
+    V2[:, :, t:] = 1e30
+    Q2[:, :, t:] = -3.0
+    K2[:, :, t:] = 50.0
+    dq, dk, dv = (to_dev(x) for x in (Q2, K2, V2))
+    O2 = torch.empty_like(dv)
+    la.la_causal_fwd(dq, dk, dv, O2, None, 1e-6)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(O2)[:, :, :t], O[:, :, :t])
+
+
+def test_outputs_stay_inside_their_buffers(la):
+    """Guard bands around every output keep their NaN fill for a ragged N."""
+    B, H, N, D, M = 2, 2, 77, 32, 64
+    Q, K, V, G = wl.random_case(802, B, H, N, D, M)
+    dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+    pad = 1024
+
+    def guarded(shape):
+        n = int(np.prod(shape))
+        buf = torch.full((n + 2 * pad,), float("nan"), device=DEV)
+        return buf, buf[pad:pad + n].view(*shape)
+
+    bO, O = guarded(dv.shape); bd, den = guarded(Q.shape[:-1])
+    bq, gq = guarded(dq.shape); bk, gk = guarded(dk.shape); bv, gv = guarded(dv.shape)
+    with schedule(**SCHEDULES["many_segments"]):
+        la.la_causal_fwd(dq, dk, dv, O, den, 1e-6)
+        la.la_causal_bwd(dq, dk, dv, O, den, dg, gq, gk, gv, 1e-6)
+    torch.cuda.synchronize()
+    for buf, view in ((bO, O), (bd, den), (bq, gq), (bk, gk), (bv, gv)):
+        assert torch.isnan(buf[:pad]).all() and torch.isnan(buf[-pad:]).all()
+        assert torch.isfinite(view).all()
+
+
+def test_underflowed_keys_give_zero_rows(la):
+    B, H, N, D, M = 1, 1, 40, 32, 32
+    Q, K, V = wl.random_case(803, B, H, N, D, M)[:3]
+    K[:, :, :20] = -200.0                     # exp underflows to 0 in fp32
+    O, den = run_fwd(la, Q, K, V, 1e-6)
+    assert np.all(O[:, :, :20] == 0.0)
+    assert np.all(np.isfinite(O))
