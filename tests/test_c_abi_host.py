@@ -1,0 +1,115 @@
+"""Host-side checks of the C ABI that need no GPU: the shared library loads, exports every
+symbol that include/la.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "la.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2006_16236_amd import build
+    if not os.path.exists(build.LIB):
+        build.build_library(force=True)
+    from paper_2006_16236_amd import binding
+    return binding.raw()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(la_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2006_16236_amd import binding
+    names = declared_functions()
+    assert {"la_causal_fwd", "la_causal_bwd", "la_global_fwd", "la_recurrent_step"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in la.h but not exported"
+    assert set(binding.EXPORTS) == set(names)
+
+
+def test_version_and_status_strings(lib):
+    from paper_2006_16236_amd import binding
+    assert binding.la_version() >= 100
+    seen = set()
+    for st in range(0, -7, -1):
+        s = binding.status_string(st)
+        assert s and s != "unknown status" and s not in seen
+        seen.add(s)
+    assert binding.status_string(-99) == "unknown status"
+    assert binding.la_kernel_name(3) == "causal_pass_fwd" and binding.la_kernel_name(99) == "unknown"
+
+
+def test_workspace_queries(lib):
+    from paper_2006_16236_amd import binding as b
+    assert b.la_causal_fwd_workspace(256, 8, 512, 64, 64) == 0          # 2048 sequences: one segment each
+    long = b.la_causal_fwd_workspace(2, 8, 65536, 64, 64)
+    assert long == 16 * 128 * (64 * 64 + 64) * 4                        # 128 segments of 512 tokens
+    assert b.la_causal_bwd_workspace(2, 8, 65536, 64, 64) > 2 * long
+    assert b.la_global_fwd_workspace(1, 1, 1, 32, 32) >= (32 * 32 + 32) * 4
+    assert b.la_causal_fwd_workspace(1, 1, 100, 48, 64) == 0            # invalid D: query returns 0
+    assert b.la_causal_fwd_workspace(0, 1, 100, 64, 64) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    """Fake (never dereferenced) device addresses: every call must fail in validation."""
+    from paper_2006_16236_amd import binding as b
+    p = ctypes.c_void_p(0x10000)
+    odd = ctypes.c_void_p(0x10004)
+    null = ctypes.c_void_p(None)
+    f = ctypes.c_float
+    fwd = lib.la_causal_fwd
+    assert fwd(null, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_NULL
+    assert fwd(p, p, p, null, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_NULL
+    assert fwd(p, p, p, p, null, 0, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_SHAPE
+    assert fwd(p, p, p, p, null, 1, 1, 0, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_SHAPE
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(-1.0), 0, null, 0, null) == b.LA_ERR_SHAPE
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(float("nan")), 0, null, 0, null) == b.LA_ERR_SHAPE
+    assert fwd(p, p, p, p, null, 1 << 20, 1 << 10, 1 << 20, 64, 64, f(0), 0, null, 0, null) == b.LA_ERR_SHAPE
+    assert fwd(p, p, p, p, null, 1, 1, 16, 48, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 128, f(1e-6), 0, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 7, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd(p, odd, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_ALIGN
+    # a long sequence needs a workspace
+    assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, p, 1024, null) == b.LA_ERR_WORKSPACE
+
+    bwd = lib.la_causal_bwd
+    assert bwd(p, p, p, p, p, null, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_NULL
+    assert bwd(p, p, p, p, p, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert bwd(p, p, p, p, p, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 8, null) == b.LA_ERR_WORKSPACE
+    assert bwd(p, p, p, p, p, p, p, p, odd, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
+
+    glob = lib.la_global_fwd
+    assert glob(p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert glob(p, p, null, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 20, null) == b.LA_ERR_NULL
+
+    step = lib.la_recurrent_step
+    assert step(p, p, p, null, p, p, 1, 1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_NULL
+    assert step(p, p, p, p, p, p, 1, 1, 16, 64, f(1e-6), 0, null) == b.LA_ERR_UNSUPPORTED
+    assert step(p, p, p, p, p, p, 1, -1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_SHAPE
+
+
+def test_schedule_knobs_change_the_workspace(lib, monkeypatch):
+    from paper_2006_16236_amd import binding as b
+    monkeypatch.setenv("LA_TARGET_WAVES", "1")
+    assert b.la_causal_fwd_workspace(1, 1, 4096, 64, 64) == 0
+    monkeypatch.setenv("LA_TARGET_WAVES", str(1 << 20))
+    monkeypatch.setenv("LA_MIN_SEG_CHUNKS", "1")
+    assert b.la_causal_fwd_workspace(1, 1, 4096, 64, 64) == 256 * (64 * 64 + 64) * 4
+
+
+def test_binding_refuses_host_tensors(lib):
+    import torch
+    from paper_2006_16236_amd import binding as b
+    x = torch.zeros(1, 1, 16, 64)
+    with pytest.raises(ValueError):
+        b.la_causal_fwd(x, x, x, x)
+    with pytest.raises(TypeError):
+        b.la_causal_fwd(x.double(), x, x, x)

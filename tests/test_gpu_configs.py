@@ -1,0 +1,157 @@
+"""GPU parity at the benchmark's own workloads (full sizes, default launch configuration).
+
+Small configurations are compared element by element on every slab.  At the metric's size
+(B=2, H=8, N=65536) the oracle is run on sampled (batch, head) slabs, which are independent
+problems, so each sampled slab is still compared element by element over all 65536 tokens.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads as wl
+from gpu_util import DEV, grad_errs, rel_err, to_dev, to_host, tol_for
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def la():
+    import paper_2006_16236_amd as la_mod
+    assert torch.cuda.is_available()
+    return la_mod
+
+
+def gpu_fwd_bwd(la, host, bf16=False, eps=1e-6):
+    Q, K, V, G = (to_dev(x, bf16) for x in host)
+    O = torch.empty_like(V)
+    den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=DEV)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    la.la_causal_fwd(Q, K, V, O, den, eps)
+    la.la_causal_bwd(Q, K, V, O, den, G, dQ, dK, dV, eps)
+    torch.cuda.synchronize()
+    return O, den, dQ, dK, dV
+
+
+def test_config1_forward_and_quadratic_form(la, oracle):
+    w = wl.CFG1
+    Q, K, V = wl.qkvg(w, with_grad=False)
+    V = V.copy()
+    V[..., 0] = 1.0                     # a ones column reads back the row sum of the weights
+    dq, dk, dv = (to_dev(x) for x in (Q, K, V))
+    O = torch.empty_like(dv)
+    den = torch.empty(w.B, w.H, w.N, device=DEV)
+    la.la_causal_fwd(dq, dk, dv, O, den, w.eps)
+    torch.cuda.synchronize()
+    O, den = to_host(O), den.cpu().numpy()
+    ref_q = oracle.causal_fwd_quadratic(Q, K, V, w.eps)          # eq. 8, the definition
+    ref_p, den_p = oracle.causal_fwd_prefix(Q, K, V, w.eps, return_den=True)
+    assert rel_err(O, ref_q) <= 1e-4 and rel_err(O, ref_p) <= 1e-4
+    assert rel_err(den, den_p) <= 1e-4
+    # weights are non-negative and each row sums to 1 - eps/den: the ones column shows it
+    np.testing.assert_allclose(O[..., 0], 1.0 - w.eps / den_p, rtol=0, atol=2e-6)
+    # and the output is a convex combination: inside the running range of V
+    Wm = oracle.causal_weights(Q[0, 0], K[0, 0], w.eps)
+    assert Wm.min() >= 0.0
+    assert np.all(O[0, 0] <= np.maximum(np.maximum.accumulate(V[0, 0], 0), 0) + 1e-4)
+    assert np.all(O[0, 0] >= np.minimum(np.minimum.accumulate(V[0, 0], 0), 0) - 1e-4)
+
+
+def test_config2_mnist_shape_forward_backward(la, oracle):
+    w = wl.CFG2
+    host = wl.qkvg(w)
+    O, den, dQ, dK, dV = gpu_fwd_bwd(la, host, eps=w.eps)
+    ref, dref = oracle.causal_fwd_prefix(*host[:3], w.eps, return_den=True)
+    gref = oracle.causal_bwd_linear(*host, w.eps)
+    assert rel_err(to_host(O), ref) <= 1e-4
+    assert rel_err(den.cpu().numpy(), dref) <= 1e-4
+    assert max(grad_errs([to_host(x) for x in (dQ, dK, dV)], gref)) <= 1e-4
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_config3_cifar_shape_forward_backward(la, oracle, bf16):
+    w = wl.CFG3
+    host = wl.qkvg(w)
+    if bf16:
+        host = [wl.round_to_bf16(x) for x in host]
+    O, den, dQ, dK, dV = gpu_fwd_bwd(la, host, bf16=bf16, eps=w.eps)
+    ref = oracle.causal_fwd_prefix(*host[:3], w.eps)
+    gref = oracle.causal_bwd_linear(*host, w.eps)
+    tol = tol_for(w.N, bf16)
+    assert rel_err(to_host(O), ref) <= tol
+    assert max(grad_errs([to_host(x) for x in (dQ, dK, dV)], gref)) <= tol
+
+
+SWEEP_SAMPLES = {9: [(0, 0), (17, 3), (255, 7)], 12: [(0, 0), (31, 5)], 16: [(0, 3), (1, 6)]}
+
+
+@pytest.mark.parametrize("log2n", sorted(SWEEP_SAMPLES))
+def test_sweep_points_on_sampled_slabs(la, oracle, log2n):
+    w = wl.sweep_point(log2n)
+    host = wl.qkvg(w)
+    O, den, dQ, dK, dV = gpu_fwd_bwd(la, host, eps=w.eps)
+    Q, K, V = (to_dev(x) for x in host[:3])
+    Og = torch.empty_like(V)
+    la.la_global_fwd(Q, K, V, Og, w.eps)
+    torch.cuda.synchronize()
+    tol = tol_for(w.N)
+    for b, h in SWEEP_SAMPLES[log2n]:
+        sl = [x[b:b + 1, h:h + 1] for x in host]
+        ref, dref = oracle.causal_fwd_prefix(*sl[:3], w.eps, return_den=True)
+        gref = oracle.causal_bwd_linear(*sl, w.eps)
+        assert rel_err(to_host(O[b:b + 1, h:h + 1]), ref) <= tol
+        assert rel_err(den[b:b + 1, h:h + 1].cpu().numpy(), dref) <= tol
+        got = [to_host(x[b:b + 1, h:h + 1]) for x in (dQ, dK, dV)]
+        assert max(grad_errs(got, gref)) <= tol, (b, h)
+        assert rel_err(to_host(Og[b:b + 1, h:h + 1]), oracle.global_fwd_linear(*sl[:3], w.eps)) <= tol
+    # properties that hold for every slab at any size
+    assert torch.isfinite(O).all() and torch.isfinite(dQ).all() and torch.isfinite(dK).all()
+    assert torch.isfinite(dV).all() and (den > 0).all()
+
+
+def test_config5_decode_3072_steps(la, oracle):
+    d = wl.CFG5
+    q, k, v = wl.decode_streams(d)
+    dq, dk, dv = (to_dev(x) for x in (q, k, v))
+    S = torch.zeros(d.B, d.H, d.D, d.M, device=DEV)
+    z = torch.zeros(d.B, d.H, d.D, device=DEV)
+    out = torch.empty(d.T, d.B, d.H, d.M, device=DEV)
+    for t in range(d.T):
+        la.la_recurrent_step(dq[t], dk[t], dv[t], S, z, out[t], d.eps)
+    torch.cuda.synchronize()
+    So = np.zeros((d.B, d.H, d.D, d.M)); zo = np.zeros((d.B, d.H, d.D))
+    worst = 0.0
+    got = to_host(out)
+    for t in range(d.T):
+        ref = oracle.recurrent_step(q[t], k[t], v[t], So, zo, d.eps)
+        worst = max(worst, rel_err(got[t], ref))
+    assert worst <= 1e-4
+    assert rel_err(S.cpu().numpy(), So) <= 1e-4 and rel_err(z.cpu().numpy(), zo) <= 1e-4
+    # run-to-run bitwise determinism of the whole 3072-step trajectory
+    S2 = torch.zeros_like(S); z2 = torch.zeros_like(z); out2 = torch.empty_like(out)
+    for t in range(d.T):
+        la.la_recurrent_step(dq[t], dk[t], dv[t], S2, z2, out2[t], d.eps)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(S, S2) and torch.equal(z, z2)
+    # the same tokens as one stacked sequence through the parallel forward
+    Qs, Ks, Vs = (x.permute(1, 2, 0, 3).contiguous() for x in (dq, dk, dv))
+    O = torch.empty_like(Vs)
+    la.la_causal_fwd(Qs, Ks, Vs, O, None, d.eps)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(O), np.moveaxis(got, 0, 2)) <= 1e-4
+
+
+def test_decode_suspend_and_resume(la):
+    d = wl.DecodeWorkload("resume", 4, 8, 64, 64, 64, 1006)
+    q, k, v = (to_dev(x) for x in wl.decode_streams(d))
+    S = torch.zeros(d.B, d.H, d.D, d.M, device=DEV); z = torch.zeros(d.B, d.H, d.D, device=DEV)
+    out = torch.empty(d.T, d.B, d.H, d.M, device=DEV)
+    for t in range(d.T):
+        la.la_recurrent_step(q[t], k[t], v[t], S, z, out[t])
+    S2 = torch.zeros_like(S); z2 = torch.zeros_like(z); out2 = torch.empty_like(out)
+    for t in range(d.T // 2):
+        la.la_recurrent_step(q[t], k[t], v[t], S2, z2, out2[t])
+    S3, z3 = S2.cpu().to(DEV), z2.cpu().to(DEV)          # state leaves the device and returns
+    for t in range(d.T // 2, d.T):
+        la.la_recurrent_step(q[t], k[t], v[t], S3, z3, out2[t])
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(S, S3) and torch.equal(z, z3)
