@@ -1,6 +1,6 @@
 // Device-side building blocks shared by the gfx950 linear-attention kernels:
-// feature map, element conversion, the two register layouts in which 16-token
-// tiles are fetched, and the fp32 16x16x4 MFMA wrapper.
+// feature map, element conversion, coalesced tile fetch, the LDS image of a tile with
+// the two MFMA operand layouts read from it, and the fp32 16x16x4 MFMA wrapper.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -73,48 +73,59 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 acc) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
 }
 
-// ---- the two tile layouts -------------------------------------------------------------------
+// ---- tiles ------------------------------------------------------------------------------------
 // A tile is 16 consecutive tokens x F features of one [N, F] slab, F in {32, 64}.
 //
-// token-lane:   lane (c, g) holds token c, features 16*ft + 4g + r   -> x[ft][r]
-//               (the operand of an MFMA whose non-contracted index is the token;
-//               contraction step (ft, r) pairs feature 16*ft + 4g + r on both sides)
-// feature-lane: lane (c, g) holds feature 16*ft + c of tokens 4g + s -> x[ft][s]
-//               (the operand of an MFMA whose non-contracted index is the feature;
-//               contraction step s pairs token 4g + s on both sides)
-//
-// Rows at or beyond `nvalid` read as zero.  `base` points at token 0 of the tile.
+// Fetch: the tile is one contiguous run of 16*F elements.  Load i of lane l takes the four
+// elements starting at 4*(l + 64*i): a wave reads 1 KiB (fp32) of consecutive memory per
+// instruction.  Rows at or beyond `nvalid` are redirected to the last valid row, so every
+// address stays inside the tensor without a branch; park_tile() zeroes them afterwards.
+template <int F> __device__ __forceinline__ int stage_row(int lane, int i) { return (4 * (lane + 64 * i)) / F; }
+template <int F> __device__ __forceinline__ int stage_col(int lane, int i) { return (4 * (lane + 64 * i)) % F; }
+
 template <int F, typename T>
-__device__ __forceinline__ void load_token_lane(const T *base, int nvalid, int c, int g,
-                                                float (&x)[F / 16][4]) {
-    const bool ok = c < nvalid;
-    const T *p = base + (size_t)c * F + 4 * g;
+__device__ __forceinline__ void stage_load(const T *base, int nvalid, int lane, f32x4 (&st)[F / 16]) {
+#pragma unroll
+    for (int i = 0; i < F / 16; ++i) {
+        const int row = min(stage_row<F>(lane, i), nvalid - 1);
+        st[i] = load4(base + (size_t)row * F + stage_col<F>(lane, i));
+    }
+}
+
+// LDS image of a tile: row-major with 4 floats of padding per row.  With that stride the
+// 16-byte token-lane reads, the 4-byte feature-lane reads and the 16-byte parking writes
+// all spread over the banks without conflicts (for F = 32 and F = 64 alike).
+__host__ __device__ constexpr int tile_stride(int F) { return F + 4; }
+__host__ __device__ constexpr int tile_floats(int F) { return 16 * (F + 4); }
+
+__device__ __forceinline__ void lds_store4(float *p, f32x4 v) { *reinterpret_cast<f32x4 *>(p) = v; }
+
+// The two operand layouts of a 16x16x4 MFMA:
+// token-lane:   lane (c, g) holds token c, features 16*ft + 4g + r   -> x[ft][r]
+//               (operand whose non-contracted index is the token; contraction step
+//               (ft, r) pairs feature 16*ft + 4g + r on both sides)
+// feature-lane: lane (c, g) holds feature 16*ft + c of tokens 4g + s -> x[ft][s]
+//               (operand whose non-contracted index is the feature; contraction step s
+//               pairs token 4g + s on both sides)
+template <int F>
+__device__ __forceinline__ void lds_token_lane(const float *tile, int c, int g, float (&x)[F / 16][4]) {
+    const float *p = tile + c * tile_stride(F) + 4 * g;
 #pragma unroll
     for (int ft = 0; ft < F / 16; ++ft) {
-        f32x4 v = {0.f, 0.f, 0.f, 0.f};
-        if (ok) v = load4(p + 16 * ft);
+        const f32x4 v = *reinterpret_cast<const f32x4 *>(p + 16 * ft);
 #pragma unroll
         for (int r = 0; r < 4; ++r) x[ft][r] = v[r];
     }
 }
 
-template <int F, typename T>
-__device__ __forceinline__ void load_feature_lane(const T *base, int nvalid, int c, int g,
-                                                  float (&x)[F / 16][4]) {
+template <int F>
+__device__ __forceinline__ void lds_feature_lane(const float *tile, int c, int g, float (&x)[F / 16][4]) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-        const int row = 4 * g + s;
-        const bool ok = row < nvalid;
-        const T *p = base + (size_t)row * F + c;
+        const float *p = tile + (4 * g + s) * tile_stride(F) + c;
 #pragma unroll
-        for (int ft = 0; ft < F / 16; ++ft) x[ft][s] = ok ? to_f32(p[16 * ft]) : 0.0f;
+        for (int ft = 0; ft < F / 16; ++ft) x[ft][s] = p[16 * ft];
     }
-}
-
-// four per-token scalars for tokens 4g + s (fp32 side arrays such as 1/den)
-__device__ __forceinline__ void load_rows4(const float *base, int nvalid, int g, float (&x)[4]) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s) x[s] = (4 * g + s) < nvalid ? base[4 * g + s] : 0.0f;
 }
 
 }  // namespace la

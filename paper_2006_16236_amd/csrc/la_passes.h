@@ -25,6 +25,12 @@
 //         delta_a = -(dO_a . O_a)/den_a being the gradient that reaches den_a;
 //   kDk   adds delta_b to every kept entry and carries rho = sum delta_b phi(Q_b).
 // kDq and kDk finish with the chain rule through phi (times phi'(Q), phi'(K)).
+//
+// Data movement per chunk: every input tile (16 tokens x 32|64 features) is fetched
+// once with fully coalesced 16-byte loads into staging registers while the previous
+// chunk is being computed, then mapped (phi, phi', 1/den scaling, zero fill of rows past
+// the end of the sequence) and parked in LDS, from where the MFMA operands are read in
+// whichever of the two layouts of la_device.h each product needs.
 #pragma once
 
 #include "la_device.h"
@@ -48,25 +54,65 @@ struct PassArgs {
     float eps;
 };
 
+enum Map { kMapId = 0, kMapPhi = 1, kMapDphi = 2, kMapScale = 3 };
+
+template <int MAP>
+__device__ __forceinline__ float map_value(float v, float scale) {
+    if constexpr (MAP == kMapPhi) return phi(v);
+    if constexpr (MAP == kMapDphi) return dphi(v);
+    if constexpr (MAP == kMapScale) return v * scale;
+    return v;
+}
+
+// Park a staged tile in LDS: apply the map, zero the rows past the end of the sequence.
+template <int F, int MAP>
+__device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16],
+                                          const float (&scale)[F / 16], int nvalid, int lane) {
+#pragma unroll
+    for (int i = 0; i < F / 16; ++i) {
+        const int row = stage_row<F>(lane, i);
+        f32x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = row < nvalid ? map_value<MAP>(st[i][r], scale[i]) : 0.0f;
+        lds_store4(tile + row * tile_stride(F) + stage_col<F>(lane, i), v);
+    }
+}
+
 template <int PASS, int D, int M, typename T>
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void causal_pass_kernel(const PassArgs a) {
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void causal_pass_kernel(
+    const PassArgs a) {
     constexpr bool kXisD = (PASS == kFwd || PASS == kDv || PASS == kGlobal);
     constexpr int DX = kXisD ? D : M;     // contraction width of X . Y and of X . U
     constexpr int DZ = kXisD ? M : D;     // width of Z, of the output and of U's columns
     constexpr int XT = DX / 16, ZT = DZ / 16;
     constexpr bool kReverse = (PASS == kDv || PASS == kDk);
+    constexpr bool kHasRaw = (PASS == kDq || PASS == kDk);       // phi' under the output
+    constexpr bool kHasYZ = (PASS != kGlobal);
+
+    __shared__ float lds_x[tile_floats(DX)];
+    __shared__ float lds_y[kHasYZ ? tile_floats(DX) : 4];
+    __shared__ float lds_z[kHasYZ ? tile_floats(DZ) : 4];
+    __shared__ float lds_r[kHasRaw ? tile_floats(DZ) : 4];
 
     const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
+    const int count = ch_end - ch_begin;
 
     const size_t rowbase = (size_t)bh * a.N;
-    const T *Qs = static_cast<const T *>(a.Q) + rowbase * D;
-    const T *Ks = static_cast<const T *>(a.K) + rowbase * D;
-    const T *Vs = static_cast<const T *>(a.V) + rowbase * M;
-    const T *Gs = static_cast<const T *>(a.G) + rowbase * M;
+    // which raw tensor feeds which operand
+    const T *Xs = static_cast<const T *>(PASS == kFwd || PASS == kGlobal ? a.Q
+                                         : PASS == kDq ? a.G : PASS == kDv ? a.K : a.V) + rowbase * DX;
+    const T *Ys = static_cast<const T *>(PASS == kFwd ? a.K : PASS == kDq ? a.V
+                                         : PASS == kDv ? a.Q : a.G) + rowbase * DX;
+    const T *Zs = static_cast<const T *>(PASS == kFwd ? a.V : PASS == kDq ? a.K
+                                         : PASS == kDv ? a.G : a.Q) + rowbase * DZ;
+    const T *Rs = static_cast<const T *>(PASS == kDq ? a.Q : a.K) + rowbase * DZ;
+    constexpr int kMapX = (PASS == kDq) ? kMapScale : (PASS == kDk) ? kMapId : kMapPhi;
+    constexpr int kMapY = (PASS == kDq) ? kMapId : (PASS == kDk) ? kMapScale : kMapPhi;
+    constexpr int kMapZ = (PASS == kFwd) ? kMapId : (PASS == kDv) ? kMapScale : kMapPhi;
     const float *rden = a.rden + rowbase;
     const float *delta = a.delta + rowbase;
     T *outs = static_cast<T *>(a.out) + rowbase * DZ;
@@ -114,100 +160,69 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
         }
     }
 
-    for (int it = 0; it < ch_end - ch_begin; ++it) {
-        const int ch = kReverse ? ch_end - 1 - it : ch_begin + it;
+    // ---- staging registers: the next chunk, in flight while this one is computed ------------
+    f32x4 sx[XT], sy[XT], sz[ZT], sr[ZT];
+    float scx[XT], scz[ZT];             // 1/den of the staged rows of the dO tile
+    float n_dl1 = 0.f, n_dl4[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < XT; ++i) scx[i] = 1.0f;
+#pragma unroll
+    for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
+
+    auto fetch = [&](const int ch) {
+        const int t0 = ch * kChunk;
+        const int nvalid = min(kChunk, a.N - t0);
+        stage_load<DX>(Xs + (size_t)t0 * DX, nvalid, lane, sx);
+        if constexpr (kHasYZ) {
+            stage_load<DX>(Ys + (size_t)t0 * DX, nvalid, lane, sy);
+            stage_load<DZ>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
+        }
+        if constexpr (kHasRaw) stage_load<DZ>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
+        if constexpr (PASS == kDq || PASS == kDk) {          // dO is the X (kDq) or Y (kDk) tile
+#pragma unroll
+            for (int i = 0; i < XT; ++i) scx[i] = rden[t0 + min(stage_row<DX>(lane, i), nvalid - 1)];
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
+                n_dl4[s] = (4 * g + s) < nvalid ? v : 0.f;
+            }
+        }
+        if constexpr (PASS == kDq) {
+            const float v = delta[t0 + min(c, nvalid - 1)];
+            n_dl1 = c < nvalid ? v : 0.f;
+        }
+        if constexpr (PASS == kDv) {                          // dO is the Z tile
+#pragma unroll
+            for (int i = 0; i < ZT; ++i) scz[i] = rden[t0 + min(stage_row<DZ>(lane, i), nvalid - 1)];
+        }
+    };
+
+    int ch = kReverse ? ch_end - 1 : ch_begin;
+    if (count > 0) fetch(ch);
+
+    for (int it = 0; it < count; ++it) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
         const bool tok_ok = c < nvalid;
 
-        float xa[XT][4];                 // X, token-lane
-        float ya[XT][4];                 // Y, token-lane
-        float yf[XT][4];                 // Y, feature-lane
-        float zf[ZT][4];                 // Z, feature-lane
-        float raw[ZT][4];                // raw Q or K under the output, for phi'
-        float sc1 = 0.f, dl1 = 0.f;      // per-token scalars of token c
-        float sc4[4] = {0.f, 0.f, 0.f, 0.f}, dl4[4] = {0.f, 0.f, 0.f, 0.f};   // of tokens 4g + s
-
-        // ---- fetch and prepare the chunk's operands ---------------------------------------
-        if constexpr (PASS == kFwd || PASS == kGlobal) {
-            load_token_lane<D>(Qs + (size_t)t0 * D, nvalid, c, g, xa);
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) xa[xt][r] = tok_ok ? phi(xa[xt][r]) : 0.f;
+        // ---- park the staged chunk in LDS, start fetching the next one ----------------------
+        __syncthreads();                 // every operand read of the previous chunk is done
+        park_tile<DX, kMapX>(lds_x, sx, scx, nvalid, lane);
+        if constexpr (kHasYZ) {
+            park_tile<DX, kMapY>(lds_y, sy, scx, nvalid, lane);
+            park_tile<DZ, kMapZ>(lds_z, sz, scz, nvalid, lane);
         }
-        if constexpr (PASS == kFwd) {
-            load_token_lane<D>(Ks + (size_t)t0 * D, nvalid, c, g, ya);
-            load_feature_lane<D>(Ks + (size_t)t0 * D, nvalid, c, g, yf);
-            load_feature_lane<M>(Vs + (size_t)t0 * M, nvalid, c, g, zf);
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    ya[xt][r] = tok_ok ? phi(ya[xt][r]) : 0.f;
-                    yf[xt][r] = (4 * g + r) < nvalid ? phi(yf[xt][r]) : 0.f;
-                }
-        }
-        if constexpr (PASS == kDq) {
-            sc1 = tok_ok ? rden[t0 + c] : 0.f;
-            dl1 = tok_ok ? delta[t0 + c] : 0.f;
-            load_rows4(delta + t0, nvalid, g, dl4);
-            load_token_lane<M>(Gs + (size_t)t0 * M, nvalid, c, g, xa);
-            load_token_lane<M>(Vs + (size_t)t0 * M, nvalid, c, g, ya);
-            load_feature_lane<M>(Vs + (size_t)t0 * M, nvalid, c, g, yf);
-            load_feature_lane<D>(Ks + (size_t)t0 * D, nvalid, c, g, zf);
-            load_feature_lane<D>(Qs + (size_t)t0 * D, nvalid, c, g, raw);
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) xa[xt][r] *= sc1;
-#pragma unroll
-            for (int zt = 0; zt < ZT; ++zt)
-#pragma unroll
-                for (int s = 0; s < 4; ++s) zf[zt][s] = (4 * g + s) < nvalid ? phi(zf[zt][s]) : 0.f;
-        }
-        if constexpr (PASS == kDv) {
-            load_rows4(rden + t0, nvalid, g, sc4);
-            load_token_lane<D>(Ks + (size_t)t0 * D, nvalid, c, g, xa);
-            load_token_lane<D>(Qs + (size_t)t0 * D, nvalid, c, g, ya);
-            load_feature_lane<D>(Qs + (size_t)t0 * D, nvalid, c, g, yf);
-            load_feature_lane<M>(Gs + (size_t)t0 * M, nvalid, c, g, zf);
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    xa[xt][r] = tok_ok ? phi(xa[xt][r]) : 0.f;
-                    ya[xt][r] = tok_ok ? phi(ya[xt][r]) : 0.f;
-                    yf[xt][r] = (4 * g + r) < nvalid ? phi(yf[xt][r]) : 0.f;
-                }
-#pragma unroll
-            for (int zt = 0; zt < ZT; ++zt)
-#pragma unroll
-                for (int s = 0; s < 4; ++s) zf[zt][s] *= sc4[s];
-        }
-        if constexpr (PASS == kDk) {
-            sc1 = tok_ok ? rden[t0 + c] : 0.f;
-            load_rows4(rden + t0, nvalid, g, sc4);
-            load_rows4(delta + t0, nvalid, g, dl4);
-            load_token_lane<M>(Vs + (size_t)t0 * M, nvalid, c, g, xa);
-            load_token_lane<M>(Gs + (size_t)t0 * M, nvalid, c, g, ya);
-            load_feature_lane<M>(Gs + (size_t)t0 * M, nvalid, c, g, yf);
-            load_feature_lane<D>(Qs + (size_t)t0 * D, nvalid, c, g, zf);
-            load_feature_lane<D>(Ks + (size_t)t0 * D, nvalid, c, g, raw);
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    ya[xt][r] *= sc1;
-                    yf[xt][r] *= sc4[r];
-                }
-#pragma unroll
-            for (int zt = 0; zt < ZT; ++zt)
-#pragma unroll
-                for (int s = 0; s < 4; ++s) zf[zt][s] = (4 * g + s) < nvalid ? phi(zf[zt][s]) : 0.f;
-        }
+        if constexpr (kHasRaw) park_tile<DZ, kMapDphi>(lds_r, sr, scz, nvalid, lane);
+        const float dl1 = n_dl1;
+        const float dl4[4] = {n_dl4[0], n_dl4[1], n_dl4[2], n_dl4[3]};
+        const int next = kReverse ? ch - 1 : ch + 1;
+        if (it + 1 < count) fetch(next);
+        __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the arithmetic
+        __syncthreads();
 
         // ---- state term: out = X U  (lane (c, g), register r: token 4g + r, column 16zt + c)
+        float xa[XT][4];                 // X, token-lane
+        lds_token_lane<DX>(lds_x, c, g, xa);
         f32x4 out[ZT];
 #pragma unroll
         for (int zt = 0; zt < ZT; ++zt) out[zt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -219,6 +234,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
                 for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16(xa[xt][r], U[xt][zt][r], out[zt]);
 
         float den_a = 1.0f;              // kFwd / kGlobal: denominator of token c
+        float zf[ZT][4];                 // Z, feature-lane
         if constexpr (PASS == kGlobal) {
             float p = 0.f;
 #pragma unroll
@@ -228,6 +244,8 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
             den_a = sum_over_groups(p) + a.eps;
         } else {
             // ---- W[a][b] = X_a . Y_b, lane (c = a, g), register r: b = 4g + r --------------
+            float ya[XT][4];             // Y, token-lane
+            lds_token_lane<DX>(lds_y, c, g, ya);
             f32x4 w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int xt = 0; xt < XT; xt += 2)
@@ -243,7 +261,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
                 if constexpr (PASS == kDq) v += dl1;
                 if constexpr (PASS == kDk) v += dl4[r];
                 const bool keep = kReverse ? (4 * g + r) >= c : (4 * g + r) <= c;
-                w[r] = keep ? v : 0.f;               // select, never multiply: no NaN leaks
+                w[r] = keep ? v : 0.f;               // select, never multiply
             }
             if constexpr (PASS == kFwd) {
                 float p = (w[0] + w[1]) + (w[2] + w[3]);
@@ -254,6 +272,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
                 den_a = sum_over_groups(p) + a.eps;
             }
             // ---- in-chunk term: out += W Z -------------------------------------------------
+            lds_feature_lane<DZ>(lds_z, c, g, zf);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -273,18 +292,16 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
                 for (int zt = 0; zt < ZT; ++zt) out[zt][r] *= ri;
             }
         }
-        if constexpr (PASS == kDq) {
+        if constexpr (kHasRaw) {
+            float dp[ZT][4];             // phi' of the raw Q (kDq) or K (kDk) under the output
+            lds_feature_lane<DZ>(lds_r, c, g, dp);
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    out[zt][r] = fmaf(dl4[r], ec[zt], out[zt][r]) * dphi(raw[zt][r]);
-        }
-        if constexpr (PASS == kDk) {
-#pragma unroll
-            for (int zt = 0; zt < ZT; ++zt)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) out[zt][r] = (out[zt][r] + ec[zt]) * dphi(raw[zt][r]);
+                for (int r = 0; r < 4; ++r) {
+                    const float extra = (PASS == kDq) ? dl4[r] * ec[zt] : ec[zt];
+                    out[zt][r] = (out[zt][r] + extra) * dp[zt][r];
+                }
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -297,7 +314,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
         }
 
         // ---- carry: U += Y^T Z, and the ones-column vector --------------------------------
-        if constexpr (PASS != kGlobal) {
+        if constexpr (kHasYZ) {
+            float yf[XT][4];             // Y, feature-lane
+            lds_feature_lane<DX>(lds_y, c, g, yf);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -305,13 +324,14 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt)
                         U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
-        }
-        if constexpr (PASS == kFwd) {
+            if constexpr (PASS == kFwd) {
 #pragma unroll
-            for (int xt = 0; xt < XT; ++xt) {
-                const float zc = sum_over_groups((yf[xt][0] + yf[xt][1]) + (yf[xt][2] + yf[xt][3]));
+                for (int xt = 0; xt < XT; ++xt) {
+                    const float zc =
+                        sum_over_groups((yf[xt][0] + yf[xt][1]) + (yf[xt][2] + yf[xt][3]));
 #pragma unroll
-                for (int r = 0; r < 4; ++r) zg[xt][r] += __shfl(zc, 4 * g + r);
+                    for (int r = 0; r < 4; ++r) zg[xt][r] += __shfl(zc, 4 * g + r);
+                }
             }
         }
         if constexpr (PASS == kDq) {
@@ -328,6 +348,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
                 ec[zt] += sum_over_groups(p);
             }
         }
+        ch = next;
     }
 }
 
@@ -348,6 +369,8 @@ struct SegArgs {
 template <int KIND, int D, int M, typename T>
 __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     constexpr int XT = D / 16, ZT = M / 16;
+    __shared__ float lds_y[tile_floats(D)];
+    __shared__ float lds_z[tile_floats(M)];
     const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (seg == a.skip_seg) return;
@@ -357,6 +380,8 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     const size_t rowbase = (size_t)bh * a.N;
     const T *Ys = static_cast<const T *>(a.Y) + rowbase * D;
     const T *Zs = static_cast<const T *>(a.Z) + rowbase * M;
+    const float *rden = a.rden + rowbase;
+    const float *delta = a.delta + rowbase;
 
     f32x4 U[XT][ZT];
     float ec[XT];
@@ -366,26 +391,45 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
 #pragma unroll
         for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    for (int ch = ch_begin; ch < ch_end; ++ch) {
+
+    f32x4 sy[XT], sz[ZT];
+    float scy[XT], scz[ZT];
+    float n_w4[4] = {1.f, 1.f, 1.f, 1.f};
+#pragma unroll
+    for (int i = 0; i < XT; ++i) scy[i] = 1.0f;
+#pragma unroll
+    for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
+
+    auto fetch = [&](const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
-        float yf[XT][4], zf[ZT][4];
-        float w4[4] = {1.f, 1.f, 1.f, 1.f};
-        load_feature_lane<D>(Ys + (size_t)t0 * D, nvalid, c, g, yf);
-        load_feature_lane<M>(Zs + (size_t)t0 * M, nvalid, c, g, zf);
-#pragma unroll
-        for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) yf[xt][s] = (4 * g + s) < nvalid ? phi(yf[xt][s]) : 0.f;
+        stage_load<D>(Ys + (size_t)t0 * D, nvalid, lane, sy);
+        stage_load<M>(Zs + (size_t)t0 * M, nvalid, lane, sz);
         if constexpr (KIND == 1) {
-            float sc4[4];
-            load_rows4(a.rden + rowbase + t0, nvalid, g, sc4);
-            load_rows4(a.delta + rowbase + t0, nvalid, g, w4);
 #pragma unroll
-            for (int zt = 0; zt < ZT; ++zt)
+            for (int i = 0; i < ZT; ++i) scz[i] = rden[t0 + min(stage_row<M>(lane, i), nvalid - 1)];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) zf[zt][s] *= sc4[s];
+            for (int s = 0; s < 4; ++s) {
+                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
+                n_w4[s] = (4 * g + s) < nvalid ? v : 0.f;
+            }
         }
+    };
+
+    if (ch_begin < ch_end) fetch(ch_begin);
+    for (int ch = ch_begin; ch < ch_end; ++ch) {
+        const int nvalid = min(kChunk, a.N - ch * kChunk);
+        __syncthreads();
+        park_tile<D, kMapPhi>(lds_y, sy, scy, nvalid, lane);
+        park_tile<M, KIND == 1 ? kMapScale : kMapId>(lds_z, sz, scz, nvalid, lane);
+        const float w4[4] = {n_w4[0], n_w4[1], n_w4[2], n_w4[3]};
+        if (ch + 1 < ch_end) fetch(ch + 1);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+
+        float yf[XT][4], zf[ZT][4];
+        lds_feature_lane<D>(lds_y, c, g, yf);
+        lds_feature_lane<M>(lds_z, c, g, zf);
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
