@@ -38,8 +38,7 @@ def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
     return {
         "causal_pass_fwd": e * (2 * D + 2 * M) + 4,     # Q K V -> O, den
         "causal_pass_dq": e * (3 * D + 2 * M) + 8,      # dO V K Q, 1/den, delta -> dQ
-        "causal_pass_dv": e * (2 * D + 2 * M) + 4,      # K Q dO, 1/den -> dV
-        "causal_pass_dk": e * (3 * D + 2 * M) + 8,      # V dO Q K, 1/den, delta -> dK
+        "reverse_pass_dv_dk": e * (3 * D + 3 * M) + 8,  # Q K V dO, 1/den, delta -> dV, dK
         "segment_state_kv": e * (D + M),                # K V
         "segment_state_qg": e * (D + M) + 8,            # Q dO, 1/den, delta
         "bwd_prep": e * 2 * M + 12,                     # dO O den -> 1/den, delta
@@ -51,8 +50,8 @@ def kernel_flops(name: str, D: int, M: int) -> float:
     """Algorithmic flops per token-head: the state update and the state read-out
     (2*D*(M+1) each, ones column included) that the pass performs."""
     full = 4.0 * D * (M + 1)
-    return {"causal_pass_fwd": full, "causal_pass_dq": full, "causal_pass_dv": full,
-            "causal_pass_dk": full, "segment_state_kv": full / 2, "segment_state_qg": full / 2,
+    return {"causal_pass_fwd": full, "causal_pass_dq": full, "reverse_pass_dv_dk": 1.5 * full,
+            "segment_state_kv": full / 2, "segment_state_qg": full / 2,
             "global_readout": full / 2}.get(name, 0.0)
 
 
@@ -145,7 +144,7 @@ def run_headline(args):
     prof_all = profile_kernels(la, fb.step, 3, torch)
     per_step = {k: ms * n for k, (ms, n) in prof_all.items()}
     dominant = max(per_step, key=per_step.get)
-    kid = [la.la_kernel_name(i) for i in range(10)].index(dominant)
+    kid = [la.la_kernel_name(i) for i in range(9)].index(dominant)
 
     # the timed region: exactly `steps` steps, events only around the dominant kernel
     torch.cuda.synchronize()

@@ -149,10 +149,9 @@ typedef enum {
     LA_K_GLOBAL = 4,   /* non-causal read-out                                  */
     LA_K_PREP = 5,     /* 1/den and delta per token                            */
     LA_K_DQ = 6,       /* gradient for Q (forward direction)                   */
-    LA_K_DV = 7,       /* gradient for V (reverse direction)                   */
-    LA_K_DK = 8,       /* gradient for K (reverse direction)                   */
-    LA_K_STEP = 9,     /* recurrent decode step                                */
-    LA_K_COUNT = 10
+    LA_K_REV = 7,      /* gradients for V and K (reverse direction)            */
+    LA_K_STEP = 8,     /* recurrent decode step                                */
+    LA_K_COUNT = 9
 } la_kernel_id;
 
 const char *la_kernel_name(int kernel_id);

@@ -21,7 +21,7 @@ LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN = -4, -5, -6
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
            "la_global_fwd_workspace", "la_causal_fwd", "la_causal_bwd", "la_global_fwd",
            "la_recurrent_step", "la_kernel_name", "la_profile_begin", "la_profile_end")
-LA_K_COUNT = 10
+LA_K_COUNT = 9
 
 
 class LaError(RuntimeError):

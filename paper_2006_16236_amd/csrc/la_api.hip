@@ -259,10 +259,8 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
     a.out = dQ; a.state = stS;
     { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(D, M, (int)t, a, nblocks, s)); }
-    a.out = dV; a.state = stR;
-    { ProfScope ps(LA_K_DV, s); LA_TRY(la::launch_pass_dv(D, M, (int)t, a, nblocks, s)); }
-    a.out = dK; a.state = stR;
-    { ProfScope ps(LA_K_DK, s); LA_TRY(la::launch_pass_dk(D, M, (int)t, a, nblocks, s)); }
+    a.out = dV; a.out2 = dK; a.state = stR;
+    { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks, s)); }
     return LA_OK;
 }
 
@@ -312,8 +310,7 @@ int la_recurrent_step(const void *q, const void *k, const void *v, float *S, flo
 const char *la_kernel_name(int kernel_id) {
     static const char *const names[LA_K_COUNT] = {"segment_state_kv", "segment_state_qg", "scan_states",
                                                   "causal_pass_fwd", "global_readout", "bwd_prep",
-                                                  "causal_pass_dq", "causal_pass_dv", "causal_pass_dk",
-                                                  "recurrent_step"};
+                                                  "causal_pass_dq", "reverse_pass_dv_dk", "recurrent_step"};
     return kernel_id >= 0 && kernel_id < LA_K_COUNT ? names[kernel_id] : "unknown";
 }
 

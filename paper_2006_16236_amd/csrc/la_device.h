@@ -67,6 +67,20 @@ __device__ __forceinline__ float sum_over_groups(float v) {          // over g, 
     return v;
 }
 
+// Sum over the 16 lanes of a group (same g), result in all 16: four rotate-and-add steps on
+// the DPP path (row_ror 8, 4, 2, 1), no LDS traffic.
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row_sum16(float v) {
+    v += dpp_move<0x128>(v);
+    v += dpp_move<0x124>(v);
+    v += dpp_move<0x122>(v);
+    v += dpp_move<0x121>(v);
+    return v;
+}
+
 // D = A * B + C for one 16x16 tile, contraction depth 4.  Lane (c, g) supplies
 // A[c][g] and B[g][c]; register r of the accumulator holds C[4g + r][c].
 __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 acc) {

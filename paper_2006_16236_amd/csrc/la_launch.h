@@ -12,8 +12,9 @@ namespace la {
 hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs &a, int nblocks,
                            hipStream_t s);
 hipError_t launch_pass_dq(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
-hipError_t launch_pass_dv(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
-hipError_t launch_pass_dk(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
+// both reverse passes (dV into a.out, dK into a.out2) on one fetch of the inputs
+hipError_t launch_pass_reverse(int D, int M, int dtype, const PassArgs &a, int nblocks,
+                               hipStream_t s);
 hipError_t launch_segment_state(int kind, int D, int M, int dtype, const SegArgs &a, int nblocks,
                                 hipStream_t s);
 

@@ -47,7 +47,8 @@ struct PassArgs {
     const void *Q, *K, *V, *G;   // raw tensors, [BH, N, D] / [BH, N, M]
     const float *rden;           // [BH, N] 1/den_i             (backward passes)
     const float *delta;          // [BH, N] -(dO_i.O_i)/den_i   (backward passes)
-    void *out;                   // [BH, N, DZ]
+    void *out;                   // [BH, N, DZ]  (reverse_pass_kernel: dV)
+    void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
     float *den;                  // [BH, N] or null             (kFwd)
     const float *state;          // [BH, nseg, state_stride] exclusive states; null = zero state
     int N, nseg, chunks_per_seg;
@@ -78,49 +79,189 @@ __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16]
     }
 }
 
+// Which raw tensor feeds which operand of a pass, and how it is mapped when parked.
+template <int PASS, int D, int M>
+struct PassTraits {
+    static constexpr bool kXisD = (PASS == kFwd || PASS == kDv || PASS == kGlobal);
+    static constexpr int DX = kXisD ? D : M;     // contraction width of X . Y and of X . U
+    static constexpr int DZ = kXisD ? M : D;     // width of Z, of the output and of U's columns
+    static constexpr bool kReverse = (PASS == kDv || PASS == kDk);
+    static constexpr bool kHasRaw = (PASS == kDq || PASS == kDk);     // phi' under the output
+    static constexpr bool kHasYZ = (PASS != kGlobal);
+    static constexpr int kMapX = (PASS == kDq) ? kMapScale : (PASS == kDk) ? kMapId : kMapPhi;
+    static constexpr int kMapY = (PASS == kDq) ? kMapId : (PASS == kDk) ? kMapScale : kMapPhi;
+    static constexpr int kMapZ = (PASS == kFwd) ? kMapId : (PASS == kDv) ? kMapScale : kMapPhi;
+};
+
+// Staging of one pass run by one wave on its own: the wave fetches and parks all its tiles.
 template <int PASS, int D, int M, typename T>
-__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void causal_pass_kernel(
-    const PassArgs a) {
-    constexpr bool kXisD = (PASS == kFwd || PASS == kDv || PASS == kGlobal);
-    constexpr int DX = kXisD ? D : M;     // contraction width of X . Y and of X . U
-    constexpr int DZ = kXisD ? M : D;     // width of Z, of the output and of U's columns
+struct PassStager {
+    using Tr = PassTraits<PASS, D, M>;
+    static constexpr int DX = Tr::DX, DZ = Tr::DZ, XT = DX / 16, ZT = DZ / 16;
+    const T *Xs, *Ys, *Zs, *Rs;
+    const float *rden, *delta;
+    float *lds_x, *lds_y, *lds_z, *lds_r;
+    int N, lane, c, g;
+    f32x4 sx[XT], sy[XT], sz[ZT], sr[ZT];
+    float scx[XT], scz[ZT];             // 1/den of the staged rows of the dO tile
+    float n_dl1, n_dl4[4];
+    float dl1, dl4[4];                  // delta of token c / of tokens 4g + s of the parked chunk
+
+    __device__ __forceinline__ PassStager(const PassArgs &a, size_t rowbase, int lane_, float *lx,
+                                          float *ly, float *lz, float *lr)
+        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_), c(lane_ & 15),
+          g(lane_ >> 4) {
+        Xs = static_cast<const T *>(PASS == kFwd || PASS == kGlobal ? a.Q
+                                    : PASS == kDq ? a.G : PASS == kDv ? a.K : a.V) + rowbase * DX;
+        Ys = static_cast<const T *>(PASS == kFwd ? a.K : PASS == kDq ? a.V
+                                    : PASS == kDv ? a.Q : a.G) + rowbase * DX;
+        Zs = static_cast<const T *>(PASS == kFwd ? a.V : PASS == kDq ? a.K
+                                    : PASS == kDv ? a.G : a.Q) + rowbase * DZ;
+        Rs = static_cast<const T *>(PASS == kDq ? a.Q : a.K) + rowbase * DZ;
+        rden = a.rden + rowbase;
+        delta = a.delta + rowbase;
+        n_dl1 = dl1 = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) n_dl4[s] = dl4[s] = 0.f;
+#pragma unroll
+        for (int i = 0; i < XT; ++i) scx[i] = 1.0f;
+#pragma unroll
+        for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
+    }
+
+    __device__ __forceinline__ void fetch(const int ch) {
+        const int t0 = ch * kChunk;
+        const int nvalid = min(kChunk, N - t0);
+        stage_load<DX>(Xs + (size_t)t0 * DX, nvalid, lane, sx);
+        if constexpr (Tr::kHasYZ) {
+            stage_load<DX>(Ys + (size_t)t0 * DX, nvalid, lane, sy);
+            stage_load<DZ>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
+        }
+        if constexpr (Tr::kHasRaw) stage_load<DZ>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
+        if constexpr (PASS == kDq || PASS == kDk) {          // dO is the X (kDq) or Y (kDk) tile
+#pragma unroll
+            for (int i = 0; i < XT; ++i) scx[i] = rden[t0 + min(stage_row<DX>(lane, i), nvalid - 1)];
+        }
+        if constexpr (PASS == kDk) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
+                n_dl4[s] = (4 * g + s) < nvalid ? v : 0.f;
+            }
+        }
+        if constexpr (PASS == kDq) {
+            const float v = delta[t0 + min(c, nvalid - 1)];
+            n_dl1 = c < nvalid ? v : 0.f;
+        }
+        if constexpr (PASS == kDv) {                          // dO is the Z tile
+#pragma unroll
+            for (int i = 0; i < ZT; ++i) scz[i] = rden[t0 + min(stage_row<DZ>(lane, i), nvalid - 1)];
+        }
+    }
+
+    __device__ __forceinline__ void park(const int nvalid) {
+        park_tile<DX, Tr::kMapX>(lds_x, sx, scx, nvalid, lane);
+        if constexpr (Tr::kHasYZ) {
+            park_tile<DX, Tr::kMapY>(lds_y, sy, scx, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ>(lds_z, sz, scz, nvalid, lane);
+        }
+        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi>(lds_r, sr, scz, nvalid, lane);
+        dl1 = n_dl1;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) dl4[s] = n_dl4[s];
+    }
+};
+
+// Staging of the two reverse passes run side by side by the two waves of one workgroup:
+// the four input tiles are fetched once and shared.  Wave 0 (the kDv role) brings Q and
+// dO, wave 1 (the kDk role) brings K (parked twice, as phi and as phi') and V.
+template <int ROLE, int D, int M, typename T>
+struct ReverseStager {
+    static constexpr int DT = D / 16, MT = M / 16;
+    const T *As, *Bs;                   // role 0: Q, dO; role 1: K, V
+    const float *rden, *delta;
+    float *lds_a, *lds_a2, *lds_b;      // role 0: phi(Q), -, dO/den; role 1: phi(K), phi'(K), V
+    int N, lane, g;
+    f32x4 sa[DT], sb[MT];
+    float scd[DT], scb[MT];
+    float n_dl4[4];
+    float dl1, dl4[4];
+
+    __device__ __forceinline__ ReverseStager(const PassArgs &a, size_t rowbase, int lane_, float *la,
+                                             float *la2, float *lb)
+        : lds_a(la), lds_a2(la2), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4) {
+        As = static_cast<const T *>(ROLE == 0 ? a.Q : a.K) + rowbase * D;
+        Bs = static_cast<const T *>(ROLE == 0 ? a.G : a.V) + rowbase * M;
+        rden = a.rden + rowbase;
+        delta = a.delta + rowbase;
+        dl1 = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) n_dl4[s] = dl4[s] = 0.f;
+#pragma unroll
+        for (int i = 0; i < DT; ++i) scd[i] = 1.0f;
+#pragma unroll
+        for (int i = 0; i < MT; ++i) scb[i] = 1.0f;
+    }
+
+    __device__ __forceinline__ void fetch(const int ch) {
+        const int t0 = ch * kChunk;
+        const int nvalid = min(kChunk, N - t0);
+        stage_load<D>(As + (size_t)t0 * D, nvalid, lane, sa);
+        stage_load<M>(Bs + (size_t)t0 * M, nvalid, lane, sb);
+        if constexpr (ROLE == 0) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i) scb[i] = rden[t0 + min(stage_row<M>(lane, i), nvalid - 1)];
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
+                n_dl4[s] = (4 * g + s) < nvalid ? v : 0.f;
+            }
+        }
+    }
+
+    __device__ __forceinline__ void park(const int nvalid) {
+        park_tile<D, kMapPhi>(lds_a, sa, scd, nvalid, lane);
+        if constexpr (ROLE == 0) {
+            park_tile<M, kMapScale>(lds_b, sb, scb, nvalid, lane);
+        } else {
+            park_tile<D, kMapDphi>(lds_a2, sa, scd, nvalid, lane);
+            park_tile<M, kMapId>(lds_b, sb, scb, nvalid, lane);
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) dl4[s] = n_dl4[s];
+    }
+};
+
+// One pass over the chunks [ch_begin, ch_end) of sequence bh by the calling wave.  `stg`
+// fetches the next chunk and parks the current one; lds_* are the parked tiles this pass
+// reads its operands from (they may be shared with the other wave of the workgroup).
+template <int PASS, int D, int M, typename T, typename Stager>
+__device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const float *lds_x,
+                                         const float *lds_y, const float *lds_z,
+                                         const float *lds_r, void *out_tensor, const int bh,
+                                         const int seg, const int lane) {
+    using Tr = PassTraits<PASS, D, M>;
+    constexpr bool kXisD = Tr::kXisD;
+    constexpr int DX = Tr::DX, DZ = Tr::DZ;
     constexpr int XT = DX / 16, ZT = DZ / 16;
-    constexpr bool kReverse = (PASS == kDv || PASS == kDk);
-    constexpr bool kHasRaw = (PASS == kDq || PASS == kDk);       // phi' under the output
-    constexpr bool kHasYZ = (PASS != kGlobal);
+    constexpr bool kReverse = Tr::kReverse;
+    constexpr bool kHasRaw = Tr::kHasRaw;
+    constexpr bool kHasYZ = Tr::kHasYZ;
 
-    __shared__ float lds_x[tile_floats(DX)];
-    __shared__ float lds_y[kHasYZ ? tile_floats(DX) : 4];
-    __shared__ float lds_z[kHasYZ ? tile_floats(DZ) : 4];
-    __shared__ float lds_r[kHasRaw ? tile_floats(DZ) : 4];
-
-    const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
-    const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
+    const int c = lane & 15, g = lane >> 4;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const int count = ch_end - ch_begin;
-
     const size_t rowbase = (size_t)bh * a.N;
-    // which raw tensor feeds which operand
-    const T *Xs = static_cast<const T *>(PASS == kFwd || PASS == kGlobal ? a.Q
-                                         : PASS == kDq ? a.G : PASS == kDv ? a.K : a.V) + rowbase * DX;
-    const T *Ys = static_cast<const T *>(PASS == kFwd ? a.K : PASS == kDq ? a.V
-                                         : PASS == kDv ? a.Q : a.G) + rowbase * DX;
-    const T *Zs = static_cast<const T *>(PASS == kFwd ? a.V : PASS == kDq ? a.K
-                                         : PASS == kDv ? a.G : a.Q) + rowbase * DZ;
-    const T *Rs = static_cast<const T *>(PASS == kDq ? a.Q : a.K) + rowbase * DZ;
-    constexpr int kMapX = (PASS == kDq) ? kMapScale : (PASS == kDk) ? kMapId : kMapPhi;
-    constexpr int kMapY = (PASS == kDq) ? kMapId : (PASS == kDk) ? kMapScale : kMapPhi;
-    constexpr int kMapZ = (PASS == kFwd) ? kMapId : (PASS == kDv) ? kMapScale : kMapPhi;
-    const float *rden = a.rden + rowbase;
-    const float *delta = a.delta + rowbase;
-    T *outs = static_cast<T *>(a.out) + rowbase * DZ;
+    T *outs = static_cast<T *>(out_tensor) + rowbase * DZ;
 
     // ---- carried state --------------------------------------------------------------------
     f32x4 U[XT][ZT];
     float zg[XT][4];   // kFwd/kGlobal: z[16xt + 4g + r]  (lines up with the token-lane X)
-    float ec[ZT];      // kDq: z[16zt + c];  kDk: rho[16zt + c]  (lines up with the output)
+    float ecp[ZT];     // kDq: z[16zt + c], kDk: rho[16zt + c], as per-lane partial sums: the
+                       // four lanes (c, g = 0..3) together hold the value (an MFMA adds them up)
 #pragma unroll
     for (int xt = 0; xt < XT; ++xt) {
 #pragma unroll
@@ -129,7 +270,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
         for (int r = 0; r < 4; ++r) zg[xt][r] = 0.f;
     }
 #pragma unroll
-    for (int zt = 0; zt < ZT; ++zt) ec[zt] = 0.f;
+    for (int zt = 0; zt < ZT; ++zt) ecp[zt] = 0.f;
 
     if (a.state != nullptr) {
         const float *st = a.state +
@@ -156,67 +297,24 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
         }
         if constexpr (PASS == kDq || PASS == kDk) {
 #pragma unroll
-            for (int zt = 0; zt < ZT; ++zt) ec[zt] = st[D * M + 16 * zt + c];
+            for (int zt = 0; zt < ZT; ++zt) ecp[zt] = g == 0 ? st[D * M + 16 * zt + c] : 0.f;
         }
     }
 
-    // ---- staging registers: the next chunk, in flight while this one is computed ------------
-    f32x4 sx[XT], sy[XT], sz[ZT], sr[ZT];
-    float scx[XT], scz[ZT];             // 1/den of the staged rows of the dO tile
-    float n_dl1 = 0.f, n_dl4[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int i = 0; i < XT; ++i) scx[i] = 1.0f;
-#pragma unroll
-    for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
-
-    auto fetch = [&](const int ch) {
-        const int t0 = ch * kChunk;
-        const int nvalid = min(kChunk, a.N - t0);
-        stage_load<DX>(Xs + (size_t)t0 * DX, nvalid, lane, sx);
-        if constexpr (kHasYZ) {
-            stage_load<DX>(Ys + (size_t)t0 * DX, nvalid, lane, sy);
-            stage_load<DZ>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
-        }
-        if constexpr (kHasRaw) stage_load<DZ>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
-        if constexpr (PASS == kDq || PASS == kDk) {          // dO is the X (kDq) or Y (kDk) tile
-#pragma unroll
-            for (int i = 0; i < XT; ++i) scx[i] = rden[t0 + min(stage_row<DX>(lane, i), nvalid - 1)];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
-                n_dl4[s] = (4 * g + s) < nvalid ? v : 0.f;
-            }
-        }
-        if constexpr (PASS == kDq) {
-            const float v = delta[t0 + min(c, nvalid - 1)];
-            n_dl1 = c < nvalid ? v : 0.f;
-        }
-        if constexpr (PASS == kDv) {                          // dO is the Z tile
-#pragma unroll
-            for (int i = 0; i < ZT; ++i) scz[i] = rden[t0 + min(stage_row<DZ>(lane, i), nvalid - 1)];
-        }
-    };
-
     int ch = kReverse ? ch_end - 1 : ch_begin;
-    if (count > 0) fetch(ch);
+    if (count > 0) stg.fetch(ch);
 
     for (int it = 0; it < count; ++it) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
-        const bool tok_ok = c < nvalid;
 
         // ---- park the staged chunk in LDS, start fetching the next one ----------------------
         __syncthreads();                 // every operand read of the previous chunk is done
-        park_tile<DX, kMapX>(lds_x, sx, scx, nvalid, lane);
-        if constexpr (kHasYZ) {
-            park_tile<DX, kMapY>(lds_y, sy, scx, nvalid, lane);
-            park_tile<DZ, kMapZ>(lds_z, sz, scz, nvalid, lane);
-        }
-        if constexpr (kHasRaw) park_tile<DZ, kMapDphi>(lds_r, sr, scz, nvalid, lane);
-        const float dl1 = n_dl1;
-        const float dl4[4] = {n_dl4[0], n_dl4[1], n_dl4[2], n_dl4[3]};
+        stg.park(nvalid);
+        const float dl1 = stg.dl1;
+        const float dl4[4] = {stg.dl4[0], stg.dl4[1], stg.dl4[2], stg.dl4[3]};
         const int next = kReverse ? ch - 1 : ch + 1;
-        if (it + 1 < count) fetch(next);
+        if (it + 1 < count) stg.fetch(next);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the arithmetic
         __syncthreads();
 
@@ -233,7 +331,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16(xa[xt][r], U[xt][zt][r], out[zt]);
 
-        float den_a = 1.0f;              // kFwd / kGlobal: denominator of token c
+        // kFwd / kGlobal: den4[r] = denominator of token 4g + r.  Each lane (c = a, g) holds a
+        // partial sum of token a's denominator; one MFMA against a matrix of ones adds the four
+        // partials and lands the totals in the row layout of `out` (eps is the addend).
+        f32x4 den4 = {1.f, 1.f, 1.f, 1.f};
+        const f32x4 eps4 = {a.eps, a.eps, a.eps, a.eps};
         float zf[ZT][4];                 // Z, feature-lane
         if constexpr (PASS == kGlobal) {
             float p = 0.f;
@@ -241,7 +343,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
             for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) p = fmaf(xa[xt][r], zg[xt][r], p);
-            den_a = sum_over_groups(p) + a.eps;
+            den4 = mfma16(p, 1.0f, eps4);
         } else {
             // ---- W[a][b] = X_a . Y_b, lane (c = a, g), register r: b = 4g + r --------------
             float ya[XT][4];             // Y, token-lane
@@ -269,7 +371,18 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
                 for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) p = fmaf(xa[xt][r], zg[xt][r], p);
-                den_a = sum_over_groups(p) + a.eps;
+                den4 = mfma16(p, 1.0f, eps4);
+                // z += sum of the chunk's phi(K) rows: a sum over the 16 lanes of a group
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) zg[xt][r] += row_sum16(ya[xt][r]);
+            }
+            // the ones-column part of the state term: delta_a * z (kDq), rho (kDk)
+            if constexpr (PASS == kDq || PASS == kDk) {
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+                    out[zt] = mfma16(PASS == kDq ? dl1 : 1.0f, ecp[zt], out[zt]);
             }
             // ---- in-chunk term: out += W Z -------------------------------------------------
             lds_feature_lane<DZ>(lds_z, c, g, zf);
@@ -281,13 +394,14 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
 
         // ---- finish and store ---------------------------------------------------------------
         if constexpr (PASS == kFwd || PASS == kGlobal) {
-            const float rinv = tok_ok ? 1.0f / den_a : 0.f;
             if constexpr (PASS == kFwd) {
-                if (a.den != nullptr && g == 0 && tok_ok) a.den[rowbase + t0 + c] = den_a;
+                // lanes c < 4 of each group write den of token 4g + c: 16 consecutive floats
+                const float dsel = c == 0 ? den4[0] : c == 1 ? den4[1] : c == 2 ? den4[2] : den4[3];
+                if (a.den != nullptr && c < 4 && 4 * g + c < nvalid) a.den[rowbase + t0 + 4 * g + c] = dsel;
             }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const float ri = __shfl(rinv, 4 * g + r);
+                const float ri = __builtin_amdgcn_rcpf(den4[r]);
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) out[zt][r] *= ri;
             }
@@ -298,10 +412,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float extra = (PASS == kDq) ? dl4[r] * ec[zt] : ec[zt];
-                    out[zt][r] = (out[zt][r] + extra) * dp[zt][r];
-                }
+                for (int r = 0; r < 4; ++r) out[zt][r] *= dp[zt][r];
         }
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -324,20 +435,11 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt)
                         U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
-            if constexpr (PASS == kFwd) {
-#pragma unroll
-                for (int xt = 0; xt < XT; ++xt) {
-                    const float zc =
-                        sum_over_groups((yf[xt][0] + yf[xt][1]) + (yf[xt][2] + yf[xt][3]));
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) zg[xt][r] += __shfl(zc, 4 * g + r);
-                }
-            }
         }
         if constexpr (PASS == kDq) {
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt)
-                ec[zt] += sum_over_groups((zf[zt][0] + zf[zt][1]) + (zf[zt][2] + zf[zt][3]));
+                ecp[zt] += (zf[zt][0] + zf[zt][1]) + (zf[zt][2] + zf[zt][3]);
         }
         if constexpr (PASS == kDk) {
 #pragma unroll
@@ -345,10 +447,47 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
                 float p = dl4[0] * zf[zt][0];
 #pragma unroll
                 for (int s = 1; s < 4; ++s) p = fmaf(dl4[s], zf[zt][s], p);
-                ec[zt] += sum_over_groups(p);
+                ecp[zt] += p;
             }
         }
         ch = next;
+    }
+}
+
+template <int PASS, int D, int M, typename T>
+__global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void causal_pass_kernel(
+    const PassArgs a) {
+    using Tr = PassTraits<PASS, D, M>;
+    __shared__ float lds_x[tile_floats(Tr::DX)];
+    __shared__ float lds_y[Tr::kHasYZ ? tile_floats(Tr::DX) : 4];
+    __shared__ float lds_z[Tr::kHasYZ ? tile_floats(Tr::DZ) : 4];
+    __shared__ float lds_r[Tr::kHasRaw ? tile_floats(Tr::DZ) : 4];
+    const int lane = threadIdx.x;
+    const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
+    PassStager<PASS, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_x, lds_y, lds_z, lds_r);
+    run_pass<PASS, D, M, T>(a, stg, lds_x, lds_y, lds_z, lds_r, a.out, bh, seg, lane);
+}
+
+// Both reverse passes of the backward (eq. 14 and eq. 15) on one fetch of Q, K, V, dO:
+// wave 0 produces dV (a.out), wave 1 produces dK (a.out2).  Each wave owns its copy of the
+// reverse state in the layout its read-out needs (R for dV, R^T for dK).
+template <int D, int M, typename T>
+__global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void reverse_pass_kernel(
+    const PassArgs a) {
+    __shared__ float lds_fq[tile_floats(D)];    // phi(Q)
+    __shared__ float lds_g[tile_floats(M)];     // dO / den
+    __shared__ float lds_fk[tile_floats(D)];    // phi(K)
+    __shared__ float lds_dk[tile_floats(D)];    // phi'(K)
+    __shared__ float lds_v[tile_floats(M)];     // V
+    const int lane = threadIdx.x & (kWave - 1);
+    const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
+    const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
+    if (role == 0) {
+        ReverseStager<0, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fq, nullptr, lds_g);
+        run_pass<kDv, D, M, T>(a, stg, lds_fk, lds_fq, lds_g, nullptr, a.out, bh, seg, lane);
+    } else {
+        ReverseStager<1, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fk, lds_dk, lds_v);
+        run_pass<kDk, D, M, T>(a, stg, lds_v, lds_g, lds_fq, lds_dk, a.out2, bh, seg, lane);
     }
 }
 
