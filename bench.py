@@ -84,7 +84,7 @@ class FwdBwd:
         la, w = self.la, self.w
         la.la_causal_fwd(self.Q, self.K, self.V, self.O, self.den, w.eps, ws=self.ws_f)
         la.la_causal_bwd(self.Q, self.K, self.V, self.O, self.den, self.G, self.dQ, self.dK,
-                         self.dV, w.eps, ws=self.ws_b)
+                         self.dV, w.eps, ws=self.ws_b, fwd_ws=self.ws_f)
 
     def fwd_only(self):
         self.la.la_causal_fwd(self.Q, self.K, self.V, self.O, self.den, self.w.eps, ws=self.ws_f)

@@ -101,11 +101,17 @@ int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *d
  * O(N max(D,M)), no per-position state is stored.
  * O [B,H,N,M] and den [B,H,N] are the results of la_causal_fwd on the same
  * Q, K, V, eps; if either is NULL both are recomputed into the workspace.
+ * fwd_ws is optional (NULL allowed): the workspace that la_causal_fwd used for
+ * that same call, untouched since.  It then still holds the running sums of
+ * eq. 10-11 at the segment borders, and the backward reuses them instead of
+ * re-reading K and V to rebuild them (one state per segment of a few hundred
+ * tokens, not one per position).  Must come from the same sizes, dtype and
+ * schedule; ignored when the sizes need no forward workspace.
  * dQ, dK [B,H,N,D] out; dV [B,H,N,M] out.  ws as above
  * (la_causal_bwd_workspace()).
  */
 int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
-                  const void *dO, void *dQ, void *dK, void *dV,
+                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
                   int B, int H, int N, int D, int M, float eps, la_dtype t,
                   void *ws, size_t ws_bytes, void *stream);
 

@@ -47,7 +47,7 @@ def _load() -> ctypes.CDLL:
     lib.la_causal_fwd.restype = i
     lib.la_causal_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_causal_bwd.restype = i
-    lib.la_causal_bwd.argtypes = [vp] * 9 + [i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_causal_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_global_fwd.restype = i
     lib.la_global_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_recurrent_step.restype = i
@@ -130,16 +130,17 @@ def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None):
     return ws
 
 
-def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None):
+def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None):
     """dQ, dK, dV <- gradients of causal linear attention for upstream dO; O and den are the
-    forward results (either may be None: both are then recomputed)."""
+    forward results (either may be None: both are then recomputed).  fwd_ws (optional) is the
+    workspace tensor la_causal_fwd returned for the same call: its segment states are reused."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
     t = _dtype_code(Q)
     ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(dO), _ptr(dQ),
-                              _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t, wp, wb,
-                              _stream(stream)), "la_causal_bwd")
+    _check(_lib.la_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
+                              _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
+                              wp, wb, _stream(stream)), "la_causal_bwd")
     return ws
 
 

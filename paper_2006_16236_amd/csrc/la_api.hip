@@ -205,7 +205,7 @@ int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *d
 }
 
 int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
-                  const void *dO, void *dQ, void *dK, void *dV,
+                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
                   int B, int H, int N, int D, int M, float eps, la_dtype t,
                   void *ws, size_t ws_bytes, void *stream) {
     if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr ||
@@ -214,7 +214,8 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) ||
-        misaligned(dK) || misaligned(dV) || misaligned(O) || misaligned(den) || misaligned(ws))
+        misaligned(dK) || misaligned(dV) || misaligned(O) || misaligned(den) || misaligned(ws) ||
+        misaligned(fwd_ws))
         return LA_ERR_ALIGN;
     const size_t need = la_causal_bwd_workspace(B, H, N, D, M, t);
     if (ws == nullptr || ws_bytes < need) return LA_ERR_WORKSPACE;
@@ -231,7 +232,12 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
         stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
         stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
     }
-    if (O == nullptr || den == nullptr) {      // recompute the forward results
+    const bool recompute_fwd = (O == nullptr || den == nullptr);
+    // the forward's own workspace still holds the prefix states: no need to rebuild them
+    const bool have_states = p.nseg > 1 && (fwd_ws != nullptr || recompute_fwd);
+    if (p.nseg > 1 && fwd_ws != nullptr && !recompute_fwd)
+        stS = const_cast<float *>(static_cast<const float *>(fwd_ws));
+    if (recompute_fwd) {                       // recompute the forward results
         void *Otmp = cv.take(rows * M * esize(t));
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
         const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s);
@@ -245,10 +251,12 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
     if (p.nseg > 1) {
         la::SegArgs sa{};
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps;
-        sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = stS;
-        sa.skip_seg = p.nseg - 1;
-        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s)); }
+        if (!have_states) {
+            sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = stS;
+            sa.skip_seg = p.nseg - 1;
+            { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s)); }
+        }
         sa.Y = Q; sa.Z = dO; sa.rden = rden; sa.delta = delta; sa.state = stR;
         sa.skip_seg = 0;
         { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(1, D, M, (int)t, sa, nblocks, s)); }

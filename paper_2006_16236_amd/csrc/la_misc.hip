@@ -5,33 +5,44 @@
 namespace la {
 
 // ---- scan over the segment states of each sequence ------------------------------------------
-// state: [BH, nseg, stride]; one thread per (sequence, element) walks the nseg slots.
+// state: [BH, nseg, stride].  A workgroup takes 32 consecutive elements of one sequence; its
+// 8 groups of 32 threads split the nseg slots into 8 consecutive runs.  Each group first sums
+// its run (all loads independent), the run totals are exchanged through LDS, then the group
+// walks its run again (now from cache) and writes the exclusive prefix.  Slots are visited in
+// scan order: ascending for the prefix, descending for the suffix.  Fixed order: deterministic.
 __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg, int stride,
                                                           int mode) {
-    const int e = blockIdx.x * 256 + threadIdx.x;
-    if (e >= stride) return;
-    float *p = state + (size_t)blockIdx.y * nseg * stride + e;
+    __shared__ float part_total[8][32];
+    const int el = threadIdx.x & 31, part = threadIdx.x >> 5;
+    const int e = blockIdx.x * 32 + el;
+    const bool live = e < stride;
+    float *p = state + (size_t)blockIdx.y * nseg * stride + (live ? e : 0);
+    const bool reverse = mode == kScanReverse;
+    const int per = (nseg + 7) / 8;
+    const int k0 = min(part * per, nseg), k1 = min(k0 + per, nseg);
+    // the last slot in scan order holds no total (nobody reads past it): never read it
+    const int klast = mode == kScanTotal ? nseg : nseg - 1;
+
+    float total = 0.f;
+    for (int k = k0; k < min(k1, klast); ++k) total += p[(size_t)(reverse ? nseg - 1 - k : k) * stride];
+    part_total[part][el] = total;
+    __syncthreads();
     float acc = 0.f;
-    if (mode == kScanForward) {            // slot s <- sum of slots before s (the last total is unread)
-        for (int s = 0; s < nseg; ++s) {
-            const float t = (s + 1 < nseg) ? p[(size_t)s * stride] : 0.f;
-            p[(size_t)s * stride] = acc;
-            acc += t;
-        }
-    } else if (mode == kScanReverse) {     // slot s <- sum of slots after s (the first total is unread)
-        for (int s = nseg - 1; s >= 0; --s) {
-            const float t = (s > 0) ? p[(size_t)s * stride] : 0.f;
-            p[(size_t)s * stride] = acc;
-            acc += t;
-        }
-    } else {                               // slot 0 <- sum of all slots
-        for (int s = 0; s < nseg; ++s) acc += p[(size_t)s * stride];
-        p[0] = acc;
+    for (int q = 0; q < part; ++q) acc += part_total[q][el];
+    if (mode == kScanTotal) {
+        if (part == 7 && live) p[0] = acc + total;
+        return;
+    }
+    for (int k = k0; k < k1; ++k) {
+        float *slot = p + (size_t)(reverse ? nseg - 1 - k : k) * stride;
+        const float t = k < klast ? *slot : 0.f;
+        if (live) *slot = acc;
+        acc += t;
     }
 }
 
 hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s) {
-    dim3 grid((stride + 255) / 256, BH);
+    dim3 grid((stride + 31) / 32, BH);
     scan_states_kernel<<<grid, 256, 0, s>>>(state, nseg, stride, mode);
     return hipGetLastError();
 }

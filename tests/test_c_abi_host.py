@@ -81,10 +81,11 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, p, 1024, null) == b.LA_ERR_WORKSPACE
 
     bwd = lib.la_causal_bwd
-    assert bwd(p, p, p, p, p, null, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_NULL
-    assert bwd(p, p, p, p, p, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
-    assert bwd(p, p, p, p, p, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 8, null) == b.LA_ERR_WORKSPACE
-    assert bwd(p, p, p, p, p, p, p, p, odd, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
+    assert bwd(p, p, p, p, p, null, null, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_NULL
+    assert bwd(p, p, p, p, p, null, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert bwd(p, p, p, p, p, null, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 8, null) == b.LA_ERR_WORKSPACE
+    assert bwd(p, p, p, p, p, null, p, p, p, odd, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
+    assert bwd(p, p, p, p, p, odd, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
 
     glob = lib.la_global_fwd
     assert glob(p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE

@@ -26,8 +26,8 @@ def gpu_fwd_bwd(la, host, bf16=False, eps=1e-6):
     O = torch.empty_like(V)
     den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=DEV)
     dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
-    la.la_causal_fwd(Q, K, V, O, den, eps)
-    la.la_causal_bwd(Q, K, V, O, den, G, dQ, dK, dV, eps)
+    fwd_ws = la.la_causal_fwd(Q, K, V, O, den, eps)
+    la.la_causal_bwd(Q, K, V, O, den, G, dQ, dK, dV, eps, fwd_ws=fwd_ws)
     torch.cuda.synchronize()
     return O, den, dQ, dK, dV
 

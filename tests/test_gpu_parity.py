@@ -28,17 +28,18 @@ def run_fwd(la, Q, K, V, eps, bf16=False, want_den=True):
     return to_host(O), (den.cpu().numpy() if want_den else None)
 
 
-def run_bwd(la, Q, K, V, G, eps, bf16=False, reuse_fwd=True):
+def run_bwd(la, Q, K, V, G, eps, bf16=False, reuse_fwd=True, reuse_states=True):
     dq, dk, dv, dg = (to_dev(x, bf16) for x in (Q, K, V, G))
-    O = den = None
+    O = den = fwd_ws = None
     if reuse_fwd:
         O = torch.empty_like(dv)
         den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=DEV)
-        la.la_causal_fwd(dq, dk, dv, O, den, eps)
+        fwd_ws = la.la_causal_fwd(dq, dk, dv, O, den, eps)
     gq = torch.full_like(dq, float("nan"))
     gk = torch.full_like(dk, float("nan"))
     gv = torch.full_like(dv, float("nan"))
-    la.la_causal_bwd(dq, dk, dv, O, den, dg, gq, gk, gv, eps)
+    la.la_causal_bwd(dq, dk, dv, O, den, dg, gq, gk, gv, eps,
+                     fwd_ws=fwd_ws if reuse_states else None)
     torch.cuda.synchronize()
     return to_host(gq), to_host(gk), to_host(gv)
 
@@ -94,7 +95,9 @@ def test_causal_bwd_recomputes_forward_when_not_given(la, oracle):
         with schedule(**SCHEDULES[sched]):
             a = run_bwd(la, Q, K, V, G, 1e-6, reuse_fwd=False)
             b = run_bwd(la, Q, K, V, G, 1e-6, reuse_fwd=True)
+            c = run_bwd(la, Q, K, V, G, 1e-6, reuse_fwd=True, reuse_states=False)
         assert all(np.array_equal(x, y) for x, y in zip(a, b))
+        assert all(np.array_equal(x, y) for x, y in zip(a, c))
         assert max(grad_errs(a, gref)) <= tol_for(N)
 
 
