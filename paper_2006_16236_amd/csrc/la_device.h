@@ -14,15 +14,17 @@ constexpr int kChunk = 16;       // tokens per chunk = MFMA tile edge
 constexpr int kWave = 64;
 
 // ---- feature map (paper eq. 7): phi(x) = elu(x) + 1 ------------------------------------
-// x > 0: x + 1; otherwise exp(x).  The exponential is only ever taken of a
-// non-positive argument (the untaken branch cannot overflow).
+// x > 0: x + 1; otherwise exp(x).  Both branches are evaluated and one is SELECTED: for a
+// large positive x the exponential overflows to +inf, which the select discards (a select
+// never turns inf into NaN, a multiply by zero would).  fp32 vector instructions and fp32
+// MFMAs share one pipeline on this chip, so every instruction saved here is matrix time won.
 __device__ __forceinline__ float phi(float x) {
-    const float e = __expf(fminf(x, 0.0f));
+    const float e = __expf(x);
     return x > 0.0f ? x + 1.0f : e;
 }
 // phi'(x) = 1 for x > 0, exp(x) otherwise.
 __device__ __forceinline__ float dphi(float x) {
-    const float e = __expf(fminf(x, 0.0f));
+    const float e = __expf(x);
     return x > 0.0f ? 1.0f : e;
 }
 
@@ -97,12 +99,36 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 acc) {
 template <int F> __device__ __forceinline__ int stage_row(int lane, int i) { return (4 * (lane + 64 * i)) / F; }
 template <int F> __device__ __forceinline__ int stage_col(int lane, int i) { return (4 * (lane + 64 * i)) % F; }
 
-template <int F, typename T>
+// kFull: all 16 rows exist (the common case): one lane offset for the whole kernel plus an
+// immediate per load, no clamping.
+template <int F, bool kFull, typename T>
 __device__ __forceinline__ void stage_load(const T *base, int nvalid, int lane, f32x4 (&st)[F / 16]) {
 #pragma unroll
     for (int i = 0; i < F / 16; ++i) {
-        const int row = min(stage_row<F>(lane, i), nvalid - 1);
-        st[i] = load4(base + (size_t)row * F + stage_col<F>(lane, i));
+        if constexpr (kFull) {
+            st[i] = load4(base + 4 * lane + 256 * i);
+        } else {
+            const int row = min(stage_row<F>(lane, i), nvalid - 1);
+            st[i] = load4(base + (size_t)row * F + stage_col<F>(lane, i));
+        }
+    }
+}
+
+// per-token fp32 scalars (1/den) of the rows a lane stages
+template <int F, bool kFull>
+__device__ __forceinline__ void stage_rows(const float *base, int nvalid, int lane, float (&sc)[F / 16]) {
+#pragma unroll
+    for (int i = 0; i < F / 16; ++i)
+        sc[i] = base[kFull ? stage_row<F>(lane, i) : min(stage_row<F>(lane, i), nvalid - 1)];
+}
+
+// four per-token fp32 scalars of tokens 4g + s, zero past the end
+template <bool kFull>
+__device__ __forceinline__ void rows4(const float *base, int nvalid, int g, float (&x)[4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        const float v = base[kFull ? 4 * g + s : min(4 * g + s, nvalid - 1)];
+        x[s] = (kFull || (4 * g + s) < nvalid) ? v : 0.f;
     }
 }
 

@@ -33,7 +33,13 @@
 // whichever of the two layouts of la_device.h each product needs.
 #pragma once
 
+#include <type_traits>
+
 #include "la_device.h"
+
+#ifndef LA_SLEEP_AFTER_FETCH
+#define LA_SLEEP_AFTER_FETCH 1   // in units of 64 clocks
+#endif
 
 namespace la {
 
@@ -65,8 +71,9 @@ __device__ __forceinline__ float map_value(float v, float scale) {
     return v;
 }
 
-// Park a staged tile in LDS: apply the map, zero the rows past the end of the sequence.
-template <int F, int MAP>
+// Park a staged tile in LDS: apply the map; kFull = false also zeroes the rows past the end
+// of the sequence.
+template <int F, int MAP, bool kFull>
 __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16],
                                           const float (&scale)[F / 16], int nvalid, int lane) {
 #pragma unroll
@@ -74,7 +81,10 @@ __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16]
         const int row = stage_row<F>(lane, i);
         f32x4 v;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = row < nvalid ? map_value<MAP>(st[i][r], scale[i]) : 0.0f;
+        for (int r = 0; r < 4; ++r) {
+            const float m = map_value<MAP>(st[i][r], scale[i]);
+            v[r] = (kFull || row < nvalid) ? m : 0.0f;
+        }
         lds_store4(tile + row * tile_stride(F) + stage_col<F>(lane, i), v);
     }
 }
@@ -129,43 +139,49 @@ struct PassStager {
         for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
     }
 
+    static constexpr int kDepth = 1;
+
+    template <bool kFull>
+    __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
+        stage_load<DX, kFull>(Xs + (size_t)t0 * DX, nvalid, lane, sx);
+        if constexpr (Tr::kHasYZ) {
+            stage_load<DX, kFull>(Ys + (size_t)t0 * DX, nvalid, lane, sy);
+            stage_load<DZ, kFull>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
+        }
+        if constexpr (Tr::kHasRaw) stage_load<DZ, kFull>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
+        if constexpr (PASS == kDq || PASS == kDk)             // dO is the X (kDq) or Y (kDk) tile
+            stage_rows<DX, kFull>(rden + t0, nvalid, lane, scx);
+        if constexpr (PASS == kDk) rows4<kFull>(delta + t0, nvalid, g, n_dl4);
+        if constexpr (PASS == kDq) {
+            const float v = delta[t0 + (kFull ? c : min(c, nvalid - 1))];
+            n_dl1 = (kFull || c < nvalid) ? v : 0.f;
+        }
+        if constexpr (PASS == kDv)                            // dO is the Z tile
+            stage_rows<DZ, kFull>(rden + t0, nvalid, lane, scz);
+    }
+
+    template <int SLOT>
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        stage_load<DX>(Xs + (size_t)t0 * DX, nvalid, lane, sx);
-        if constexpr (Tr::kHasYZ) {
-            stage_load<DX>(Ys + (size_t)t0 * DX, nvalid, lane, sy);
-            stage_load<DZ>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
-        }
-        if constexpr (Tr::kHasRaw) stage_load<DZ>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
-        if constexpr (PASS == kDq || PASS == kDk) {          // dO is the X (kDq) or Y (kDk) tile
-#pragma unroll
-            for (int i = 0; i < XT; ++i) scx[i] = rden[t0 + min(stage_row<DX>(lane, i), nvalid - 1)];
-        }
-        if constexpr (PASS == kDk) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
-                n_dl4[s] = (4 * g + s) < nvalid ? v : 0.f;
-            }
-        }
-        if constexpr (PASS == kDq) {
-            const float v = delta[t0 + min(c, nvalid - 1)];
-            n_dl1 = c < nvalid ? v : 0.f;
-        }
-        if constexpr (PASS == kDv) {                          // dO is the Z tile
-#pragma unroll
-            for (int i = 0; i < ZT; ++i) scz[i] = rden[t0 + min(stage_row<DZ>(lane, i), nvalid - 1)];
-        }
+        if (nvalid == kChunk) fetch_impl<true>(t0, nvalid);      // uniform branch
+        else fetch_impl<false>(t0, nvalid);
     }
 
-    __device__ __forceinline__ void park(const int nvalid) {
-        park_tile<DX, Tr::kMapX>(lds_x, sx, scx, nvalid, lane);
+    template <bool kFull>
+    __device__ __forceinline__ void park_impl(const int nvalid) {
+        park_tile<DX, Tr::kMapX, kFull>(lds_x, sx, scx, nvalid, lane);
         if constexpr (Tr::kHasYZ) {
-            park_tile<DX, Tr::kMapY>(lds_y, sy, scx, nvalid, lane);
-            park_tile<DZ, Tr::kMapZ>(lds_z, sz, scz, nvalid, lane);
+            park_tile<DX, Tr::kMapY, kFull>(lds_y, sy, scx, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ, kFull>(lds_z, sz, scz, nvalid, lane);
         }
-        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi>(lds_r, sr, scz, nvalid, lane);
+        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull>(lds_r, sr, scz, nvalid, lane);
+    }
+
+    template <int SLOT>
+    __device__ __forceinline__ void park(const int nvalid) {
+        if (nvalid == kChunk) park_impl<true>(nvalid);
+        else park_impl<false>(nvalid);
         dl1 = n_dl1;
 #pragma unroll
         for (int s = 0; s < 4; ++s) dl4[s] = n_dl4[s];
@@ -178,13 +194,14 @@ struct PassStager {
 template <int ROLE, int D, int M, typename T>
 struct ReverseStager {
     static constexpr int DT = D / 16, MT = M / 16;
+    static constexpr int kDepth = 1;    // chunks in flight = sets of staging registers (1 or 2)
     const T *As, *Bs;                   // role 0: Q, dO; role 1: K, V
     const float *rden, *delta;
     float *lds_a, *lds_a2, *lds_b;      // role 0: phi(Q), -, dO/den; role 1: phi(K), phi'(K), V
     int N, lane, g;
-    f32x4 sa[DT], sb[MT];
-    float scd[DT], scb[MT];
-    float n_dl4[4];
+    f32x4 sa[kDepth][DT], sb[kDepth][MT];
+    float scd[DT], scb[kDepth][MT];
+    float n_dl4[kDepth][4];
     float dl1, dl4[4];
 
     __device__ __forceinline__ ReverseStager(const PassArgs &a, size_t rowbase, int lane_, float *la,
@@ -196,40 +213,51 @@ struct ReverseStager {
         delta = a.delta + rowbase;
         dl1 = 0.f;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) n_dl4[s] = dl4[s] = 0.f;
+        for (int s = 0; s < 4; ++s) dl4[s] = 0.f;
 #pragma unroll
         for (int i = 0; i < DT; ++i) scd[i] = 1.0f;
 #pragma unroll
-        for (int i = 0; i < MT; ++i) scb[i] = 1.0f;
+        for (int k = 0; k < kDepth; ++k) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) n_dl4[k][s] = 0.f;
+#pragma unroll
+            for (int i = 0; i < MT; ++i) scb[k][i] = 1.0f;
+        }
     }
 
+    template <int SLOT, bool kFull>
+    __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
+        stage_load<D, kFull>(As + (size_t)t0 * D, nvalid, lane, sa[SLOT]);
+        stage_load<M, kFull>(Bs + (size_t)t0 * M, nvalid, lane, sb[SLOT]);
+        if constexpr (ROLE == 0) stage_rows<M, kFull>(rden + t0, nvalid, lane, scb[SLOT]);
+        else rows4<kFull>(delta + t0, nvalid, g, n_dl4[SLOT]);
+    }
+
+    template <int SLOT>
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        stage_load<D>(As + (size_t)t0 * D, nvalid, lane, sa);
-        stage_load<M>(Bs + (size_t)t0 * M, nvalid, lane, sb);
+        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);
+        else fetch_impl<SLOT, false>(t0, nvalid);
+    }
+
+    template <int SLOT, bool kFull>
+    __device__ __forceinline__ void park_impl(const int nvalid) {
+        park_tile<D, kMapPhi, kFull>(lds_a, sa[SLOT], scd, nvalid, lane);
         if constexpr (ROLE == 0) {
-#pragma unroll
-            for (int i = 0; i < MT; ++i) scb[i] = rden[t0 + min(stage_row<M>(lane, i), nvalid - 1)];
+            park_tile<M, kMapScale, kFull>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         } else {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
-                n_dl4[s] = (4 * g + s) < nvalid ? v : 0.f;
-            }
+            park_tile<D, kMapDphi, kFull>(lds_a2, sa[SLOT], scd, nvalid, lane);
+            park_tile<M, kMapId, kFull>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         }
     }
 
+    template <int SLOT>
     __device__ __forceinline__ void park(const int nvalid) {
-        park_tile<D, kMapPhi>(lds_a, sa, scd, nvalid, lane);
-        if constexpr (ROLE == 0) {
-            park_tile<M, kMapScale>(lds_b, sb, scb, nvalid, lane);
-        } else {
-            park_tile<D, kMapDphi>(lds_a2, sa, scd, nvalid, lane);
-            park_tile<M, kMapId>(lds_b, sb, scb, nvalid, lane);
-        }
+        if (nvalid == kChunk) park_impl<SLOT, true>(nvalid);
+        else park_impl<SLOT, false>(nvalid);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) dl4[s] = n_dl4[s];
+        for (int s = 0; s < 4; ++s) dl4[s] = n_dl4[SLOT][s];
     }
 };
 
@@ -259,15 +287,14 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 
     // ---- carried state --------------------------------------------------------------------
     f32x4 U[XT][ZT];
-    float zg[XT][4];   // kFwd/kGlobal: z[16xt + 4g + r]  (lines up with the token-lane X)
+    f32x4 zg[XT];      // kFwd/kGlobal: z[16xt + 4g + r]  (lines up with the token-lane X)
     float ecp[ZT];     // kDq: z[16zt + c], kDk: rho[16zt + c], as per-lane partial sums: the
                        // four lanes (c, g = 0..3) together hold the value (an MFMA adds them up)
 #pragma unroll
     for (int xt = 0; xt < XT; ++xt) {
 #pragma unroll
         for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int r = 0; r < 4; ++r) zg[xt][r] = 0.f;
+        zg[xt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
     for (int zt = 0; zt < ZT; ++zt) ecp[zt] = 0.f;
@@ -289,11 +316,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             }
         if constexpr (PASS == kFwd || PASS == kGlobal) {
 #pragma unroll
-            for (int xt = 0; xt < XT; ++xt) {
-                const f32x4 v = load4(st + D * M + 16 * xt + 4 * g);
-#pragma unroll
-                for (int r = 0; r < 4; ++r) zg[xt][r] = v[r];
-            }
+            for (int xt = 0; xt < XT; ++xt) zg[xt] = load4(st + D * M + 16 * xt + 4 * g);
         }
         if constexpr (PASS == kDq || PASS == kDk) {
 #pragma unroll
@@ -301,20 +324,32 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         }
     }
 
-    int ch = kReverse ? ch_end - 1 : ch_begin;
-    if (count > 0) stg.fetch(ch);
+    // Chunks are visited in steps of `dir`; the stager keeps kDepth chunks in flight, each in
+    // its own set of staging registers (the set is a compile-time index, hence the tag).
+    constexpr int kDepth = Stager::kDepth;
+    constexpr int dir = kReverse ? -1 : 1;
+    const int ch0 = kReverse ? ch_end - 1 : ch_begin;
+    if (count > 0) stg.template fetch<0>(ch0);
+    if constexpr (kDepth == 2) {
+        if (count > 1) stg.template fetch<1>(ch0 + dir);
+    }
 
-    for (int it = 0; it < count; ++it) {
+    auto step = [&](auto slot_tag, const int it) {
+        constexpr int kSlot = decltype(slot_tag)::value;
+        const int ch = ch0 + dir * it;
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
 
-        // ---- park the staged chunk in LDS, start fetching the next one ----------------------
+        // ---- park the staged chunk in LDS, refill its staging registers ---------------------
         __syncthreads();                 // every operand read of the previous chunk is done
-        stg.park(nvalid);
+        stg.template park<kSlot>(nvalid);
         const float dl1 = stg.dl1;
         const float dl4[4] = {stg.dl4[0], stg.dl4[1], stg.dl4[2], stg.dl4[3]};
-        const int next = kReverse ? ch - 1 : ch + 1;
-        if (it + 1 < count) stg.fetch(next);
+        if (it + kDepth < count) stg.template fetch<kSlot>(ch + dir * kDepth);
+        // Let the loads leave the wave before the matrix instructions start: measured on
+        // MI355X, a burst of MFMAs issued right behind a batch of global loads delays those
+        // loads by the length of the burst (the chunk then arrives one iteration late).
+        __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the arithmetic
         __syncthreads();
 
@@ -372,11 +407,6 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                     for (int r = 0; r < 4; ++r) p = fmaf(xa[xt][r], zg[xt][r], p);
                 den4 = mfma16(p, 1.0f, eps4);
-                // z += sum of the chunk's phi(K) rows: a sum over the 16 lanes of a group
-#pragma unroll
-                for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) zg[xt][r] += row_sum16(ya[xt][r]);
             }
             // the ones-column part of the state term: delta_a * z (kDq), rho (kDk)
             if constexpr (PASS == kDq || PASS == kDk) {
@@ -414,14 +444,21 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                 for (int r = 0; r < 4; ++r) out[zt][r] *= dp[zt][r];
         }
+        T *chunk_out = outs + (size_t)t0 * DZ;          // uniform; lane offsets stay 32-bit
+        if (nvalid == kChunk) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int row = 4 * g + r;
-            if (row < nvalid) {
-                T *p = outs + (size_t)(t0 + row) * DZ + c;
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) store_elem(p + 16 * zt, out[zt][r]);
-            }
+                for (int zt = 0; zt < ZT; ++zt)
+                    store_elem(chunk_out + ((4 * g + r) * DZ + c + 16 * zt), out[zt][r]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (4 * g + r < nvalid) {
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt)
+                        store_elem(chunk_out + ((4 * g + r) * DZ + c + 16 * zt), out[zt][r]);
+                }
         }
 
         // ---- carry: U += Y^T Z, and the ones-column vector --------------------------------
@@ -435,6 +472,14 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt)
                         U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+            if constexpr (PASS == kFwd) {
+                // z += column sums of the chunk's phi(K).  Each lane adds up its four tokens;
+                // an MFMA against ones adds the four groups and delivers the sums of features
+                // 16xt + 4g + r in register r: the very layout z is kept in.
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt)
+                    zg[xt] = mfma16((yf[xt][0] + yf[xt][1]) + (yf[xt][2] + yf[xt][3]), 1.0f, zg[xt]);
+            }
         }
         if constexpr (PASS == kDq) {
 #pragma unroll
@@ -450,7 +495,13 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 ecp[zt] += p;
             }
         }
-        ch = next;
+    };
+
+    for (int it = 0; it < count; it += kDepth) {
+        step(std::integral_constant<int, 0>{}, it);
+        if constexpr (kDepth == 2) {
+            if (it + 1 < count) step(std::integral_constant<int, 1>{}, it + 1);
+        }
     }
 }
 
@@ -539,30 +590,36 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
 #pragma unroll
     for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
 
+    auto fetch_impl = [&](auto full_tag, const int t0, const int nvalid) {
+        constexpr bool kFull = decltype(full_tag)::value;
+        stage_load<D, kFull>(Ys + (size_t)t0 * D, nvalid, lane, sy);
+        stage_load<M, kFull>(Zs + (size_t)t0 * M, nvalid, lane, sz);
+        if constexpr (KIND == 1) {
+            stage_rows<M, kFull>(rden + t0, nvalid, lane, scz);
+            rows4<kFull>(delta + t0, nvalid, g, n_w4);
+        }
+    };
     auto fetch = [&](const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
-        stage_load<D>(Ys + (size_t)t0 * D, nvalid, lane, sy);
-        stage_load<M>(Zs + (size_t)t0 * M, nvalid, lane, sz);
-        if constexpr (KIND == 1) {
-#pragma unroll
-            for (int i = 0; i < ZT; ++i) scz[i] = rden[t0 + min(stage_row<M>(lane, i), nvalid - 1)];
-#pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float v = delta[t0 + min(4 * g + s, nvalid - 1)];
-                n_w4[s] = (4 * g + s) < nvalid ? v : 0.f;
-            }
-        }
+        if (nvalid == kChunk) fetch_impl(std::true_type{}, t0, nvalid);
+        else fetch_impl(std::false_type{}, t0, nvalid);
     };
 
     if (ch_begin < ch_end) fetch(ch_begin);
     for (int ch = ch_begin; ch < ch_end; ++ch) {
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
-        park_tile<D, kMapPhi>(lds_y, sy, scy, nvalid, lane);
-        park_tile<M, KIND == 1 ? kMapScale : kMapId>(lds_z, sz, scz, nvalid, lane);
+        if (nvalid == kChunk) {
+            park_tile<D, kMapPhi, true>(lds_y, sy, scy, nvalid, lane);
+            park_tile<M, KIND == 1 ? kMapScale : kMapId, true>(lds_z, sz, scz, nvalid, lane);
+        } else {
+            park_tile<D, kMapPhi, false>(lds_y, sy, scy, nvalid, lane);
+            park_tile<M, KIND == 1 ? kMapScale : kMapId, false>(lds_z, sz, scz, nvalid, lane);
+        }
         const float w4[4] = {n_w4[0], n_w4[1], n_w4[2], n_w4[3]};
         if (ch + 1 < ch_end) fetch(ch + 1);
+        __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
 
