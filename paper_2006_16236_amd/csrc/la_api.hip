@@ -245,7 +245,10 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
         O = Otmp;
         den = dentmp;
     }
-    { ProfScope ps(LA_K_PREP, s); LA_TRY(la::launch_bwd_prep(dO, O, den, rden, delta, rows, M, (int)t, s)); }
+    // the per-token scalars 1/den and delta: fused into the Q, dO segment sums when the
+    // sequences are cut into segments, a sweep of its own otherwise
+    if (p.nseg == 1)
+        { ProfScope ps(LA_K_PREP, s); LA_TRY(la::launch_bwd_prep(dO, O, den, rden, delta, rows, M, (int)t, s)); }
 
     const int nblocks = (int)(BH * p.nseg);
     if (p.nseg > 1) {
@@ -257,9 +260,10 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
             { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
             { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s)); }
         }
-        sa.Y = Q; sa.Z = dO; sa.rden = rden; sa.delta = delta; sa.state = stR;
-        sa.skip_seg = 0;
-        { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(1, D, M, (int)t, sa, nblocks, s)); }
+        sa.Y = Q; sa.Z = dO; sa.rden = nullptr; sa.delta = nullptr; sa.state = stR;
+        sa.O = O; sa.den = den; sa.rden_out = rden; sa.delta_out = delta;
+        sa.skip_seg = -1;          // every segment must produce its tokens' scalars
+        { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(2, D, M, (int)t, sa, nblocks, s)); }
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanReverse, s)); }
     }
     la::PassArgs a{};

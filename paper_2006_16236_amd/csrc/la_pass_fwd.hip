@@ -23,9 +23,12 @@ hipError_t launch_segment_state(int kind, int D, int M, int dtype, const SegArgs
         if (kind == 0) {
             if (dtype == 0) segment_state_kernel<0, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
             else segment_state_kernel<0, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
-        } else {
+        } else if (kind == 1) {
             if (dtype == 0) segment_state_kernel<1, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
             else segment_state_kernel<1, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
+        } else {
+            if (dtype == 0) segment_state_kernel<2, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
+            else segment_state_kernel<2, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
         }
     });
     return hipGetLastError();

@@ -545,12 +545,19 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 // ---- per-segment totals (first phase of the segment scan) ---------------------------------
 // KIND 0: S = sum phi(K_b)^T V_b,      z   = sum phi(K_b)            (eq. 10-11 over a segment)
 // KIND 1: R = sum phi(Q_b)^T dO_b/den, rho = sum delta_b phi(Q_b)    (eq. 14-15 over a segment)
+// KIND 2: as KIND 1, but 1/den and delta = -(dO.O)/den are formed here from O and den and also
+//         written out for the passes that follow (rden_out, delta_out): the backward then needs
+//         no separate sweep over dO and O.
 // Written as [D][M] row-major followed by the D-vector.
 struct SegArgs {
     const void *Y;        // K or Q  [BH, N, D]
     const void *Z;        // V or dO [BH, N, M]
     const float *rden;    // KIND 1
     const float *delta;   // KIND 1
+    const void *O;        // KIND 2: forward output [BH, N, M]
+    const float *den;     // KIND 2: forward denominators [BH, N]
+    float *rden_out;      // KIND 2
+    float *delta_out;     // KIND 2
     float *state;         // [BH, nseg, state_stride]
     int N, nseg, chunks_per_seg;
     int skip_seg;         // segment whose total nobody reads (-1: none)
@@ -570,8 +577,10 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     const size_t rowbase = (size_t)bh * a.N;
     const T *Ys = static_cast<const T *>(a.Y) + rowbase * D;
     const T *Zs = static_cast<const T *>(a.Z) + rowbase * M;
-    const float *rden = a.rden + rowbase;
+    const float *rden = (KIND == 2 ? a.den : a.rden) + rowbase;   // KIND 2 stages den itself
     const float *delta = a.delta + rowbase;
+    const T *Os = static_cast<const T *>(a.O) + rowbase * M;
+    __shared__ float lds_delta[kChunk];
 
     f32x4 U[XT][ZT];
     float ec[XT];
@@ -582,7 +591,7 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    f32x4 sy[XT], sz[ZT];
+    f32x4 sy[XT], sz[ZT], so[ZT];
     float scy[XT], scz[ZT];
     float n_w4[4] = {1.f, 1.f, 1.f, 1.f};
 #pragma unroll
@@ -598,6 +607,10 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
             stage_rows<M, kFull>(rden + t0, nvalid, lane, scz);
             rows4<kFull>(delta + t0, nvalid, g, n_w4);
         }
+        if constexpr (KIND == 2) {
+            stage_load<M, kFull>(Os + (size_t)t0 * M, nvalid, lane, so);
+            stage_rows<M, kFull>(rden + t0, nvalid, lane, scz);       // den of the staged rows
+        }
     };
     auto fetch = [&](const int ch) {
         const int t0 = ch * kChunk;
@@ -610,14 +623,37 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     for (int ch = ch_begin; ch < ch_end; ++ch) {
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
+        if constexpr (KIND == 2) {
+            // quotient rule per token: 1/den, and delta = -(dO . O)/den; the M/4 lanes that
+            // stage one row add up their partial dot products
+            constexpr int LPR = M / 4;
+#pragma unroll
+            for (int i = 0; i < ZT; ++i) {
+                float p = (sz[i][0] * so[i][0] + sz[i][1] * so[i][1]) +
+                          (sz[i][2] * so[i][2] + sz[i][3] * so[i][3]);
+#pragma unroll
+                for (int off = 1; off < LPR; off <<= 1) p += __shfl_xor(p, off);
+                const int row = stage_row<M>(lane, i);
+                const float r = 1.0f / scz[i];
+                const float dl = row < nvalid ? -p * r : 0.f;
+                scz[i] = r;
+                if (lane % LPR == 0) {
+                    lds_delta[row] = dl;
+                    if (row < nvalid) {
+                        a.rden_out[rowbase + ch * kChunk + row] = r;
+                        a.delta_out[rowbase + ch * kChunk + row] = dl;
+                    }
+                }
+            }
+        }
         if (nvalid == kChunk) {
             park_tile<D, kMapPhi, true>(lds_y, sy, scy, nvalid, lane);
-            park_tile<M, KIND == 1 ? kMapScale : kMapId, true>(lds_z, sz, scz, nvalid, lane);
+            park_tile<M, KIND == 0 ? kMapId : kMapScale, true>(lds_z, sz, scz, nvalid, lane);
         } else {
             park_tile<D, kMapPhi, false>(lds_y, sy, scy, nvalid, lane);
-            park_tile<M, KIND == 1 ? kMapScale : kMapId, false>(lds_z, sz, scz, nvalid, lane);
+            park_tile<M, KIND == 0 ? kMapId : kMapScale, false>(lds_z, sz, scz, nvalid, lane);
         }
-        const float w4[4] = {n_w4[0], n_w4[1], n_w4[2], n_w4[3]};
+        float w4[4] = {n_w4[0], n_w4[1], n_w4[2], n_w4[3]};
         if (ch + 1 < ch_end) fetch(ch + 1);
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
         __builtin_amdgcn_sched_barrier(0);
@@ -626,6 +662,10 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         float yf[XT][4], zf[ZT][4];
         lds_feature_lane<D>(lds_y, c, g, yf);
         lds_feature_lane<M>(lds_z, c, g, zf);
+        if constexpr (KIND == 2) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) w4[s] = lds_delta[4 * g + s];
+        }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
