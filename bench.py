@@ -31,6 +31,19 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3     # MI355X dense fp32 matrix, published
 
 
+# HBM bytes per launch at the metric's workload, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# and scaled by a copy kernel of known size (factors 2.000 / 1.000); the runs and their commands are
+# in profiles/hbm_traffic_and_pipe_counters_N65536_B2_H8_D64_f32.md.  Read + written, in bytes.
+MEASURED_TRAFFIC_BYTES = {
+    "causal_pass_fwd": (839.5 + 273.6) * 1e6,
+    "causal_pass_dq": (1122.0 + 268.4) * 1e6,
+    "reverse_pass_dv_dk": (1119.8 + 536.9) * 1e6,
+    "segment_state_kv": (532.8 + 33.8) * 1e6,
+    "segment_state_qg": (810.7 + 45.6) * 1e6,
+    "scan_states": (54.8 + 34.1) * 1e6,
+}
+
+
 def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
     """Algorithmic HBM bytes per token-head of one launch of `name`: the tensors it must
     read and write once (e = bytes per element of the N-sized tensors; den, 1/den and
@@ -40,7 +53,7 @@ def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
         "causal_pass_dq": e * (3 * D + 2 * M) + 8,      # dO V K Q, 1/den, delta -> dQ
         "reverse_pass_dv_dk": e * (3 * D + 3 * M) + 8,  # Q K V dO, 1/den, delta -> dV, dK
         "segment_state_kv": e * (D + M),                # K V
-        "segment_state_qg": e * (D + M) + 8,            # Q dO, 1/den, delta
+        "segment_state_qg": e * (D + 2 * M) + 12,       # Q dO O den -> 1/den, delta
         "bwd_prep": e * 2 * M + 12,                     # dO O den -> 1/den, delta
         "global_readout": e * (D + M),                  # Q -> O
     }.get(name, 0.0)
@@ -172,7 +185,7 @@ def run_headline(args):
                    "eps": w.eps, "step": "la_causal_fwd + la_causal_bwd", "seed": w.seed},
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(ach_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None, "avg_kernel_ms": round(dom_ms, 4),
+                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant), "avg_kernel_ms": round(dom_ms, 4),
                      "mfma_f32_tflops_algorithmic": round(ach_tf, 2),
                      "mfma_f32_frac": round(ach_tf / MFMA_F32_PEAK_TFLOPS, 4)},
         "path_frac_of_hbm_roofline": round(value / hbm_ceiling, 4),
@@ -258,6 +271,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
     ap.add_argument("--table", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a 1 GiB device-to-device copy first (a kernel of known traffic, "
+                         "to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters in the same run)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -267,6 +283,13 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(3)
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     out, fb = run_headline(args)
     del fb
     if args.table:
