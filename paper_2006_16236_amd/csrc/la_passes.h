@@ -264,11 +264,20 @@ struct ReverseStager {
 // One pass over the chunks [ch_begin, ch_end) of sequence bh by the calling wave.  `stg`
 // fetches the next chunk and parks the current one; lds_* are the parked tiles this pass
 // reads its operands from (they may be shared with the other wave of the workgroup).
-template <int PASS, int D, int M, typename T, typename Stager>
+//
+// kStateMode: kOwnState    the wave carries U in its accumulators (the usual case);
+//             kPublishState as kOwnState, and before each chunk it also writes U to `lds_u` for the
+//                          other wave of the workgroup (layout [column][row], stride rows + 4);
+//             kBorrowState  the wave keeps no U of its own: each chunk it reads the partner's U from
+//                          `lds_u` as its own TRANSPOSE (this wave's U is the partner's U^T), and
+//                          skips the update.  Only its ones-column vector is its own.
+enum StateMode { kOwnState = 0, kPublishState = 1, kBorrowState = 2 };
+
+template <int PASS, int D, int M, typename T, int kStateMode = kOwnState, typename Stager>
 __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const float *lds_x,
                                          const float *lds_y, const float *lds_z,
                                          const float *lds_r, void *out_tensor, const int bh,
-                                         const int seg, const int lane) {
+                                         const int seg, const int lane, float *lds_u = nullptr) {
     using Tr = PassTraits<PASS, D, M>;
     constexpr bool kXisD = Tr::kXisD;
     constexpr int DX = Tr::DX, DZ = Tr::DZ;
@@ -306,6 +315,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) {
+                if constexpr (kStateMode == kBorrowState) continue;
                 if constexpr (kXisD) {        // U[d][m], d = 16xt + 4g + r, m = 16zt + c
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
@@ -346,12 +356,33 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         const float dl1 = stg.dl1;
         const float dl4[4] = {stg.dl4[0], stg.dl4[1], stg.dl4[2], stg.dl4[3]};
         if (it + kDepth < count) stg.template fetch<kSlot>(ch + dir * kDepth);
+        if constexpr (kStateMode == kPublishState) {
+            // U as it stands before this chunk (the exclusive state), element (row 16xt + 4g + r,
+            // column 16zt + c) at lds_u[column][row]: four rows per 16-byte write
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+                    lds_store4(lds_u + (16 * zt + c) * (DX + 4) + 16 * xt + 4 * g, U[xt][zt]);
+        }
         // Let the loads leave the wave before the matrix instructions start: measured on
         // MI355X, a burst of MFMAs issued right behind a batch of global loads delays those
         // loads by the length of the burst (the chunk then arrives one iteration late).
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);
         __builtin_amdgcn_sched_barrier(0);   // keep the prefetch ahead of the arithmetic
         __syncthreads();
+
+        if constexpr (kStateMode == kBorrowState) {
+            // this wave's U[row 16xt + 4g + r][column 16zt + c] is the partner's U[16zt + c][16xt + 4g + r],
+            // parked at lds_u[partner column = 16xt + 4g + r][partner row = 16zt + c]
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        U[xt][zt][r] = lds_u[(16 * xt + 4 * g + r) * (DZ + 4) + 16 * zt + c];
+        }
 
         // ---- state term: out = X U  (lane (c, g), register r: token 4g + r, column 16zt + c)
         float xa[XT][4];                 // X, token-lane
@@ -464,14 +495,17 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         // ---- carry: U += Y^T Z, and the ones-column vector --------------------------------
         if constexpr (kHasYZ) {
             float yf[XT][4];             // Y, feature-lane
-            lds_feature_lane<DX>(lds_y, c, g, yf);
+            if constexpr (kStateMode != kBorrowState || PASS == kFwd)
+                lds_feature_lane<DX>(lds_y, c, g, yf);
+            if constexpr (kStateMode != kBorrowState) {
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+                for (int s = 0; s < 4; ++s)
 #pragma unroll
-                for (int xt = 0; xt < XT; ++xt)
+                    for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
-                    for (int zt = 0; zt < ZT; ++zt)
-                        U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+                        for (int zt = 0; zt < ZT; ++zt)
+                            U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+            }
             if constexpr (PASS == kFwd) {
                 // z += column sums of the chunk's phi(K).  Each lane adds up its four tokens;
                 // an MFMA against ones adds the four groups and delivers the sums of features
@@ -520,8 +554,9 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
 }
 
 // Both reverse passes of the backward (eq. 14 and eq. 15) on one fetch of Q, K, V, dO:
-// wave 0 produces dV (a.out), wave 1 produces dK (a.out2).  Each wave owns its copy of the
-// reverse state in the layout its read-out needs (R for dV, R^T for dK).
+// wave 0 produces dV (a.out), wave 1 produces dK (a.out2).  Wave 0 carries the reverse state R
+// (D x M) and republishes it in LDS before every chunk; wave 1, whose read-out needs R^T, reads
+// it from there transposed instead of keeping (and updating) a second copy.
 template <int D, int M, typename T>
 __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void reverse_pass_kernel(
     const PassArgs a) {
@@ -530,15 +565,18 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     __shared__ float lds_fk[tile_floats(D)];    // phi(K)
     __shared__ float lds_dk[tile_floats(D)];    // phi'(K)
     __shared__ float lds_v[tile_floats(M)];     // V
+    __shared__ float lds_R[M * (D + 4)];        // R before the current chunk, as [m][d]
     const int lane = threadIdx.x & (kWave - 1);
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
         ReverseStager<0, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fq, nullptr, lds_g);
-        run_pass<kDv, D, M, T>(a, stg, lds_fk, lds_fq, lds_g, nullptr, a.out, bh, seg, lane);
+        run_pass<kDv, D, M, T, kPublishState>(a, stg, lds_fk, lds_fq, lds_g, nullptr, a.out, bh, seg,
+                                              lane, lds_R);
     } else {
         ReverseStager<1, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fk, lds_dk, lds_v);
-        run_pass<kDk, D, M, T>(a, stg, lds_v, lds_g, lds_fq, lds_dk, a.out2, bh, seg, lane);
+        run_pass<kDk, D, M, T, kBorrowState>(a, stg, lds_v, lds_g, lds_fq, lds_dk, a.out2, bh, seg,
+                                             lane, lds_R);
     }
 }
 
