@@ -258,6 +258,18 @@ def run_table(args):
                      "tokens_per_s": B / sec, "achieved_GBs": bytes_step / sec / 1e9,
                      "frac_hbm": bytes_step / sec / 1e9 / HBM_PEAK_GBS})
         print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    # the same 3072 steps in one launch (tokens known in advance)
+    d = wl.CFG5
+    q = torch.randn(d.T, d.B, d.H, d.D, device="cuda:0")
+    k = torch.randn(d.T, d.B, d.H, d.D, device="cuda:0")
+    v = torch.randn(d.T, d.B, d.H, d.M, device="cuda:0")
+    S = torch.zeros(d.B, d.H, d.D, d.M, device="cuda:0")
+    z = torch.zeros(d.B, d.H, d.D, device="cuda:0")
+    out = torch.empty_like(v)
+    sec = time_steps(lambda: la.la_recurrent_steps(q, k, v, S, z, out, d.eps), 5, 2, torch)
+    rows.append({"workload": f"decode_B{d.B}_H8_D64_{d.T}_steps_one_launch", "steps": d.T,
+                 "us_per_step": sec * 1e6 / d.T, "tokens_per_s": d.B * d.T / sec})
+    print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
     os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
     with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
         json.dump(rows, f, indent=1)

@@ -138,6 +138,18 @@ int la_recurrent_step(const void *q, const void *k, const void *v, float *S, flo
                       int B, int H, int D, int M, float eps, la_dtype t, void *stream);
 
 /*
+ * T consecutive decode steps in one launch (eq. 16-20 applied T times), for callers that
+ * already hold every token's q, k, v (scoring a given sequence, teacher forcing): the state
+ * stays on chip between steps, which removes the per-step launch that dominates the
+ * single-step loop (the paper's "outer loop over the sequence", supplementary C).
+ * q, k [T,B,H,D] in; v [T,B,H,M] in; out [T,B,H,M] out; S, z as in la_recurrent_step
+ * (read at the start, written back at the end).  T >= 1.  Outputs and final state are
+ * bit-identical to T calls of la_recurrent_step.
+ */
+int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, float *z, void *out,
+                       int T, int B, int H, int D, int M, float eps, la_dtype t, void *stream);
+
+/*
  * Optional profiling hook (measurement aid, not part of the method).  Between
  * la_profile_begin(mask) and la_profile_end() every launch of a kernel whose
  * bit (1u << la_kernel_id) is set in `mask` is bracketed by two HIP events on

@@ -20,7 +20,8 @@ LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN = -4, -5, -6
 
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
            "la_global_fwd_workspace", "la_causal_fwd", "la_causal_bwd", "la_global_fwd",
-           "la_recurrent_step", "la_kernel_name", "la_profile_begin", "la_profile_end")
+           "la_recurrent_step", "la_recurrent_steps", "la_kernel_name", "la_profile_begin",
+           "la_profile_end")
 LA_K_COUNT = 9
 
 
@@ -52,6 +53,8 @@ def _load() -> ctypes.CDLL:
     lib.la_global_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_recurrent_step.restype = i
     lib.la_recurrent_step.argtypes = [vp] * 6 + [i, i, i, i, f, i, vp]
+    lib.la_recurrent_steps.restype = i
+    lib.la_recurrent_steps.argtypes = [vp] * 6 + [i, i, i, i, i, f, i, vp]
     lib.la_kernel_name.restype = ctypes.c_char_p
     lib.la_kernel_name.argtypes = [i]
     lib.la_profile_begin.restype = i
@@ -163,6 +166,15 @@ def la_recurrent_step(q, k, v, S, z, out, eps=1e-6, stream=None):
     _check(_lib.la_recurrent_step(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(z), _ptr(out), B, H, D,
                                   M, float(eps), _dtype_code(q), _stream(stream)),
            "la_recurrent_step")
+
+
+def la_recurrent_steps(q, k, v, S, z, out, eps=1e-6, stream=None):
+    """T decode steps in one launch: q, k [T,B,H,D], v, out [T,B,H,M]; S, z updated in place."""
+    T, B, H, D = q.shape
+    M = v.shape[-1]
+    _check(_lib.la_recurrent_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(z), _ptr(out), T, B, H,
+                                   D, M, float(eps), _dtype_code(q), _stream(stream)),
+           "la_recurrent_steps")
 
 
 def la_kernel_name(kernel_id: int) -> str:

@@ -319,6 +319,22 @@ int la_recurrent_step(const void *q, const void *k, const void *v, float *S, flo
     return LA_OK;
 }
 
+int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, float *z, void *out,
+                       int T, int B, int H, int D, int M, float eps, la_dtype t, void *stream) {
+    if (q == nullptr || k == nullptr || v == nullptr || S == nullptr || z == nullptr ||
+        out == nullptr)
+        return LA_ERR_NULL;
+    const int st = check_dims(B, H, T, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(S) || misaligned(z) ||
+        misaligned(out))
+        return LA_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    ProfScope ps(LA_K_STEP, s);
+    LA_TRY(la::launch_recurrent_steps(q, k, v, S, z, out, T, (int)((long)B * H), D, M, eps, (int)t, s));
+    return LA_OK;
+}
+
 const char *la_kernel_name(int kernel_id) {
     static const char *const names[LA_K_COUNT] = {"segment_state_kv", "segment_state_qg", "scan_states",
                                                   "causal_pass_fwd", "global_readout", "bwd_prep",

@@ -31,6 +31,11 @@ hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, fl
                                  void *out, int BH, int D, int M, float eps, int dtype,
                                  hipStream_t s);
 
+// T steps in one launch; q, k [T, BH, D], v, out [T, BH, M]
+hipError_t launch_recurrent_steps(const void *q, const void *k, const void *v, float *S, float *z,
+                                  void *out, int steps, int BH, int D, int M, float eps, int dtype,
+                                  hipStream_t s);
+
 #define LA_DISPATCH_DM(D, M, ...)                                              \
     do {                                                                       \
         if ((D) == 32 && (M) == 32) { constexpr int kD = 32, kM = 32; __VA_ARGS__; }  \

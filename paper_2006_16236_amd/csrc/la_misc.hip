@@ -151,6 +151,111 @@ __global__ __launch_bounds__(256) void recurrent_step_kernel(const T *q, const T
     }
 }
 
+// T consecutive decode steps in one launch, for callers that already hold the q, k, v of
+// all T tokens (scoring, teacher forcing): the state stays in registers between steps, the
+// next token's q, k, v are fetched while the current one is processed.  The arithmetic of a
+// step, lane for lane, is that of recurrent_step_kernel: T steps here and T launches of
+// the single step give bit-identical outputs and states.
+template <int D, int M, typename T>
+__global__ __launch_bounds__(256) void recurrent_steps_kernel(const T *q, const T *k, const T *v,
+                                                              float *S, float *z, T *out,
+                                                              float eps, int steps, size_t BH) {
+    constexpr int LPR = M / 4, RPW = kWave / LPR, RPI = 4 * RPW, NIT = D / RPI;
+    __shared__ float red[2][4][M];
+    __shared__ float dred[2][4];
+
+    const int bh = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int col4 = (lane % LPR) * 4, rsub = lane / LPR;
+    float *Sh = S + (size_t)bh * D * M, *zh = z + (size_t)bh * D;
+
+    f32x4 s4[NIT];
+    float zr[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int d = it * RPI + wave * RPW + rsub;
+        s4[it] = *reinterpret_cast<const f32x4 *>(Sh + (size_t)d * M + col4);
+        zr[it] = zh[d];
+    }
+    auto fetch = [&](int t, float (&kq)[2][NIT], f32x4 &v4) {
+        const T *qh = q + ((size_t)t * BH + bh) * D, *kh = k + ((size_t)t * BH + bh) * D;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int d = it * RPI + wave * RPW + rsub;
+            kq[0][it] = to_f32(kh[d]);
+            kq[1][it] = to_f32(qh[d]);
+        }
+        v4 = load4(v + ((size_t)t * BH + bh) * M + col4);
+    };
+    float kq_next[2][NIT];
+    f32x4 v_next;
+    fetch(0, kq_next, v_next);
+    for (int t = 0; t < steps; ++t) {
+        float kq[2][NIT];
+        const f32x4 v4 = v_next;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) { kq[0][it] = kq_next[0][it]; kq[1][it] = kq_next[1][it]; }
+        if (t + 1 < steps) fetch(t + 1, kq_next, v_next);
+
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        float dpart = 0.f;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const float kd = phi(kq[0][it]);
+            const float qd = phi(kq[1][it]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                s4[it][e] = fmaf(kd, v4[e], s4[it][e]);
+                acc[e] = fmaf(qd, s4[it][e], acc[e]);
+            }
+            if (col4 == 0) {
+                zr[it] += kd;
+                dpart = fmaf(qd, zr[it], dpart);
+            }
+        }
+#pragma unroll
+        for (int off = LPR; off < kWave; off <<= 1) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[e] += __shfl_xor(acc[e], off);
+        }
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) dpart += __shfl_xor(dpart, off);
+        const int buf = t & 1;            // two LDS buffers: one barrier per step suffices
+        if (rsub == 0) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) red[buf][wave][col4 + e] = acc[e];
+        }
+        if (lane == 0) dred[buf][wave] = dpart;
+        __syncthreads();
+        if (tid < M) {
+            const float num = (red[buf][0][tid] + red[buf][1][tid]) + (red[buf][2][tid] + red[buf][3][tid]);
+            const float den = ((dred[buf][0] + dred[buf][1]) + (dred[buf][2] + dred[buf][3])) + eps;
+            store_elem(out + ((size_t)t * BH + bh) * M + tid, num / den);
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int d = it * RPI + wave * RPW + rsub;
+        *reinterpret_cast<f32x4 *>(Sh + (size_t)d * M + col4) = s4[it];
+        if (col4 == 0) zh[d] = zr[it];
+    }
+}
+
+hipError_t launch_recurrent_steps(const void *q, const void *k, const void *v, float *S, float *z,
+                                  void *out, int steps, int BH, int D, int M, float eps, int dtype,
+                                  hipStream_t s) {
+    LA_DISPATCH_DM(D, M, {
+        if (dtype == 0)
+            recurrent_steps_kernel<kD, kM, float><<<BH, 256, 0, s>>>(
+                (const float *)q, (const float *)k, (const float *)v, S, z, (float *)out, eps, steps,
+                (size_t)BH);
+        else
+            recurrent_steps_kernel<kD, kM, bf16_t><<<BH, 256, 0, s>>>(
+                (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, S, z, (bf16_t *)out, eps,
+                steps, (size_t)BH);
+    });
+    return hipGetLastError();
+}
+
 hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z,
                                  void *out, int BH, int D, int M, float eps, int dtype,
                                  hipStream_t s) {

@@ -95,6 +95,10 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert step(p, p, p, null, p, p, 1, 1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_NULL
     assert step(p, p, p, p, p, p, 1, 1, 16, 64, f(1e-6), 0, null) == b.LA_ERR_UNSUPPORTED
     assert step(p, p, p, p, p, p, 1, -1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_SHAPE
+    steps = lib.la_recurrent_steps
+    assert steps(p, p, p, p, p, null, 4, 1, 1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_NULL
+    assert steps(p, p, p, p, p, p, 0, 1, 1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_SHAPE
+    assert steps(p, p, p, p, p, p, 4, 1, 1, 64, 48, f(1e-6), 0, null) == b.LA_ERR_UNSUPPORTED
 
 
 def test_schedule_knobs_change_the_workspace(lib, monkeypatch):

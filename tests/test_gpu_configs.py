@@ -132,6 +132,11 @@ def test_config5_decode_3072_steps(la, oracle):
         la.la_recurrent_step(dq[t], dk[t], dv[t], S2, z2, out2[t], d.eps)
     torch.cuda.synchronize()
     assert torch.equal(out, out2) and torch.equal(S, S2) and torch.equal(z, z2)
+    # all 3072 steps in one launch: bit-identical to the step-by-step loop
+    S3 = torch.zeros_like(S); z3 = torch.zeros_like(z); out3 = torch.empty_like(out)
+    la.la_recurrent_steps(dq, dk, dv, S3, z3, out3, d.eps)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out3) and torch.equal(S, S3) and torch.equal(z, z3)
     # the same tokens as one stacked sequence through the parallel forward
     Qs, Ks, Vs = (x.permute(1, 2, 0, 3).contiguous() for x in (dq, dk, dv))
     O = torch.empty_like(Vs)

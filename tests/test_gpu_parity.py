@@ -149,6 +149,28 @@ def test_recurrent_steps_against_oracle_and_causal_fwd(la, oracle, D, M):
     assert rel_err(O, np.moveaxis(ref, 0, 2)) <= 1e-4
 
 
+@pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32), (64, 64)])
+@pytest.mark.parametrize("bf16", [False, True])
+def test_multi_step_decode_equals_single_steps_bit_for_bit(la, oracle, D, M, bf16):
+    B, H, T = 2, 3, 37
+    w = wl.DecodeWorkload("t", B, H, D, M, T, 650 + D + 2 * M)
+    q, k, v = maybe_bf16(wl.decode_streams(w), bf16)
+    dq, dk, dv = (to_dev(x, bf16) for x in (q, k, v))
+    S1 = torch.zeros(B, H, D, M, device=DEV); z1 = torch.zeros(B, H, D, device=DEV)
+    out1 = torch.empty_like(dv)
+    for t in range(T):
+        la.la_recurrent_step(dq[t], dk[t], dv[t], S1, z1, out1[t], 1e-6)
+    S2 = torch.zeros_like(S1); z2 = torch.zeros_like(z1); out2 = torch.full_like(dv, float("nan"))
+    la.la_recurrent_steps(dq[:20], dk[:20], dv[:20], S2, z2, out2[:20], 1e-6)     # two launches:
+    la.la_recurrent_steps(dq[20:], dk[20:], dv[20:], S2, z2, out2[20:], 1e-6)     # the state carries over
+    torch.cuda.synchronize()
+    assert torch.equal(out1, out2) and torch.equal(S1, S2) and torch.equal(z1, z2)
+    So = np.zeros((B, H, D, M)); zo = np.zeros((B, H, D))
+    ref = np.stack([oracle.recurrent_step(q[t], k[t], v[t], So, zo, 1e-6) for t in range(T)])
+    assert rel_err(to_host(out2), ref) <= (2e-2 if bf16 else 1e-4)
+    assert rel_err(S2.cpu().numpy(), So) <= 1e-4
+
+
 @pytest.mark.parametrize("sched", ["default", "many_segments"])
 def test_bf16_tensors_fp32_state(la, oracle, sched):
     B, H, N, D, M = 2, 2, 300, 64, 64
