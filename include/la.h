@@ -94,6 +94,18 @@ int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *d
                   void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The same forward with the recurrent state handed in and out (eq. 16-19 seen from the
+ * parallel side): S0 [B,H,D,M], z0 [B,H,D] fp32 are the state before token 0 (both NULL: zero,
+ * eq. 16-17), S1, z1 receive the state after token N-1 (both NULL: not wanted).  A prompt can
+ * be processed in parallel and continued token by token with la_recurrent_step, or a long
+ * sequence processed in pieces.  S0/z0 must not alias S1/z1.  Workspace as la_causal_fwd.
+ */
+int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float *S0,
+                        const float *z0, void *O, float *den, float *S1, float *z1,
+                        int B, int H, int N, int D, int M, float eps, la_dtype t,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Causal linear attention, backward (eq. 13-15 / Algorithm 1 applied to the
  * numerator and to the denominator together, then the chain rule through phi):
  * given dO = dL/dO it writes dQ, dK (with respect to the RAW Q, K, i.e.

@@ -19,7 +19,8 @@ LA_OK, LA_ERR_NULL, LA_ERR_SHAPE, LA_ERR_UNSUPPORTED = 0, -1, -2, -3
 LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN = -4, -5, -6
 
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
-           "la_global_fwd_workspace", "la_causal_fwd", "la_causal_bwd", "la_global_fwd",
+           "la_global_fwd_workspace", "la_causal_fwd", "la_causal_fwd_state", "la_causal_bwd",
+           "la_global_fwd",
            "la_recurrent_step", "la_recurrent_steps", "la_kernel_name", "la_profile_begin",
            "la_profile_end")
 LA_K_COUNT = 9
@@ -47,6 +48,8 @@ def _load() -> ctypes.CDLL:
         fn.argtypes = [i, i, i, i, i, i]
     lib.la_causal_fwd.restype = i
     lib.la_causal_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_causal_fwd_state.restype = i
+    lib.la_causal_fwd_state.argtypes = [vp] * 9 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_causal_bwd.restype = i
     lib.la_causal_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_global_fwd.restype = i
@@ -130,6 +133,20 @@ def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None):
     ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
     _check(_lib.la_causal_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
                               float(eps), t, wp, wb, _stream(stream)), "la_causal_fwd")
+    return ws
+
+
+def la_causal_fwd_state(Q, K, V, O, den=None, S0=None, z0=None, S1=None, z1=None, eps=1e-6, ws=None,
+                        stream=None):
+    """Causal forward that starts from the state (S0, z0) (None: zero) and returns the state
+    after the last token in (S1, z1) (None: not wanted); all four fp32 [B,H,D,M] / [B,H,D]."""
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q)
+    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_causal_fwd_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O),
+                                    _ptr(den), _ptr(S1), _ptr(z1), B, H, N, D, M, float(eps), t,
+                                    wp, wb, _stream(stream)), "la_causal_fwd_state")
     return ws
 
 

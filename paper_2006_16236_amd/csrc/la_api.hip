@@ -128,18 +128,20 @@ struct ProfScope {
 // forward on already-validated arguments; `states` holds states_bytes() when p.nseg > 1
 int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den, long BH, int N,
                    int D, int M, float eps, la_dtype t, const Plan &p, float *states,
-                   hipStream_t s) {
+                   hipStream_t s, const float *S0 = nullptr, const float *z0 = nullptr,
+                   float *S1 = nullptr, float *z1 = nullptr) {
     const int nblocks = (int)(BH * p.nseg);
     if (p.nseg > 1) {
         la::SegArgs sa{};
         sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = states;
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = p.nseg - 1;
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
     la::PassArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.G = nullptr; a.rden = nullptr; a.delta = nullptr;
     a.out = O; a.den = den; a.state = p.nseg > 1 ? states : nullptr;
+    a.init_S = S0; a.init_z = z0; a.final_S = S1; a.final_z = z1;
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
     { ProfScope ps(LA_K_FWD, s); LA_TRY(la::launch_pass_fwd(false, D, M, (int)t, a, nblocks, s)); }
     return LA_OK;
@@ -202,6 +204,25 @@ int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *d
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return LA_ERR_WORKSPACE;
     return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
                           static_cast<hipStream_t>(stream));
+}
+
+int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float *S0,
+                        const float *z0, void *O, float *den, float *S1, float *z1,
+                        int B, int H, int N, int D, int M, float eps, la_dtype t,
+                        void *ws, size_t ws_bytes, void *stream) {
+    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
+    if ((S0 == nullptr) != (z0 == nullptr) || (S1 == nullptr) != (z1 == nullptr)) return LA_ERR_NULL;
+    const int st = check_dims(B, H, N, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws) ||
+        misaligned(S0) || misaligned(z0) || misaligned(S1) || misaligned(z1))
+        return LA_ERR_ALIGN;
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+    if (need > 0 && (ws == nullptr || ws_bytes < need)) return LA_ERR_WORKSPACE;
+    return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
+                          static_cast<hipStream_t>(stream), S0, z0, S1, z1);
 }
 
 int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,

@@ -21,7 +21,9 @@ hipError_t launch_segment_state(int kind, int D, int M, int dtype, const SegArgs
 enum ScanMode { kScanForward = 0, kScanReverse = 1, kScanTotal = 2 };
 // In-place scan over the nseg slots of every sequence: exclusive prefix, exclusive
 // suffix, or the grand total written to slot 0.
-hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s);
+// init_S [BH, DM] / init_z [BH, stride - DM]: optional starting value of the forward prefix.
+hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s,
+                       const float *init_S = nullptr, const float *init_z = nullptr, int DM = 0);
 
 // rden_i = 1/den_i, delta_i = -(dO_i . O_i)/den_i for all rows.
 hipError_t launch_bwd_prep(const void *dO, const void *O, const float *den, float *rden,

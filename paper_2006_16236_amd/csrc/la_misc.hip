@@ -11,7 +11,8 @@ namespace la {
 // walks its run again (now from cache) and writes the exclusive prefix.  Slots are visited in
 // scan order: ascending for the prefix, descending for the suffix.  Fixed order: deterministic.
 __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg, int stride,
-                                                          int mode) {
+                                                          int mode, const float *init_S,
+                                                          const float *init_z, int DM) {
     __shared__ float part_total[8][32];
     const int el = threadIdx.x & 31, part = threadIdx.x >> 5;
     const int e = blockIdx.x * 32 + el;
@@ -27,7 +28,11 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg
     for (int k = k0; k < min(k1, klast); ++k) total += p[(size_t)(reverse ? nseg - 1 - k : k) * stride];
     part_total[part][el] = total;
     __syncthreads();
+    // the scan starts from the caller's initial state when there is one (forward prefix only)
     float acc = 0.f;
+    if (init_S != nullptr && live)
+        acc = e < DM ? init_S[(size_t)blockIdx.y * DM + e]
+                     : init_z[(size_t)blockIdx.y * (stride - DM) + (e - DM)];
     for (int q = 0; q < part; ++q) acc += part_total[q][el];
     if (mode == kScanTotal) {
         if (part == 7 && live) p[0] = acc + total;
@@ -41,9 +46,10 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg
     }
 }
 
-hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s) {
+hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s,
+                       const float *init_S, const float *init_z, int DM) {
     dim3 grid((stride + 31) / 32, BH);
-    scan_states_kernel<<<grid, 256, 0, s>>>(state, nseg, stride, mode);
+    scan_states_kernel<<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
     return hipGetLastError();
 }
 

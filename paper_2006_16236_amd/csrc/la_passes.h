@@ -57,6 +57,8 @@ struct PassArgs {
     void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
     float *den;                  // [BH, N] or null             (kFwd)
     const float *state;          // [BH, nseg, state_stride] exclusive states; null = zero state
+    const float *init_S, *init_z;  // kFwd, nseg == 1: state before token 0, [BH, D, M] / [BH, D]; may be null
+    float *final_S, *final_z;      // kFwd: state after the last token, same shapes; may be null
     int N, nseg, chunks_per_seg;
     float eps;
 };
@@ -334,6 +336,22 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         }
     }
 
+    if constexpr (PASS == kFwd) {
+        if (a.state == nullptr && a.init_S != nullptr) {      // caller-supplied initial state
+            const float *s0 = a.init_S + (size_t)bh * D * M;
+            const float *z0 = a.init_z + (size_t)bh * D;
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt) {
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        U[xt][zt][r] = s0[(16 * xt + 4 * g + r) * M + 16 * zt + c];
+                zg[xt] = load4(z0 + 16 * xt + 4 * g);
+            }
+        }
+    }
+
     // Chunks are visited in steps of `dir`; the stager keeps kDepth chunks in flight, each in
     // its own set of staging registers (the set is a compile-time index, hence the tag).
     constexpr int kDepth = Stager::kDepth;
@@ -535,6 +553,22 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         step(std::integral_constant<int, 0>{}, it);
         if constexpr (kDepth == 2) {
             if (it + 1 < count) step(std::integral_constant<int, 1>{}, it + 1);
+        }
+    }
+
+    if constexpr (PASS == kFwd) {       // the wave of the last segment ends with the final state
+        if (a.final_S != nullptr && seg == a.nseg - 1) {
+            float *s1 = a.final_S + (size_t)bh * D * M;
+            float *z1 = a.final_z + (size_t)bh * D;
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt) {
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        s1[(16 * xt + 4 * g + r) * M + 16 * zt + c] = U[xt][zt][r];
+                if (c == 0) *reinterpret_cast<f32x4 *>(z1 + 16 * xt + 4 * g) = zg[xt];
+            }
         }
     }
 }

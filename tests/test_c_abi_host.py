@@ -80,6 +80,13 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, p, 1024, null) == b.LA_ERR_WORKSPACE
 
+    fws = lib.la_causal_fwd_state
+    assert fws(p, p, p, p, null, p, null, null, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_NULL
+    assert fws(p, p, p, null, null, p, null, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_NULL
+    assert fws(p, p, p, null, null, null, null, null, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_NULL
+    assert fws(p, p, p, odd, p, p, null, null, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_ALIGN
+    assert fws(p, p, p, null, null, p, null, null, null, 1, 1, 4096, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+
     bwd = lib.la_causal_bwd
     assert bwd(p, p, p, p, p, null, null, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_NULL
     assert bwd(p, p, p, p, p, null, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE

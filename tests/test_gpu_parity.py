@@ -187,6 +187,42 @@ def test_bf16_tensors_fp32_state(la, oracle, sched):
         assert e <= tol_for(N, True), name
 
 
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+def test_forward_with_state_in_and_out(la, oracle, sched):
+    """A sequence processed in two pieces through la_causal_fwd_state, then continued token by
+    token with la_recurrent_step, reproduces the one-shot causal forward (eq. 12 == eq. 20)."""
+    B, H, D, M = 2, 2, 64, 32
+    N1, N2, N3 = 150, 333, 5
+    N = N1 + N2 + N3
+    Q, K, V = wl.random_case(900, B, H, N, D, M)[:3]
+    ref = oracle.causal_fwd_prefix(Q, K, V, 1e-6)
+    dq, dk, dv = (to_dev(x) for x in (Q, K, V))
+    O = torch.full_like(dv, float("nan"))
+    Sa = torch.empty(B, H, D, M, device=DEV); za = torch.empty(B, H, D, device=DEV)
+    Sb = torch.empty_like(Sa); zb = torch.empty_like(za)
+    piece = lambda t, a, b: t[:, :, a:b].contiguous()
+    with schedule(**SCHEDULES[sched]):
+        O1 = torch.empty(B, H, N1, M, device=DEV)
+        la.la_causal_fwd_state(piece(dq, 0, N1), piece(dk, 0, N1), piece(dv, 0, N1), O1, None,
+                               None, None, Sa, za, 1e-6)
+        O2 = torch.empty(B, H, N2, M, device=DEV)
+        la.la_causal_fwd_state(piece(dq, N1, N1 + N2), piece(dk, N1, N1 + N2), piece(dv, N1, N1 + N2),
+                               O2, None, Sa, za, Sb, zb, 1e-6)
+    O3 = torch.empty(B, H, N3, M, device=DEV)
+    for t in range(N3):
+        i = N1 + N2 + t
+        step_out = torch.empty(B, H, M, device=DEV)
+        la.la_recurrent_step(dq[:, :, i].contiguous(), dk[:, :, i].contiguous(),
+                             dv[:, :, i].contiguous(), Sb, zb, step_out, 1e-6)
+        O3[:, :, t] = step_out
+    torch.cuda.synchronize()
+    got = np.concatenate([to_host(O1), to_host(O2), to_host(O3)], axis=2)
+    assert rel_err(got, ref) <= 1e-4
+    fk = oracle.phi(K.astype(np.float64))
+    assert rel_err(Sb.cpu().numpy(), np.einsum("bhnd,bhnm->bhdm", fk, V.astype(np.float64))) <= 1e-4
+    assert rel_err(zb.cpu().numpy(), fk.sum(2)) <= 1e-4
+
+
 def test_bitwise_determinism_and_slab_independence(la):
     B, H, N, D, M = 2, 4, 500, 64, 64
     Q, K, V, G = wl.random_case(800, B, H, N, D, M)
