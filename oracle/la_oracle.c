@@ -21,6 +21,10 @@
  *   causal_numerator_fwd / _bwd      Algorithm 1, forward and backward, as printed
  *                                    (takes already-mapped phi(Q), phi(K))
  *   causal_bwd_quadratic             gradient of eq. 8 by brute force           (definition)
+ *   global_bwd_quadratic             gradient of eq. 3 by brute force           (definition)
+ *   global_bwd_linear                the same gradient from the two global sums
+ *                                    sum_j phi(K_j)[V_j,1]^T and sum_i phi(Q_i) Gt_i^T
+ *                                    (eq. 5-6 differentiated; no causal mask)
  *   causal_bwd_linear                Algorithm 1 backward applied to values
  *                                    augmented with a column of ones, then the
  *                                    chain rule through phi (the paper leaves the
@@ -429,5 +433,116 @@ void la_oracle_causal_bwd_linear(const double *Q, const double *K, const double 
             dKs[t] *= la_oracle_dphi(Ks[t]);
         }
         free(fq); free(fk); free(Va); free(Nu); free(Gt); free(gVa);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Gradient of eq. 3 (every query sees every key) by brute force: as        */
+/* causal_bwd_quadratic with the sums over all j.                            */
+void la_oracle_global_bwd_quadratic(const double *Q, const double *K, const double *V,
+                                    const double *G, double *dQ, double *dK, double *dV,
+                                    int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M, *Gs = G + (size_t)s * N * M;
+        double *dQs = dQ + (size_t)s * N * D, *dKs = dK + (size_t)s * N * D;
+        double *dVs = dV + (size_t)s * N * M;
+        double *fq = map_rows(Qs, N, D, la_oracle_phi);
+        double *fk = map_rows(Ks, N, D, la_oracle_phi);
+        double *A = (double *)malloc(sizeof(double) * (size_t)N);
+        double *Oi = (double *)malloc(sizeof(double) * (size_t)M);
+        memset(dQs, 0, sizeof(double) * (size_t)N * D);
+        memset(dKs, 0, sizeof(double) * (size_t)N * D);
+        memset(dVs, 0, sizeof(double) * (size_t)N * M);
+        for (int i = 0; i < N; ++i) {
+            double dn = 0.0;
+            for (int e = 0; e < M; ++e) Oi[e] = 0.0;
+            for (int j = 0; j < N; ++j) {
+                A[j] = dot(fq + (size_t)i * D, fk + (size_t)j * D, D);
+                dn += A[j];
+                for (int e = 0; e < M; ++e) Oi[e] += A[j] * Vs[(size_t)j * M + e];
+            }
+            dn += eps;
+            for (int e = 0; e < M; ++e) Oi[e] /= dn;
+            for (int j = 0; j < N; ++j) {
+                double dA = 0.0;
+                for (int e = 0; e < M; ++e) {
+                    dVs[(size_t)j * M + e] += (A[j] / dn) * Gs[(size_t)i * M + e];
+                    dA += Gs[(size_t)i * M + e] * (Vs[(size_t)j * M + e] - Oi[e]);
+                }
+                dA /= dn;
+                for (int d = 0; d < D; ++d) {
+                    dQs[(size_t)i * D + d] += dA * fk[(size_t)j * D + d];
+                    dKs[(size_t)j * D + d] += dA * fq[(size_t)i * D + d];
+                }
+            }
+        }
+        for (long t = 0; t < (long)N * D; ++t) {
+            dQs[t] *= la_oracle_dphi(Qs[t]);
+            dKs[t] *= la_oracle_dphi(Ks[t]);
+        }
+        free(A); free(Oi); free(fq); free(fk);
+    }
+}
+
+/* Linear-time gradient of eq. 5-6.  With St = sum_j phi(K_j) [V_j, 1]^T       */
+/* (D x (M+1)), [num_i, den_i - eps] = phi(Q_i)^T St and Gt_i as in the causal  */
+/* case:  grad phi(Q_i) = St Gt_i;  Rt = sum_i phi(Q_i) Gt_i^T;                  */
+/* grad phi(K_j) = Rt [V_j, 1];  grad V_j = (Rt^T phi(K_j))[0:M].                */
+void la_oracle_global_bwd_linear(const double *Q, const double *K, const double *V,
+                                 const double *G, double *dQ, double *dK, double *dV,
+                                 int BH, int N, int D, int M, double eps) {
+    const int Ma = M + 1;
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M, *Gs = G + (size_t)s * N * M;
+        double *dQs = dQ + (size_t)s * N * D, *dKs = dK + (size_t)s * N * D;
+        double *dVs = dV + (size_t)s * N * M;
+        double *fq = map_rows(Qs, N, D, la_oracle_phi);
+        double *fk = map_rows(Ks, N, D, la_oracle_phi);
+        double *St = (double *)calloc((size_t)D * Ma, sizeof(double));
+        double *Rt = (double *)calloc((size_t)D * Ma, sizeof(double));
+        double *Gt = (double *)malloc(sizeof(double) * (size_t)Ma);
+        for (int j = 0; j < N; ++j)
+            for (int d = 0; d < D; ++d) {
+                for (int e = 0; e < M; ++e)
+                    St[(size_t)d * Ma + e] += fk[(size_t)j * D + d] * Vs[(size_t)j * M + e];
+                St[(size_t)d * Ma + M] += fk[(size_t)j * D + d];
+            }
+        for (int i = 0; i < N; ++i) {
+            double dn = eps;
+            for (int d = 0; d < D; ++d) dn += fq[(size_t)i * D + d] * St[(size_t)d * Ma + M];
+            double go = 0.0;
+            for (int e = 0; e < M; ++e) {
+                double num = 0.0;
+                for (int d = 0; d < D; ++d) num += fq[(size_t)i * D + d] * St[(size_t)d * Ma + e];
+                Gt[e] = Gs[(size_t)i * M + e] / dn;
+                go += Gs[(size_t)i * M + e] * (num / dn);
+            }
+            Gt[M] = -go / dn;
+            for (int d = 0; d < D; ++d) {
+                double a = 0.0;
+                for (int e = 0; e < Ma; ++e) {
+                    a += St[(size_t)d * Ma + e] * Gt[e];
+                    Rt[(size_t)d * Ma + e] += fq[(size_t)i * D + d] * Gt[e];
+                }
+                dQs[(size_t)i * D + d] = a * la_oracle_dphi(Qs[(size_t)i * D + d]);
+            }
+        }
+        for (int j = 0; j < N; ++j) {
+            for (int d = 0; d < D; ++d) {
+                double a = Rt[(size_t)d * Ma + M];
+                for (int e = 0; e < M; ++e) a += Rt[(size_t)d * Ma + e] * Vs[(size_t)j * M + e];
+                dKs[(size_t)j * D + d] = a * la_oracle_dphi(Ks[(size_t)j * D + d]);
+            }
+            for (int e = 0; e < M; ++e) {
+                double a = 0.0;
+                for (int d = 0; d < D; ++d) a += Rt[(size_t)d * Ma + e] * fk[(size_t)j * D + d];
+                dVs[(size_t)j * M + e] = a;
+            }
+        }
+        free(fq); free(fk); free(St); free(Rt); free(Gt);
     }
 }

@@ -197,3 +197,13 @@ def causal_bwd_quadratic(Q, K, V, G, eps=1e-6):
 def causal_bwd_linear(Q, K, V, G, eps=1e-6):
     """Algorithm 1 backward on ones-augmented values + chain rule; O(N D M)."""
     return _bwd("la_oracle_causal_bwd_linear", Q, K, V, G, eps)
+
+
+def global_bwd_quadratic(Q, K, V, G, eps=1e-6):
+    """Gradient of eq. 3 (non-causal) by brute force; O(N^2)."""
+    return _bwd("la_oracle_global_bwd_quadratic", Q, K, V, G, eps)
+
+
+def global_bwd_linear(Q, K, V, G, eps=1e-6):
+    """Gradient of eq. 5-6 from the two global sums; O(N D M)."""
+    return _bwd("la_oracle_global_bwd_linear", Q, K, V, G, eps)

@@ -355,3 +355,54 @@ def test_bwd_closed_forms(oracle):
     w = G * D / (D * i + eps)
     expect = np.flip(np.cumsum(np.flip(w, 2), 2), 2)
     np.testing.assert_allclose(dV0, expect, rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------ global backward
+
+@pytest.mark.parametrize("shape", [(1, 1, 1, 3, 2), (2, 2, 23, 8, 5), (1, 1, 70, 32, 16)])
+def test_global_bwd_linear_equals_quadratic_and_autograd(oracle, shape):
+    B, H, N, D, M = shape
+    Q, K, V, G = _rand(40 + N, B, H, N, D, M)
+    for eps in (0.0, 1e-6, 0.3):
+        lin = oracle.global_bwd_linear(Q, K, V, G, eps)
+        qua = oracle.global_bwd_quadratic(Q, K, V, G, eps)
+        tq, tk, tv = (torch.tensor(a, requires_grad=True) for a in (Q, K, V))
+        fq = torch.nn.functional.elu(tq) + 1
+        fk = torch.nn.functional.elu(tk) + 1
+        A = fq @ fk.transpose(-1, -2)
+        O = (A @ tv) / (A.sum(-1, keepdim=True) + eps)
+        O.backward(torch.tensor(G))
+        scale = max(np.abs(b).max() for b in qua)
+        for a, b, c in zip(lin, qua, (tq.grad, tk.grad, tv.grad)):
+            assert np.abs(a - b).max() / scale < 1e-12
+            assert np.abs(b - c.numpy()).max() / scale < 1e-11
+
+
+def test_global_bwd_finite_differences_and_closed_forms(oracle):
+    B, H, N, D, M = 1, 1, 6, 3, 2
+    Q, K, V, G = _rand(41, B, H, N, D, M)
+    eps = 1e-3
+    dQ, dK, dV = oracle.global_bwd_linear(Q, K, V, G, eps)
+
+    def loss(q, k, v):
+        return float((G * oracle.global_fwd_quadratic(q, k, v, eps)).sum())
+
+    h = 1e-6
+    for X, dX, which in ((Q, dQ, 0), (K, dK, 1), (V, dV, 2)):
+        fd = np.zeros_like(X)
+        for idx in np.ndindex(X.shape):
+            args = [Q.copy(), K.copy(), V.copy()]
+            args[which][idx] += h
+            up = loss(*args)
+            args[which][idx] -= 2 * h
+            fd[idx] = (up - loss(*args)) / (2 * h)
+        np.testing.assert_allclose(dX, fd, rtol=2e-6, atol=1e-8)
+    # Q = K = 0: every weight is D/(D N + eps), so dV_j is the same for all j
+    Zq = np.zeros_like(Q)
+    _, _, dV0 = oracle.global_bwd_linear(Zq, Zq, V, G, eps)
+    expect = np.broadcast_to(G.sum(2, keepdims=True) * D / (D * N + eps), V.shape)
+    np.testing.assert_allclose(dV0, expect, rtol=1e-12)
+    # constant V, eps = 0: the output does not depend on Q, K
+    Vc = np.broadcast_to(np.array([0.5, -1.0]), V.shape).copy()
+    dQc, dKc, _ = oracle.global_bwd_linear(Q, K, Vc, G, 0.0)
+    assert np.abs(dQc).max() < 1e-13 and np.abs(dKc).max() < 1e-13
