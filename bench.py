@@ -234,7 +234,23 @@ def run_table(args):
                      "fwd_mtok_s": w.B * w.N / sec / 1e6,
                      "hbm_ceiling_mtok_s": HBM_PEAK_GBS * 1e9 / (w.H * 4 * (2 * w.D + 2 * w.M)) / 1e6})
         print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
-        del fb, ws
+        # ... and forward + backward of the non-causal form
+        deng = torch.empty(w.B, w.H, w.N, dtype=torch.float32, device="cuda:0")
+        wsb = torch.empty(la.la_global_bwd_workspace(w.B, w.H, w.N, w.D, w.M), dtype=torch.uint8,
+                          device="cuda:0")
+
+        def global_step():
+            la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws, den=deng)
+            la.la_global_bwd(fb.Q, fb.K, fb.V, fb.O, deng, fb.G, fb.dQ, fb.dK, fb.dV, w.eps, ws=wsb,
+                             fwd_ws=ws)
+        sec = time_steps(global_step, 5, 2, torch)
+        prof = profile_kernels(la, global_step, 3, torch)
+        rows.append({"workload": w.name + "_global_fwd_bwd", "tokens": w.B * w.N,
+                     "fwd_bwd_ms": sec * 1e3, "fwd_bwd_mtok_s": w.B * w.N / sec / 1e6,
+                     "hbm_ceiling_mtok_s": HBM_PEAK_GBS * 1e9 / (w.H * 4 * (6 * w.D + 6 * w.M)) / 1e6,
+                     "kernels_ms": {k: round(ms * n, 4) for k, (ms, n) in prof.items()}})
+        print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
+        del fb, ws, wsb, deng
     # recurrent decode: 3072 sequential steps, one token per head per step
     for B in (wl.CFG5.B, 4096):
         d = wl.CFG5

@@ -80,6 +80,7 @@ int la_version(void);
 size_t la_causal_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
 size_t la_causal_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
 size_t la_global_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
+size_t la_global_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
 
 /*
  * Causal linear attention, forward (eq. 9 in its prefix-sum form eq. 10-12):
@@ -131,10 +132,30 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
  * Non-causal linear attention, forward (eq. 5-6): the sums over all N keys are
  * formed once and reused for every query,
  *   O_i = phi(Q_i)^T (sum_j phi(K_j) V_j^T) / (phi(Q_i) . sum_j phi(K_j) + eps).
- * Arguments as la_causal_fwd without den.  ws: la_global_fwd_workspace() bytes
- * (never 0).
+ * Arguments as la_causal_fwd; den [B,H,N] fp32 out (the denominators, eps
+ * included) or NULL.  ws: la_global_fwd_workspace() bytes (never 0).
  */
-int la_global_fwd(const void *Q, const void *K, const void *V, void *O,
+int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * Non-causal linear attention, backward: the gradient of eq. 4-6 for Q, K, V
+ * given dO.  With no mask both sums of the causal gradients (eq. 13-15) run
+ * over the whole sequence, so with the ones-augmented values of the causal
+ * backward (V~ = [V, 1], G~_i = [dO_i/den_i, -(dO_i.O_i)/den_i]) and the two
+ * totals S~ = sum_j phi(K_j) V~_j^T and R~ = sum_i phi(Q_i) G~_i^T,
+ *   dphi(Q)_i = S~ G~_i,   dphi(K)_j = R~ V~_j,   dV_j = (R~^T phi(K_j))[0:M],
+ * followed by the chain rule through phi (elementwise times phi'(Q), phi'(K)).
+ * O and den are the results of la_global_fwd on the same Q, K, V, eps; if
+ * either is NULL both are recomputed into the workspace.  fwd_ws is optional
+ * (NULL allowed): the workspace la_global_fwd used for that call, untouched
+ * since; it still holds S~ and the backward then does not re-read K and V to
+ * rebuild it.  dQ, dK [B,H,N,D] out; dV [B,H,N,M] out.  ws:
+ * la_global_bwd_workspace() bytes.  Errors as the other entry points.
+ */
+int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
                   int B, int H, int N, int D, int M, float eps, la_dtype t,
                   void *ws, size_t ws_bytes, void *stream);
 
@@ -181,7 +202,8 @@ typedef enum {
     LA_K_DQ = 6,       /* gradient for Q (forward direction)                   */
     LA_K_REV = 7,      /* gradients for V and K (reverse direction)            */
     LA_K_STEP = 8,     /* recurrent decode step                                */
-    LA_K_COUNT = 9
+    LA_K_GLOBAL_BWD = 9, /* the three non-causal gradient read-outs, as one span */
+    LA_K_COUNT = 10
 } la_kernel_id;
 
 const char *la_kernel_name(int kernel_id);

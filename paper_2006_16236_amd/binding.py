@@ -19,11 +19,11 @@ LA_OK, LA_ERR_NULL, LA_ERR_SHAPE, LA_ERR_UNSUPPORTED = 0, -1, -2, -3
 LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN = -4, -5, -6
 
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
-           "la_global_fwd_workspace", "la_causal_fwd", "la_causal_fwd_state", "la_causal_bwd",
-           "la_global_fwd",
+           "la_global_fwd_workspace", "la_global_bwd_workspace", "la_causal_fwd", "la_causal_fwd_state",
+           "la_causal_bwd", "la_global_fwd", "la_global_bwd",
            "la_recurrent_step", "la_recurrent_steps", "la_kernel_name", "la_profile_begin",
            "la_profile_end")
-LA_K_COUNT = 9
+LA_K_COUNT = 10
 
 
 class LaError(RuntimeError):
@@ -35,14 +35,19 @@ class LaError(RuntimeError):
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            f"{LIB_PATH} is missing: build it first (python -m paper_2006_16236_amd.build "
+            f"{LIB_PATH} is missing: build it first (python paper_2006_16236_amd/build.py "
             "or __graft_entry__.build()); this package has no fallback path")
     lib = ctypes.CDLL(LIB_PATH)
+    missing = [name for name in EXPORTS if not hasattr(lib, name)]
+    if missing:
+        raise ImportError(f"{LIB_PATH} lacks {missing}: it was built from older sources, rebuild "
+                          "it (python paper_2006_16236_amd/build.py)")
     vp, i, f, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     lib.la_status_string.restype = ctypes.c_char_p
     lib.la_status_string.argtypes = [i]
     lib.la_version.restype = i
-    for name in ("la_causal_fwd_workspace", "la_causal_bwd_workspace", "la_global_fwd_workspace"):
+    for name in ("la_causal_fwd_workspace", "la_causal_bwd_workspace", "la_global_fwd_workspace",
+                 "la_global_bwd_workspace"):
         fn = getattr(lib, name)
         fn.restype = sz
         fn.argtypes = [i, i, i, i, i, i]
@@ -53,7 +58,9 @@ def _load() -> ctypes.CDLL:
     lib.la_causal_bwd.restype = i
     lib.la_causal_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_global_fwd.restype = i
-    lib.la_global_fwd.argtypes = [vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_global_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_global_bwd.restype = i
+    lib.la_global_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_recurrent_step.restype = i
     lib.la_recurrent_step.argtypes = [vp] * 6 + [i, i, i, i, f, i, vp]
     lib.la_recurrent_steps.restype = i
@@ -124,6 +131,10 @@ def la_global_fwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
     return int(_lib.la_global_fwd_workspace(B, H, N, D, M, dtype_code))
 
 
+def la_global_bwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
+    return int(_lib.la_global_bwd_workspace(B, H, N, D, M, dtype_code))
+
+
 def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None):
     """O [B,H,N,M] <- causal linear attention of Q, K [B,H,N,D], V [B,H,N,M]; den [B,H,N] fp32
     (optional) receives the denominators.  Enqueues on `stream` (default: torch's current)."""
@@ -164,14 +175,29 @@ def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=Non
     return ws
 
 
-def la_global_fwd(Q, K, V, O, eps=1e-6, ws=None, stream=None):
-    """O <- non-causal linear attention (every query sees every key)."""
+def la_global_fwd(Q, K, V, O, eps=1e-6, ws=None, stream=None, den=None):
+    """O <- non-causal linear attention (every query sees every key); den [B,H,N] fp32
+    (optional) receives the denominators."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
     t = _dtype_code(Q)
     ws, wp, wb = _ws(ws, la_global_fwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_global_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), B, H, N, D, M, float(eps), t,
-                              wp, wb, _stream(stream)), "la_global_fwd")
+    _check(_lib.la_global_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
+                              float(eps), t, wp, wb, _stream(stream)), "la_global_fwd")
+    return ws
+
+
+def la_global_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None):
+    """dQ, dK, dV <- gradients of non-causal linear attention for upstream dO; O and den are the
+    results of la_global_fwd (either may be None: both are then recomputed).  fwd_ws (optional)
+    is the workspace tensor la_global_fwd returned for the same call."""
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q)
+    ws, wp, wb = _ws(ws, la_global_bwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_global_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
+                              _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
+                              wp, wb, _stream(stream)), "la_global_bwd")
     return ws
 
 

@@ -147,6 +147,23 @@ int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *
     return LA_OK;
 }
 
+// eq. 5-6: the K, V grand total (left in slot 0 of `states`), then the read-out
+int run_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den, long BH,
+                   int N, int D, int M, float eps, la_dtype t, const Plan &p, float *states,
+                   hipStream_t s) {
+    const int nblocks = (int)(BH * p.nseg);
+    la::SegArgs sa{};
+    sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = states;
+    sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
+    { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+    if (p.nseg > 1)
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+    la::PassArgs a{};
+    a.Q = Q; a.K = K; a.V = V; a.out = O; a.den = den; a.state = states;
+    a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
+    { ProfScope ps(LA_K_GLOBAL, s); LA_TRY(la::launch_pass_fwd(true, D, M, (int)t, a, nblocks, s)); }
+    return LA_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -188,6 +205,17 @@ size_t la_global_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
     const long BH = (long)B * H;
     return states_bytes(BH, make_plan(BH, N), D, M);
+}
+
+size_t la_global_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
+    if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    const size_t rows = (size_t)BH * N;
+    size_t bytes = 2 * align256(rows * sizeof(float));                      // rden, delta
+    bytes += 2 * states_bytes(BH, p, D, M);                                 // the two grand totals
+    bytes += align256(rows * M * esize(t)) + align256(rows * sizeof(float)); // O, den if recomputed
+    return bytes;
 }
 
 int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
@@ -297,32 +325,87 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
     return LA_OK;
 }
 
-int la_global_fwd(const void *Q, const void *K, const void *V, void *O,
+int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
                   int B, int H, int N, int D, int M, float eps, la_dtype t,
                   void *ws, size_t ws_bytes, void *stream) {
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
-    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws))
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws) ||
+        misaligned(den))
         return LA_ERR_ALIGN;
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     if (ws == nullptr || ws_bytes < states_bytes(BH, p, D, M)) return LA_ERR_WORKSPACE;
+    return run_global_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
+                          static_cast<hipStream_t>(stream));
+}
+
+int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream) {
+    if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr ||
+        dK == nullptr || dV == nullptr)
+        return LA_ERR_NULL;
+    const int st = check_dims(B, H, N, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) ||
+        misaligned(dK) || misaligned(dV) || misaligned(O) || misaligned(den) || misaligned(ws) ||
+        misaligned(fwd_ws))
+        return LA_ERR_ALIGN;
+    const size_t need = la_global_bwd_workspace(B, H, N, D, M, t);
+    if (ws == nullptr || ws_bytes < need) return LA_ERR_WORKSPACE;
+
     hipStream_t s = static_cast<hipStream_t>(stream);
-    float *states = static_cast<float *>(ws);
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    const size_t rows = (size_t)BH * N;
+    Carver cv{static_cast<char *>(ws), 0};
+    float *rden = static_cast<float *>(cv.take(rows * sizeof(float)));
+    float *delta = static_cast<float *>(cv.take(rows * sizeof(float)));
+    float *stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
+    float *stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
+    const bool recompute_fwd = (O == nullptr || den == nullptr);
     const int nblocks = (int)(BH * p.nseg);
     la::SegArgs sa{};
-    sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = states;
     sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
-    { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+    if (recompute_fwd) {                       // also leaves the K, V total in slot 0 of stS
+        void *Otmp = cv.take(rows * M * esize(t));
+        float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
+        const int fs = run_global_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s);
+        if (fs != LA_OK) return fs;
+        O = Otmp;
+        den = dentmp;
+    } else if (fwd_ws != nullptr) {            // the forward's workspace still holds that total
+        stS = const_cast<float *>(static_cast<const float *>(fwd_ws));
+    } else {
+        sa.Y = K; sa.Z = V; sa.state = stS;
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+        if (p.nseg > 1)
+            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+    }
+    // the Q, dO total, with the per-token scalars 1/den and delta formed on the way
+    sa.Y = Q; sa.Z = dO; sa.state = stR;
+    sa.O = O; sa.den = den; sa.rden_out = rden; sa.delta_out = delta;
+    { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(2, D, M, (int)t, sa, nblocks, s)); }
     if (p.nseg > 1)
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+
     la::PassArgs a{};
-    a.Q = Q; a.K = K; a.V = V; a.out = O; a.den = nullptr; a.state = states;
+    a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
-    { ProfScope ps(LA_K_GLOBAL, s); LA_TRY(la::launch_pass_fwd(true, D, M, (int)t, a, nblocks, s)); }
+    ProfScope ps(LA_K_GLOBAL_BWD, s);
+    a.out = dQ; a.state = stS;
+    LA_TRY(la::launch_pass_global_bwd(0, D, M, (int)t, a, nblocks, s));
+    a.state = stR;
+    a.out = dV;
+    LA_TRY(la::launch_pass_global_bwd(1, D, M, (int)t, a, nblocks, s));
+    a.out = dK;
+    LA_TRY(la::launch_pass_global_bwd(2, D, M, (int)t, a, nblocks, s));
     return LA_OK;
 }
+
 
 int la_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z, void *out,
                       int B, int H, int D, int M, float eps, la_dtype t, void *stream) {
@@ -359,7 +442,8 @@ int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, fl
 const char *la_kernel_name(int kernel_id) {
     static const char *const names[LA_K_COUNT] = {"segment_state_kv", "segment_state_qg", "scan_states",
                                                   "causal_pass_fwd", "global_readout", "bwd_prep",
-                                                  "causal_pass_dq", "reverse_pass_dv_dk", "recurrent_step"};
+                                                  "causal_pass_dq", "reverse_pass_dv_dk", "recurrent_step",
+                                                  "global_bwd_readouts"};
     return kernel_id >= 0 && kernel_id < LA_K_COUNT ? names[kernel_id] : "unknown";
 }
 

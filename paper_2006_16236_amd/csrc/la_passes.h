@@ -19,6 +19,12 @@
 //   kDk       V            dO/den       phi(Q)       R^T    M x D         reverse
 //   kGlobal   phi(Q)       -            -            total  D x M         (read-out only, eq. 5-6)
 //
+// Without the causal mask (eq. 4-6) both sums run over the whole sequence, so the gradients
+// are read-outs against the two grand totals, with no in-chunk part and no carried update:
+//   kGlobalDq dO/den       -            -            total S^T            then times phi'(Q)
+//   kGlobalDv phi(K)       -            -            total R
+//   kGlobalDk V            -            -            total R^T            then times phi'(K)
+//
 // The denominator of eq. 12 rides along as the "ones column" of the values:
 //   kFwd  also carries z = sum phi(K_b) and forms den_a = rowsum(mask(XY^T)) + X_a.z + eps;
 //   kDq   adds delta_a to every kept entry of X Y^T and delta_a * z to the state term,
@@ -43,7 +49,12 @@
 
 namespace la {
 
-enum Pass { kFwd = 0, kDq = 1, kDv = 2, kDk = 3, kGlobal = 4 };
+enum Pass { kFwd = 0, kDq = 1, kDv = 2, kDk = 3, kGlobal = 4, kGlobalDq = 5, kGlobalDv = 6, kGlobalDk = 7 };
+
+// the causal pass whose operand roles a read-out-only pass shares
+__host__ __device__ constexpr int base_pass(int p) {
+    return p == kGlobal ? kFwd : p == kGlobalDq ? kDq : p == kGlobalDv ? kDv : p == kGlobalDk ? kDk : p;
+}
 
 // floats per carried state in the workspace: the D x M matrix (row-major [D][M])
 // followed by the D-vector that belongs to the ones column (z or rho).
@@ -55,7 +66,7 @@ struct PassArgs {
     const float *delta;          // [BH, N] -(dO_i.O_i)/den_i   (backward passes)
     void *out;                   // [BH, N, DZ]  (reverse_pass_kernel: dV)
     void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
-    float *den;                  // [BH, N] or null             (kFwd)
+    float *den;                  // [BH, N] or null             (kFwd, kGlobal)
     const float *state;          // [BH, nseg, state_stride] exclusive states; null = zero state
     const float *init_S, *init_z;  // kFwd, nseg == 1: state before token 0, [BH, D, M] / [BH, D]; may be null
     float *final_S, *final_z;      // kFwd: state after the last token, same shapes; may be null
@@ -94,13 +105,14 @@ __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16]
 // Which raw tensor feeds which operand of a pass, and how it is mapped when parked.
 template <int PASS, int D, int M>
 struct PassTraits {
-    static constexpr bool kXisD = (PASS == kFwd || PASS == kDv || PASS == kGlobal);
+    static constexpr int BP = base_pass(PASS);
+    static constexpr bool kXisD = (BP == kFwd || BP == kDv);
     static constexpr int DX = kXisD ? D : M;     // contraction width of X . Y and of X . U
     static constexpr int DZ = kXisD ? M : D;     // width of Z, of the output and of U's columns
     static constexpr bool kReverse = (PASS == kDv || PASS == kDk);
-    static constexpr bool kHasRaw = (PASS == kDq || PASS == kDk);     // phi' under the output
-    static constexpr bool kHasYZ = (PASS != kGlobal);
-    static constexpr int kMapX = (PASS == kDq) ? kMapScale : (PASS == kDk) ? kMapId : kMapPhi;
+    static constexpr bool kHasRaw = (BP == kDq || BP == kDk);         // phi' under the output
+    static constexpr bool kHasYZ = (PASS < kGlobal);                  // false: read-out only
+    static constexpr int kMapX = (BP == kDq) ? kMapScale : (BP == kDk) ? kMapId : kMapPhi;
     static constexpr int kMapY = (PASS == kDq) ? kMapId : (PASS == kDk) ? kMapScale : kMapPhi;
     static constexpr int kMapZ = (PASS == kFwd) ? kMapId : (PASS == kDv) ? kMapScale : kMapPhi;
 };
@@ -123,13 +135,14 @@ struct PassStager {
                                           float *ly, float *lz, float *lr)
         : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_), c(lane_ & 15),
           g(lane_ >> 4) {
-        Xs = static_cast<const T *>(PASS == kFwd || PASS == kGlobal ? a.Q
-                                    : PASS == kDq ? a.G : PASS == kDv ? a.K : a.V) + rowbase * DX;
+        constexpr int BP = Tr::BP;
+        Xs = static_cast<const T *>(BP == kFwd ? a.Q : BP == kDq ? a.G : BP == kDv ? a.K : a.V) +
+             rowbase * DX;
         Ys = static_cast<const T *>(PASS == kFwd ? a.K : PASS == kDq ? a.V
                                     : PASS == kDv ? a.Q : a.G) + rowbase * DX;
         Zs = static_cast<const T *>(PASS == kFwd ? a.V : PASS == kDq ? a.K
                                     : PASS == kDv ? a.G : a.Q) + rowbase * DZ;
-        Rs = static_cast<const T *>(PASS == kDq ? a.Q : a.K) + rowbase * DZ;
+        Rs = static_cast<const T *>(BP == kDq ? a.Q : a.K) + rowbase * DZ;
         rden = a.rden + rowbase;
         delta = a.delta + rowbase;
         n_dl1 = dl1 = 0.f;
@@ -151,10 +164,10 @@ struct PassStager {
             stage_load<DZ, kFull>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
         }
         if constexpr (Tr::kHasRaw) stage_load<DZ, kFull>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
-        if constexpr (PASS == kDq || PASS == kDk)             // dO is the X (kDq) or Y (kDk) tile
+        if constexpr (Tr::BP == kDq || PASS == kDk)           // dO is the X (kDq) or Y (kDk) tile
             stage_rows<DX, kFull>(rden + t0, nvalid, lane, scx);
         if constexpr (PASS == kDk) rows4<kFull>(delta + t0, nvalid, g, n_dl4);
-        if constexpr (PASS == kDq) {
+        if constexpr (Tr::BP == kDq) {
             const float v = delta[t0 + (kFull ? c : min(c, nvalid - 1))];
             n_dl1 = (kFull || c < nvalid) ? v : 0.f;
         }
@@ -312,7 +325,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 
     if (a.state != nullptr) {
         const float *st = a.state +
-                          ((size_t)bh * a.nseg + (PASS == kGlobal ? 0 : seg)) * state_stride(D, M);
+                          ((size_t)bh * a.nseg + (kHasYZ ? seg : 0)) * state_stride(D, M);
 #pragma unroll
         for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
@@ -330,7 +343,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
             for (int xt = 0; xt < XT; ++xt) zg[xt] = load4(st + D * M + 16 * xt + 4 * g);
         }
-        if constexpr (PASS == kDq || PASS == kDk) {
+        if constexpr (Tr::BP == kDq || Tr::BP == kDk) {
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) ecp[zt] = g == 0 ? st[D * M + 16 * zt + c] : 0.f;
         }
@@ -421,13 +434,20 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         f32x4 den4 = {1.f, 1.f, 1.f, 1.f};
         const f32x4 eps4 = {a.eps, a.eps, a.eps, a.eps};
         float zf[ZT][4];                 // Z, feature-lane
-        if constexpr (PASS == kGlobal) {
-            float p = 0.f;
+        if constexpr (!kHasYZ) {
+            if constexpr (PASS == kGlobal) {
+                float p = 0.f;
 #pragma unroll
-            for (int xt = 0; xt < XT; ++xt)
+                for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) p = fmaf(xa[xt][r], zg[xt][r], p);
-            den4 = mfma16(p, 1.0f, eps4);
+                    for (int r = 0; r < 4; ++r) p = fmaf(xa[xt][r], zg[xt][r], p);
+                den4 = mfma16(p, 1.0f, eps4);
+            } else if constexpr (kHasRaw) {
+                // the ones-column part: delta_a * z (kGlobalDq), rho (kGlobalDk)
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+                    out[zt] = mfma16(PASS == kGlobalDq ? dl1 : 1.0f, ecp[zt], out[zt]);
+            }
         } else {
             // ---- W[a][b] = X_a . Y_b, lane (c = a, g), register r: b = 4g + r --------------
             float ya[XT][4];             // Y, token-lane
@@ -473,7 +493,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 
         // ---- finish and store ---------------------------------------------------------------
         if constexpr (PASS == kFwd || PASS == kGlobal) {
-            if constexpr (PASS == kFwd) {
+            {
                 // lanes c < 4 of each group write den of token 4g + c: 16 consecutive floats
                 const float dsel = c == 0 ? den4[0] : c == 1 ? den4[1] : c == 2 ? den4[2] : den4[3];
                 if (a.den != nullptr && c < 4 && 4 * g + c < nvalid) a.den[rowbase + t0 + 4 * g + c] = dsel;

@@ -53,6 +53,7 @@ def test_workspace_queries(lib):
     assert long == 16 * 128 * (64 * 64 + 64) * 4                        # 128 segments of 512 tokens
     assert b.la_causal_bwd_workspace(2, 8, 65536, 64, 64) > 2 * long
     assert b.la_global_fwd_workspace(1, 1, 1, 32, 32) >= (32 * 32 + 32) * 4
+    assert b.la_global_bwd_workspace(1, 1, 1, 32, 32) >= 2 * (32 * 32 + 32) * 4 + 8
     assert b.la_causal_fwd_workspace(1, 1, 100, 48, 64) == 0            # invalid D: query returns 0
     assert b.la_causal_fwd_workspace(0, 1, 100, 64, 64) == 0
 
@@ -95,8 +96,16 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert bwd(p, p, p, p, p, odd, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
 
     glob = lib.la_global_fwd
-    assert glob(p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
-    assert glob(p, p, null, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 20, null) == b.LA_ERR_NULL
+    assert glob(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert glob(p, p, null, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 20, null) == b.LA_ERR_NULL
+    assert glob(p, p, p, p, odd, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 20, null) == b.LA_ERR_ALIGN
+
+    gbwd = lib.la_global_bwd
+    assert gbwd(p, p, p, p, p, null, null, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_NULL
+    assert gbwd(p, p, p, p, p, null, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert gbwd(p, p, p, p, p, null, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 8, null) == b.LA_ERR_WORKSPACE
+    assert gbwd(p, p, p, p, p, null, p, p, odd, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
+    assert gbwd(p, p, p, p, p, null, p, p, p, p, 1, 1, 16, 64, 40, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_UNSUPPORTED
 
     step = lib.la_recurrent_step
     assert step(p, p, p, null, p, p, 1, 1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_NULL

@@ -91,7 +91,10 @@ def test_sweep_points_on_sampled_slabs(la, oracle, log2n):
     O, den, dQ, dK, dV = gpu_fwd_bwd(la, host, eps=w.eps)
     Q, K, V = (to_dev(x) for x in host[:3])
     Og = torch.empty_like(V)
-    la.la_global_fwd(Q, K, V, Og, w.eps)
+    deng = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
+    gws = la.la_global_fwd(Q, K, V, Og, w.eps, den=deng)
+    gQ, gK, gV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    la.la_global_bwd(Q, K, V, Og, deng, to_dev(host[3]), gQ, gK, gV, w.eps, fwd_ws=gws)
     torch.cuda.synchronize()
     tol = tol_for(w.N)
     for b, h in SWEEP_SAMPLES[log2n]:
@@ -103,6 +106,8 @@ def test_sweep_points_on_sampled_slabs(la, oracle, log2n):
         got = [to_host(x[b:b + 1, h:h + 1]) for x in (dQ, dK, dV)]
         assert max(grad_errs(got, gref)) <= tol, (b, h)
         assert rel_err(to_host(Og[b:b + 1, h:h + 1]), oracle.global_fwd_linear(*sl[:3], w.eps)) <= tol
+        got = [to_host(x[b:b + 1, h:h + 1]) for x in (gQ, gK, gV)]
+        assert max(grad_errs(got, oracle.global_bwd_linear(*sl, w.eps))) <= tol, (b, h)
     # properties that hold for every slab at any size
     assert torch.isfinite(O).all() and torch.isfinite(dQ).all() and torch.isfinite(dK).all()
     assert torch.isfinite(dV).all() and (den > 0).all()

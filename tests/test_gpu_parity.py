@@ -126,6 +126,60 @@ def test_global_fwd(la, oracle, N, sched):
     assert rel_err(to_host(O), ref) <= tol_for(N)
 
 
+def run_global(la, Q, K, V, G, eps, bf16=False, reuse_fwd=True, reuse_states=True):
+    """Non-causal forward (with den) and backward; returns O, den, (dQ, dK, dV) on the host."""
+    dq, dk, dv, dg = (to_dev(x, bf16) for x in (Q, K, V, G))
+    O = torch.full_like(dv, float("nan"))
+    den = torch.full(Q.shape[:-1], float("nan"), dtype=torch.float32, device=DEV)
+    fwd_ws = la.la_global_fwd(dq, dk, dv, O, eps, den=den)
+    gq = torch.full_like(dq, float("nan"))
+    gk = torch.full_like(dk, float("nan"))
+    gv = torch.full_like(dv, float("nan"))
+    la.la_global_bwd(dq, dk, dv, O if reuse_fwd else None, den if reuse_fwd else None, dg, gq, gk,
+                     gv, eps, fwd_ws=fwd_ws if reuse_states else None)
+    torch.cuda.synchronize()
+    return to_host(O), den.cpu().numpy(), (to_host(gq), to_host(gk), to_host(gv))
+
+
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+@pytest.mark.parametrize("N", [1, 15, 16, 17, 64, 257, 1000])
+def test_global_bwd_edge_lengths(la, oracle, N, sched):
+    B, H, D, M = 2, 2, 64, 64
+    Q, K, V, G = wl.random_case(520 + N, B, H, N, D, M)
+    gref = oracle.global_bwd_linear(Q, K, V, G, 1e-6)
+    with schedule(**SCHEDULES[sched]):
+        O, den, grads = run_global(la, Q, K, V, G, 1e-6)
+    assert rel_err(O, oracle.global_fwd_linear(Q, K, V, 1e-6)) <= tol_for(N)
+    # the denominator of eq. 5-6: phi(Q_i) . sum_j phi(K_j) + eps, here from the oracle's phi
+    dref = np.einsum("bhnd,bhd->bhn", oracle.phi(Q), oracle.phi(K).sum(axis=2)) + 1e-6
+    assert rel_err(den, dref) <= tol_for(N)
+    assert max(grad_errs(grads, gref)) <= tol_for(N)
+
+
+@pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32)])
+@pytest.mark.parametrize("reuse", ["all", "no_states", "recompute"])
+def test_global_bwd_head_sizes_and_recompute(la, oracle, D, M, reuse):
+    B, H, N = 1, 3, 333
+    Q, K, V, G = wl.random_case(560 + D + 2 * M, B, H, N, D, M)
+    gref = oracle.global_bwd_linear(Q, K, V, G, 1e-6)
+    with schedule(**SCHEDULES["three_chunk_segments"]):
+        _, _, grads = run_global(la, Q, K, V, G, 1e-6, reuse_fwd=reuse != "recompute",
+                                 reuse_states=reuse == "all")
+    assert max(grad_errs(grads, gref)) <= tol_for(N)
+
+
+def test_global_bwd_quadratic_definition_and_bf16(la, oracle):
+    B, H, N, D, M = 1, 2, 200, 64, 64
+    Q, K, V, G = wl.random_case(590, B, H, N, D, M)
+    gref = oracle.global_bwd_quadratic(Q, K, V, G, 1e-6)
+    _, _, grads = run_global(la, Q, K, V, G, 1e-6)
+    assert max(grad_errs(grads, gref)) <= tol_for(N)
+    Qb, Kb, Vb, Gb = (wl.round_to_bf16(x) for x in (Q, K, V, G))
+    gref = oracle.global_bwd_linear(Qb, Kb, Vb, Gb, 1e-6)
+    _, _, grads = run_global(la, Qb, Kb, Vb, Gb, 1e-6, bf16=True)
+    assert max(grad_errs(grads, gref)) <= tol_for(N, bf16=True)
+
+
 @pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32), (64, 64)])
 def test_recurrent_steps_against_oracle_and_causal_fwd(la, oracle, D, M):
     B, H, T = 3, 2, 40
