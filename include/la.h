@@ -38,8 +38,9 @@
  *              segment schedule (for tests and experiments): LA_TARGET_WAVES
  *              (default 2048: wavefronts wanted in flight) and
  *              LA_MIN_SEG_CHUNKS (default 4: shortest segment, in 16-token
- *              chunks).  The workspace query and the call must see the same
- *              values.
+ *              chunks).  Sequences are not cut at all once B*H reaches half of
+ *              LA_TARGET_WAVES.  The workspace query and the call must see the
+ *              same values.
  */
 #ifndef LA_H_
 #define LA_H_

@@ -40,6 +40,9 @@ Plan make_plan(long BH, int N) {
     long maxseg = p.nchunks / min_chunks;
     if (maxseg < 1) maxseg = 1;
     long nseg = want < 1 ? 1 : (want > maxseg ? maxseg : want);
+    // Cutting costs a second sweep over K, V (and Q, dO) plus the scan: measured on MI355X it
+    // pays from four segments per sequence on; with half the target already there, don't cut.
+    if (2 * BH >= target_waves) nseg = 1;
     p.cps = (int)((p.nchunks + nseg - 1) / nseg);
     p.nseg = (p.nchunks + p.cps - 1) / p.cps;
     return p;

@@ -5,37 +5,43 @@
 namespace la {
 
 // ---- scan over the segment states of each sequence ------------------------------------------
-// state: [BH, nseg, stride].  A workgroup takes 32 consecutive elements of one sequence; its
-// 8 groups of 32 threads split the nseg slots into 8 consecutive runs.  Each group first sums
-// its run (all loads independent), the run totals are exchanged through LDS, then the group
-// walks its run again (now from cache) and writes the exclusive prefix.  Slots are visited in
-// scan order: ascending for the prefix, descending for the suffix.  Fixed order: deterministic.
+// state: [BH, nseg, stride].  A workgroup takes 256 / PARTS consecutive elements of one
+// sequence; its PARTS groups of threads split the nseg slots into PARTS consecutive runs.
+// Each group first sums its run (all loads independent), the run totals are exchanged through
+// LDS, then the group walks its run again (now from cache) and writes the exclusive prefix.
+// Slots are visited in scan order: ascending for the prefix, descending for the suffix.
+// Fixed order: deterministic.  PARTS grows with nseg (1 for a handful of slots: every thread
+// then has an element of its own and no thread idles).
+template <int PARTS>
 __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg, int stride,
                                                           int mode, const float *init_S,
                                                           const float *init_z, int DM) {
-    __shared__ float part_total[8][32];
-    const int el = threadIdx.x & 31, part = threadIdx.x >> 5;
-    const int e = blockIdx.x * 32 + el;
+    constexpr int EPW = 256 / PARTS;          // elements per workgroup
+    __shared__ float part_total[PARTS][EPW];
+    const int el = threadIdx.x % EPW, part = threadIdx.x / EPW;
+    const int e = blockIdx.x * EPW + el;
     const bool live = e < stride;
     float *p = state + (size_t)blockIdx.y * nseg * stride + (live ? e : 0);
     const bool reverse = mode == kScanReverse;
-    const int per = (nseg + 7) / 8;
+    const int per = (nseg + PARTS - 1) / PARTS;
     const int k0 = min(part * per, nseg), k1 = min(k0 + per, nseg);
     // the last slot in scan order holds no total (nobody reads past it): never read it
     const int klast = mode == kScanTotal ? nseg : nseg - 1;
 
     float total = 0.f;
     for (int k = k0; k < min(k1, klast); ++k) total += p[(size_t)(reverse ? nseg - 1 - k : k) * stride];
-    part_total[part][el] = total;
-    __syncthreads();
     // the scan starts from the caller's initial state when there is one (forward prefix only)
     float acc = 0.f;
     if (init_S != nullptr && live)
         acc = e < DM ? init_S[(size_t)blockIdx.y * DM + e]
                      : init_z[(size_t)blockIdx.y * (stride - DM) + (e - DM)];
-    for (int q = 0; q < part; ++q) acc += part_total[q][el];
+    if constexpr (PARTS > 1) {
+        part_total[part][el] = total;
+        __syncthreads();
+        for (int q = 0; q < part; ++q) acc += part_total[q][el];
+    }
     if (mode == kScanTotal) {
-        if (part == 7 && live) p[0] = acc + total;
+        if (part == PARTS - 1 && live) p[0] = acc + total;
         return;
     }
     for (int k = k0; k < k1; ++k) {
@@ -48,8 +54,19 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg
 
 hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s,
                        const float *init_S, const float *init_z, int DM) {
-    dim3 grid((stride + 31) / 32, BH);
-    scan_states_kernel<<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
+    if (nseg <= 4) {
+        dim3 grid((stride + 255) / 256, BH);
+        scan_states_kernel<1><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
+    } else if (nseg <= 16) {
+        dim3 grid((stride + 127) / 128, BH);
+        scan_states_kernel<2><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
+    } else if (nseg <= 32) {
+        dim3 grid((stride + 63) / 64, BH);
+        scan_states_kernel<4><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
+    } else {
+        dim3 grid((stride + 31) / 32, BH);
+        scan_states_kernel<8><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
+    }
     return hipGetLastError();
 }
 
