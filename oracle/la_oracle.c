@@ -25,6 +25,12 @@
  *   global_bwd_linear                the same gradient from the two global sums
  *                                    sum_j phi(K_j)[V_j,1]^T and sum_i phi(Q_i) Gt_i^T
  *                                    (eq. 5-6 differentiated; no causal mask)
+ *   causal_fwd_state                 eq. 10-12 started from a given (S_0, Z_0) instead of
+ *                                    zero, also returning (S_N, Z_N): the RNN view of
+ *                                    section 3.4 with its hidden state handed in and out
+ *   causal_bwd_state                 backpropagation through time for that RNN: the
+ *                                    loss gradient also arrives at (S_N, Z_N) and leaves
+ *                                    at (S_0, Z_0); same two loops as Algorithm 1 backward
  *   causal_bwd_linear                Algorithm 1 backward applied to values
  *                                    augmented with a column of ones, then the
  *                                    chain rule through phi (the paper leaves the
@@ -47,7 +53,10 @@
  * Pins (tests/test_oracle_*.py): prefix == quadratic == stepwise; linear
  * backward == brute-force backward == central finite differences == autograd
  * of the quadratic form; closed forms (Q = K = 0 gives a running mean, constant
- * V gives a constant output, N = 1); rational hand-worked case in tests/golden.
+ * V gives a constant output, N = 1); rational hand-worked case in tests/golden;
+ * the state-carrying pair: a sequence cut in two and chained through the state
+ * equals the uncut sequence (outputs and gradients), zero state equals the plain
+ * functions, central finite differences with respect to S_0, Z_0.
  */
 #include <math.h>
 #include <stdlib.h>
@@ -544,5 +553,126 @@ void la_oracle_global_bwd_linear(const double *Q, const double *K, const double 
             }
         }
         free(fq); free(fk); free(St); free(Rt); free(Gt);
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* eq. 10-12 with the running sums started at (S0, Z0) [BH, D, M] / [BH, D]  */
+/* (NULL: zero) and the sums after the last token returned in (S1, Z1)       */
+/* (NULL: not wanted).  With zero initial state this is causal_fwd_prefix.   */
+void la_oracle_causal_fwd_state(const double *Q, const double *K, const double *V,
+                                const double *S0, const double *Z0, double *O, double *den,
+                                double *S1, double *Z1,
+                                int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M;
+        double *Os = O + (size_t)s * N * M;
+        double *S = (double *)calloc((size_t)D * M, sizeof(double));
+        double *Z = (double *)calloc((size_t)D, sizeof(double));
+        double *fq = (double *)malloc(sizeof(double) * (size_t)D);
+        if (S0) memcpy(S, S0 + (size_t)s * D * M, sizeof(double) * (size_t)D * M);
+        if (Z0) memcpy(Z, Z0 + (size_t)s * D, sizeof(double) * (size_t)D);
+        for (int i = 0; i < N; ++i) {
+            for (int d = 0; d < D; ++d) {
+                double fk = la_oracle_phi(Ks[(size_t)i * D + d]);
+                for (int e = 0; e < M; ++e) S[(size_t)d * M + e] += fk * Vs[(size_t)i * M + e];
+                Z[d] += fk;
+            }
+            for (int d = 0; d < D; ++d) fq[d] = la_oracle_phi(Qs[(size_t)i * D + d]);
+            double dn = dot(fq, Z, D) + eps;
+            for (int e = 0; e < M; ++e) {
+                double a = 0.0;
+                for (int d = 0; d < D; ++d) a += fq[d] * S[(size_t)d * M + e];
+                Os[(size_t)i * M + e] = a / dn;
+            }
+            if (den) den[(size_t)s * N + i] = dn;
+        }
+        if (S1) memcpy(S1 + (size_t)s * D * M, S, sizeof(double) * (size_t)D * M);
+        if (Z1) memcpy(Z1 + (size_t)s * D, Z, sizeof(double) * (size_t)D);
+        free(S); free(Z); free(fq);
+    }
+}
+
+/* Backpropagation through time for the recurrence above.  The loss reaches   */
+/* the outputs through G_i = dL/dO_i and the final state through              */
+/* dS1 = dL/dS_N, dZ1 = dL/dZ_N (NULL: zero).  Step i reads the state         */
+/*   O_i = S_i^T phi(Q_i) / den_i,  den_i = phi(Q_i) . Z_i + eps,             */
+/* so it sends into the state the gradient                                    */
+/*   dS_i += phi(Q_i) (G_i/den_i)^T,   dZ_i += -(G_i . O_i)/den_i phi(Q_i),   */
+/* and dL/dphi(Q_i) = S_i G_i/den_i - (G_i . O_i)/den_i Z_i.  The state       */
+/* gradient then flows back through S_i = S_{i-1} + phi(K_i) V_i^T,           */
+/* Z_i = Z_{i-1} + phi(K_i):  dL/dphi(K_i) = dS_i V_i + dZ_i,                 */
+/* dL/dV_i = dS_i^T phi(K_i), and dS_{i-1} = dS_i, dZ_{i-1} = dZ_i.  What is   */
+/* left after token 1 is dL/dS_0, dL/dZ_0 (returned in dS0, dZ0 unless NULL).  */
+/* A first loop runs forward to get S_i (for dQ), a second one backward.      */
+void la_oracle_causal_bwd_state(const double *Q, const double *K, const double *V,
+                                const double *S0, const double *Z0, const double *G,
+                                const double *dS1, const double *dZ1,
+                                double *dQ, double *dK, double *dV, double *dS0, double *dZ0,
+                                int BH, int N, int D, int M, double eps) {
+#pragma omp parallel for schedule(dynamic)
+    for (int s = 0; s < BH; ++s) {
+        const double *Qs = Q + (size_t)s * N * D, *Ks = K + (size_t)s * N * D;
+        const double *Vs = V + (size_t)s * N * M, *Gs = G + (size_t)s * N * M;
+        double *dQs = dQ + (size_t)s * N * D, *dKs = dK + (size_t)s * N * D;
+        double *dVs = dV + (size_t)s * N * M;
+        double *S = (double *)calloc((size_t)D * M, sizeof(double));
+        double *Z = (double *)calloc((size_t)D, sizeof(double));
+        double *gS = (double *)calloc((size_t)D * M, sizeof(double));
+        double *gZ = (double *)calloc((size_t)D, sizeof(double));
+        double *fq = (double *)malloc(sizeof(double) * (size_t)D);
+        double *Gb = (double *)malloc(sizeof(double) * (size_t)N * M);   /* G_i / den_i      */
+        double *dl = (double *)malloc(sizeof(double) * (size_t)N);       /* -(G_i.O_i)/den_i */
+        if (S0) memcpy(S, S0 + (size_t)s * D * M, sizeof(double) * (size_t)D * M);
+        if (Z0) memcpy(Z, Z0 + (size_t)s * D, sizeof(double) * (size_t)D);
+        if (dS1) memcpy(gS, dS1 + (size_t)s * D * M, sizeof(double) * (size_t)D * M);
+        if (dZ1) memcpy(gZ, dZ1 + (size_t)s * D, sizeof(double) * (size_t)D);
+        /* forward in time: the state, the outputs, and the gradient for phi(Q) */
+        for (int i = 0; i < N; ++i) {
+            for (int d = 0; d < D; ++d) {
+                double fk = la_oracle_phi(Ks[(size_t)i * D + d]);
+                for (int e = 0; e < M; ++e) S[(size_t)d * M + e] += fk * Vs[(size_t)i * M + e];
+                Z[d] += fk;
+            }
+            for (int d = 0; d < D; ++d) fq[d] = la_oracle_phi(Qs[(size_t)i * D + d]);
+            double dn = dot(fq, Z, D) + eps;
+            double go = 0.0;
+            for (int e = 0; e < M; ++e) {
+                double a = 0.0;
+                for (int d = 0; d < D; ++d) a += fq[d] * S[(size_t)d * M + e];
+                go += Gs[(size_t)i * M + e] * (a / dn);
+                Gb[(size_t)i * M + e] = Gs[(size_t)i * M + e] / dn;
+            }
+            dl[i] = -go / dn;
+            for (int d = 0; d < D; ++d) {
+                double a = dl[i] * Z[d];
+                for (int e = 0; e < M; ++e) a += S[(size_t)d * M + e] * Gb[(size_t)i * M + e];
+                dQs[(size_t)i * D + d] = a * la_oracle_dphi(Qs[(size_t)i * D + d]);
+            }
+        }
+        /* backward in time: the state gradient, and the gradients for phi(K) and V */
+        for (int i = N - 1; i >= 0; --i) {
+            for (int d = 0; d < D; ++d) {
+                double q = la_oracle_phi(Qs[(size_t)i * D + d]);
+                for (int e = 0; e < M; ++e) gS[(size_t)d * M + e] += q * Gb[(size_t)i * M + e];
+                gZ[d] += dl[i] * q;
+            }
+            for (int d = 0; d < D; ++d) {
+                double a = gZ[d];
+                for (int e = 0; e < M; ++e) a += gS[(size_t)d * M + e] * Vs[(size_t)i * M + e];
+                dKs[(size_t)i * D + d] = a * la_oracle_dphi(Ks[(size_t)i * D + d]);
+            }
+            for (int e = 0; e < M; ++e) {
+                double a = 0.0;
+                for (int d = 0; d < D; ++d)
+                    a += gS[(size_t)d * M + e] * la_oracle_phi(Ks[(size_t)i * D + d]);
+                dVs[(size_t)i * M + e] = a;
+            }
+        }
+        if (dS0) memcpy(dS0 + (size_t)s * D * M, gS, sizeof(double) * (size_t)D * M);
+        if (dZ0) memcpy(dZ0 + (size_t)s * D, gZ, sizeof(double) * (size_t)D);
+        free(S); free(Z); free(gS); free(gZ); free(fq); free(Gb); free(dl);
     }
 }

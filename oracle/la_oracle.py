@@ -207,3 +207,47 @@ def global_bwd_quadratic(Q, K, V, G, eps=1e-6):
 def global_bwd_linear(Q, K, V, G, eps=1e-6):
     """Gradient of eq. 5-6 from the two global sums; O(N D M)."""
     return _bwd("la_oracle_global_bwd_linear", Q, K, V, G, eps)
+
+
+def _opt(a):
+    if a is None:
+        return None, None
+    return _c(a)
+
+
+def causal_fwd_state(Q, K, V, S0=None, Z0=None, eps=1e-6):
+    """eq. 10-12 started from (S0 [..., D, M], Z0 [..., D]) (None: zero).
+    Returns O, den, S_N, Z_N."""
+    lib = _load()
+    BH, N, D, M = _slabs(Q, V)
+    Q, pq = _c(Q); K, pk = _c(K); V, pv = _c(V)
+    S0, ps0 = _opt(S0); Z0, pz0 = _opt(Z0)
+    O = np.empty(V.shape, dtype=np.float64)
+    den = np.empty(Q.shape[:-1], dtype=np.float64)
+    S1 = np.empty(Q.shape[:-2] + (D, M), dtype=np.float64)
+    Z1 = np.empty(Q.shape[:-2] + (D,), dtype=np.float64)
+    lib.la_oracle_causal_fwd_state(pq, pk, pv, ps0, pz0, O.ctypes.data_as(_dp),
+                                   den.ctypes.data_as(_dp), S1.ctypes.data_as(_dp),
+                                   Z1.ctypes.data_as(_dp), ctypes.c_int(BH), ctypes.c_int(N),
+                                   ctypes.c_int(D), ctypes.c_int(M), ctypes.c_double(eps))
+    return O, den, S1, Z1
+
+
+def causal_bwd_state(Q, K, V, G, S0=None, Z0=None, dS1=None, dZ1=None, eps=1e-6):
+    """Backpropagation through time with the state gradient handed in (dS1, dZ1 at the
+    final state; None: zero) and out.  Returns dQ, dK, dV, dS0, dZ0."""
+    lib = _load()
+    BH, N, D, M = _slabs(Q, V)
+    Q, pq = _c(Q); K, pk = _c(K); V, pv = _c(V); G, pg = _c(G)
+    S0, ps0 = _opt(S0); Z0, pz0 = _opt(Z0); dS1, pds1 = _opt(dS1); dZ1, pdz1 = _opt(dZ1)
+    dQ = np.empty(Q.shape, dtype=np.float64)
+    dK = np.empty(K.shape, dtype=np.float64)
+    dV = np.empty(V.shape, dtype=np.float64)
+    dS0 = np.empty(Q.shape[:-2] + (D, M), dtype=np.float64)
+    dZ0 = np.empty(Q.shape[:-2] + (D,), dtype=np.float64)
+    lib.la_oracle_causal_bwd_state(pq, pk, pv, ps0, pz0, pg, pds1, pdz1, dQ.ctypes.data_as(_dp),
+                                   dK.ctypes.data_as(_dp), dV.ctypes.data_as(_dp),
+                                   dS0.ctypes.data_as(_dp), dZ0.ctypes.data_as(_dp),
+                                   ctypes.c_int(BH), ctypes.c_int(N), ctypes.c_int(D),
+                                   ctypes.c_int(M), ctypes.c_double(eps))
+    return dQ, dK, dV, dS0, dZ0

@@ -406,3 +406,100 @@ def test_global_bwd_finite_differences_and_closed_forms(oracle):
     Vc = np.broadcast_to(np.array([0.5, -1.0]), V.shape).copy()
     dQc, dKc, _ = oracle.global_bwd_linear(Q, K, Vc, G, 0.0)
     assert np.abs(dQc).max() < 1e-13 and np.abs(dKc).max() < 1e-13
+
+
+# ------------------------------------------------------------------ state handed in and out
+
+def _elu1(x):
+    return torch.nn.functional.elu(torch.tensor(x, dtype=torch.float64)).numpy() + 1.0
+
+
+def test_state_functions_with_zero_state_are_the_plain_ones(oracle):
+    Q, K, V, G = _rand(50, 2, 2, 19, 8, 5)
+    O, den, S1, Z1 = oracle.causal_fwd_state(Q, K, V, None, None, 1e-6)
+    ref, dref = oracle.causal_fwd_quadratic(Q, K, V, 1e-6, return_den=True)
+    np.testing.assert_allclose(O, ref, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(den, dref, rtol=1e-13)
+    # the final state is the pair of sums of eq. 5-6 over the whole sequence (library einsum)
+    np.testing.assert_allclose(S1, np.einsum("bhnd,bhnm->bhdm", _elu1(K), V), rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(Z1, _elu1(K).sum(2), rtol=1e-13)
+    got = oracle.causal_bwd_state(Q, K, V, G, eps=1e-6)
+    want = oracle.causal_bwd_quadratic(Q, K, V, G, 1e-6)
+    scale = max(np.abs(b).max() for b in want)
+    for a, b in zip(got[:3], want):
+        assert np.abs(a - b).max() / scale < 1e-12
+
+
+def test_state_equals_a_real_prefix(oracle):
+    """A state built from P real tokens stands for those tokens: outputs and gradients of the
+    remaining tokens equal those of the uncut sequence (brute force, eq. 8), and the gradient
+    that leaves through the state reproduces the prefix tokens' dK, dV."""
+    B, H, N, D, M, P = 1, 2, 17, 6, 4, 7
+    Q, K, V, G = _rand(51, B, H, N, D, M)
+    G[:, :, :P] = 0.0                               # the loss sees the tail only
+    eps = 1e-4
+    fk = _elu1(K[:, :, :P])
+    S0 = np.einsum("bhnd,bhnm->bhdm", fk, V[:, :, :P])
+    Z0 = fk.sum(2)
+    tail = [x[:, :, P:] for x in (Q, K, V, G)]
+    O, den, S1, Z1 = oracle.causal_fwd_state(*tail[:3], S0, Z0, eps)
+    ref = oracle.causal_fwd_quadratic(Q, K, V, eps)
+    np.testing.assert_allclose(O, ref[:, :, P:], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(S1, np.einsum("bhnd,bhnm->bhdm", _elu1(K), V), rtol=1e-12, atol=1e-13)
+    dQ, dK, dV, dS0, dZ0 = oracle.causal_bwd_state(*tail, S0, Z0, None, None, eps)
+    wq, wk, wv = oracle.causal_bwd_quadratic(Q, K, V, G, eps)
+    scale = max(np.abs(b).max() for b in (wq, wk, wv))
+    for a, b in ((dQ, wq), (dK, wk), (dV, wv)):
+        assert np.abs(a - b[:, :, P:]).max() / scale < 1e-12
+    # prefix token p entered the state as phi(K_p) V_p^T and phi(K_p)
+    dphi = np.where(K[:, :, :P] > 0, 1.0, np.exp(np.minimum(K[:, :, :P], 0.0)))
+    dK_prefix = (np.einsum("bhdm,bhnm->bhnd", dS0, V[:, :, :P]) + dZ0[:, :, None, :]) * dphi
+    dV_prefix = np.einsum("bhdm,bhnd->bhnm", dS0, fk)
+    assert np.abs(dK_prefix - wk[:, :, :P]).max() / scale < 1e-12
+    assert np.abs(dV_prefix - wv[:, :, :P]).max() / scale < 1e-12
+
+
+def test_two_chained_pieces_equal_the_uncut_sequence(oracle):
+    B, H, N, D, M, cut = 2, 1, 29, 5, 7, 11
+    Q, K, V, G = _rand(52, B, H, N, D, M)
+    eps = 1e-6
+    a = [x[:, :, :cut] for x in (Q, K, V, G)]
+    b = [x[:, :, cut:] for x in (Q, K, V, G)]
+    Oa, _, Sa, Za = oracle.causal_fwd_state(*a[:3], None, None, eps)
+    Ob, _, _, _ = oracle.causal_fwd_state(*b[:3], Sa, Za, eps)
+    ref = oracle.causal_fwd_quadratic(Q, K, V, eps)
+    np.testing.assert_allclose(np.concatenate([Oa, Ob], 2), ref, rtol=1e-12, atol=1e-14)
+    gb = oracle.causal_bwd_state(*b, Sa, Za, None, None, eps)
+    ga = oracle.causal_bwd_state(*a, None, None, gb[3], gb[4], eps)
+    want = oracle.causal_bwd_quadratic(Q, K, V, G, eps)
+    scale = max(np.abs(w).max() for w in want)
+    for xa, xb, w in zip(ga[:3], gb[:3], want):
+        assert np.abs(np.concatenate([xa, xb], 2) - w).max() / scale < 1e-12
+
+
+def test_state_gradients_against_central_finite_differences(oracle):
+    B, H, N, D, M = 1, 1, 5, 3, 2
+    Q, K, V, G = _rand(53, B, H, N, D, M)
+    rng = np.random.default_rng(54)
+    S0 = rng.standard_normal((B, H, D, M))
+    Z0 = rng.uniform(0.5, 2.0, (B, H, D))
+    W = rng.standard_normal((B, H, D, M))           # dL/dS_N
+    w = rng.standard_normal((B, H, D))              # dL/dZ_N
+    eps = 1e-3
+
+    def loss(q, k, v, s0, z0):
+        O, _, S1, Z1 = oracle.causal_fwd_state(q, k, v, s0, z0, eps)
+        return float((G * O).sum() + (W * S1).sum() + (w * Z1).sum())
+
+    grads = oracle.causal_bwd_state(Q, K, V, G, S0, Z0, W, w, eps)
+    args = [Q, K, V, S0, Z0]
+    h = 1e-6
+    for which, dX in enumerate(grads):
+        fd = np.zeros_like(args[which])
+        for idx in np.ndindex(fd.shape):
+            up = [x.copy() for x in args]
+            dn = [x.copy() for x in args]
+            up[which][idx] += h
+            dn[which][idx] -= h
+            fd[idx] = (loss(*up) - loss(*dn)) / (2 * h)
+        np.testing.assert_allclose(dX, fd, rtol=3e-6, atol=1e-8)
