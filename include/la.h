@@ -130,6 +130,26 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
                   void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The same backward for a piece of a sequence whose recurrent state was handed in
+ * and out by la_causal_fwd_state (backpropagation through time for the RNN of
+ * eq. 16-20, section 3.4).  S0, z0: the state before token 0 that the forward
+ * started from (both NULL: zero).  dS1 [B,H,D,M], dz1 [B,H,D] fp32 in: gradient
+ * of the loss with respect to the state after token N-1, from whatever consumed
+ * that state (both NULL: zero); it is the starting value of the reverse sum of
+ * eq. 14-15.  dS0, dz0 fp32 out (both NULL: not wanted): gradient with respect
+ * to (S0, z0), i.e. the reverse sum after token 0, to be handed to the piece
+ * before as its dS1, dz1.  Pieces chained this way reproduce the gradients of
+ * the uncut sequence.  O, den, fwd_ws: results (and workspace) of
+ * la_causal_fwd_state with the same S0, z0; O/den NULL: recomputed.  The
+ * in-buffers must not alias the out-buffers.  Workspace as la_causal_bwd.
+ */
+int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float *S0,
+                        const float *z0, const void *O, const float *den, const void *fwd_ws,
+                        const void *dO, const float *dS1, const float *dz1, void *dQ, void *dK,
+                        void *dV, float *dS0, float *dz0, int B, int H, int N, int D, int M,
+                        float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Non-causal linear attention, forward (eq. 5-6): the sums over all N keys are
  * formed once and reused for every query,
  *   O_i = phi(Q_i)^T (sum_j phi(K_j) V_j^T) / (phi(Q_i) . sum_j phi(K_j) + eps).

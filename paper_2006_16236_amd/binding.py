@@ -20,7 +20,7 @@ LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN = -4, -5, -6
 
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
            "la_global_fwd_workspace", "la_global_bwd_workspace", "la_causal_fwd", "la_causal_fwd_state",
-           "la_causal_bwd", "la_global_fwd", "la_global_bwd",
+           "la_causal_bwd", "la_causal_bwd_state", "la_global_fwd", "la_global_bwd",
            "la_recurrent_step", "la_recurrent_steps", "la_kernel_name", "la_profile_begin",
            "la_profile_end")
 LA_K_COUNT = 10
@@ -57,6 +57,8 @@ def _load() -> ctypes.CDLL:
     lib.la_causal_fwd_state.argtypes = [vp] * 9 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_causal_bwd.restype = i
     lib.la_causal_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_causal_bwd_state.restype = i
+    lib.la_causal_bwd_state.argtypes = [vp] * 16 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_global_fwd.restype = i
     lib.la_global_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_global_bwd.restype = i
@@ -172,6 +174,23 @@ def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=Non
     _check(_lib.la_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
                               _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
                               wp, wb, _stream(stream)), "la_causal_bwd")
+    return ws
+
+
+def la_causal_bwd_state(Q, K, V, O, den, dO, dQ, dK, dV, S0=None, z0=None, dS1=None, dz1=None,
+                        dS0=None, dz0=None, eps=1e-6, ws=None, stream=None, fwd_ws=None):
+    """la_causal_bwd for a piece whose forward started from (S0, z0): (dS1, dz1) is the gradient
+    arriving at the state after the last token (None: zero), (dS0, dz0) receives the gradient
+    for (S0, z0) (None: not wanted); all fp32 [B,H,D,M] / [B,H,D]."""
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q)
+    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_causal_bwd_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O),
+                                    _ptr(den), _ptr(fwd_ws), _ptr(dO), _ptr(dS1), _ptr(dz1),
+                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dS0), _ptr(dz0), B, H, N, D,
+                                    M, float(eps), t, wp, wb, _stream(stream)),
+           "la_causal_bwd_state")
     return ws
 
 

@@ -256,18 +256,23 @@ int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float
                           static_cast<hipStream_t>(stream), S0, z0, S1, z1);
 }
 
-int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
-                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
-                  int B, int H, int N, int D, int M, float eps, la_dtype t,
-                  void *ws, size_t ws_bytes, void *stream) {
+static int causal_bwd_impl(const void *Q, const void *K, const void *V, const float *S0,
+                           const float *z0, const void *O, const float *den, const void *fwd_ws,
+                           const void *dO, const float *dS1, const float *dz1, void *dQ, void *dK,
+                           void *dV, float *dS0, float *dz0, int B, int H, int N, int D, int M,
+                           float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream) {
     if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr ||
         dK == nullptr || dV == nullptr)
+        return LA_ERR_NULL;
+    if ((S0 == nullptr) != (z0 == nullptr) || (dS1 == nullptr) != (dz1 == nullptr) ||
+        (dS0 == nullptr) != (dz0 == nullptr))
         return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) ||
         misaligned(dK) || misaligned(dV) || misaligned(O) || misaligned(den) || misaligned(ws) ||
-        misaligned(fwd_ws))
+        misaligned(fwd_ws) || misaligned(S0) || misaligned(z0) || misaligned(dS1) ||
+        misaligned(dz1) || misaligned(dS0) || misaligned(dz0))
         return LA_ERR_ALIGN;
     const size_t need = la_causal_bwd_workspace(B, H, N, D, M, t);
     if (ws == nullptr || ws_bytes < need) return LA_ERR_WORKSPACE;
@@ -292,7 +297,7 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
     if (recompute_fwd) {                       // recompute the forward results
         void *Otmp = cv.take(rows * M * esize(t));
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
-        const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s);
+        const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s, S0, z0);
         if (fs != LA_OK) return fs;
         O = Otmp;
         den = dentmp;
@@ -310,22 +315,41 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
             sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = stS;
             sa.skip_seg = p.nseg - 1;
             { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
-            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s)); }
+            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
         }
         sa.Y = Q; sa.Z = dO; sa.rden = nullptr; sa.delta = nullptr; sa.state = stR;
         sa.O = O; sa.den = den; sa.rden_out = rden; sa.delta_out = delta;
         sa.skip_seg = -1;          // every segment must produce its tokens' scalars
         { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(2, D, M, (int)t, sa, nblocks, s)); }
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanReverse, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
     }
     la::PassArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
     a.out = dQ; a.state = stS;
+    a.init_S = S0; a.init_z = z0;            // read only where the sequences are not cut
     { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(D, M, (int)t, a, nblocks, s)); }
     a.out = dV; a.out2 = dK; a.state = stR;
+    a.init_S = dS1; a.init_z = dz1; a.final_S = dS0; a.final_z = dz0;
     { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks, s)); }
     return LA_OK;
+}
+
+int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream) {
+    return causal_bwd_impl(Q, K, V, nullptr, nullptr, O, den, fwd_ws, dO, nullptr, nullptr, dQ, dK,
+                           dV, nullptr, nullptr, B, H, N, D, M, eps, t, ws, ws_bytes, stream);
+}
+
+int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float *S0,
+                        const float *z0, const void *O, const float *den, const void *fwd_ws,
+                        const void *dO, const float *dS1, const float *dz1, void *dQ, void *dK,
+                        void *dV, float *dS0, float *dz0, int B, int H, int N, int D, int M,
+                        float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream) {
+    return causal_bwd_impl(Q, K, V, S0, z0, O, den, fwd_ws, dO, dS1, dz1, dQ, dK, dV, dS0, dz0, B, H,
+                           N, D, M, eps, t, ws, ws_bytes, stream);
 }
 
 int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den,

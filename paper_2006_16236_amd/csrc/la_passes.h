@@ -68,8 +68,12 @@ struct PassArgs {
     void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
     float *den;                  // [BH, N] or null             (kFwd, kGlobal)
     const float *state;          // [BH, nseg, state_stride] exclusive states; null = zero state
-    const float *init_S, *init_z;  // kFwd, nseg == 1: state before token 0, [BH, D, M] / [BH, D]; may be null
-    float *final_S, *final_z;      // kFwd: state after the last token, same shapes; may be null
+    // State at the end a pass starts from, used when the sequences are not cut (nseg == 1),
+    // [BH, D, M] / [BH, D], may be null: kFwd, kDq the sums before token 0; kDv (matrix) and
+    // kDk (vector) the gradient that arrives at the state after the last token.
+    const float *init_S, *init_z;
+    // kFwd: state after the last token; kDv / kDk: gradient for the state before token 0.
+    float *final_S, *final_z;      // same shapes; may be null
     int N, nseg, chunks_per_seg;
     float eps;
 };
@@ -349,18 +353,30 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         }
     }
 
-    if constexpr (PASS == kFwd) {
-        if (a.state == nullptr && a.init_S != nullptr) {      // caller-supplied initial state
+    if constexpr (kHasYZ) {
+        // caller-supplied state at the end the pass starts from (sequences that are not cut;
+        // otherwise the scan has already folded it into the segment states): [D][M] and [D]
+        if (a.state == nullptr && a.init_S != nullptr) {
             const float *s0 = a.init_S + (size_t)bh * D * M;
             const float *z0 = a.init_z + (size_t)bh * D;
 #pragma unroll
             for (int xt = 0; xt < XT; ++xt) {
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt)
+                for (int zt = 0; zt < ZT; ++zt) {
+                    if constexpr (kStateMode == kBorrowState) continue;
+                    if constexpr (kXisD) {
 #pragma unroll
-                    for (int r = 0; r < 4; ++r)
-                        U[xt][zt][r] = s0[(16 * xt + 4 * g + r) * M + 16 * zt + c];
-                zg[xt] = load4(z0 + 16 * xt + 4 * g);
+                        for (int r = 0; r < 4; ++r)
+                            U[xt][zt][r] = s0[(16 * xt + 4 * g + r) * M + 16 * zt + c];
+                    } else {
+                        U[xt][zt] = load4(s0 + (16 * zt + c) * M + 16 * xt + 4 * g);
+                    }
+                }
+                if constexpr (PASS == kFwd) zg[xt] = load4(z0 + 16 * xt + 4 * g);
+            }
+            if constexpr (PASS == kDq || PASS == kDk) {
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt) ecp[zt] = g == 0 ? z0[16 * zt + c] : 0.f;
             }
         }
     }
@@ -588,6 +604,30 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     for (int r = 0; r < 4; ++r)
                         s1[(16 * xt + 4 * g + r) * M + 16 * zt + c] = U[xt][zt][r];
                 if (c == 0) *reinterpret_cast<f32x4 *>(z1 + 16 * xt + 4 * g) = zg[xt];
+            }
+        }
+    }
+    // reverse passes: what has piled up when the wave of the first segment is through is the
+    // gradient that leaves through the initial state (kDv carries the matrix, kDk the vector)
+    if constexpr (PASS == kDv) {
+        if (a.final_S != nullptr && seg == 0) {
+            float *s1 = a.final_S + (size_t)bh * D * M;
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        s1[(16 * xt + 4 * g + r) * M + 16 * zt + c] = U[xt][zt][r];
+        }
+    }
+    if constexpr (PASS == kDk) {
+        if (a.final_z != nullptr && seg == 0) {
+            float *z1 = a.final_z + (size_t)bh * D;
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt) {
+                const float e = sum_over_groups(ecp[zt]);
+                if (g == 0) z1[16 * zt + c] = e;
             }
         }
     }

@@ -95,6 +95,22 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert bwd(p, p, p, p, p, null, p, p, p, odd, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
     assert bwd(p, p, p, p, p, odd, p, p, p, p, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null) == b.LA_ERR_ALIGN
 
+    bws = lib.la_causal_bwd_state
+    # Q K V S0 z0 O den fwd_ws dO dS1 dz1 dQ dK dV dS0 dz0
+    ok16 = [p, p, p, null, null, p, p, null, p, null, null, p, p, p, null, null]
+    tail = (1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 30, null)
+    for pos in (3, 9, 14):                      # one half of a state pair without the other
+        args = list(ok16)
+        args[pos] = p
+        assert bws(*args, *tail) == b.LA_ERR_NULL
+    args = list(ok16)
+    args[8] = null
+    assert bws(*args, *tail) == b.LA_ERR_NULL
+    args = list(ok16)
+    args[14], args[15] = p, odd
+    assert bws(*args, *tail) == b.LA_ERR_ALIGN
+    assert bws(*ok16, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
+
     glob = lib.la_global_fwd
     assert glob(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
     assert glob(p, p, null, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 20, null) == b.LA_ERR_NULL

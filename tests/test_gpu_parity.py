@@ -277,6 +277,88 @@ def test_forward_with_state_in_and_out(la, oracle, sched):
     assert rel_err(zb.cpu().numpy(), fk.sum(2)) <= 1e-4
 
 
+def _state_case(seed, B, H, N, D, M):
+    """Inputs plus a non-zero initial state and a non-zero gradient arriving at the final state
+    (the state is that of P imaginary earlier tokens: positive z0, S0 of matching size)."""
+    Q, K, V, G = wl.random_case(seed, B, H, N, D, M)
+    rng = np.random.default_rng(seed + 7)
+    S0 = (rng.standard_normal((B, H, D, M)) * 3.0).astype(np.float32)
+    z0 = rng.uniform(2.0, 9.0, (B, H, D)).astype(np.float32)
+    dS1 = (rng.standard_normal((B, H, D, M)) * 0.5).astype(np.float32)
+    dz1 = (rng.standard_normal((B, H, D)) * 0.5).astype(np.float32)
+    return Q, K, V, G, S0, z0, dS1, dz1
+
+
+def _gpu_bwd_state(la, Q, K, V, G, S0, z0, dS1, dz1, eps, reuse="all", want_state_grad=True):
+    dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+    s0, zz0, ds1, dzz1 = (None if x is None else to_dev(x) for x in (S0, z0, dS1, dz1))
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    O = torch.empty_like(dv)
+    den = torch.empty(B, H, N, device=DEV)
+    fwd_ws = la.la_causal_fwd_state(dq, dk, dv, O, den, s0, zz0, None, None, eps)
+    gq, gk, gv = (torch.full_like(x, float("nan")) for x in (dq, dk, dv))
+    ds0 = torch.full((B, H, D, M), float("nan"), device=DEV) if want_state_grad else None
+    dzz0 = torch.full((B, H, D), float("nan"), device=DEV) if want_state_grad else None
+    la.la_causal_bwd_state(dq, dk, dv, O if reuse != "recompute" else None,
+                           den if reuse != "recompute" else None, dg, gq, gk, gv, s0, zz0, ds1, dzz1,
+                           ds0, dzz0, eps, fwd_ws=fwd_ws if reuse == "all" else None)
+    torch.cuda.synchronize()
+    out = [to_host(gq), to_host(gk), to_host(gv)]
+    if want_state_grad:
+        out += [ds0.cpu().numpy(), dzz0.cpu().numpy()]
+    return out
+
+
+@pytest.mark.parametrize("sched", list(SCHEDULES))
+@pytest.mark.parametrize("N", [1, 16, 17, 100, 257, 1000])
+def test_backward_with_state_gradient_in_and_out(la, oracle, N, sched):
+    B, H, D, M = 2, 2, 64, 64
+    Q, K, V, G, S0, z0, dS1, dz1 = _state_case(930 + N, B, H, N, D, M)
+    ref = oracle.causal_bwd_state(Q, K, V, G, S0, z0, dS1, dz1, 1e-6)
+    with schedule(**SCHEDULES[sched]):
+        got = _gpu_bwd_state(la, Q, K, V, G, S0, z0, dS1, dz1, 1e-6)
+    assert max(grad_errs(got[:3], ref[:3])) <= tol_for(N)
+    assert rel_err(got[3], ref[3]) <= tol_for(N)
+    assert rel_err(got[4], ref[4]) <= tol_for(N)
+
+
+@pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32)])
+@pytest.mark.parametrize("reuse", ["all", "no_states", "recompute"])
+def test_backward_with_state_head_sizes_and_recompute(la, oracle, D, M, reuse):
+    B, H, N = 1, 3, 333
+    Q, K, V, G, S0, z0, dS1, dz1 = _state_case(960 + D + 2 * M, B, H, N, D, M)
+    ref = oracle.causal_bwd_state(Q, K, V, G, S0, z0, dS1, dz1, 1e-6)
+    for sched in ("one_segment", "three_chunk_segments"):
+        with schedule(**SCHEDULES[sched]):
+            got = _gpu_bwd_state(la, Q, K, V, G, S0, z0, dS1, dz1, 1e-6, reuse=reuse)
+        assert max(grad_errs(got[:3], ref[:3])) <= tol_for(N), sched
+        assert rel_err(got[3], ref[3]) <= tol_for(N) and rel_err(got[4], ref[4]) <= tol_for(N), sched
+
+
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+def test_backward_chained_over_two_pieces_equals_the_uncut_sequence(la, oracle, sched):
+    """Forward piece by piece through the state, backward piece by piece in reverse through the
+    state gradient: the gradients equal those of the uncut sequence (oracle: Algorithm 1 backward
+    on the whole sequence, which knows nothing of pieces)."""
+    B, H, D, M = 2, 2, 64, 64
+    N1, N2 = 200, 350
+    Q, K, V, G = wl.random_case(990, B, H, N1 + N2, D, M)
+    ref = oracle.causal_bwd_linear(Q, K, V, G, 1e-6)
+    a = [np.ascontiguousarray(x[:, :, :N1]) for x in (Q, K, V, G)]
+    b = [np.ascontiguousarray(x[:, :, N1:]) for x in (Q, K, V, G)]
+    with schedule(**SCHEDULES[sched]):
+        da = [to_dev(x) for x in a[:3]]
+        Oa = torch.empty_like(da[2])
+        Sa = torch.empty(B, H, D, M, device=DEV); za = torch.empty(B, H, D, device=DEV)
+        la.la_causal_fwd_state(*da, Oa, None, None, None, Sa, za, 1e-6)
+        torch.cuda.synchronize()
+        gb = _gpu_bwd_state(la, *b, Sa.cpu().numpy(), za.cpu().numpy(), None, None, 1e-6)
+        ga = _gpu_bwd_state(la, *a, None, None, gb[3], gb[4], 1e-6, want_state_grad=False)
+    got = [np.concatenate([x, y], axis=2) for x, y in zip(ga[:3], gb[:3])]
+    assert max(grad_errs(got, ref)) <= tol_for(N1 + N2)
+
+
 def test_bitwise_determinism_and_slab_independence(la):
     B, H, N, D, M = 2, 4, 500, 64, 64
     Q, K, V, G = wl.random_case(800, B, H, N, D, M)
