@@ -289,46 +289,39 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
         stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
         stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
     }
-    const bool recompute_fwd = (O == nullptr || den == nullptr);
+    (void)O;                                   // not read: delta is rebuilt from the state
+    const bool recompute_fwd = (den == nullptr);
     // the forward's own workspace still holds the prefix states: no need to rebuild them
     const bool have_states = p.nseg > 1 && (fwd_ws != nullptr || recompute_fwd);
     if (p.nseg > 1 && fwd_ws != nullptr && !recompute_fwd)
         stS = const_cast<float *>(static_cast<const float *>(fwd_ws));
-    if (recompute_fwd) {                       // recompute the forward results
+    if (recompute_fwd) {                       // recompute the forward's denominators
         void *Otmp = cv.take(rows * M * esize(t));
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
         const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s, S0, z0);
         if (fs != LA_OK) return fs;
-        O = Otmp;
         den = dentmp;
     }
-    // the per-token scalars 1/den and delta: fused into the Q, dO segment sums when the
-    // sequences are cut into segments, a sweep of its own otherwise
-    if (p.nseg == 1)
-        { ProfScope ps(LA_K_PREP, s); LA_TRY(la::launch_bwd_prep(dO, O, den, rden, delta, rows, M, (int)t, s)); }
-
     const int nblocks = (int)(BH * p.nseg);
-    if (p.nseg > 1) {
+    if (p.nseg > 1 && !have_states) {
         la::SegArgs sa{};
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps;
-        if (!have_states) {
-            sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = stS;
-            sa.skip_seg = p.nseg - 1;
-            { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
-            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
-        }
-        sa.Y = Q; sa.Z = dO; sa.rden = nullptr; sa.delta = nullptr; sa.state = stR;
-        sa.O = O; sa.den = den; sa.rden_out = rden; sa.delta_out = delta;
-        sa.skip_seg = -1;          // every segment must produce its tokens' scalars
-        { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(2, D, M, (int)t, sa, nblocks, s)); }
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
+        sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = stS;
+        sa.skip_seg = p.nseg - 1;
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
+    // forward direction: dQ; on the way 1/den and delta per token and, when the sequences
+    // are cut, the per-segment sums that the reverse direction starts from
     la::PassArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
+    a.den_in = den; a.rden_out = rden; a.delta_out = delta; a.totals = stR;
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
     a.out = dQ; a.state = stS;
     a.init_S = S0; a.init_z = z0;            // read only where the sequences are not cut
     { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(D, M, (int)t, a, nblocks, s)); }
+    if (p.nseg > 1)
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
     a.out = dV; a.out2 = dK; a.state = stR;
     a.init_S = dS1; a.init_z = dz1; a.final_S = dS0; a.final_z = dz0;
     { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks, s)); }

@@ -14,19 +14,20 @@ constexpr int kChunk = 16;       // tokens per chunk = MFMA tile edge
 constexpr int kWave = 64;
 
 // ---- feature map (paper eq. 7): phi(x) = elu(x) + 1 ------------------------------------
-// x > 0: x + 1; otherwise exp(x).  Both branches are evaluated and one is SELECTED: for a
-// large positive x the exponential overflows to +inf, which the select discards (a select
-// never turns inf into NaN, a multiply by zero would).  fp32 vector instructions and fp32
-// MFMAs share one pipeline on this chip, so every instruction saved here is matrix time won.
-__device__ __forceinline__ float phi(float x) {
-    const float e = __expf(x);
-    return x > 0.0f ? x + 1.0f : e;
-}
-// phi'(x) = 1 for x > 0, exp(x) otherwise.
+// x > 0: x + 1; otherwise exp(x).  Written without a branch or a select:
+//   t      = min(exp(x), 1) = exp(min(x, 0))      (one exponential, result clamped to [0, 1];
+//                                                  an overflow to +inf for large x clamps to 1)
+//   phi'(x) = t                                   (1 for x > 0, exp(x) otherwise)
+//   phi(x)  = max(x + 1, t)                       (exp(x) >= x + 1 everywhere, and t = 1 < x + 1
+//                                                  for x > 0)
+// fp32 vector instructions and fp32 MFMAs share one pipeline on this chip, so every
+// instruction saved here is matrix time won.
 __device__ __forceinline__ float dphi(float x) {
-    const float e = __expf(x);
-    return x > 0.0f ? 1.0f : e;
+    return __builtin_amdgcn_fmed3f(__expf(x), 0.0f, 1.0f);
 }
+__device__ __forceinline__ float phi(float x) { return fmaxf(x + 1.0f, dphi(x)); }
+// phi' from phi: x + 1 > 1 for x > 0, exp(x) <= 1 otherwise, so phi' = min(phi, 1) (phi > 0)
+__device__ __forceinline__ float dphi_from_phi(float f) { return __builtin_amdgcn_fmed3f(f, 0.0f, 1.0f); }
 
 // ---- element types ------------------------------------------------------------------------
 struct bf16_t { uint16_t bits; };

@@ -5,8 +5,8 @@ namespace la {
 
 hipError_t launch_pass_dq(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s) {
     LA_DISPATCH_DM(D, M, {
-        if (dtype == 0) causal_pass_kernel<kDq, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
-        else causal_pass_kernel<kDq, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
+        if (dtype == 0) dq_pass_kernel<kD, kM, float><<<nblocks, 2 * kWave, 0, s>>>(a);
+        else dq_pass_kernel<kD, kM, bf16_t><<<nblocks, 2 * kWave, 0, s>>>(a);
     });
     return hipGetLastError();
 }

@@ -27,8 +27,12 @@
 //
 // The denominator of eq. 12 rides along as the "ones column" of the values:
 //   kFwd  also carries z = sum phi(K_b) and forms den_a = rowsum(mask(XY^T)) + X_a.z + eps;
-//   kDq   adds delta_a to every kept entry of X Y^T and delta_a * z to the state term,
-//         delta_a = -(dO_a . O_a)/den_a being the gradient that reaches den_a;
+//   kDq   needs delta_a = -(dO_a . O_a)/den_a, the gradient that reaches den_a.  It does not
+//         read O for it: with A_a = S_a dO_a/den_a (its own result before the ones column is
+//         added) dO_a . O_a = phi(Q_a) . A_a, so delta_a = -(phi(Q_a) . A_a)/den_a.  Then
+//         dphi(Q)_a = A_a + delta_a z_a with z_a = z + the in-chunk running sum of phi(K)
+//         (one more product against the constant lower-triangular mask).  delta and 1/den
+//         are written out for the reverse passes;
 //   kDk   adds delta_b to every kept entry and carries rho = sum delta_b phi(Q_b).
 // kDq and kDk finish with the chain rule through phi (times phi'(Q), phi'(K)).
 //
@@ -67,6 +71,10 @@ struct PassArgs {
     void *out;                   // [BH, N, DZ]  (reverse_pass_kernel: dV)
     void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
     float *den;                  // [BH, N] or null             (kFwd, kGlobal)
+    const float *den_in;         // kDq: the forward's denominators [BH, N]
+    float *rden_out, *delta_out; // kDq: [BH, N] 1/den_i and delta_i for the reverse passes
+    float *totals;               // kDq: [BH, nseg, state_stride] per-segment sums of
+                                 // phi(Q)^T dO/den and delta phi(Q), or null
     const float *state;          // [BH, nseg, state_stride] exclusive states; null = zero state
     // State at the end a pass starts from, used when the sequences are not cut (nseg == 1),
     // [BH, D, M] / [BH, D], may be null: kFwd, kDq the sums before token 0; kDv (matrix) and
@@ -318,6 +326,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     f32x4 zg[XT];      // kFwd/kGlobal: z[16xt + 4g + r]  (lines up with the token-lane X)
     float ecp[ZT];     // kDq: z[16zt + c], kDk: rho[16zt + c], as per-lane partial sums: the
                        // four lanes (c, g = 0..3) together hold the value (an MFMA adds them up)
+    float rho[ZT];     // kDq: this segment's sum of delta_b phi(Q_b)[16zt + c], same partial form
 #pragma unroll
     for (int xt = 0; xt < XT; ++xt) {
 #pragma unroll
@@ -325,7 +334,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         zg[xt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
-    for (int zt = 0; zt < ZT; ++zt) ecp[zt] = 0.f;
+    for (int zt = 0; zt < ZT; ++zt) ecp[zt] = rho[zt] = 0.f;
 
     if (a.state != nullptr) {
         const float *st = a.state +
@@ -402,6 +411,11 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         stg.template park<kSlot>(nvalid);
         const float dl1 = stg.dl1;
         const float dl4[4] = {stg.dl4[0], stg.dl4[1], stg.dl4[2], stg.dl4[3]};
+        float rd4[4] = {0.f, 0.f, 0.f, 0.f};          // kDq: 1/den of tokens 4g + s (0 past the end)
+        if constexpr (PASS == kDq) {
+#pragma unroll
+            for (int s = 0; s < 4; ++s) rd4[s] = stg.rd4[s];
+        }
         if (it + kDepth < count) stg.template fetch<kSlot>(ch + dir * kDepth);
         if constexpr (kStateMode == kPublishState) {
             // U as it stands before this chunk (the exclusive state), element (row 16xt + 4g + r,
@@ -480,7 +494,6 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 float v = w0[r] + w1[r];
-                if constexpr (PASS == kDq) v += dl1;
                 if constexpr (PASS == kDk) v += dl4[r];
                 const bool keep = kReverse ? (4 * g + r) >= c : (4 * g + r) <= c;
                 w[r] = keep ? v : 0.f;               // select, never multiply
@@ -493,11 +506,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     for (int r = 0; r < 4; ++r) p = fmaf(xa[xt][r], zg[xt][r], p);
                 den4 = mfma16(p, 1.0f, eps4);
             }
-            // the ones-column part of the state term: delta_a * z (kDq), rho (kDk)
-            if constexpr (PASS == kDq || PASS == kDk) {
+            // the ones-column part of the state term: rho (kDk; kDq adds its own further down)
+            if constexpr (PASS == kDk) {
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt)
-                    out[zt] = mfma16(PASS == kDq ? dl1 : 1.0f, ecp[zt], out[zt]);
+                for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16(1.0f, ecp[zt], out[zt]);
             }
             // ---- in-chunk term: out += W Z -------------------------------------------------
             lds_feature_lane<DZ>(lds_z, c, g, zf);
@@ -521,28 +533,71 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 for (int zt = 0; zt < ZT; ++zt) out[zt][r] *= ri;
             }
         }
-        if constexpr (kHasRaw) {
-            float dp[ZT][4];             // phi' of the raw Q (kDq) or K (kDk) under the output
+        if constexpr (PASS == kDq) {
+            // `out` is A_a = S_a dO_a/den_a so far (rows: tokens 4g + r, columns: features
+            // 16zt + c).  delta_a = -(phi(Q_a) . A_a)/den_a: multiply by phi(Q) in the same
+            // layout, add up the 16 lanes of the group and the ZT registers.
+            float fq[ZT][4];
+            lds_feature_lane<DZ>(lds_r, c, g, fq);
+            float d4[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float p = out[0][r] * fq[0][r];
+#pragma unroll
+                for (int zt = 1; zt < ZT; ++zt) p = fmaf(out[zt][r], fq[zt][r], p);
+                d4[r] = -row_sum16(p) * rd4[r];
+            }
+            // z_a = z before the chunk (an MFMA against ones adds the four partial sums and
+            // leaves the total in every register) + running sum of phi(K) up to token a (the
+            // constant lower-triangular mask times the phi(K) tile)
+            f32x4 cz[ZT];
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(1.0f, ecp[zt], f32x4{0.f, 0.f, 0.f, 0.f});
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                const float m = (4 * g + s) <= c ? 1.0f : 0.0f;
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(m, zf[zt][s], cz[zt]);
+            }
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt) {
+                float rp = 0.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    rp = fmaf(d4[r], fq[zt][r], rp);
+                    out[zt][r] = fmaf(d4[r], cz[zt][r], out[zt][r]) * dphi_from_phi(fq[zt][r]);
+                }
+                rho[zt] += rp;
+            }
+            // lanes c < 4 of each group write 1/den and delta of token 4g + c
+            const float dsel = c == 0 ? d4[0] : c == 1 ? d4[1] : c == 2 ? d4[2] : d4[3];
+            const float rsel = c == 0 ? rd4[0] : c == 1 ? rd4[1] : c == 2 ? rd4[2] : rd4[3];
+            if (c < 4 && 4 * g + c < nvalid) {
+                a.delta_out[rowbase + t0 + 4 * g + c] = dsel;
+                a.rden_out[rowbase + t0 + 4 * g + c] = rsel;
+            }
+        } else if constexpr (kHasRaw) {
+            float dp[ZT][4];             // phi' of the raw Q (kGlobalDq) or K (kDk) under the output
             lds_feature_lane<DZ>(lds_r, c, g, dp);
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) out[zt][r] *= dp[zt][r];
         }
-        T *chunk_out = outs + (size_t)t0 * DZ;          // uniform; lane offsets stay 32-bit
+        // uniform chunk base + one lane offset; the 16 stores differ by constants only
+        T *lane_out = outs + (size_t)t0 * DZ + (4 * g * DZ + c);
         if (nvalid == kChunk) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt)
-                    store_elem(chunk_out + ((4 * g + r) * DZ + c + 16 * zt), out[zt][r]);
+                for (int zt = 0; zt < ZT; ++zt) store_elem(lane_out + (r * DZ + 16 * zt), out[zt][r]);
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 if (4 * g + r < nvalid) {
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt)
-                        store_elem(chunk_out + ((4 * g + r) * DZ + c + 16 * zt), out[zt][r]);
+                        store_elem(lane_out + (r * DZ + 16 * zt), out[zt][r]);
                 }
         }
 
@@ -604,6 +659,16 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     for (int r = 0; r < 4; ++r)
                         s1[(16 * xt + 4 * g + r) * M + 16 * zt + c] = U[xt][zt][r];
                 if (c == 0) *reinterpret_cast<f32x4 *>(z1 + 16 * xt + 4 * g) = zg[xt];
+            }
+        }
+    }
+    if constexpr (PASS == kDq) {        // this segment's sum of delta_b phi(Q_b)
+        if (a.totals != nullptr) {
+            float *st = a.totals + ((size_t)bh * a.nseg + seg) * state_stride(D, M) + D * M;
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt) {
+                const float e = sum_over_groups(rho[zt]);
+                if (g == 0) st[16 * zt + c] = e;
             }
         }
     }
@@ -671,6 +736,157 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         ReverseStager<1, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fk, lds_dk, lds_v);
         run_pass<kDk, D, M, T, kBorrowState>(a, stg, lds_v, lds_g, lds_fq, lds_dk, a.out2, bh, seg,
                                              lane, lds_R);
+    }
+}
+
+// Staging of the dQ pass, shared by the two waves of its workgroup.  Wave 0 (the dQ role)
+// brings dO (parked as dO/den, den being the forward's denominator) and V; wave 1 brings K
+// and Q, both parked as phi.
+template <int ROLE, int D, int M, typename T>
+struct DqStager {
+    static constexpr int F = ROLE == 0 ? M : D;
+    static constexpr int FT = F / 16;
+    static constexpr int kDepth = 1;
+    const T *As, *Bs;                   // role 0: dO, V; role 1: K, Q
+    const float *den;
+    float *lds_a, *lds_b;               // role 0: dO/den, V; role 1: phi(K), phi(Q)
+    int N, lane, g;
+    f32x4 sa[FT], sb[FT];
+    float sca[FT], one[FT];
+    float n_den4[4];
+    float dl1, dl4[4];                  // unused by this pass (interface of run_pass)
+    float rd4[4];                       // 1/den of tokens 4g + s of the parked chunk, 0 past the end
+
+    __device__ __forceinline__ DqStager(const PassArgs &a, size_t rowbase, int lane_, float *la,
+                                        float *lb)
+        : lds_a(la), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4) {
+        As = static_cast<const T *>(ROLE == 0 ? a.G : a.K) + rowbase * F;
+        Bs = static_cast<const T *>(ROLE == 0 ? a.V : a.Q) + rowbase * F;
+        den = a.den_in + rowbase;
+        dl1 = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) dl4[s] = rd4[s] = 0.f, n_den4[s] = 1.f;
+#pragma unroll
+        for (int i = 0; i < FT; ++i) sca[i] = one[i] = 1.0f;
+    }
+
+    template <bool kFull>
+    __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
+        stage_load<F, kFull>(As + (size_t)t0 * F, nvalid, lane, sa);
+        stage_load<F, kFull>(Bs + (size_t)t0 * F, nvalid, lane, sb);
+        if constexpr (ROLE == 0) {
+            stage_rows<F, kFull>(den + t0, nvalid, lane, sca);      // den of the staged rows
+#pragma unroll
+            for (int s = 0; s < 4; ++s)                             // den of tokens 4g + s
+                n_den4[s] = den[t0 + (kFull ? 4 * g + s : min(4 * g + s, nvalid - 1))];
+        }
+    }
+
+    template <int SLOT>
+    __device__ __forceinline__ void fetch(const int ch) {
+        const int t0 = ch * kChunk;
+        const int nvalid = min(kChunk, N - t0);
+        if (nvalid == kChunk) fetch_impl<true>(t0, nvalid);
+        else fetch_impl<false>(t0, nvalid);
+    }
+
+    template <bool kFull>
+    __device__ __forceinline__ void park_impl(const int nvalid) {
+        if constexpr (ROLE == 0) {
+#pragma unroll
+            for (int i = 0; i < FT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
+            park_tile<F, kMapScale, kFull>(lds_a, sa, sca, nvalid, lane);
+            park_tile<F, kMapId, kFull>(lds_b, sb, one, nvalid, lane);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
+        } else {
+            park_tile<F, kMapPhi, kFull>(lds_a, sa, one, nvalid, lane);
+            park_tile<F, kMapPhi, kFull>(lds_b, sb, one, nvalid, lane);
+        }
+    }
+
+    template <int SLOT>
+    __device__ __forceinline__ void park(const int nvalid) {
+        if (nvalid == kChunk) park_impl<true>(nvalid);
+        else park_impl<false>(nvalid);
+    }
+};
+
+// Wave 1 of the dQ kernel: brings its two tiles in step with wave 0 (same barriers, same
+// chunk order) and, when the sequences are cut, adds up this segment's phi(Q)^T dO/den
+// (D x M, eq. 14-15 restricted to the segment) for the scan that feeds the reverse passes.
+template <int D, int M, typename T, typename Stager>
+__device__ __forceinline__ void run_dq_totals(const PassArgs &a, Stager &stg, const float *lds_fq,
+                                              const float *lds_g, const int bh, const int seg,
+                                              const int lane) {
+    constexpr int XT = D / 16, ZT = M / 16;
+    const int c = lane & 15, g = lane >> 4;
+    const int nchunks = (a.N + kChunk - 1) / kChunk;
+    const int ch_begin = seg * a.chunks_per_seg;
+    const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
+    const bool want = a.totals != nullptr;         // uniform
+
+    f32x4 U[XT][ZT];
+#pragma unroll
+    for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+        for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (ch_begin < ch_end) stg.template fetch<0>(ch_begin);
+    for (int ch = ch_begin; ch < ch_end; ++ch) {
+        const int nvalid = min(kChunk, a.N - ch * kChunk);
+        __syncthreads();
+        stg.template park<0>(nvalid);
+        if (ch + 1 < ch_end) stg.template fetch<0>(ch + 1);
+        __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        if (want) {
+            float yf[XT][4], zf[ZT][4];
+            lds_feature_lane<D>(lds_fq, c, g, yf);
+            lds_feature_lane<M>(lds_g, c, g, zf);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt)
+                        U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+        }
+    }
+    if (want) {
+        float *st = a.totals + ((size_t)bh * a.nseg + seg) * state_stride(D, M);
+#pragma unroll
+        for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    st[(16 * xt + 4 * g + r) * M + 16 * zt + c] = U[xt][zt][r];
+    }
+}
+
+// The forward-direction half of the backward (eq. 13): dQ, plus everything the reverse half
+// needs (1/den, delta, and per-segment sums of phi(Q)^T [dO/den, delta] when the sequences
+// are cut).  Reads Q, K, V, dO and the forward's denominators; the forward's output O is not
+// needed.
+template <int D, int M, typename T>
+__global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void dq_pass_kernel(
+    const PassArgs a) {
+    __shared__ float lds_g[tile_floats(M)];     // dO / den
+    __shared__ float lds_v[tile_floats(M)];     // V
+    __shared__ float lds_fk[tile_floats(D)];    // phi(K)
+    __shared__ float lds_fq[tile_floats(D)];    // phi(Q)
+    const int lane = threadIdx.x & (kWave - 1);
+    const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
+    const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
+    if (role == 0) {
+        DqStager<0, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_g, lds_v);
+        run_pass<kDq, D, M, T>(a, stg, lds_g, lds_v, lds_fk, lds_fq, a.out, bh, seg, lane);
+    } else {
+        DqStager<1, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fk, lds_fq);
+        run_dq_totals<D, M, T>(a, stg, lds_fq, lds_g, bh, seg, lane);
     }
 }
 
