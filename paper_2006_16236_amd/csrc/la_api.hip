@@ -311,20 +311,29 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
+    // The two kernels of the backward run two waves per workgroup, so half as many workgroups
+    // fill the machine: they take the forward's segments in pairs.  The prefix states (laid out
+    // for the forward's cut) are read at every second slot.
+    Plan pb = p;
+    if (p.nseg > 1) {
+        pb.cps = 2 * p.cps;
+        pb.nseg = (p.nchunks + pb.cps - 1) / pb.cps;
+    }
+    const int nblocks_b = (int)(BH * pb.nseg);
     // forward direction: dQ; on the way 1/den and delta per token and, when the sequences
     // are cut, the per-segment sums that the reverse direction starts from
     la::PassArgs a{};
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
-    a.den_in = den; a.rden_out = rden; a.delta_out = delta; a.totals = stR;
-    a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
-    a.out = dQ; a.state = stS;
+    a.den_in = den; a.rden_out = rden; a.delta_out = delta; a.totals = pb.nseg > 1 ? stR : nullptr;
+    a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
+    a.out = dQ; a.state = stS; a.state_nseg = p.nseg; a.state_step = 2;
     a.init_S = S0; a.init_z = z0;            // read only where the sequences are not cut
-    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(D, M, (int)t, a, nblocks, s)); }
-    if (p.nseg > 1)
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
-    a.out = dV; a.out2 = dK; a.state = stR;
+    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(D, M, (int)t, a, nblocks_b, s)); }
+    if (pb.nseg > 1)
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
+    a.out = dV; a.out2 = dK; a.state = pb.nseg > 1 ? stR : nullptr; a.state_step = 0;
     a.init_S = dS1; a.init_z = dz1; a.final_S = dS0; a.final_z = dz0;
-    { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks, s)); }
+    { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks_b, s)); }
     return LA_OK;
 }
 

@@ -76,6 +76,9 @@ struct PassArgs {
     float *totals;               // kDq: [BH, nseg, state_stride] per-segment sums of
                                  // phi(Q)^T dO/den and delta phi(Q), or null
     const float *state;          // [BH, nseg, state_stride] exclusive states; null = zero state
+    // kDq only: `state` was laid out for a finer cut, state_nseg segments per sequence, of which
+    // this pass's segment `seg` starts at segment seg * state_step (0: same cut, step 1)
+    int state_nseg, state_step;
     // State at the end a pass starts from, used when the sequences are not cut (nseg == 1),
     // [BH, D, M] / [BH, D], may be null: kFwd, kDq the sums before token 0; kDv (matrix) and
     // kDk (vector) the gradient that arrives at the state after the last token.
@@ -337,8 +340,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     for (int zt = 0; zt < ZT; ++zt) ecp[zt] = rho[zt] = 0.f;
 
     if (a.state != nullptr) {
-        const float *st = a.state +
-                          ((size_t)bh * a.nseg + (kHasYZ ? seg : 0)) * state_stride(D, M);
+        const size_t slot = (PASS == kDq && a.state_step != 0)
+                                ? (size_t)bh * a.state_nseg + (size_t)seg * a.state_step
+                                : (size_t)bh * a.nseg + (kHasYZ ? seg : 0);
+        const float *st = a.state + slot * state_stride(D, M);
 #pragma unroll
         for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
@@ -813,13 +818,18 @@ struct DqStager {
     }
 };
 
-// Wave 1 of the dQ kernel: brings its two tiles in step with wave 0 (same barriers, same
-// chunk order) and, when the sequences are cut, adds up this segment's phi(Q)^T dO/den
-// (D x M, eq. 14-15 restricted to the segment) for the scan that feeds the reverse passes.
+// Wave 1 of the dQ kernel.  It brings its two tiles in step with wave 0 (same barriers, same
+// chunk order), and it owns the two D x M sums of the pass:
+//   S  = sum_{b before the chunk} phi(K_b) V_b^T (eq. 10), which it publishes in LDS before
+//        every chunk (wave 0 reads it transposed for its read-out) and then updates;
+//   R  = this segment's sum of phi(Q_b) dO_b^T/den_b (eq. 14-15 restricted to the segment), kept
+//        only when the sequences are cut, for the scan that feeds the reverse passes.
+// So the matrix work of the pass is split evenly between the two waves.
 template <int D, int M, typename T, typename Stager>
-__device__ __forceinline__ void run_dq_totals(const PassArgs &a, Stager &stg, const float *lds_fq,
-                                              const float *lds_g, const int bh, const int seg,
-                                              const int lane) {
+__device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, const float *lds_fk,
+                                            const float *lds_v, const float *lds_fq,
+                                            const float *lds_g, float *lds_u, const int bh,
+                                            const int seg, const int lane) {
     constexpr int XT = D / 16, ZT = M / 16;
     const int c = lane & 15, g = lane >> 4;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
@@ -827,11 +837,25 @@ __device__ __forceinline__ void run_dq_totals(const PassArgs &a, Stager &stg, co
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const bool want = a.totals != nullptr;         // uniform
 
-    f32x4 U[XT][ZT];
+    f32x4 S[XT][ZT], R[XT][ZT];                    // element (d = 16xt + 4g + r, m = 16zt + c)
 #pragma unroll
     for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
-        for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int zt = 0; zt < ZT; ++zt) S[xt][zt] = R[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const size_t slot = a.state_step != 0 ? (size_t)bh * a.state_nseg + (size_t)seg * a.state_step
+                                          : (size_t)bh * a.nseg + seg;
+    const float *s0 = a.state != nullptr
+                          ? a.state + slot * state_stride(D, M)
+                          : (a.init_S != nullptr ? a.init_S + (size_t)bh * D * M : nullptr);
+    if (s0 != nullptr) {
+#pragma unroll
+        for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    S[xt][zt][r] = s0[(16 * xt + 4 * g + r) * M + 16 * zt + c];
+    }
 
     if (ch_begin < ch_end) stg.template fetch<0>(ch_begin);
     for (int ch = ch_begin; ch < ch_end; ++ch) {
@@ -839,20 +863,38 @@ __device__ __forceinline__ void run_dq_totals(const PassArgs &a, Stager &stg, co
         __syncthreads();
         stg.template park<0>(nvalid);
         if (ch + 1 < ch_end) stg.template fetch<0>(ch + 1);
+        // S as it stands before this chunk, element (d, m) at lds_u[m][d] (row stride D + 4)
+#pragma unroll
+        for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt)
+                lds_store4(lds_u + (16 * zt + c) * (D + 4) + 16 * xt + 4 * g, S[xt][zt]);
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        if (want) {
-            float yf[XT][4], zf[ZT][4];
-            lds_feature_lane<D>(lds_fq, c, g, yf);
-            lds_feature_lane<M>(lds_g, c, g, zf);
+        {
+            float kf[XT][4], vf[ZT][4];
+            lds_feature_lane<D>(lds_fk, c, g, kf);
+            lds_feature_lane<M>(lds_v, c, g, vf);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
 #pragma unroll
                 for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt)
-                        U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+                        S[xt][zt] = mfma16(kf[xt][s], vf[zt][s], S[xt][zt]);
+        }
+        if (want) {
+            float qf[XT][4], gf[ZT][4];
+            lds_feature_lane<D>(lds_fq, c, g, qf);
+            lds_feature_lane<M>(lds_g, c, g, gf);
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt)
+                        R[xt][zt] = mfma16(qf[xt][s], gf[zt][s], R[xt][zt]);
         }
     }
     if (want) {
@@ -863,14 +905,15 @@ __device__ __forceinline__ void run_dq_totals(const PassArgs &a, Stager &stg, co
             for (int zt = 0; zt < ZT; ++zt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    st[(16 * xt + 4 * g + r) * M + 16 * zt + c] = U[xt][zt][r];
+                    st[(16 * xt + 4 * g + r) * M + 16 * zt + c] = R[xt][zt][r];
     }
 }
 
 // The forward-direction half of the backward (eq. 13): dQ, plus everything the reverse half
 // needs (1/den, delta, and per-segment sums of phi(Q)^T [dO/den, delta] when the sequences
 // are cut).  Reads Q, K, V, dO and the forward's denominators; the forward's output O is not
-// needed.
+// needed.  Wave 0 does the read-out, the in-chunk part and the epilogue; wave 1 carries the
+// running sum S it reads out from (see run_dq_sums).
 template <int D, int M, typename T>
 __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void dq_pass_kernel(
     const PassArgs a) {
@@ -878,15 +921,17 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     __shared__ float lds_v[tile_floats(M)];     // V
     __shared__ float lds_fk[tile_floats(D)];    // phi(K)
     __shared__ float lds_fq[tile_floats(D)];    // phi(Q)
+    __shared__ float lds_S[M * (D + 4)];        // S before the current chunk, as [m][d]
     const int lane = threadIdx.x & (kWave - 1);
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
         DqStager<0, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_g, lds_v);
-        run_pass<kDq, D, M, T>(a, stg, lds_g, lds_v, lds_fk, lds_fq, a.out, bh, seg, lane);
+        run_pass<kDq, D, M, T, kBorrowState>(a, stg, lds_g, lds_v, lds_fk, lds_fq, a.out, bh, seg,
+                                             lane, lds_S);
     } else {
         DqStager<1, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fk, lds_fq);
-        run_dq_totals<D, M, T>(a, stg, lds_fq, lds_g, bh, seg, lane);
+        run_dq_sums<D, M, T>(a, stg, lds_fk, lds_v, lds_fq, lds_g, lds_S, bh, seg, lane);
     }
 }
 
