@@ -36,10 +36,8 @@ MFMA_F32_PEAK_TFLOPS = 157.3     # MI355X dense fp32 matrix, published
 # in profiles/hbm_traffic_and_pipe_counters_N65536_B2_H8_D64_f32.md.  Read + written, in bytes.
 MEASURED_TRAFFIC_BYTES = {
     "causal_pass_fwd": (839.5 + 273.6) * 1e6,
-    "causal_pass_dq": (1122.0 + 268.4) * 1e6,
     "reverse_pass_dv_dk": (1119.8 + 536.9) * 1e6,
     "segment_state_kv": (532.8 + 33.8) * 1e6,
-    "segment_state_qg": (810.7 + 45.6) * 1e6,
     "scan_states": (54.8 + 34.1) * 1e6,
 }
 
@@ -50,11 +48,9 @@ def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
     delta are fp32 scalars per token-head)."""
     return {
         "causal_pass_fwd": e * (2 * D + 2 * M) + 4,     # Q K V -> O, den
-        "causal_pass_dq": e * (3 * D + 2 * M) + 8,      # dO V K Q, 1/den, delta -> dQ
+        "pass_dq": e * (3 * D + 2 * M) + 12,            # dO V K Q, den -> dQ, 1/den, delta
         "reverse_pass_dv_dk": e * (3 * D + 3 * M) + 8,  # Q K V dO, 1/den, delta -> dV, dK
         "segment_state_kv": e * (D + M),                # K V
-        "segment_state_qg": e * (D + 2 * M) + 12,       # Q dO O den -> 1/den, delta
-        "bwd_prep": e * 2 * M + 12,                     # dO O den -> 1/den, delta
         "global_readout": e * (D + M),                  # Q -> O
     }.get(name, 0.0)
 
@@ -63,9 +59,8 @@ def kernel_flops(name: str, D: int, M: int) -> float:
     """Algorithmic flops per token-head: the state update and the state read-out
     (2*D*(M+1) each, ones column included) that the pass performs."""
     full = 4.0 * D * (M + 1)
-    return {"causal_pass_fwd": full, "causal_pass_dq": full, "reverse_pass_dv_dk": 1.5 * full,
-            "segment_state_kv": full / 2, "segment_state_qg": full / 2,
-            "global_readout": full / 2}.get(name, 0.0)
+    return {"causal_pass_fwd": full, "pass_dq": 1.5 * full, "reverse_pass_dv_dk": 1.5 * full,
+            "segment_state_kv": full / 2, "global_readout": full / 2}.get(name, 0.0)
 
 
 class FwdBwd:

@@ -215,16 +215,14 @@ int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, fl
  */
 typedef enum {
     LA_K_SEG_KV = 0,   /* per-segment sums of phi(K)^T V and phi(K)            */
-    LA_K_SEG_QG = 1,   /* per-segment sums of phi(Q)^T dO/den and delta phi(Q) */
-    LA_K_SCAN = 2,     /* scan over the segment sums                           */
-    LA_K_FWD = 3,      /* causal forward pass                                  */
-    LA_K_GLOBAL = 4,   /* non-causal read-out                                  */
-    LA_K_PREP = 5,     /* 1/den and delta per token                            */
-    LA_K_DQ = 6,       /* gradient for Q (forward direction)                   */
-    LA_K_REV = 7,      /* gradients for V and K (reverse direction)            */
-    LA_K_STEP = 8,     /* recurrent decode step                                */
-    LA_K_GLOBAL_BWD = 9, /* the three non-causal gradient read-outs, as one span */
-    LA_K_COUNT = 10
+    LA_K_SCAN = 1,     /* scan over the segment sums                           */
+    LA_K_FWD = 2,      /* causal forward pass                                  */
+    LA_K_GLOBAL = 3,   /* non-causal read-out                                  */
+    LA_K_DQ = 4,       /* gradient for Q, 1/den, delta, per-segment Q,dO sums  */
+    LA_K_REV = 5,      /* gradients for V and K (reverse direction)            */
+    LA_K_STEP = 6,     /* recurrent decode step                                */
+    LA_K_GLOBAL_BWD = 7, /* the non-causal read-outs for dV and dK, as one span */
+    LA_K_COUNT = 8
 } la_kernel_id;
 
 const char *la_kernel_name(int kernel_id);

@@ -23,7 +23,7 @@ EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_caus
            "la_causal_bwd", "la_causal_bwd_state", "la_global_fwd", "la_global_bwd",
            "la_recurrent_step", "la_recurrent_steps", "la_kernel_name", "la_profile_begin",
            "la_profile_end")
-LA_K_COUNT = 10
+LA_K_COUNT = 8
 
 
 class LaError(RuntimeError):

@@ -136,9 +136,9 @@ int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *
     const int nblocks = (int)(BH * p.nseg);
     if (p.nseg > 1) {
         la::SegArgs sa{};
-        sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = states;
+        sa.Y = K; sa.Z = V; sa.state = states;
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = p.nseg - 1;
-        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
     la::PassArgs a{};
@@ -156,9 +156,9 @@ int run_global_fwd(const void *Q, const void *K, const void *V, void *O, float *
                    hipStream_t s) {
     const int nblocks = (int)(BH * p.nseg);
     la::SegArgs sa{};
-    sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = states;
+    sa.Y = K; sa.Z = V; sa.state = states;
     sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
-    { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+    { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
     if (p.nseg > 1)
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
     la::PassArgs a{};
@@ -215,8 +215,7 @@ size_t la_global_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
-    size_t bytes = 2 * align256(rows * sizeof(float));                      // rden, delta
-    bytes += 2 * states_bytes(BH, p, D, M);                                 // the two grand totals
+    size_t bytes = 2 * states_bytes(BH, p, D, M);                           // the two grand totals
     bytes += align256(rows * M * esize(t)) + align256(rows * sizeof(float)); // O, den if recomputed
     return bytes;
 }
@@ -306,9 +305,9 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     if (p.nseg > 1 && !have_states) {
         la::SegArgs sa{};
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps;
-        sa.Y = K; sa.Z = V; sa.rden = nullptr; sa.delta = nullptr; sa.state = stS;
+        sa.Y = K; sa.Z = V; sa.state = stS;
         sa.skip_seg = p.nseg - 1;
-        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
     // The two kernels of the backward run two waves per workgroup, so half as many workgroups
@@ -328,10 +327,11 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
     a.out = dQ; a.state = stS; a.state_nseg = p.nseg; a.state_step = 2;
     a.init_S = S0; a.init_z = z0;            // read only where the sequences are not cut
-    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(D, M, (int)t, a, nblocks_b, s)); }
+    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(true, D, M, (int)t, a, nblocks_b, s)); }
     if (pb.nseg > 1)
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
-    a.out = dV; a.out2 = dK; a.state = pb.nseg > 1 ? stR : nullptr; a.state_step = 0;
+    a.out = dV; a.out2 = dK; a.state = pb.nseg > 1 ? stR : nullptr;
+    a.state_nseg = 0; a.state_step = 0;      // stR is laid out for this very cut
     a.init_S = dS1; a.init_z = dz1; a.final_S = dS0; a.final_z = dz0;
     { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks_b, s)); }
     return LA_OK;
@@ -385,56 +385,56 @@ int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, co
         return LA_ERR_ALIGN;
     const size_t need = la_global_bwd_workspace(B, H, N, D, M, t);
     if (ws == nullptr || ws_bytes < need) return LA_ERR_WORKSPACE;
+    (void)O;                                   // not read: delta is rebuilt from the read-out
 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
     Carver cv{static_cast<char *>(ws), 0};
-    float *rden = static_cast<float *>(cv.take(rows * sizeof(float)));
-    float *delta = static_cast<float *>(cv.take(rows * sizeof(float)));
     float *stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
     float *stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
-    const bool recompute_fwd = (O == nullptr || den == nullptr);
     const int nblocks = (int)(BH * p.nseg);
-    la::SegArgs sa{};
-    sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
-    if (recompute_fwd) {                       // also leaves the K, V total in slot 0 of stS
-        void *Otmp = cv.take(rows * M * esize(t));
+    if (den == nullptr) {                      // recompute the forward's denominators;
+        void *Otmp = cv.take(rows * M * esize(t));     // also leaves the K, V total in slot 0 of stS
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
         const int fs = run_global_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s);
         if (fs != LA_OK) return fs;
-        O = Otmp;
         den = dentmp;
     } else if (fwd_ws != nullptr) {            // the forward's workspace still holds that total
         stS = const_cast<float *>(static_cast<const float *>(fwd_ws));
     } else {
+        la::SegArgs sa{};
+        sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
         sa.Y = K; sa.Z = V; sa.state = stS;
-        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(0, D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
         if (p.nseg > 1)
             { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
     }
-    // the Q, dO total, with the per-token scalars 1/den and delta formed on the way
-    sa.Y = Q; sa.Z = dO; sa.state = stR;
-    sa.O = O; sa.den = den; sa.rden_out = rden; sa.delta_out = delta;
-    { ProfScope ps(LA_K_SEG_QG, s); LA_TRY(la::launch_segment_state(2, D, M, (int)t, sa, nblocks, s)); }
-    if (p.nseg > 1)
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
-
+    // dQ against the K, V total; on the way the per-segment Q, dO sums.  A kernel with two
+    // waves per workgroup: it takes the segments in pairs (see the causal backward).
+    Plan pb = p;
+    if (p.nseg > 1) {
+        pb.cps = 2 * p.cps;
+        pb.nseg = (p.nchunks + pb.cps - 1) / pb.cps;
+    }
     la::PassArgs a{};
-    a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
-    a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
+    a.Q = Q; a.K = K; a.V = V; a.G = dO; a.den_in = den; a.totals = stR;
+    a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
+    a.out = dQ; a.state = stS; a.state_nseg = p.nseg;
+    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(false, D, M, (int)t, a, (int)(BH * pb.nseg), s)); }
+    if (pb.nseg > 1)
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+    // dV and dK against the Q, dO total
+    a.totals = nullptr; a.nseg = p.nseg; a.chunks_per_seg = p.cps;
+    a.state = stR; a.state_nseg = pb.nseg;
     ProfScope ps(LA_K_GLOBAL_BWD, s);
-    a.out = dQ; a.state = stS;
-    LA_TRY(la::launch_pass_global_bwd(0, D, M, (int)t, a, nblocks, s));
-    a.state = stR;
     a.out = dV;
     LA_TRY(la::launch_pass_global_bwd(1, D, M, (int)t, a, nblocks, s));
     a.out = dK;
     LA_TRY(la::launch_pass_global_bwd(2, D, M, (int)t, a, nblocks, s));
     return LA_OK;
 }
-
 
 int la_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z, void *out,
                       int B, int H, int D, int M, float eps, la_dtype t, void *stream) {
@@ -469,10 +469,9 @@ int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, fl
 }
 
 const char *la_kernel_name(int kernel_id) {
-    static const char *const names[LA_K_COUNT] = {"segment_state_kv", "segment_state_qg", "scan_states",
-                                                  "causal_pass_fwd", "global_readout", "bwd_prep",
-                                                  "causal_pass_dq", "reverse_pass_dv_dk", "recurrent_step",
-                                                  "global_bwd_readouts"};
+    static const char *const names[LA_K_COUNT] = {"segment_state_kv", "scan_states", "causal_pass_fwd",
+                                                  "global_readout", "pass_dq", "reverse_pass_dv_dk",
+                                                  "recurrent_step", "global_bwd_readouts"};
     return kernel_id >= 0 && kernel_id < LA_K_COUNT ? names[kernel_id] : "unknown";
 }
 

@@ -11,14 +11,16 @@ namespace la {
 // dtype: 0 = fp32, 1 = bf16 (la_dtype of the public header)
 hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs &a, int nblocks,
                            hipStream_t s);
-hipError_t launch_pass_dq(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
+// dQ, 1/den, delta and (a.totals) the per-segment Q, dO sums; causal or against the global sums
+hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &a, int nblocks,
+                          hipStream_t s);
 // both reverse passes (dV into a.out, dK into a.out2) on one fetch of the inputs
 hipError_t launch_pass_reverse(int D, int M, int dtype, const PassArgs &a, int nblocks,
                                hipStream_t s);
-// read-out-only gradients of the non-causal form: which = 0 dQ, 1 dV, 2 dK (into a.out)
+// read-out-only gradients of the non-causal form: which = 1 dV, 2 dK (into a.out)
 hipError_t launch_pass_global_bwd(int which, int D, int M, int dtype, const PassArgs &a,
                                   int nblocks, hipStream_t s);
-hipError_t launch_segment_state(int kind, int D, int M, int dtype, const SegArgs &a, int nblocks,
+hipError_t launch_segment_state(int D, int M, int dtype, const SegArgs &a, int nblocks,
                                 hipStream_t s);
 
 enum ScanMode { kScanForward = 0, kScanReverse = 1, kScanTotal = 2 };
@@ -27,10 +29,6 @@ enum ScanMode { kScanForward = 0, kScanReverse = 1, kScanTotal = 2 };
 // init_S [BH, DM] / init_z [BH, stride - DM]: optional starting value of the forward prefix.
 hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s,
                        const float *init_S = nullptr, const float *init_z = nullptr, int DM = 0);
-
-// rden_i = 1/den_i, delta_i = -(dO_i . O_i)/den_i for all rows.
-hipError_t launch_bwd_prep(const void *dO, const void *O, const float *den, float *rden,
-                           float *delta, size_t rows, int M, int dtype, hipStream_t s);
 
 hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z,
                                  void *out, int BH, int D, int M, float eps, int dtype,

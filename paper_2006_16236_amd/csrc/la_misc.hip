@@ -1,5 +1,5 @@
-// Small bandwidth-bound kernels: the scan over segment states, the per-token
-// scalars of the backward, and the recurrent decode step (eq. 16-20).
+// Small bandwidth-bound kernels: the scan over segment states and the recurrent
+// decode step (eq. 16-20).
 #include "la_launch.h"
 
 namespace la {
@@ -66,47 +66,6 @@ hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hip
     } else {
         dim3 grid((stride + 31) / 32, BH);
         scan_states_kernel<8><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
-    }
-    return hipGetLastError();
-}
-
-// ---- per-token scalars of the backward -----------------------------------------------------
-// The fraction O = num/den sends dO/den to the numerator and -(dO . O)/den to the
-// denominator (quotient rule); both are needed by every backward pass.
-template <int M, typename T>
-__global__ __launch_bounds__(256) void bwd_prep_kernel(const T *dO, const T *O, const float *den,
-                                                       float *rden, float *delta, size_t rows) {
-    constexpr int LPR = M / 4;                       // lanes that share one row
-    const size_t t = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t row = t / LPR;
-    const int col4 = (int)(t % LPR) * 4;
-    float p = 0.f;
-    if (row < rows) {
-        const f32x4 g4 = load4(dO + row * M + col4);
-        const f32x4 o4 = load4(O + row * M + col4);
-        p = (g4[0] * o4[0] + g4[1] * o4[1]) + (g4[2] * o4[2] + g4[3] * o4[3]);
-    }
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) p += __shfl_xor(p, off);
-    if (row < rows && col4 == 0) {
-        const float r = 1.0f / den[row];
-        rden[row] = r;
-        delta[row] = -p * r;
-    }
-}
-
-hipError_t launch_bwd_prep(const void *dO, const void *O, const float *den, float *rden,
-                           float *delta, size_t rows, int M, int dtype, hipStream_t s) {
-    const size_t threads = rows * (size_t)(M / 4);
-    const unsigned blocks = (unsigned)((threads + 255) / 256);
-    if (M == 64) {
-        if (dtype == 0) bwd_prep_kernel<64, float><<<blocks, 256, 0, s>>>((const float *)dO, (const float *)O, den, rden, delta, rows);
-        else bwd_prep_kernel<64, bf16_t><<<blocks, 256, 0, s>>>((const bf16_t *)dO, (const bf16_t *)O, den, rden, delta, rows);
-    } else if (M == 32) {
-        if (dtype == 0) bwd_prep_kernel<32, float><<<blocks, 256, 0, s>>>((const float *)dO, (const float *)O, den, rden, delta, rows);
-        else bwd_prep_kernel<32, bf16_t><<<blocks, 256, 0, s>>>((const bf16_t *)dO, (const bf16_t *)O, den, rden, delta, rows);
-    } else {
-        return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }

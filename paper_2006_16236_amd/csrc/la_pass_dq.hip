@@ -1,12 +1,18 @@
-// Backward pass kDq of Algorithm 1 (see la_passes.h for the operand table).
+// Forward-direction half of the backward: dQ (eq. 13), causal and non-causal (see la_passes.h).
 #include "la_launch.h"
 
 namespace la {
 
-hipError_t launch_pass_dq(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s) {
+hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &a, int nblocks,
+                          hipStream_t s) {
     LA_DISPATCH_DM(D, M, {
-        if (dtype == 0) dq_pass_kernel<kD, kM, float><<<nblocks, 2 * kWave, 0, s>>>(a);
-        else dq_pass_kernel<kD, kM, bf16_t><<<nblocks, 2 * kWave, 0, s>>>(a);
+        if (causal) {
+            if (dtype == 0) dq_pass_kernel<kD, kM, float, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+            else dq_pass_kernel<kD, kM, bf16_t, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+        } else {
+            if (dtype == 0) dq_pass_kernel<kD, kM, float, false><<<nblocks, 2 * kWave, 0, s>>>(a);
+            else dq_pass_kernel<kD, kM, bf16_t, false><<<nblocks, 2 * kWave, 0, s>>>(a);
+        }
     });
     return hipGetLastError();
 }

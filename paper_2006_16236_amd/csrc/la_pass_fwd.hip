@@ -17,19 +17,11 @@ hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs 
     return hipGetLastError();
 }
 
-hipError_t launch_segment_state(int kind, int D, int M, int dtype, const SegArgs &a, int nblocks,
+hipError_t launch_segment_state(int D, int M, int dtype, const SegArgs &a, int nblocks,
                                 hipStream_t s) {
     LA_DISPATCH_DM(D, M, {
-        if (kind == 0) {
-            if (dtype == 0) segment_state_kernel<0, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
-            else segment_state_kernel<0, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
-        } else if (kind == 1) {
-            if (dtype == 0) segment_state_kernel<1, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
-            else segment_state_kernel<1, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
-        } else {
-            if (dtype == 0) segment_state_kernel<2, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
-            else segment_state_kernel<2, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
-        }
+        if (dtype == 0) segment_state_kernel<kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
+        else segment_state_kernel<kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
     });
     return hipGetLastError();
 }

@@ -72,12 +72,12 @@ struct PassArgs {
     void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
     float *den;                  // [BH, N] or null             (kFwd, kGlobal)
     const float *den_in;         // kDq: the forward's denominators [BH, N]
-    float *rden_out, *delta_out; // kDq: [BH, N] 1/den_i and delta_i for the reverse passes
+    float *rden_out, *delta_out; // kDq: [BH, N] 1/den_i and delta_i for the reverse passes (or both null)
     float *totals;               // kDq: [BH, nseg, state_stride] per-segment sums of
                                  // phi(Q)^T dO/den and delta phi(Q), or null
     const float *state;          // [BH, nseg, state_stride] exclusive states; null = zero state
-    // kDq only: `state` was laid out for a finer cut, state_nseg segments per sequence, of which
-    // this pass's segment `seg` starts at segment seg * state_step (0: same cut, step 1)
+    // `state` may have been laid out for a finer cut: state_nseg segments per sequence (0: nseg),
+    // of which this pass's segment `seg` starts at segment seg * state_step (0: step 1)
     int state_nseg, state_step;
     // State at the end a pass starts from, used when the sequences are not cut (nseg == 1),
     // [BH, D, M] / [BH, D], may be null: kFwd, kDq the sums before token 0; kDv (matrix) and
@@ -132,41 +132,36 @@ struct PassTraits {
     static constexpr int kMapZ = (PASS == kFwd) ? kMapId : (PASS == kDv) ? kMapScale : kMapPhi;
 };
 
-// Staging of one pass run by one wave on its own: the wave fetches and parks all its tiles.
+// Staging of a pass run by one wave on its own (kFwd and the read-out-only passes kGlobal,
+// kGlobalDv, kGlobalDk): the wave fetches and parks all its tiles.
 template <int PASS, int D, int M, typename T>
 struct PassStager {
     using Tr = PassTraits<PASS, D, M>;
+    static_assert(PASS == kFwd || PASS == kGlobal || PASS == kGlobalDv || PASS == kGlobalDk,
+                  "the other passes have stagers of their own");
     static constexpr int DX = Tr::DX, DZ = Tr::DZ, XT = DX / 16, ZT = DZ / 16;
     const T *Xs, *Ys, *Zs, *Rs;
-    const float *rden, *delta;
     float *lds_x, *lds_y, *lds_z, *lds_r;
-    int N, lane, c, g;
+    int N, lane;
     f32x4 sx[XT], sy[XT], sz[ZT], sr[ZT];
-    float scx[XT], scz[ZT];             // 1/den of the staged rows of the dO tile
-    float n_dl1, n_dl4[4];
-    float dl1, dl4[4];                  // delta of token c / of tokens 4g + s of the parked chunk
+    float onex[XT], onez[ZT];
+    float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
 
     __device__ __forceinline__ PassStager(const PassArgs &a, size_t rowbase, int lane_, float *lx,
                                           float *ly, float *lz, float *lr)
-        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_), c(lane_ & 15),
-          g(lane_ >> 4) {
+        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_) {
         constexpr int BP = Tr::BP;
-        Xs = static_cast<const T *>(BP == kFwd ? a.Q : BP == kDq ? a.G : BP == kDv ? a.K : a.V) +
-             rowbase * DX;
-        Ys = static_cast<const T *>(PASS == kFwd ? a.K : PASS == kDq ? a.V
-                                    : PASS == kDv ? a.Q : a.G) + rowbase * DX;
-        Zs = static_cast<const T *>(PASS == kFwd ? a.V : PASS == kDq ? a.K
-                                    : PASS == kDv ? a.G : a.Q) + rowbase * DZ;
-        Rs = static_cast<const T *>(BP == kDq ? a.Q : a.K) + rowbase * DZ;
-        rden = a.rden + rowbase;
-        delta = a.delta + rowbase;
-        n_dl1 = dl1 = 0.f;
+        Xs = static_cast<const T *>(BP == kFwd ? a.Q : BP == kDv ? a.K : a.V) + rowbase * DX;
+        Ys = static_cast<const T *>(a.K) + rowbase * DX;      // kFwd
+        Zs = static_cast<const T *>(a.V) + rowbase * DZ;      // kFwd
+        Rs = static_cast<const T *>(a.K) + rowbase * DZ;      // kGlobalDk
+        dl1 = 0.f;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) n_dl4[s] = dl4[s] = 0.f;
+        for (int s = 0; s < 4; ++s) dl4[s] = 0.f;
 #pragma unroll
-        for (int i = 0; i < XT; ++i) scx[i] = 1.0f;
+        for (int i = 0; i < XT; ++i) onex[i] = 1.0f;
 #pragma unroll
-        for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
+        for (int i = 0; i < ZT; ++i) onez[i] = 1.0f;
     }
 
     static constexpr int kDepth = 1;
@@ -179,15 +174,6 @@ struct PassStager {
             stage_load<DZ, kFull>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
         }
         if constexpr (Tr::kHasRaw) stage_load<DZ, kFull>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
-        if constexpr (Tr::BP == kDq || PASS == kDk)           // dO is the X (kDq) or Y (kDk) tile
-            stage_rows<DX, kFull>(rden + t0, nvalid, lane, scx);
-        if constexpr (PASS == kDk) rows4<kFull>(delta + t0, nvalid, g, n_dl4);
-        if constexpr (Tr::BP == kDq) {
-            const float v = delta[t0 + (kFull ? c : min(c, nvalid - 1))];
-            n_dl1 = (kFull || c < nvalid) ? v : 0.f;
-        }
-        if constexpr (PASS == kDv)                            // dO is the Z tile
-            stage_rows<DZ, kFull>(rden + t0, nvalid, lane, scz);
     }
 
     template <int SLOT>
@@ -200,21 +186,18 @@ struct PassStager {
 
     template <bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<DX, Tr::kMapX, kFull>(lds_x, sx, scx, nvalid, lane);
+        park_tile<DX, Tr::kMapX, kFull>(lds_x, sx, onex, nvalid, lane);
         if constexpr (Tr::kHasYZ) {
-            park_tile<DX, Tr::kMapY, kFull>(lds_y, sy, scx, nvalid, lane);
-            park_tile<DZ, Tr::kMapZ, kFull>(lds_z, sz, scz, nvalid, lane);
+            park_tile<DX, Tr::kMapY, kFull>(lds_y, sy, onex, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ, kFull>(lds_z, sz, onez, nvalid, lane);
         }
-        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull>(lds_r, sr, scz, nvalid, lane);
+        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull>(lds_r, sr, onez, nvalid, lane);
     }
 
     template <int SLOT>
     __device__ __forceinline__ void park(const int nvalid) {
         if (nvalid == kChunk) park_impl<true>(nvalid);
         else park_impl<false>(nvalid);
-        dl1 = n_dl1;
-#pragma unroll
-        for (int s = 0; s < 4; ++s) dl4[s] = n_dl4[s];
     }
 };
 
@@ -340,9 +323,8 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     for (int zt = 0; zt < ZT; ++zt) ecp[zt] = rho[zt] = 0.f;
 
     if (a.state != nullptr) {
-        const size_t slot = (PASS == kDq && a.state_step != 0)
-                                ? (size_t)bh * a.state_nseg + (size_t)seg * a.state_step
-                                : (size_t)bh * a.nseg + (kHasYZ ? seg : 0);
+        const size_t slot = (size_t)bh * (a.state_nseg != 0 ? a.state_nseg : a.nseg) +
+                            (kHasYZ ? (size_t)seg * (a.state_step != 0 ? a.state_step : 1) : 0);
         const float *st = a.state + slot * state_stride(D, M);
 #pragma unroll
         for (int xt = 0; xt < XT; ++xt)
@@ -417,7 +399,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         const float dl1 = stg.dl1;
         const float dl4[4] = {stg.dl4[0], stg.dl4[1], stg.dl4[2], stg.dl4[3]};
         float rd4[4] = {0.f, 0.f, 0.f, 0.f};          // kDq: 1/den of tokens 4g + s (0 past the end)
-        if constexpr (PASS == kDq) {
+        if constexpr (Tr::BP == kDq) {
 #pragma unroll
             for (int s = 0; s < 4; ++s) rd4[s] = stg.rd4[s];
         }
@@ -477,11 +459,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                     for (int r = 0; r < 4; ++r) p = fmaf(xa[xt][r], zg[xt][r], p);
                 den4 = mfma16(p, 1.0f, eps4);
-            } else if constexpr (kHasRaw) {
-                // the ones-column part: delta_a * z (kGlobalDq), rho (kGlobalDk)
+            } else if constexpr (PASS == kGlobalDk) {
+                // the ones-column part: rho (kGlobalDq adds its own further down)
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt)
-                    out[zt] = mfma16(PASS == kGlobalDq ? dl1 : 1.0f, ecp[zt], out[zt]);
+                for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16(1.0f, ecp[zt], out[zt]);
             }
         } else {
             // ---- W[a][b] = X_a . Y_b, lane (c = a, g), register r: b = 4g + r --------------
@@ -538,7 +519,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 for (int zt = 0; zt < ZT; ++zt) out[zt][r] *= ri;
             }
         }
-        if constexpr (PASS == kDq) {
+        if constexpr (Tr::BP == kDq) {
             // `out` is A_a = S_a dO_a/den_a so far (rows: tokens 4g + r, columns: features
             // 16zt + c).  delta_a = -(phi(Q_a) . A_a)/den_a: multiply by phi(Q) in the same
             // layout, add up the 16 lanes of the group and the ZT registers.
@@ -558,11 +539,13 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             f32x4 cz[ZT];
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(1.0f, ecp[zt], f32x4{0.f, 0.f, 0.f, 0.f});
+            if constexpr (kHasYZ) {       // (kGlobalDq: z is the sum over the whole sequence)
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const float m = (4 * g + s) <= c ? 1.0f : 0.0f;
+                for (int s = 0; s < 4; ++s) {
+                    const float m = (4 * g + s) <= c ? 1.0f : 0.0f;
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(m, zf[zt][s], cz[zt]);
+                    for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(m, zf[zt][s], cz[zt]);
+                }
             }
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) {
@@ -577,12 +560,12 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             // lanes c < 4 of each group write 1/den and delta of token 4g + c
             const float dsel = c == 0 ? d4[0] : c == 1 ? d4[1] : c == 2 ? d4[2] : d4[3];
             const float rsel = c == 0 ? rd4[0] : c == 1 ? rd4[1] : c == 2 ? rd4[2] : rd4[3];
-            if (c < 4 && 4 * g + c < nvalid) {
+            if (a.delta_out != nullptr && c < 4 && 4 * g + c < nvalid) {
                 a.delta_out[rowbase + t0 + 4 * g + c] = dsel;
                 a.rden_out[rowbase + t0 + 4 * g + c] = rsel;
             }
         } else if constexpr (kHasRaw) {
-            float dp[ZT][4];             // phi' of the raw Q (kGlobalDq) or K (kDk) under the output
+            float dp[ZT][4];             // phi' of the raw K under the output
             lds_feature_lane<DZ>(lds_r, c, g, dp);
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt)
@@ -667,7 +650,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             }
         }
     }
-    if constexpr (PASS == kDq) {        // this segment's sum of delta_b phi(Q_b)
+    if constexpr (Tr::BP == kDq) {      // this segment's sum of delta_b phi(Q_b)
         if (a.totals != nullptr) {
             float *st = a.totals + ((size_t)bh * a.nseg + seg) * state_stride(D, M) + D * M;
 #pragma unroll
@@ -745,16 +728,17 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 }
 
 // Staging of the dQ pass, shared by the two waves of its workgroup.  Wave 0 (the dQ role)
-// brings dO (parked as dO/den, den being the forward's denominator) and V; wave 1 brings K
-// and Q, both parked as phi.
-template <int ROLE, int D, int M, typename T>
+// brings dO (parked as dO/den, den being the forward's denominator) and V; wave 1 brings Q
+// and K, both parked as phi.  The non-causal pass (kCausal = false) has no in-chunk part and
+// no running sum: V and K are not needed.
+template <int ROLE, int D, int M, typename T, bool kCausal>
 struct DqStager {
     static constexpr int F = ROLE == 0 ? M : D;
     static constexpr int FT = F / 16;
     static constexpr int kDepth = 1;
-    const T *As, *Bs;                   // role 0: dO, V; role 1: K, Q
+    const T *As, *Bs;                   // role 0: dO, V; role 1: Q, K
     const float *den;
-    float *lds_a, *lds_b;               // role 0: dO/den, V; role 1: phi(K), phi(Q)
+    float *lds_a, *lds_b;               // role 0: dO/den, V; role 1: phi(Q), phi(K)
     int N, lane, g;
     f32x4 sa[FT], sb[FT];
     float sca[FT], one[FT];
@@ -765,8 +749,8 @@ struct DqStager {
     __device__ __forceinline__ DqStager(const PassArgs &a, size_t rowbase, int lane_, float *la,
                                         float *lb)
         : lds_a(la), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4) {
-        As = static_cast<const T *>(ROLE == 0 ? a.G : a.K) + rowbase * F;
-        Bs = static_cast<const T *>(ROLE == 0 ? a.V : a.Q) + rowbase * F;
+        As = static_cast<const T *>(ROLE == 0 ? a.G : a.Q) + rowbase * F;
+        Bs = static_cast<const T *>(ROLE == 0 ? a.V : a.K) + rowbase * F;
         den = a.den_in + rowbase;
         dl1 = 0.f;
 #pragma unroll
@@ -778,7 +762,7 @@ struct DqStager {
     template <bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
         stage_load<F, kFull>(As + (size_t)t0 * F, nvalid, lane, sa);
-        stage_load<F, kFull>(Bs + (size_t)t0 * F, nvalid, lane, sb);
+        if constexpr (kCausal) stage_load<F, kFull>(Bs + (size_t)t0 * F, nvalid, lane, sb);
         if constexpr (ROLE == 0) {
             stage_rows<F, kFull>(den + t0, nvalid, lane, sca);      // den of the staged rows
 #pragma unroll
@@ -801,13 +785,13 @@ struct DqStager {
 #pragma unroll
             for (int i = 0; i < FT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
             park_tile<F, kMapScale, kFull>(lds_a, sa, sca, nvalid, lane);
-            park_tile<F, kMapId, kFull>(lds_b, sb, one, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapId, kFull>(lds_b, sb, one, nvalid, lane);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
         } else {
             park_tile<F, kMapPhi, kFull>(lds_a, sa, one, nvalid, lane);
-            park_tile<F, kMapPhi, kFull>(lds_b, sb, one, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapPhi, kFull>(lds_b, sb, one, nvalid, lane);
         }
     }
 
@@ -825,7 +809,7 @@ struct DqStager {
 //   R  = this segment's sum of phi(Q_b) dO_b^T/den_b (eq. 14-15 restricted to the segment), kept
 //        only when the sequences are cut, for the scan that feeds the reverse passes.
 // So the matrix work of the pass is split evenly between the two waves.
-template <int D, int M, typename T, typename Stager>
+template <int D, int M, typename T, bool kCausal, typename Stager>
 __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, const float *lds_fk,
                                             const float *lds_v, const float *lds_fq,
                                             const float *lds_g, float *lds_u, const int bh,
@@ -847,7 +831,7 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
     const float *s0 = a.state != nullptr
                           ? a.state + slot * state_stride(D, M)
                           : (a.init_S != nullptr ? a.init_S + (size_t)bh * D * M : nullptr);
-    if (s0 != nullptr) {
+    if (kCausal && s0 != nullptr) {
 #pragma unroll
         for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
@@ -863,16 +847,18 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
         __syncthreads();
         stg.template park<0>(nvalid);
         if (ch + 1 < ch_end) stg.template fetch<0>(ch + 1);
-        // S as it stands before this chunk, element (d, m) at lds_u[m][d] (row stride D + 4)
+        if constexpr (kCausal) {
+            // S as it stands before this chunk, element (d, m) at lds_u[m][d] (row stride D + 4)
 #pragma unroll
-        for (int xt = 0; xt < XT; ++xt)
+            for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
-            for (int zt = 0; zt < ZT; ++zt)
-                lds_store4(lds_u + (16 * zt + c) * (D + 4) + 16 * xt + 4 * g, S[xt][zt]);
+                for (int zt = 0; zt < ZT; ++zt)
+                    lds_store4(lds_u + (16 * zt + c) * (D + 4) + 16 * xt + 4 * g, S[xt][zt]);
+        }
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        {
+        if constexpr (kCausal) {
             float kf[XT][4], vf[ZT][4];
             lds_feature_lane<D>(lds_fk, c, g, kf);
             lds_feature_lane<M>(lds_v, c, g, vf);
@@ -914,49 +900,47 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
 // are cut).  Reads Q, K, V, dO and the forward's denominators; the forward's output O is not
 // needed.  Wave 0 does the read-out, the in-chunk part and the epilogue; wave 1 carries the
 // running sum S it reads out from (see run_dq_sums).
-template <int D, int M, typename T>
+// kCausal = false is the same step of the non-causal backward: the read-out is against the sum
+// over the whole sequence (a.state, slot 0), wave 0 keeps it in registers, and there is no
+// in-chunk part; only Q, dO and the denominators are read.
+template <int D, int M, typename T, bool kCausal>
 __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void dq_pass_kernel(
     const PassArgs a) {
-    __shared__ float lds_g[tile_floats(M)];     // dO / den
-    __shared__ float lds_v[tile_floats(M)];     // V
-    __shared__ float lds_fk[tile_floats(D)];    // phi(K)
-    __shared__ float lds_fq[tile_floats(D)];    // phi(Q)
-    __shared__ float lds_S[M * (D + 4)];        // S before the current chunk, as [m][d]
+    __shared__ float lds_g[tile_floats(M)];                       // dO / den
+    __shared__ float lds_v[kCausal ? tile_floats(M) : 4];         // V
+    __shared__ float lds_fk[kCausal ? tile_floats(D) : 4];        // phi(K)
+    __shared__ float lds_fq[tile_floats(D)];                      // phi(Q)
+    __shared__ float lds_S[kCausal ? M * (D + 4) : 4];            // S before the current chunk, as [m][d]
     const int lane = threadIdx.x & (kWave - 1);
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
-        DqStager<0, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_g, lds_v);
-        run_pass<kDq, D, M, T, kBorrowState>(a, stg, lds_g, lds_v, lds_fk, lds_fq, a.out, bh, seg,
-                                             lane, lds_S);
+        DqStager<0, D, M, T, kCausal> stg(a, (size_t)bh * a.N, lane, lds_g, lds_v);
+        if constexpr (kCausal)
+            run_pass<kDq, D, M, T, kBorrowState>(a, stg, lds_g, lds_v, lds_fk, lds_fq, a.out, bh,
+                                                 seg, lane, lds_S);
+        else
+            run_pass<kGlobalDq, D, M, T>(a, stg, lds_g, nullptr, nullptr, lds_fq, a.out, bh, seg,
+                                         lane);
     } else {
-        DqStager<1, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fk, lds_fq);
-        run_dq_sums<D, M, T>(a, stg, lds_fk, lds_v, lds_fq, lds_g, lds_S, bh, seg, lane);
+        DqStager<1, D, M, T, kCausal> stg(a, (size_t)bh * a.N, lane, lds_fq, lds_fk);
+        run_dq_sums<D, M, T, kCausal>(a, stg, lds_fk, lds_v, lds_fq, lds_g, lds_S, bh, seg, lane);
     }
 }
 
 // ---- per-segment totals (first phase of the segment scan) ---------------------------------
-// KIND 0: S = sum phi(K_b)^T V_b,      z   = sum phi(K_b)            (eq. 10-11 over a segment)
-// KIND 1: R = sum phi(Q_b)^T dO_b/den, rho = sum delta_b phi(Q_b)    (eq. 14-15 over a segment)
-// KIND 2: as KIND 1, but 1/den and delta = -(dO.O)/den are formed here from O and den and also
-//         written out for the passes that follow (rden_out, delta_out): the backward then needs
-//         no separate sweep over dO and O.
-// Written as [D][M] row-major followed by the D-vector.
+// S = sum phi(K_b)^T V_b, z = sum phi(K_b) over the tokens of one segment (eq. 10-11), written
+// as [D][M] row-major followed by the D-vector.  (The matching sums of the backward, over Q and
+// dO, come out of the dQ kernel.)
 struct SegArgs {
-    const void *Y;        // K or Q  [BH, N, D]
-    const void *Z;        // V or dO [BH, N, M]
-    const float *rden;    // KIND 1
-    const float *delta;   // KIND 1
-    const void *O;        // KIND 2: forward output [BH, N, M]
-    const float *den;     // KIND 2: forward denominators [BH, N]
-    float *rden_out;      // KIND 2
-    float *delta_out;     // KIND 2
+    const void *Y;        // K [BH, N, D]
+    const void *Z;        // V [BH, N, M]
     float *state;         // [BH, nseg, state_stride]
     int N, nseg, chunks_per_seg;
     int skip_seg;         // segment whose total nobody reads (-1: none)
 };
 
-template <int KIND, int D, int M, typename T>
+template <int D, int M, typename T>
 __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     constexpr int XT = D / 16, ZT = M / 16;
     __shared__ float lds_y[tile_floats(D)];
@@ -970,10 +954,6 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     const size_t rowbase = (size_t)bh * a.N;
     const T *Ys = static_cast<const T *>(a.Y) + rowbase * D;
     const T *Zs = static_cast<const T *>(a.Z) + rowbase * M;
-    const float *rden = (KIND == 2 ? a.den : a.rden) + rowbase;   // KIND 2 stages den itself
-    const float *delta = a.delta + rowbase;
-    const T *Os = static_cast<const T *>(a.O) + rowbase * M;
-    __shared__ float lds_delta[kChunk];
 
     f32x4 U[XT][ZT];
     float ec[XT];
@@ -984,69 +964,36 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    f32x4 sy[XT], sz[ZT], so[ZT];
-    float scy[XT], scz[ZT];
-    float n_w4[4] = {1.f, 1.f, 1.f, 1.f};
+    f32x4 sy[XT], sz[ZT];
+    float oney[XT], onez[ZT];
 #pragma unroll
-    for (int i = 0; i < XT; ++i) scy[i] = 1.0f;
+    for (int i = 0; i < XT; ++i) oney[i] = 1.0f;
 #pragma unroll
-    for (int i = 0; i < ZT; ++i) scz[i] = 1.0f;
+    for (int i = 0; i < ZT; ++i) onez[i] = 1.0f;
 
-    auto fetch_impl = [&](auto full_tag, const int t0, const int nvalid) {
-        constexpr bool kFull = decltype(full_tag)::value;
-        stage_load<D, kFull>(Ys + (size_t)t0 * D, nvalid, lane, sy);
-        stage_load<M, kFull>(Zs + (size_t)t0 * M, nvalid, lane, sz);
-        if constexpr (KIND == 1) {
-            stage_rows<M, kFull>(rden + t0, nvalid, lane, scz);
-            rows4<kFull>(delta + t0, nvalid, g, n_w4);
-        }
-        if constexpr (KIND == 2) {
-            stage_load<M, kFull>(Os + (size_t)t0 * M, nvalid, lane, so);
-            stage_rows<M, kFull>(rden + t0, nvalid, lane, scz);       // den of the staged rows
-        }
-    };
     auto fetch = [&](const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
-        if (nvalid == kChunk) fetch_impl(std::true_type{}, t0, nvalid);
-        else fetch_impl(std::false_type{}, t0, nvalid);
+        if (nvalid == kChunk) {
+            stage_load<D, true>(Ys + (size_t)t0 * D, nvalid, lane, sy);
+            stage_load<M, true>(Zs + (size_t)t0 * M, nvalid, lane, sz);
+        } else {
+            stage_load<D, false>(Ys + (size_t)t0 * D, nvalid, lane, sy);
+            stage_load<M, false>(Zs + (size_t)t0 * M, nvalid, lane, sz);
+        }
     };
 
     if (ch_begin < ch_end) fetch(ch_begin);
     for (int ch = ch_begin; ch < ch_end; ++ch) {
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
-        if constexpr (KIND == 2) {
-            // quotient rule per token: 1/den, and delta = -(dO . O)/den; the M/4 lanes that
-            // stage one row add up their partial dot products
-            constexpr int LPR = M / 4;
-#pragma unroll
-            for (int i = 0; i < ZT; ++i) {
-                float p = (sz[i][0] * so[i][0] + sz[i][1] * so[i][1]) +
-                          (sz[i][2] * so[i][2] + sz[i][3] * so[i][3]);
-#pragma unroll
-                for (int off = 1; off < LPR; off <<= 1) p += __shfl_xor(p, off);
-                const int row = stage_row<M>(lane, i);
-                const float r = 1.0f / scz[i];
-                const float dl = row < nvalid ? -p * r : 0.f;
-                scz[i] = r;
-                if (lane % LPR == 0) {
-                    lds_delta[row] = dl;
-                    if (row < nvalid) {
-                        a.rden_out[rowbase + ch * kChunk + row] = r;
-                        a.delta_out[rowbase + ch * kChunk + row] = dl;
-                    }
-                }
-            }
-        }
         if (nvalid == kChunk) {
-            park_tile<D, kMapPhi, true>(lds_y, sy, scy, nvalid, lane);
-            park_tile<M, KIND == 0 ? kMapId : kMapScale, true>(lds_z, sz, scz, nvalid, lane);
+            park_tile<D, kMapPhi, true>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, true>(lds_z, sz, onez, nvalid, lane);
         } else {
-            park_tile<D, kMapPhi, false>(lds_y, sy, scy, nvalid, lane);
-            park_tile<M, KIND == 0 ? kMapId : kMapScale, false>(lds_z, sz, scz, nvalid, lane);
+            park_tile<D, kMapPhi, false>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, false>(lds_z, sz, onez, nvalid, lane);
         }
-        float w4[4] = {n_w4[0], n_w4[1], n_w4[2], n_w4[3]};
         if (ch + 1 < ch_end) fetch(ch + 1);
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
         __builtin_amdgcn_sched_barrier(0);
@@ -1055,10 +1002,6 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         float yf[XT][4], zf[ZT][4];
         lds_feature_lane<D>(lds_y, c, g, yf);
         lds_feature_lane<M>(lds_z, c, g, zf);
-        if constexpr (KIND == 2) {
-#pragma unroll
-            for (int s = 0; s < 4; ++s) w4[s] = lds_delta[4 * g + s];
-        }
 #pragma unroll
         for (int s = 0; s < 4; ++s)
 #pragma unroll
@@ -1066,9 +1009,7 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
 #pragma unroll
-        for (int xt = 0; xt < XT; ++xt)
-#pragma unroll
-            for (int s = 0; s < 4; ++s) ec[xt] = fmaf(w4[s], yf[xt][s], ec[xt]);
+        for (int xt = 0; xt < XT; ++xt) ec[xt] += (yf[xt][0] + yf[xt][1]) + (yf[xt][2] + yf[xt][3]);
     }
     float *st = a.state + ((size_t)bh * a.nseg + seg) * state_stride(D, M);
 #pragma unroll

@@ -43,7 +43,7 @@ def test_version_and_status_strings(lib):
         assert s and s != "unknown status" and s not in seen
         seen.add(s)
     assert binding.status_string(-99) == "unknown status"
-    assert binding.la_kernel_name(3) == "causal_pass_fwd" and binding.la_kernel_name(99) == "unknown"
+    assert binding.la_kernel_name(2) == "causal_pass_fwd" and binding.la_kernel_name(99) == "unknown"
 
 
 def test_workspace_queries(lib):
