@@ -113,8 +113,11 @@ int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float
  * given dO = dL/dO it writes dQ, dK (with respect to the RAW Q, K, i.e.
  * through phi) and dV.  One forward and one reverse cumulative sum; memory is
  * O(N max(D,M)), no per-position state is stored.
- * O [B,H,N,M] and den [B,H,N] are the results of la_causal_fwd on the same
- * Q, K, V, eps; if either is NULL both are recomputed into the workspace.
+ * den [B,H,N] is the denominator output of la_causal_fwd on the same Q, K, V,
+ * eps; NULL: the forward is recomputed into the workspace.  O is NOT read and
+ * may be NULL (a caller need not keep it for the backward): the one place the
+ * gradient needs it, dO_i . O_i, equals phi(Q_i) . (S_i dO_i)/den_i, which the
+ * dQ pass has at hand.  The argument stays for symmetry with the forward.
  * fwd_ws is optional (NULL allowed): the workspace that la_causal_fwd used for
  * that same call, untouched since.  It then still holds the running sums of
  * eq. 10-11 at the segment borders, and the backward reuses them instead of
@@ -140,7 +143,7 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
  * to (S0, z0), i.e. the reverse sum after token 0, to be handed to the piece
  * before as its dS1, dz1.  Pieces chained this way reproduce the gradients of
  * the uncut sequence.  O, den, fwd_ws: results (and workspace) of
- * la_causal_fwd_state with the same S0, z0; O/den NULL: recomputed.  The
+ * la_causal_fwd_state with the same S0, z0; den NULL: recomputed; O not read.  The
  * in-buffers must not alias the out-buffers.  Workspace as la_causal_bwd.
  */
 int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float *S0,
@@ -168,8 +171,9 @@ int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *d
  * totals S~ = sum_j phi(K_j) V~_j^T and R~ = sum_i phi(Q_i) G~_i^T,
  *   dphi(Q)_i = S~ G~_i,   dphi(K)_j = R~ V~_j,   dV_j = (R~^T phi(K_j))[0:M],
  * followed by the chain rule through phi (elementwise times phi'(Q), phi'(K)).
- * O and den are the results of la_global_fwd on the same Q, K, V, eps; if
- * either is NULL both are recomputed into the workspace.  fwd_ws is optional
+ * den is the denominator output of la_global_fwd on the same Q, K, V, eps
+ * (NULL: recomputed into the workspace); O is not read and may be NULL, as in
+ * la_causal_bwd.  fwd_ws is optional
  * (NULL allowed): the workspace la_global_fwd used for that call, untouched
  * since; it still holds S~ and the backward then does not re-read K and V to
  * rebuild it.  dQ, dK [B,H,N,D] out; dV [B,H,N,M] out.  ws:

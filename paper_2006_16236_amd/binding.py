@@ -165,8 +165,8 @@ def la_causal_fwd_state(Q, K, V, O, den=None, S0=None, z0=None, S1=None, z1=None
 
 def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None):
     """dQ, dK, dV <- gradients of causal linear attention for upstream dO; O and den are the
-    forward results (either may be None: both are then recomputed).  fwd_ws (optional) is the
-    workspace tensor la_causal_fwd returned for the same call: its segment states are reused."""
+    forward results (den None: recomputed; O is not read and may be None).  fwd_ws (optional) is
+    the workspace tensor la_causal_fwd returned for the same call: its segment states are reused."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
     t = _dtype_code(Q)
@@ -208,8 +208,8 @@ def la_global_fwd(Q, K, V, O, eps=1e-6, ws=None, stream=None, den=None):
 
 def la_global_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None):
     """dQ, dK, dV <- gradients of non-causal linear attention for upstream dO; O and den are the
-    results of la_global_fwd (either may be None: both are then recomputed).  fwd_ws (optional)
-    is the workspace tensor la_global_fwd returned for the same call."""
+    results of la_global_fwd (den None: recomputed; O is not read and may be None).  fwd_ws
+    (optional) is the workspace tensor la_global_fwd returned for the same call."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
     t = _dtype_code(Q)

@@ -359,6 +359,31 @@ def test_backward_chained_over_two_pieces_equals_the_uncut_sequence(la, oracle, 
     assert max(grad_errs(got, ref)) <= tol_for(N1 + N2)
 
 
+@pytest.mark.parametrize("sched", ["default", "one_segment", "three_chunk_segments"])
+def test_backward_needs_den_but_not_O(la, oracle, sched):
+    """The backward rebuilds dO.O from its own read-out: O may be NULL, or hold anything."""
+    B, H, N, D, M = 2, 2, 300, 64, 64
+    Q, K, V, G = wl.random_case(995, B, H, N, D, M)
+    gref = oracle.causal_bwd_linear(Q, K, V, G, 1e-6)
+    ggref = oracle.global_bwd_linear(Q, K, V, G, 1e-6)
+    dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+    with schedule(**SCHEDULES[sched]):
+        O = torch.empty_like(dv)
+        den = torch.empty(B, H, N, device=DEV)
+        fwd_ws = la.la_causal_fwd(dq, dk, dv, O, den, 1e-6)
+        junk = torch.full_like(dv, float("nan"))
+        for o_arg in (None, junk):
+            gq, gk, gv = (torch.full_like(x, float("nan")) for x in (dq, dk, dv))
+            la.la_causal_bwd(dq, dk, dv, o_arg, den, dg, gq, gk, gv, 1e-6, fwd_ws=fwd_ws)
+            torch.cuda.synchronize()
+            assert max(grad_errs([to_host(gq), to_host(gk), to_host(gv)], gref)) <= tol_for(N)
+        gws = la.la_global_fwd(dq, dk, dv, O, 1e-6, den=den)
+        gq, gk, gv = (torch.full_like(x, float("nan")) for x in (dq, dk, dv))
+        la.la_global_bwd(dq, dk, dv, None, den, dg, gq, gk, gv, 1e-6, fwd_ws=gws)
+        torch.cuda.synchronize()
+        assert max(grad_errs([to_host(gq), to_host(gk), to_host(gv)], ggref)) <= tol_for(N)
+
+
 def test_bitwise_determinism_and_slab_independence(la):
     B, H, N, D, M = 2, 4, 500, 64, 64
     Q, K, V, G = wl.random_case(800, B, H, N, D, M)
