@@ -152,7 +152,7 @@ def run_headline(args):
     prof_all = profile_kernels(la, fb.step, 3, torch)
     per_step = {k: ms * n for k, (ms, n) in prof_all.items()}
     dominant = max(per_step, key=per_step.get)
-    kid = [la.la_kernel_name(i) for i in range(9)].index(dominant)
+    kid = [la.la_kernel_name(i) for i in range(la.binding.LA_K_COUNT)].index(dominant)
 
     # the timed region: exactly `steps` steps, events only around the dominant kernel
     torch.cuda.synchronize()
@@ -200,10 +200,10 @@ def run_table(args):
     import workloads as wl
     rows = []
 
-    def fwdbwd_row(w, bf16=False, steps=10):
+    def fwdbwd_row(w, bf16=False, steps=20):
         fb = FwdBwd(w, bf16)
-        sec = time_steps(fb.step, steps, 3, torch)
-        secf = time_steps(fb.fwd_only, steps, 2, torch)
+        sec = time_steps(fb.step, steps, 5, torch)
+        secf = time_steps(fb.fwd_only, steps, 5, torch)
         prof = profile_kernels(la, fb.step, 3, torch)
         e = 2 if bf16 else 4
         ceiling = HBM_PEAK_GBS * 1e9 / (w.H * e * (6 * w.D + 6 * w.M)) / 1e6
@@ -216,15 +216,15 @@ def run_table(args):
         return fb
 
     for w in (wl.CFG2, wl.CFG3):
-        fwdbwd_row(w)
-    fwdbwd_row(wl.CFG3, bf16=True)
+        fwdbwd_row(w, steps=200)
+    fwdbwd_row(wl.CFG3, bf16=True, steps=200)
     for n in range(9, 17):
         w = wl.sweep_point(n)
-        fb = fwdbwd_row(w, steps=5)
+        fb = fwdbwd_row(w)
         # the non-causal forward on the same tensors
         ws = torch.empty(la.la_global_fwd_workspace(w.B, w.H, w.N, w.D, w.M), dtype=torch.uint8,
                          device="cuda:0")
-        sec = time_steps(lambda: la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws), 5, 2, torch)
+        sec = time_steps(lambda: la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws), 20, 5, torch)
         rows.append({"workload": w.name + "_global_fwd", "tokens": w.B * w.N, "fwd_ms": sec * 1e3,
                      "fwd_mtok_s": w.B * w.N / sec / 1e6,
                      "hbm_ceiling_mtok_s": HBM_PEAK_GBS * 1e9 / (w.H * 4 * (2 * w.D + 2 * w.M)) / 1e6})
@@ -238,7 +238,7 @@ def run_table(args):
             la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws, den=deng)
             la.la_global_bwd(fb.Q, fb.K, fb.V, fb.O, deng, fb.G, fb.dQ, fb.dK, fb.dV, w.eps, ws=wsb,
                              fwd_ws=ws)
-        sec = time_steps(global_step, 5, 2, torch)
+        sec = time_steps(global_step, 20, 5, torch)
         prof = profile_kernels(la, global_step, 3, torch)
         rows.append({"workload": w.name + "_global_fwd_bwd", "tokens": w.B * w.N,
                      "fwd_bwd_ms": sec * 1e3, "fwd_bwd_mtok_s": w.B * w.N / sec / 1e6,
