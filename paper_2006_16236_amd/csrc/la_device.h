@@ -90,6 +90,28 @@ __device__ __forceinline__ f32x4 mfma16(float a, float b, f32x4 acc) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc, 0, 0, 0);
 }
 
+// bf16 tensors: the same tile products on `v_mfma_f32_16x16x16_bf16`.  Lane (c, g) supplies
+// A[c][4g + j] and B[4g + j][c], j = 0..3, packed as four bf16; the accumulator layout is that of
+// the fp32 instruction.  One such MFMA is the sum over r (or s) of four mfma16 calls, with the
+// operands rounded to bf16 (round to nearest even) and the products accumulated in fp32.
+typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ bf16x4_t pack_bf16x4(float a, float b, float c, float d) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 lo = {a, b}, hi = {c, d};
+    const u32x2 u = {__builtin_bit_cast(unsigned, __builtin_convertvector(lo, bf16x2)),
+                     __builtin_bit_cast(unsigned, __builtin_convertvector(hi, bf16x2))};
+    return __builtin_bit_cast(bf16x4_t, u);
+}
+__device__ __forceinline__ bf16x4_t pack_bf16x4(const float (&x)[4]) {
+    return pack_bf16x4(x[0], x[1], x[2], x[3]);
+}
+__device__ __forceinline__ bf16x4_t pack_bf16x4(f32x4 x) { return pack_bf16x4(x[0], x[1], x[2], x[3]); }
+__device__ __forceinline__ f32x4 mfma16_bf16(bf16x4_t a, bf16x4_t b, f32x4 acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, acc, 0, 0, 0);
+}
+
 // ---- tiles ------------------------------------------------------------------------------------
 // A tile is 16 consecutive tokens x F features of one [N, F] slab, F in {32, 64}.
 //

@@ -298,6 +298,9 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     constexpr bool kReverse = Tr::kReverse;
     constexpr bool kHasRaw = Tr::kHasRaw;
     constexpr bool kHasYZ = Tr::kHasYZ;
+    // bf16 tensors: the tile products run on the bf16 MFMA (operands rounded to bf16, fp32
+    // accumulation); the sums that ride on MFMAs against ones stay fp32
+    constexpr bool kBf = std::is_same<T, bf16_t>::value;
 
     const int c = lane & 15, g = lane >> 4;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
@@ -438,12 +441,24 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         f32x4 out[ZT];
 #pragma unroll
         for (int zt = 0; zt < ZT; ++zt) out[zt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        bf16x4_t xp[XT];                 // X packed (bf16 path)
+        if constexpr (kBf) {
 #pragma unroll
-        for (int xt = 0; xt < XT; ++xt)
+            for (int xt = 0; xt < XT; ++xt) {
+                xp[xt] = pack_bf16x4(xa[xt]);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
+                for (int zt = 0; zt < ZT; ++zt)
+                    out[zt] = mfma16_bf16(xp[xt], pack_bf16x4(U[xt][zt]), out[zt]);
+            }
+        } else {
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16(xa[xt][r], U[xt][zt][r], out[zt]);
+            for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt)
+                        out[zt] = mfma16(xa[xt][r], U[xt][zt][r], out[zt]);
+        }
 
         // kFwd / kGlobal: den4[r] = denominator of token 4g + r.  Each lane (c = a, g) holds a
         // partial sum of token a's denominator; one MFMA against a matrix of ones adds the four
@@ -451,6 +466,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         f32x4 den4 = {1.f, 1.f, 1.f, 1.f};
         const f32x4 eps4 = {a.eps, a.eps, a.eps, a.eps};
         float zf[ZT][4];                 // Z, feature-lane
+        bf16x4_t zp[ZT];                 // ... packed (bf16 path)
         if constexpr (!kHasYZ) {
             if constexpr (PASS == kGlobal) {
                 float p = 0.f;
@@ -469,13 +485,21 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             float ya[XT][4];             // Y, token-lane
             lds_token_lane<DX>(lds_y, c, g, ya);
             f32x4 w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
+            if constexpr (kBf) {
 #pragma unroll
-            for (int xt = 0; xt < XT; xt += 2)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    w0 = mfma16(ya[xt][r], xa[xt][r], w0);
-                    w1 = mfma16(ya[xt + 1][r], xa[xt + 1][r], w1);
+                for (int xt = 0; xt < XT; xt += 2) {
+                    w0 = mfma16_bf16(pack_bf16x4(ya[xt]), xp[xt], w0);
+                    w1 = mfma16_bf16(pack_bf16x4(ya[xt + 1]), xp[xt + 1], w1);
                 }
+            } else {
+#pragma unroll
+                for (int xt = 0; xt < XT; xt += 2)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        w0 = mfma16(ya[xt][r], xa[xt][r], w0);
+                        w1 = mfma16(ya[xt + 1][r], xa[xt + 1][r], w1);
+                    }
+            }
             f32x4 w;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -499,10 +523,19 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             }
             // ---- in-chunk term: out += W Z -------------------------------------------------
             lds_feature_lane<DZ>(lds_z, c, g, zf);
+            if constexpr (kBf) {
+                const bf16x4_t wp = pack_bf16x4(w);
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+                for (int zt = 0; zt < ZT; ++zt) {
+                    zp[zt] = pack_bf16x4(zf[zt]);
+                    out[zt] = mfma16_bf16(wp, zp[zt], out[zt]);
+                }
+            } else {
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16(w[s], zf[zt][s], out[zt]);
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16(w[s], zf[zt][s], out[zt]);
+            }
         }
 
         // ---- finish and store ---------------------------------------------------------------
@@ -540,11 +573,18 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(1.0f, ecp[zt], f32x4{0.f, 0.f, 0.f, 0.f});
             if constexpr (kHasYZ) {       // (kGlobalDq: z is the sum over the whole sequence)
+                float m[4];
 #pragma unroll
-                for (int s = 0; s < 4; ++s) {
-                    const float m = (4 * g + s) <= c ? 1.0f : 0.0f;
+                for (int s = 0; s < 4; ++s) m[s] = (4 * g + s) <= c ? 1.0f : 0.0f;
+                if constexpr (kBf) {
+                    const bf16x4_t mp = pack_bf16x4(m);
 #pragma unroll
-                    for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(m, zf[zt][s], cz[zt]);
+                    for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16_bf16(mp, zp[zt], cz[zt]);
+                } else {
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16(m[s], zf[zt][s], cz[zt]);
                 }
             }
 #pragma unroll
@@ -595,13 +635,22 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             if constexpr (kStateMode != kBorrowState || PASS == kFwd)
                 lds_feature_lane<DX>(lds_y, c, g, yf);
             if constexpr (kStateMode != kBorrowState) {
+                if constexpr (kBf) {
 #pragma unroll
-                for (int s = 0; s < 4; ++s)
+                    for (int xt = 0; xt < XT; ++xt) {
+                        const bf16x4_t yp = pack_bf16x4(yf[xt]);
 #pragma unroll
-                    for (int xt = 0; xt < XT; ++xt)
+                        for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_bf16(yp, zp[zt], U[xt][zt]);
+                    }
+                } else {
 #pragma unroll
-                        for (int zt = 0; zt < ZT; ++zt)
-                            U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                            for (int zt = 0; zt < ZT; ++zt)
+                                U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+                }
             }
             if constexpr (PASS == kFwd) {
                 // z += column sums of the chunk's phi(K).  Each lane adds up its four tokens;
@@ -820,6 +869,7 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const bool want = a.totals != nullptr;         // uniform
+    constexpr bool kBf = std::is_same<T, bf16_t>::value;   // see run_pass
 
     f32x4 S[XT][ZT], R[XT][ZT];                    // element (d = 16xt + 4g + r, m = 16zt + c)
 #pragma unroll
@@ -862,25 +912,49 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
             float kf[XT][4], vf[ZT][4];
             lds_feature_lane<D>(lds_fk, c, g, kf);
             lds_feature_lane<M>(lds_v, c, g, vf);
+            if constexpr (kBf) {
+                bf16x4_t vp[ZT];
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+                for (int zt = 0; zt < ZT; ++zt) vp[zt] = pack_bf16x4(vf[zt]);
 #pragma unroll
-                for (int xt = 0; xt < XT; ++xt)
+                for (int xt = 0; xt < XT; ++xt) {
+                    const bf16x4_t kp = pack_bf16x4(kf[xt]);
 #pragma unroll
-                    for (int zt = 0; zt < ZT; ++zt)
-                        S[xt][zt] = mfma16(kf[xt][s], vf[zt][s], S[xt][zt]);
+                    for (int zt = 0; zt < ZT; ++zt) S[xt][zt] = mfma16_bf16(kp, vp[zt], S[xt][zt]);
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                        for (int zt = 0; zt < ZT; ++zt)
+                            S[xt][zt] = mfma16(kf[xt][s], vf[zt][s], S[xt][zt]);
+            }
         }
         if (want) {
             float qf[XT][4], gf[ZT][4];
             lds_feature_lane<D>(lds_fq, c, g, qf);
             lds_feature_lane<M>(lds_g, c, g, gf);
+            if constexpr (kBf) {
+                bf16x4_t gp[ZT];
 #pragma unroll
-            for (int s = 0; s < 4; ++s)
+                for (int zt = 0; zt < ZT; ++zt) gp[zt] = pack_bf16x4(gf[zt]);
 #pragma unroll
-                for (int xt = 0; xt < XT; ++xt)
+                for (int xt = 0; xt < XT; ++xt) {
+                    const bf16x4_t qp = pack_bf16x4(qf[xt]);
 #pragma unroll
-                    for (int zt = 0; zt < ZT; ++zt)
-                        R[xt][zt] = mfma16(qf[xt][s], gf[zt][s], R[xt][zt]);
+                    for (int zt = 0; zt < ZT; ++zt) R[xt][zt] = mfma16_bf16(qp, gp[zt], R[xt][zt]);
+                }
+            } else {
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                        for (int zt = 0; zt < ZT; ++zt)
+                            R[xt][zt] = mfma16(qf[xt][s], gf[zt][s], R[xt][zt]);
+            }
         }
     }
     if (want) {
@@ -1002,12 +1076,25 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         float yf[XT][4], zf[ZT][4];
         lds_feature_lane<D>(lds_y, c, g, yf);
         lds_feature_lane<M>(lds_z, c, g, zf);
+        if constexpr (std::is_same<T, bf16_t>::value) {       // see run_pass
+            bf16x4_t zp[ZT];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
+            for (int zt = 0; zt < ZT; ++zt) zp[zt] = pack_bf16x4(zf[zt]);
 #pragma unroll
-            for (int xt = 0; xt < XT; ++xt)
+            for (int xt = 0; xt < XT; ++xt) {
+                const bf16x4_t yp = pack_bf16x4(yf[xt]);
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+                for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_bf16(yp, zp[zt], U[xt][zt]);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt)
+                        U[xt][zt] = mfma16(yf[xt][s], zf[zt][s], U[xt][zt]);
+        }
 #pragma unroll
         for (int xt = 0; xt < XT; ++xt) ec[xt] += (yf[xt][0] + yf[xt][1]) + (yf[xt][2] + yf[xt][3]);
     }
