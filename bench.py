@@ -219,6 +219,7 @@ def run_table(args):
     for w in (wl.CFG2, wl.CFG3):
         fwdbwd_row(w, steps=200)
     fwdbwd_row(wl.CFG3, bf16=True, steps=200)
+    fwdbwd_row(wl.sweep_point(16), bf16=True)
     for n in range(9, 17):
         w = wl.sweep_point(n)
         fb = fwdbwd_row(w)

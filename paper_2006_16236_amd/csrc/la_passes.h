@@ -99,9 +99,14 @@ __device__ __forceinline__ float map_value(float v, float scale) {
     return v;
 }
 
+template <typename T> constexpr bool is_bf16 = std::is_same<T, bf16_t>::value;
+
 // Park a staged tile in LDS: apply the map; kFull = false also zeroes the rows past the end
-// of the sequence.
-template <int F, int MAP, bool kFull>
+// of the sequence.  kRound (bf16 tensors): the mapped values phi(x) and dO/den are rounded to
+// bf16 here, once, so that every product and every sum that uses them sees the same values:
+// the numerator S and the denominator z of eq. 10-12 are then built from identical features
+// (the attention weights still sum to one), and packing them as MFMA operands is exact.
+template <int F, int MAP, bool kFull, bool kRound>
 __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16],
                                           const float (&scale)[F / 16], int nvalid, int lane) {
 #pragma unroll
@@ -113,6 +118,7 @@ __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16]
             const float m = map_value<MAP>(st[i][r], scale[i]);
             v[r] = (kFull || row < nvalid) ? m : 0.0f;
         }
+        if constexpr (kRound && (MAP == kMapPhi || MAP == kMapScale)) v = round_to_bf16(v);
         lds_store4(tile + row * tile_stride(F) + stage_col<F>(lane, i), v);
     }
 }
@@ -186,12 +192,12 @@ struct PassStager {
 
     template <bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<DX, Tr::kMapX, kFull>(lds_x, sx, onex, nvalid, lane);
+        park_tile<DX, Tr::kMapX, kFull, is_bf16<T>>(lds_x, sx, onex, nvalid, lane);
         if constexpr (Tr::kHasYZ) {
-            park_tile<DX, Tr::kMapY, kFull>(lds_y, sy, onex, nvalid, lane);
-            park_tile<DZ, Tr::kMapZ, kFull>(lds_z, sz, onez, nvalid, lane);
+            park_tile<DX, Tr::kMapY, kFull, is_bf16<T>>(lds_y, sy, onex, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ, kFull, is_bf16<T>>(lds_z, sz, onez, nvalid, lane);
         }
-        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull>(lds_r, sr, onez, nvalid, lane);
+        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, is_bf16<T>>(lds_r, sr, onez, nvalid, lane);
     }
 
     template <int SLOT>
@@ -256,12 +262,12 @@ struct ReverseStager {
 
     template <int SLOT, bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<D, kMapPhi, kFull>(lds_a, sa[SLOT], scd, nvalid, lane);
+        park_tile<D, kMapPhi, kFull, is_bf16<T>>(lds_a, sa[SLOT], scd, nvalid, lane);
         if constexpr (ROLE == 0) {
-            park_tile<M, kMapScale, kFull>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<M, kMapScale, kFull, is_bf16<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         } else {
-            park_tile<D, kMapDphi, kFull>(lds_a2, sa[SLOT], scd, nvalid, lane);
-            park_tile<M, kMapId, kFull>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<D, kMapDphi, kFull, is_bf16<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
+            park_tile<M, kMapId, kFull, is_bf16<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         }
     }
 
@@ -833,14 +839,14 @@ struct DqStager {
         if constexpr (ROLE == 0) {
 #pragma unroll
             for (int i = 0; i < FT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
-            park_tile<F, kMapScale, kFull>(lds_a, sa, sca, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapId, kFull>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapScale, kFull, is_bf16<T>>(lds_a, sa, sca, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapId, kFull, is_bf16<T>>(lds_b, sb, one, nvalid, lane);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
         } else {
-            park_tile<F, kMapPhi, kFull>(lds_a, sa, one, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapPhi, kFull>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapPhi, kFull, is_bf16<T>>(lds_a, sa, one, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_bf16<T>>(lds_b, sb, one, nvalid, lane);
         }
     }
 
@@ -1062,11 +1068,11 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
         if (nvalid == kChunk) {
-            park_tile<D, kMapPhi, true>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, true>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, true, is_bf16<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, true, is_bf16<T>>(lds_z, sz, onez, nvalid, lane);
         } else {
-            park_tile<D, kMapPhi, false>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, false>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, false, is_bf16<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, false, is_bf16<T>>(lds_z, sz, onez, nvalid, lane);
         }
         if (ch + 1 < ch_end) fetch(ch + 1);
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
