@@ -135,8 +135,8 @@ def cpu_baseline(w, host, sample_tokens):
             "kind": "oracle",
             "sample": f"fp64 oracle forward+backward on the first {sample_tokens} of {w.N} tokens of "
                       f"all {w.B * w.H} (batch, head) sequences of the same inputs, one run, "
-                      f"{dt:.1f} s wall; OpenMP over sequences ({la_oracle.max_threads()} threads "
-                      f"available, {threads} busy)"}
+                      f"{dt:.1f} s wall x {threads} threads = {dt * threads:.0f} s of CPU work; OpenMP "
+                      f"over sequences ({la_oracle.max_threads()} threads available, {threads} busy)"}
 
 
 def run_headline(args):
@@ -294,7 +294,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=32768)
+    ap.add_argument("--cpu-sample-tokens", type=int, default=65536)
     ap.add_argument("--table", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy first (a kernel of known traffic, "

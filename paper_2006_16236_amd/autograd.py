@@ -1,0 +1,62 @@
+"""torch.autograd front end of the C ABI: two differentiable functions.
+
+Marshalling only: forward and backward are the library's kernels (la_causal_fwd / la_causal_bwd,
+la_global_fwd / la_global_bwd); this file allocates the outputs and tells autograd what to keep.
+What is kept for the backward is Q, K, V, the denominators [B, H, N] and the forward's workspace
+(the running sums at the segment borders): the attention output itself is not needed, and no
+per-position state is stored (the constant-memory backward of section 3.3.1).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as _b
+
+
+class _CausalLinearAttention(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, Q, K, V, eps):
+        Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
+        O = torch.empty_like(V)
+        den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
+        ws = _b.la_causal_fwd(Q, K, V, O, den, eps)
+        ctx.save_for_backward(Q, K, V, den, ws)
+        ctx.eps = eps
+        return O
+
+    @staticmethod
+    def backward(ctx, dO):
+        Q, K, V, den, ws = ctx.saved_tensors
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+        _b.la_causal_bwd(Q, K, V, None, den, dO.contiguous(), dQ, dK, dV, ctx.eps, fwd_ws=ws)
+        return dQ, dK, dV, None
+
+
+class _LinearAttention(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, Q, K, V, eps):
+        Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
+        O = torch.empty_like(V)
+        den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
+        ws = _b.la_global_fwd(Q, K, V, O, eps, den=den)
+        ctx.save_for_backward(Q, K, V, den, ws)
+        ctx.eps = eps
+        return O
+
+    @staticmethod
+    def backward(ctx, dO):
+        Q, K, V, den, ws = ctx.saved_tensors
+        dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+        _b.la_global_bwd(Q, K, V, None, den, dO.contiguous(), dQ, dK, dV, ctx.eps, fwd_ws=ws)
+        return dQ, dK, dV, None
+
+
+def causal_linear_attention(Q, K, V, eps: float = 1e-6):
+    """Causal linear attention (eq. 9-12) of Q, K [B, H, N, D], V [B, H, N, M] with
+    phi(x) = elu(x) + 1; differentiable with respect to Q, K, V."""
+    return _CausalLinearAttention.apply(Q, K, V, float(eps))
+
+
+def linear_attention(Q, K, V, eps: float = 1e-6):
+    """Non-causal linear attention (eq. 4-6); differentiable with respect to Q, K, V."""
+    return _LinearAttention.apply(Q, K, V, float(eps))

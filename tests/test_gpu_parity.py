@@ -384,6 +384,24 @@ def test_backward_needs_den_but_not_O(la, oracle, sched):
         assert max(grad_errs([to_host(gq), to_host(gk), to_host(gv)], ggref)) <= tol_for(N)
 
 
+@pytest.mark.parametrize("causal", [True, False])
+def test_autograd_front_end(la, oracle, causal):
+    """The torch.autograd wrappers run the library's forward and backward: loss = sum(G * O)."""
+    B, H, N, D, M = 2, 2, 333, 64, 32
+    Q, K, V, G = wl.random_case(997, B, H, N, D, M)
+    tq, tk, tv = (to_dev(x).requires_grad_(True) for x in (Q, K, V))
+    fn = la.causal_linear_attention if causal else la.linear_attention
+    O = fn(tq, tk, tv, 1e-6)
+    (O * to_dev(G)).sum().backward()
+    torch.cuda.synchronize()
+    if causal:
+        ref, gref = oracle.causal_fwd_prefix(Q, K, V, 1e-6), oracle.causal_bwd_linear(Q, K, V, G, 1e-6)
+    else:
+        ref, gref = oracle.global_fwd_linear(Q, K, V, 1e-6), oracle.global_bwd_linear(Q, K, V, G, 1e-6)
+    assert rel_err(to_host(O), ref) <= tol_for(N)
+    assert max(grad_errs([to_host(t.grad) for t in (tq, tk, tv)], gref)) <= tol_for(N)
+
+
 def test_bitwise_determinism_and_slab_independence(la):
     B, H, N, D, M = 2, 4, 500, 64, 64
     Q, K, V, G = wl.random_case(800, B, H, N, D, M)
