@@ -402,6 +402,37 @@ def test_autograd_front_end(la, oracle, causal):
     assert max(grad_errs([to_host(t.grad) for t in (tq, tk, tv)], gref)) <= tol_for(N)
 
 
+def _random_shapes(count, seed):
+    rng = np.random.default_rng(seed)
+    sched_names = list(SCHEDULES)
+    for i in range(count):
+        yield (int(rng.integers(1, 4)), int(rng.integers(1, 5)), int(rng.integers(1, 700)),
+               int(rng.choice([32, 64])), int(rng.choice([32, 64])),
+               sched_names[int(rng.integers(len(sched_names)))], float(rng.choice([0.0, 1e-6, 1e-2])),
+               2000 + i)
+
+
+@pytest.mark.parametrize("B,H,N,D,M,sched,eps,seed", list(_random_shapes(24, 31337)))
+def test_random_shapes_all_entry_points(la, oracle, B, H, N, D, M, sched, eps, seed):
+    """Seeded random sizes, head widths, schedules and eps: causal forward + backward (with a
+    state handed in and out) and the non-causal pair, each against the oracle."""
+    Q, K, V, G, S0, z0, dS1, dz1 = _state_case(seed, B, H, N, D, M)
+    tol = tol_for(N)
+    with schedule(**SCHEDULES[sched]):
+        O, den = run_fwd(la, Q, K, V, eps)
+        grads = run_bwd(la, Q, K, V, G, eps)
+        gs = _gpu_bwd_state(la, Q, K, V, G, S0, z0, dS1, dz1, eps)
+        Og, deng, gg = run_global(la, Q, K, V, G, eps)
+    ref, dref = oracle.causal_fwd_prefix(Q, K, V, eps, return_den=True)
+    assert rel_err(O, ref) <= tol and rel_err(den, dref) <= tol
+    assert max(grad_errs(grads, oracle.causal_bwd_linear(Q, K, V, G, eps))) <= tol
+    rs = oracle.causal_bwd_state(Q, K, V, G, S0, z0, dS1, dz1, eps)
+    assert max(grad_errs(gs[:3], rs[:3])) <= tol
+    assert rel_err(gs[3], rs[3]) <= tol and rel_err(gs[4], rs[4]) <= tol
+    assert rel_err(Og, oracle.global_fwd_linear(Q, K, V, eps)) <= tol
+    assert max(grad_errs(gg, oracle.global_bwd_linear(Q, K, V, G, eps))) <= tol
+
+
 def test_bitwise_determinism_and_slab_independence(la):
     B, H, N, D, M = 2, 4, 500, 64, 64
     Q, K, V, G = wl.random_case(800, B, H, N, D, M)
