@@ -165,3 +165,18 @@ def test_decode_suspend_and_resume(la):
         la.la_recurrent_step(q[t], k[t], v[t], S3, z3, out2[t])
     torch.cuda.synchronize()
     assert torch.equal(out, out2) and torch.equal(S, S3) and torch.equal(z, z3)
+
+
+def test_one_very_long_sequence(la, oracle):
+    """B = H = 1, N = 2^18: every wave of the machine works on the same sequence (2048 segments);
+    fp32 running sums over a quarter of a million tokens stay inside the long-sequence gate."""
+    w = wl.Workload("long_B1_H1_N2^18_D64", 1, 1, 1 << 18, 64, 64, 1500)
+    host = wl.qkvg(w)
+    O, den, dQ, dK, dV = gpu_fwd_bwd(la, host, eps=w.eps)
+    ref, dref = oracle.causal_fwd_prefix(*host[:3], w.eps, return_den=True)
+    gref = oracle.causal_bwd_linear(*host, w.eps)
+    tol = tol_for(w.N)
+    assert rel_err(to_host(O), ref) <= tol
+    assert rel_err(den.cpu().numpy(), dref) <= tol
+    errs = grad_errs([to_host(x) for x in (dQ, dK, dV)], gref)
+    assert max(errs) <= tol, errs
