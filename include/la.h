@@ -28,7 +28,10 @@
  *   Errors     Return value: LA_OK (0) or a negative la_status.  Argument
  *              errors are detected on the host before anything is launched;
  *              a failed launch returns LA_ERR_HIP.  No exceptions, no abort.
- *   Aliasing   Outputs must not overlap inputs or each other (undefined).
+ *   Aliasing   A buffer that a call writes (outputs, workspace, the decode state)
+ *              must not overlap any other buffer of the call: LA_ERR_ALIAS,
+ *              checked on the host from the pointers and the sizes, last of
+ *              the argument checks.
  *   Determinism No floating-point atomics: the same call on the same inputs
  *              gives bit-identical results.
  *   Threads    No global mutable state apart from the optional profiling hook
@@ -60,7 +63,8 @@ typedef enum {
     LA_ERR_UNSUPPORTED = -3,  /* D or M not in {32, 64}, unknown dtype              */
     LA_ERR_WORKSPACE = -4,    /* ws is NULL or ws_bytes is smaller than the query   */
     LA_ERR_HIP = -5,          /* a HIP call or kernel launch failed                 */
-    LA_ERR_ALIGN = -6         /* a tensor pointer is not 16-byte aligned            */
+    LA_ERR_ALIGN = -6,        /* a tensor pointer is not 16-byte aligned            */
+    LA_ERR_ALIAS = -7         /* a written buffer overlaps another buffer of the call */
 } la_status;
 
 /* Static, NUL-terminated description of a status code. */

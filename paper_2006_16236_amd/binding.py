@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libla_hip.so")
 
 LA_F32, LA_BF16 = 0, 1
 LA_OK, LA_ERR_NULL, LA_ERR_SHAPE, LA_ERR_UNSUPPORTED = 0, -1, -2, -3
-LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN = -4, -5, -6
+LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN, LA_ERR_ALIAS = -4, -5, -6, -7
 
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
            "la_global_fwd_workspace", "la_global_bwd_workspace", "la_causal_fwd", "la_causal_fwd_state",

@@ -69,6 +69,28 @@ int check_dims(int B, int H, int N, int D, int M, float eps, la_dtype t) {
 
 bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Aliasing: no buffer that a call writes may overlap any other buffer of the call.
+struct Span {
+    const void *p;
+    size_t bytes;
+};
+bool overlap(const Span &a, const Span &b) {
+    if (a.p == nullptr || b.p == nullptr || a.bytes == 0 || b.bytes == 0) return false;
+    const uintptr_t x = reinterpret_cast<uintptr_t>(a.p), y = reinterpret_cast<uintptr_t>(b.p);
+    return x < y + b.bytes && y < x + a.bytes;
+}
+// outs: written (or read and written); ins: read only
+template <size_t NO, size_t NI>
+bool aliased(const Span (&outs)[NO], const Span (&ins)[NI]) {
+    for (size_t i = 0; i < NO; ++i) {
+        for (size_t j = i + 1; j < NO; ++j)
+            if (overlap(outs[i], outs[j])) return true;
+        for (size_t j = 0; j < NI; ++j)
+            if (overlap(outs[i], ins[j])) return true;
+    }
+    return false;
+}
+
 struct Carver {
     char *base;
     size_t off;
@@ -180,6 +202,7 @@ const char *la_status_string(int status) {
         case LA_ERR_WORKSPACE: return "workspace is NULL or smaller than the workspace query";
         case LA_ERR_HIP: return "a HIP call or kernel launch failed";
         case LA_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
+        case LA_ERR_ALIAS: return "an output or workspace buffer overlaps another buffer of the call";
         default: return "unknown status";
     }
 }
@@ -232,6 +255,10 @@ int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *d
     const Plan p = make_plan(BH, N);
     const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return LA_ERR_WORKSPACE;
+    const size_t rows = (size_t)BH * N, e = esize(t);
+    const Span outs[] = {{O, rows * M * e}, {den, rows * 4}, {ws, need}};
+    const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e}};
+    if (aliased(outs, ins)) return LA_ERR_ALIAS;
     return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
                           static_cast<hipStream_t>(stream));
 }
@@ -251,6 +278,12 @@ int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float
     const Plan p = make_plan(BH, N);
     const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return LA_ERR_WORKSPACE;
+    const size_t rows = (size_t)BH * N, e = esize(t);
+    const Span outs[] = {{O, rows * M * e}, {den, rows * 4}, {ws, need},
+                         {S1, (size_t)BH * D * M * 4}, {z1, (size_t)BH * D * 4}};
+    const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e},
+                        {S0, (size_t)BH * D * M * 4}, {z0, (size_t)BH * D * 4}};
+    if (aliased(outs, ins)) return LA_ERR_ALIAS;
     return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
                           static_cast<hipStream_t>(stream), S0, z0, S1, z1);
 }
@@ -280,6 +313,15 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
+    {
+        const size_t e = esize(t), sb = (size_t)BH * D * M * 4, zb = (size_t)BH * D * 4;
+        const Span outs[] = {{dQ, rows * D * e}, {dK, rows * D * e}, {dV, rows * M * e},
+                             {ws, need}, {dS0, sb}, {dz0, zb}};
+        const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e},
+                            {dO, rows * M * e}, {den, rows * 4}, {S0, sb}, {z0, zb}, {dS1, sb},
+                            {dz1, zb}, {fwd_ws, p.nseg > 1 ? states_bytes(BH, p, D, M) : 0}};
+        if (aliased(outs, ins)) return LA_ERR_ALIAS;
+    }
     Carver cv{static_cast<char *>(ws), 0};
     float *rden = static_cast<float *>(cv.take(rows * sizeof(float)));
     float *delta = static_cast<float *>(cv.take(rows * sizeof(float)));
@@ -366,6 +408,10 @@ int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *d
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     if (ws == nullptr || ws_bytes < states_bytes(BH, p, D, M)) return LA_ERR_WORKSPACE;
+    const size_t rows = (size_t)BH * N, e = esize(t);
+    const Span outs[] = {{O, rows * M * e}, {den, rows * 4}, {ws, states_bytes(BH, p, D, M)}};
+    const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e}};
+    if (aliased(outs, ins)) return LA_ERR_ALIAS;
     return run_global_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
                           static_cast<hipStream_t>(stream));
 }
@@ -391,6 +437,13 @@ int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, co
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
+    {
+        const size_t e = esize(t);
+        const Span outs[] = {{dQ, rows * D * e}, {dK, rows * D * e}, {dV, rows * M * e}, {ws, need}};
+        const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e},
+                            {dO, rows * M * e}, {den, rows * 4}, {fwd_ws, states_bytes(BH, p, D, M)}};
+        if (aliased(outs, ins)) return LA_ERR_ALIAS;
+    }
     Carver cv{static_cast<char *>(ws), 0};
     float *stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
     float *stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
@@ -446,6 +499,12 @@ int la_recurrent_step(const void *q, const void *k, const void *v, float *S, flo
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(S) || misaligned(z) ||
         misaligned(out))
         return LA_ERR_ALIGN;
+    {
+        const size_t bh = (size_t)B * H, e = esize(t);
+        const Span outs[] = {{out, bh * M * e}, {S, bh * D * M * 4}, {z, bh * D * 4}};
+        const Span ins[] = {{q, bh * D * e}, {k, bh * D * e}, {v, bh * M * e}};
+        if (aliased(outs, ins)) return LA_ERR_ALIAS;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     ProfScope ps(LA_K_STEP, s);
     LA_TRY(la::launch_recurrent_step(q, k, v, S, z, out, (int)((long)B * H), D, M, eps, (int)t, s));
@@ -462,6 +521,13 @@ int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, fl
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(S) || misaligned(z) ||
         misaligned(out))
         return LA_ERR_ALIGN;
+    {
+        const size_t bh = (size_t)B * H, e = esize(t);
+        const Span outs[] = {{out, (size_t)T * bh * M * e}, {S, bh * D * M * 4}, {z, bh * D * 4}};
+        const Span ins[] = {{q, (size_t)T * bh * D * e}, {k, (size_t)T * bh * D * e},
+                            {v, (size_t)T * bh * M * e}};
+        if (aliased(outs, ins)) return LA_ERR_ALIAS;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     ProfScope ps(LA_K_STEP, s);
     LA_TRY(la::launch_recurrent_steps(q, k, v, S, z, out, T, (int)((long)B * H), D, M, eps, (int)t, s));

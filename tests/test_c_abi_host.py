@@ -38,7 +38,7 @@ def test_version_and_status_strings(lib):
     from paper_2006_16236_amd import binding
     assert binding.la_version() >= 100
     seen = set()
-    for st in range(0, -7, -1):
+    for st in range(0, -8, -1):
         s = binding.status_string(st)
         assert s and s != "unknown status" and s not in seen
         seen.add(s)
@@ -131,6 +131,29 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert steps(p, p, p, p, p, null, 4, 1, 1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_NULL
     assert steps(p, p, p, p, p, p, 0, 1, 1, 64, 64, f(1e-6), 0, null) == b.LA_ERR_SHAPE
     assert steps(p, p, p, p, p, p, 4, 1, 1, 64, 48, f(1e-6), 0, null) == b.LA_ERR_UNSUPPORTED
+
+
+def test_aliasing_is_refused(lib):
+    """Overlap of a written buffer with any other buffer, found from pointers and sizes alone
+    (fake addresses, nothing is launched)."""
+    from paper_2006_16236_amd import binding as b
+    f, vp, null = ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p(None)
+    B, H, N, D, M = 1, 2, 64, 64, 64
+    tensor = B * H * N * D * 4
+    base = 0x100000
+    at = lambda i: vp(base + i * 2 * tensor)                  # disjoint, 16-byte aligned
+    Q, K, V, O, dO, dQ, dK, dV, den, ws = (at(i) for i in range(10))
+    dims = (B, H, N, D, M, f(1e-6), 0)
+    fwd, bwd = lib.la_causal_fwd, lib.la_causal_bwd
+    assert fwd(Q, K, V, V, null, *dims, null, 0, null) == b.LA_ERR_ALIAS               # O is V
+    assert fwd(Q, K, V, vp(Q.value + tensor - 16), null, *dims, null, 0, null) == b.LA_ERR_ALIAS  # O starts inside Q
+    big = 1 << 30
+    assert bwd(Q, K, V, null, den, null, dO, dQ, dQ, dV, *dims, ws, big, null) == b.LA_ERR_ALIAS  # dK is dQ
+    assert bwd(Q, K, V, null, den, null, dO, dQ, dK, dO, *dims, ws, big, null) == b.LA_ERR_ALIAS  # dV is dO
+    assert bwd(Q, K, V, null, den, null, dO, dQ, dK, dV, *dims, dV, big, null) == b.LA_ERR_ALIAS  # ws is dV
+    step = lib.la_recurrent_step
+    q, k, v, S, z, out = (at(i) for i in range(6))
+    assert step(q, k, v, S, z, S, B, H, D, M, f(1e-6), 0, null) == b.LA_ERR_ALIAS      # out is the state
 
 
 def test_schedule_knobs_change_the_workspace(lib, monkeypatch):
