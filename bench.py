@@ -271,6 +271,29 @@ def run_table(args):
                      "tokens_per_s": B / sec, "achieved_GBs": bytes_step / sec / 1e9,
                      "frac_hbm": bytes_step / sec / 1e9 / HBM_PEAK_GBS})
         print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    # per-step launches recorded once into a HIP graph of 64 steps, replayed 48 times
+    d = wl.CFG5
+    q = torch.randn(64, d.B, d.H, d.D, device="cuda:0")
+    k = torch.randn(64, d.B, d.H, d.D, device="cuda:0")
+    v = torch.randn(64, d.B, d.H, d.M, device="cuda:0")
+    S = torch.zeros(d.B, d.H, d.D, d.M, device="cuda:0")
+    z = torch.zeros(d.B, d.H, d.D, device="cuda:0")
+    out = torch.empty(64, d.B, d.H, d.M, device="cuda:0")
+
+    def steps64():
+        for t in range(64):
+            la.la_recurrent_step(q[t], k[t], v[t], S, z, out[t], d.eps)
+    steps64()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        steps64()
+    sec = time_steps(graph.replay, d.T // 64, 4, torch)
+    rows.append({"workload": f"decode_B{d.B}_H8_D64_graph_of_64_steps", "steps": d.T,
+                 "us_per_step": sec * 1e6 / 64, "tokens_per_s": d.B * 64 / sec})
+    print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
     # the same 3072 steps in one launch (tokens known in advance)
     d = wl.CFG5
     q = torch.randn(d.T, d.B, d.H, d.D, device="cuda:0")

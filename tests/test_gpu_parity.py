@@ -203,6 +203,59 @@ def test_recurrent_steps_against_oracle_and_causal_fwd(la, oracle, D, M):
     assert rel_err(O, np.moveaxis(ref, 0, 2)) <= 1e-4
 
 
+def test_entry_points_under_hip_graph_capture(la):
+    """The entry points only enqueue kernels on the caller's stream (no allocation, no memset,
+    no synchronisation), so they can be recorded into a HIP graph.  A graph of 8 decode steps
+    plus a causal forward + backward is replayed several times, with eager work and
+    synchronisations in between, and every replay must equal the eager result bit for bit."""
+    B, H, T, N, D, M = 4, 2, 8, 300, 64, 64
+    w = wl.DecodeWorkload("g", B, H, D, M, 4 * T, 660)
+    q, k, v = (to_dev(x) for x in wl.decode_streams(w))
+    Q, K, V, G = (to_dev(x) for x in wl.random_case(661, B, H, N, D, M))
+    # static buffers of the graph
+    qs, ks, vs = torch.empty_like(q[:T]), torch.empty_like(k[:T]), torch.empty_like(v[:T])
+    S = torch.zeros(B, H, D, M, device=DEV); z = torch.zeros(B, H, D, device=DEV)
+    outs = torch.empty(T, B, H, M, device=DEV)
+    O = torch.empty_like(V); den = torch.empty(B, H, N, device=DEV)
+    dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
+    ws_f = torch.empty(max(la.la_causal_fwd_workspace(B, H, N, D, M), 16), dtype=torch.uint8, device=DEV)
+    ws_b = torch.empty(la.la_causal_bwd_workspace(B, H, N, D, M), dtype=torch.uint8, device=DEV)
+
+    def work():
+        for t in range(T):
+            la.la_recurrent_step(qs[t], ks[t], vs[t], S, z, outs[t], 1e-6)
+        la.la_causal_fwd(Q, K, V, O, den, 1e-6, ws=ws_f)
+        la.la_causal_bwd(Q, K, V, None, den, G, dQ, dK, dV, 1e-6, ws=ws_b, fwd_ws=ws_f)
+
+    # eager reference: four rounds of T steps, the state carried across rounds
+    S_e = torch.zeros_like(S); z_e = torch.zeros_like(z)
+    eager_outs = []
+    for r in range(4):
+        o = torch.empty(T, B, H, M, device=DEV)
+        for t in range(T):
+            la.la_recurrent_step(q[r * T + t], k[r * T + t], v[r * T + t], S_e, z_e, o[t], 1e-6)
+        eager_outs.append(o)
+    work()                                             # warm-up on static buffers, also gives
+    torch.cuda.synchronize()                           # the eager forward / backward results
+    ref = [x.clone() for x in (O, den, dQ, dK, dV)]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        work()
+    S.zero_(); z.zero_()
+    for r in range(4):
+        qs.copy_(q[r * T:(r + 1) * T]); ks.copy_(k[r * T:(r + 1) * T]); vs.copy_(v[r * T:(r + 1) * T])
+        for x in (O, den, dQ, dK, dV):
+            x.fill_(float("nan"))                      # eager work between the replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(outs, eager_outs[r]), r
+        assert all(torch.equal(a, b) for a, b in zip((O, den, dQ, dK, dV), ref)), r
+    assert torch.equal(S, S_e) and torch.equal(z, z_e)
+
+
 @pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32), (64, 64)])
 @pytest.mark.parametrize("bf16", [False, True])
 def test_multi_step_decode_equals_single_steps_bit_for_bit(la, oracle, D, M, bf16):
