@@ -131,12 +131,30 @@ def cpu_baseline(w, host, sample_tokens):
     la_oracle.causal_fwd_prefix(Q, K, V, w.eps)
     la_oracle.causal_bwd_linear(Q, K, V, G, w.eps)
     dt = time.perf_counter() - t0
+    # one thread on one (batch, head) sequence, first 16384 tokens: the per-core rate
+    n1 = min(sample_tokens, 16384)
+    one = [np.ascontiguousarray(x[:1, :1, :n1]) for x in (Q, K, V, G)]
+    nmax = la_oracle.max_threads()
+    la_oracle.set_threads(1)
+    t1 = time.perf_counter()
+    la_oracle.causal_fwd_prefix(*one[:3], w.eps)
+    la_oracle.causal_bwd_linear(*one, w.eps)
+    dt1 = time.perf_counter() - t1
+    la_oracle.set_threads(nmax)
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next(l.split(":", 1)[1].strip() for l in f if l.startswith("model name"))
+    except (OSError, StopIteration):
+        pass
     return {"value": w.B * sample_tokens / dt / 1e6, "unit": "Mtokens/s", "cores": threads,
-            "kind": "oracle",
+            "kind": "oracle", "cpu_model": model,
+            "single_thread_mtok_s": n1 / w.H / dt1 / 1e6,   # one head of n1 tokens = n1/H tokens
+
             "sample": f"fp64 oracle forward+backward on the first {sample_tokens} of {w.N} tokens of "
                       f"all {w.B * w.H} (batch, head) sequences of the same inputs, one run, "
                       f"{dt:.1f} s wall x {threads} threads = {dt * threads:.0f} s of CPU work; OpenMP "
-                      f"over sequences ({la_oracle.max_threads()} threads available, {threads} busy)"}
+                      f"over sequences ({nmax} threads available, {threads} busy)"}
 
 
 def run_headline(args):
@@ -213,6 +231,10 @@ def run_table(args):
                      "fwd_bwd_mtok_s": w.B * w.N / sec / 1e6, "fwd_mtok_s": w.B * w.N / secf / 1e6,
                      "hbm_ceiling_mtok_s": ceiling, "frac": w.B * w.N / sec / 1e6 / ceiling,
                      "kernels_ms": {k: round(ms * n, 4) for k, (ms, n) in prof.items()}})
+        if not args.no_cpu_baseline:      # the oracle on the same inputs, beside it
+            cb = cpu_baseline(w, fb.host, w.N)
+            rows[-1]["oracle_mtok_s"] = cb["value"]
+            rows[-1]["oracle_cores"] = cb["cores"]
         print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
         return fb
 
