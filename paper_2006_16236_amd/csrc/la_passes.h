@@ -1,4 +1,6 @@
-// Chunked causal products on fp32 MFMA, one wavefront per (sequence, segment).
+// Chunked causal products on the matrix units (fp32 MFMA; bf16 MFMA for bf16 tensors).
+// The forward runs one wavefront per (sequence, segment); the two kernels of the backward run
+// two wavefronts per (sequence, segment) that share one fetch of the inputs.
 //
 // The causal forward (paper eq. 9-12) and the three gradients of Algorithm 1
 // (eq. 13-15) are all the same operation on different operands,
@@ -21,9 +23,9 @@
 //
 // Without the causal mask (eq. 4-6) both sums run over the whole sequence, so the gradients
 // are read-outs against the two grand totals, with no in-chunk part and no carried update:
-//   kGlobalDq dO/den       -            -            total S^T            then times phi'(Q)
+//   kGlobalDq dO/den       -            -            total S^T            delta as in kDq, then times phi'(Q)
 //   kGlobalDv phi(K)       -            -            total R
-//   kGlobalDk V            -            -            total R^T            then times phi'(K)
+//   kGlobalDk V            -            -            total R^T            plus rho, then times phi'(K)
 //
 // The denominator of eq. 12 rides along as the "ones column" of the values:
 //   kFwd  also carries z = sum phi(K_b) and forms den_a = rowsum(mask(XY^T)) + X_a.z + eps;
@@ -39,7 +41,7 @@
 // Data movement per chunk: every input tile (16 tokens x 32|64 features) is fetched
 // once with fully coalesced 16-byte loads into staging registers while the previous
 // chunk is being computed, then mapped (phi, phi', 1/den scaling, zero fill of rows past
-// the end of the sequence) and parked in LDS, from where the MFMA operands are read in
+// the end of the sequence; for bf16 tensors also rounded to bf16) and parked in LDS, from where the MFMA operands are read in
 // whichever of the two layouts of la_device.h each product needs.
 #pragma once
 
@@ -66,8 +68,8 @@ __host__ __device__ constexpr int state_stride(int D, int M) { return D * M + D;
 
 struct PassArgs {
     const void *Q, *K, *V, *G;   // raw tensors, [BH, N, D] / [BH, N, M]
-    const float *rden;           // [BH, N] 1/den_i             (backward passes)
-    const float *delta;          // [BH, N] -(dO_i.O_i)/den_i   (backward passes)
+    const float *rden;           // [BH, N] 1/den_i             (reverse passes; written by the dQ pass)
+    const float *delta;          // [BH, N] -(dO_i.O_i)/den_i   (reverse passes; written by the dQ pass)
     void *out;                   // [BH, N, DZ]  (reverse_pass_kernel: dV)
     void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
     float *den;                  // [BH, N] or null             (kFwd, kGlobal)
@@ -306,7 +308,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     constexpr bool kHasYZ = Tr::kHasYZ;
     // bf16 tensors: the tile products run on the bf16 MFMA (operands rounded to bf16, fp32
     // accumulation); the sums that ride on MFMAs against ones stay fp32
-    constexpr bool kBf = std::is_same<T, bf16_t>::value;
+    constexpr bool kBf = is_bf16<T>;
 
     const int c = lane & 15, g = lane >> 4;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
@@ -875,7 +877,7 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const bool want = a.totals != nullptr;         // uniform
-    constexpr bool kBf = std::is_same<T, bf16_t>::value;   // see run_pass
+    constexpr bool kBf = is_bf16<T>;   // see run_pass
 
     f32x4 S[XT][ZT], R[XT][ZT];                    // element (d = 16xt + 4g + r, m = 16zt + c)
 #pragma unroll
@@ -1082,7 +1084,7 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         float yf[XT][4], zf[ZT][4];
         lds_feature_lane<D>(lds_y, c, g, yf);
         lds_feature_lane<M>(lds_z, c, g, zf);
-        if constexpr (std::is_same<T, bf16_t>::value) {       // see run_pass
+        if constexpr (is_bf16<T>) {       // see run_pass
             bf16x4_t zp[ZT];
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) zp[zt] = pack_bf16x4(zf[zt]);
