@@ -11,9 +11,9 @@ throughput in Mtokens/s (a token = all 8 heads), the roofline fraction of the
 dominant kernel (HIP events around its launches inside the timed region) and the
 fp64 CPU oracle timed on this machine's host cores on a bounded sample.
 
-`--table` additionally times the other workloads (sequence-length sweep, the
-MNIST/CIFAR-shaped configs, bf16, the global forward and the decode loop) and writes
-gpurun_out/bench_table.json; it is a reporting aid and prints no extra stdout line.
+`--table PATH` additionally times the other workloads (sequence-length sweep, the
+MNIST/CIFAR-shaped configs, bf16, the non-causal pair and the decode loop) and writes
+them to PATH as JSON; it is a reporting aid and prints no extra stdout line.
 """
 from __future__ import annotations
 
@@ -212,7 +212,7 @@ def run_headline(args):
 
 
 def run_table(args):
-    """Everything else worth a number; written to gpurun_out/bench_table.json."""
+    """Everything else worth a number; written to the file `--table` names."""
     import torch
 
     import paper_2006_16236_amd as la
@@ -328,8 +328,8 @@ def run_table(args):
     rows.append({"workload": f"decode_B{d.B}_H8_D64_{d.T}_steps_one_launch", "steps": d.T,
                  "us_per_step": sec * 1e6 / d.T, "tokens_per_s": d.B * d.T / sec})
     print("table:", json.dumps(rows[-1]), file=sys.stderr, flush=True)
-    os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
-    with open(os.path.join(ROOT, "gpurun_out", "bench_table.json"), "w") as f:
+    os.makedirs(os.path.dirname(os.path.abspath(args.table)), exist_ok=True)
+    with open(args.table, "w") as f:
         json.dump(rows, f, indent=1)
 
 
@@ -340,7 +340,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=65536)
-    ap.add_argument("--table", action="store_true")
+    ap.add_argument("--table", metavar="PATH", default=None,
+                    help="also time the other workloads and write them to PATH (JSON)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a 1 GiB device-to-device copy first (a kernel of known traffic, "
                          "to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters in the same run)")
