@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kVersion = 100;   // 0.1.0
+constexpr int kVersion = 300;   // 0.3.0
 
 // ---- schedule ---------------------------------------------------------------------------------
 // One wavefront walks one segment of one sequence.  MI355X holds 256 CUs x 4 SIMDs x 2
