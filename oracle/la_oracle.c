@@ -38,6 +38,9 @@
  *                                    supplementary section A; this is that part
  *                                    written out)
  *
+ * A switch (set_feature_map) replaces eq. 7 by the identity in all of the above:
+ * Q and K are then taken as feature values of a map the caller applied.
+ *
  * Readings of the paper that this file fixes (the paper is silent on each):
  *   - eps: den_i = phi(Q_i)^T Z_i + eps, added once after the dot product.
  *   - elu has alpha = 1; the branch is x > 0 (strict), so phi(0) = exp(0) = 1.
@@ -66,11 +69,27 @@
 #include <omp.h>
 #endif
 
+/* Which feature map every function of this file applies to Q and K:           */
+/*   0  eq. 7, phi(x) = elu(x) + 1 (the default);                                */
+/*   1  the identity: Q and K already hold feature values phi(Q), phi(K) of some */
+/*      other map (section 3.2 allows any non-negative one; Algorithm 1 itself   */
+/*      is stated on already-mapped inputs), and gradients are with respect to   */
+/*      those features.                                                          */
+/* Set between calls, never during one.                                          */
+static int g_feature_map = 0;
+void la_oracle_set_feature_map(int which) { g_feature_map = which; }
+
 /* eq. 7: phi(x) = elu(x) + 1 = x + 1 for x > 0, exp(x) otherwise. */
-double la_oracle_phi(double x) { return x > 0.0 ? x + 1.0 : exp(x); }
+double la_oracle_phi(double x) {
+    if (g_feature_map == 1) return x;
+    return x > 0.0 ? x + 1.0 : exp(x);
+}
 
 /* derivative of eq. 7: 1 for x > 0, exp(x) otherwise. */
-double la_oracle_dphi(double x) { return x > 0.0 ? 1.0 : exp(x); }
+double la_oracle_dphi(double x) {
+    if (g_feature_map == 1) return 1.0;
+    return x > 0.0 ? 1.0 : exp(x);
+}
 
 int la_oracle_max_threads(void) {
 #ifdef _OPENMP

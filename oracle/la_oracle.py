@@ -67,6 +67,11 @@ def set_threads(n: int) -> None:
     _load().la_oracle_set_threads(ctypes.c_int(int(n)))
 
 
+def set_feature_map(which: int) -> None:
+    """0: phi(x) = elu(x) + 1 (eq. 7, the default); 1: identity (Q, K hold feature values)."""
+    _load().la_oracle_set_feature_map(ctypes.c_int(int(which)))
+
+
 def phi(x):
     lib = _load()
     return np.vectorize(lambda t: lib.la_oracle_phi(float(t)), otypes=[np.float64])(np.asarray(x))

@@ -503,3 +503,60 @@ def test_state_gradients_against_central_finite_differences(oracle):
             dn[which][idx] -= h
             fd[idx] = (loss(*up) - loss(*dn)) / (2 * h)
         np.testing.assert_allclose(dX, fd, rtol=3e-6, atol=1e-8)
+
+
+# ------------------------------------------------------------------ caller-supplied features
+
+@pytest.fixture
+def features_given(oracle):
+    oracle.set_feature_map(1)
+    yield oracle
+    oracle.set_feature_map(0)
+
+
+def test_identity_feature_map_against_torch(features_given):
+    """With the identity map the oracle is attention with sim(q, k) = q . k on non-negative
+    features (section 3.2): checked against torch's matmul / tril / autograd in fp64, causal
+    and non-causal, and against Algorithm 1's numerator functions."""
+    o = features_given
+    rng = np.random.default_rng(60)
+    B, H, N, C, M = 2, 2, 21, 6, 5
+    FQ, FK = rng.uniform(0.05, 3.0, (2, B, H, N, C))
+    V, G = rng.standard_normal((2, B, H, N, M))
+    eps = 1e-4
+    for causal in (True, False):
+        tq, tk, tv = (torch.tensor(a, requires_grad=True) for a in (FQ, FK, V))
+        A = tq @ tk.transpose(-1, -2)
+        if causal:
+            A = torch.tril(A)
+        O = (A @ tv) / (A.sum(-1, keepdim=True) + eps)
+        O.backward(torch.tensor(G))
+        got = o.causal_fwd_prefix(FQ, FK, V, eps) if causal else o.global_fwd_linear(FQ, FK, V, eps)
+        np.testing.assert_allclose(got, O.detach().numpy(), rtol=1e-12, atol=1e-14)
+        grads = (o.causal_bwd_linear if causal else o.global_bwd_linear)(FQ, FK, V, G, eps)
+        for a, b in zip(grads, (tq.grad, tk.grad, tv.grad)):
+            np.testing.assert_allclose(a, b.numpy(), rtol=1e-10, atol=1e-12)
+    # numerator of the causal form == Algorithm 1 forward on the same features
+    num = o.causal_numerator_fwd(FQ, FK, V)
+    O, den = o.causal_fwd_prefix(FQ, FK, V, eps, return_den=True)
+    np.testing.assert_allclose(O * den[..., None], num, rtol=1e-12)
+
+
+def test_identity_map_equals_elu_map_on_shifted_positive_inputs(oracle):
+    """elu(x) + 1 = x + 1 with slope 1 for x > 0: features F = x + 1 through the identity map
+    give the same outputs and gradients as raw x through eq. 7."""
+    rng = np.random.default_rng(61)
+    B, H, N, D, M = 1, 2, 17, 4, 3
+    X = rng.uniform(0.01, 2.0, (2, B, H, N, D))
+    V, G = rng.standard_normal((2, B, H, N, M))
+    ref = oracle.causal_bwd_linear(X[0], X[1], V, G, 1e-6)
+    oref = oracle.causal_fwd_prefix(X[0], X[1], V, 1e-6)
+    oracle.set_feature_map(1)
+    try:
+        got = oracle.causal_bwd_linear(X[0] + 1.0, X[1] + 1.0, V, G, 1e-6)
+        ogot = oracle.causal_fwd_prefix(X[0] + 1.0, X[1] + 1.0, V, 1e-6)
+    finally:
+        oracle.set_feature_map(0)
+    np.testing.assert_allclose(ogot, oref, rtol=1e-13)
+    for a, b in zip(got, ref):
+        np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-15)
