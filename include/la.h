@@ -17,6 +17,14 @@
  *              dO, dQ, dK, dV; q, k, v, out in the step).  den, the workspace,
  *              the decode state S, z and all accumulation are always fp32.
  *              LA_BF16 tensors hold raw bfloat16 bit patterns (uint16).
+ *   Feature map phi(x) = elu(x) + 1 (eq. 7) is applied to Q and K inside every
+ *              call, and dQ, dK are gradients with respect to the raw Q, K.
+ *              With t = LA_F32_FEATURES / LA_BF16_FEATURES the caller has
+ *              applied a feature map of its own (section 3.2 allows any map
+ *              with non-negative values; Algorithm 1 is stated on mapped
+ *              inputs): Q and K (q and k of the decode calls) then hold the
+ *              feature values, no map is applied, and dQ, dK are gradients
+ *              with respect to those features.  The feature width is D.
  *   Sizes      B, H, N >= 1.  N needs no alignment.  D and M must each be 32 or
  *              64 (LA_ERR_UNSUPPORTED otherwise).  B*H*N*max(D,M) < 2^40.
  *   eps        den_i = phi(Q_i) . Z_i + eps, added once to the finished dot
@@ -54,7 +62,12 @@
 extern "C" {
 #endif
 
-typedef enum { LA_F32 = 0, LA_BF16 = 1 } la_dtype;
+typedef enum {
+    LA_F32 = 0,
+    LA_BF16 = 1,
+    LA_F32_FEATURES = 2,      /* fp32, Q and K hold feature values already  */
+    LA_BF16_FEATURES = 3      /* bf16, Q and K hold feature values already  */
+} la_dtype;
 
 typedef enum {
     LA_OK = 0,

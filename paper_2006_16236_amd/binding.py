@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla_hip.so")
 
-LA_F32, LA_BF16 = 0, 1
+LA_F32, LA_BF16, LA_F32_FEATURES, LA_BF16_FEATURES = 0, 1, 2, 3
 LA_OK, LA_ERR_NULL, LA_ERR_SHAPE, LA_ERR_UNSUPPORTED = 0, -1, -2, -3
 LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN, LA_ERR_ALIAS = -4, -5, -6, -7
 
@@ -87,11 +87,13 @@ def la_version() -> int:
     return int(_lib.la_version())
 
 
-def _dtype_code(t: torch.Tensor) -> int:
+def _dtype_code(t: torch.Tensor, features: bool = False) -> int:
+    """features=True: Q and K hold feature values of a map the caller applied (no elu + 1 inside,
+    gradients with respect to the features)."""
     if t.dtype == torch.float32:
-        return LA_F32
+        return LA_F32_FEATURES if features else LA_F32
     if t.dtype == torch.bfloat16:
-        return LA_BF16
+        return LA_BF16_FEATURES if features else LA_BF16
     raise TypeError(f"unsupported dtype {t.dtype}: float32 or bfloat16")
 
 
@@ -137,12 +139,12 @@ def la_global_bwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
     return int(_lib.la_global_bwd_workspace(B, H, N, D, M, dtype_code))
 
 
-def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None):
+def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None, features=False):
     """O [B,H,N,M] <- causal linear attention of Q, K [B,H,N,D], V [B,H,N,M]; den [B,H,N] fp32
     (optional) receives the denominators.  Enqueues on `stream` (default: torch's current)."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
-    t = _dtype_code(Q)
+    t = _dtype_code(Q, features)
     ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
     _check(_lib.la_causal_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
                               float(eps), t, wp, wb, _stream(stream)), "la_causal_fwd")
@@ -150,12 +152,12 @@ def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None):
 
 
 def la_causal_fwd_state(Q, K, V, O, den=None, S0=None, z0=None, S1=None, z1=None, eps=1e-6, ws=None,
-                        stream=None):
+                        stream=None, features=False):
     """Causal forward that starts from the state (S0, z0) (None: zero) and returns the state
     after the last token in (S1, z1) (None: not wanted); all four fp32 [B,H,D,M] / [B,H,D]."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
-    t = _dtype_code(Q)
+    t = _dtype_code(Q, features)
     ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
     _check(_lib.la_causal_fwd_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O),
                                     _ptr(den), _ptr(S1), _ptr(z1), B, H, N, D, M, float(eps), t,
@@ -163,13 +165,14 @@ def la_causal_fwd_state(Q, K, V, O, den=None, S0=None, z0=None, S1=None, z1=None
     return ws
 
 
-def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None):
+def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None,
+                  features=False):
     """dQ, dK, dV <- gradients of causal linear attention for upstream dO; O and den are the
     forward results (den None: recomputed; O is not read and may be None).  fwd_ws (optional) is
     the workspace tensor la_causal_fwd returned for the same call: its segment states are reused."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
-    t = _dtype_code(Q)
+    t = _dtype_code(Q, features)
     ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
     _check(_lib.la_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
                               _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
@@ -178,13 +181,14 @@ def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=Non
 
 
 def la_causal_bwd_state(Q, K, V, O, den, dO, dQ, dK, dV, S0=None, z0=None, dS1=None, dz1=None,
-                        dS0=None, dz0=None, eps=1e-6, ws=None, stream=None, fwd_ws=None):
+                        dS0=None, dz0=None, eps=1e-6, ws=None, stream=None, fwd_ws=None,
+                        features=False):
     """la_causal_bwd for a piece whose forward started from (S0, z0): (dS1, dz1) is the gradient
     arriving at the state after the last token (None: zero), (dS0, dz0) receives the gradient
     for (S0, z0) (None: not wanted); all fp32 [B,H,D,M] / [B,H,D]."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
-    t = _dtype_code(Q)
+    t = _dtype_code(Q, features)
     ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
     _check(_lib.la_causal_bwd_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O),
                                     _ptr(den), _ptr(fwd_ws), _ptr(dO), _ptr(dS1), _ptr(dz1),
@@ -194,25 +198,26 @@ def la_causal_bwd_state(Q, K, V, O, den, dO, dQ, dK, dV, S0=None, z0=None, dS1=N
     return ws
 
 
-def la_global_fwd(Q, K, V, O, eps=1e-6, ws=None, stream=None, den=None):
+def la_global_fwd(Q, K, V, O, eps=1e-6, ws=None, stream=None, den=None, features=False):
     """O <- non-causal linear attention (every query sees every key); den [B,H,N] fp32
     (optional) receives the denominators."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
-    t = _dtype_code(Q)
+    t = _dtype_code(Q, features)
     ws, wp, wb = _ws(ws, la_global_fwd_workspace(B, H, N, D, M, t), Q.device)
     _check(_lib.la_global_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
                               float(eps), t, wp, wb, _stream(stream)), "la_global_fwd")
     return ws
 
 
-def la_global_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None):
+def la_global_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None,
+                  features=False):
     """dQ, dK, dV <- gradients of non-causal linear attention for upstream dO; O and den are the
     results of la_global_fwd (den None: recomputed; O is not read and may be None).  fwd_ws
     (optional) is the workspace tensor la_global_fwd returned for the same call."""
     B, H, N, D = Q.shape
     M = V.shape[-1]
-    t = _dtype_code(Q)
+    t = _dtype_code(Q, features)
     ws, wp, wb = _ws(ws, la_global_bwd_workspace(B, H, N, D, M, t), Q.device)
     _check(_lib.la_global_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
                               _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
@@ -220,22 +225,22 @@ def la_global_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=Non
     return ws
 
 
-def la_recurrent_step(q, k, v, S, z, out, eps=1e-6, stream=None):
+def la_recurrent_step(q, k, v, S, z, out, eps=1e-6, stream=None, features=False):
     """One decode step for q, k [B,H,D], v [B,H,M]: S [B,H,D,M], z [B,H,D] (fp32) are updated
     in place, out [B,H,M] receives the attention output of the new token."""
     B, H, D = q.shape
     M = v.shape[-1]
     _check(_lib.la_recurrent_step(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(z), _ptr(out), B, H, D,
-                                  M, float(eps), _dtype_code(q), _stream(stream)),
+                                  M, float(eps), _dtype_code(q, features), _stream(stream)),
            "la_recurrent_step")
 
 
-def la_recurrent_steps(q, k, v, S, z, out, eps=1e-6, stream=None):
+def la_recurrent_steps(q, k, v, S, z, out, eps=1e-6, stream=None, features=False):
     """T decode steps in one launch: q, k [T,B,H,D], v, out [T,B,H,M]; S, z updated in place."""
     T, B, H, D = q.shape
     M = v.shape[-1]
     _check(_lib.la_recurrent_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(z), _ptr(out), T, B, H,
-                                   D, M, float(eps), _dtype_code(q), _stream(stream)),
+                                   D, M, float(eps), _dtype_code(q, features), _stream(stream)),
            "la_recurrent_steps")
 
 

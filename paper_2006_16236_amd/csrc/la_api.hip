@@ -50,14 +50,15 @@ Plan make_plan(long BH, int N) {
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-size_t esize(la_dtype t) { return t == LA_BF16 ? 2 : 4; }
+size_t esize(la_dtype t) { return (t == LA_BF16 || t == LA_BF16_FEATURES) ? 2 : 4; }
 
 size_t states_bytes(long BH, const Plan &p, int D, int M) {
     return align256((size_t)BH * p.nseg * la::state_stride(D, M) * sizeof(float));
 }
 
 int check_dims(int B, int H, int N, int D, int M, float eps, la_dtype t) {
-    if (t != LA_F32 && t != LA_BF16) return LA_ERR_UNSUPPORTED;
+    if (t != LA_F32 && t != LA_BF16 && t != LA_F32_FEATURES && t != LA_BF16_FEATURES)
+        return LA_ERR_UNSUPPORTED;
     if (!((D == 32 || D == 64) && (M == 32 || M == 64))) return LA_ERR_UNSUPPORTED;
     if (B < 1 || H < 1 || N < 1) return LA_ERR_SHAPE;
     if (!(eps >= 0.0f) || !isfinite(eps)) return LA_ERR_SHAPE;

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace la {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -31,9 +33,33 @@ __device__ __forceinline__ float dphi_from_phi(float f) { return __builtin_amdgc
 
 // ---- element types ------------------------------------------------------------------------
 struct bf16_t { uint16_t bits; };
+// The same two storage types for calls whose Q and K already hold feature values phi(Q), phi(K)
+// of a map the caller applied (any non-negative map, section 3.2): the kernels then apply no
+// map, and gradients are with respect to those features.  (V, O, dO and the gradients share
+// the element type; for them the tag changes nothing.)
+struct feat_f32 { float v; };
+struct feat_bf16 { uint16_t bits; };
+
+template <typename T>
+constexpr bool is_bf16 = std::is_same<T, bf16_t>::value || std::is_same<T, feat_bf16>::value;
+template <typename T>
+constexpr bool is_feat = std::is_same<T, feat_f32>::value || std::is_same<T, feat_bf16>::value;
+
+// feature value of a raw element of Q or K: eq. 7, or the element itself when the caller has
+// applied the map; and the slope of the map recovered from the feature value
+template <typename T> __device__ __forceinline__ float feature(float x) {
+    if constexpr (is_feat<T>) return x;
+    else return phi(x);
+}
+template <typename T> __device__ __forceinline__ float feature_slope(float f) {
+    if constexpr (is_feat<T>) return 1.0f;
+    else return dphi_from_phi(f);
+}
 
 __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+__device__ __forceinline__ float to_f32(feat_f32 x) { return x.v; }
+__device__ __forceinline__ float to_f32(feat_bf16 x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {      // round to nearest even
     uint32_t u = __float_as_uint(f);
@@ -45,6 +71,10 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {      // round to
 template <typename T> __device__ __forceinline__ void store_elem(T *p, float v);
 template <> __device__ __forceinline__ void store_elem<float>(float *p, float v) { *p = v; }
 template <> __device__ __forceinline__ void store_elem<bf16_t>(bf16_t *p, float v) {
+    p->bits = f32_to_bf16_bits(v);
+}
+template <> __device__ __forceinline__ void store_elem<feat_f32>(feat_f32 *p, float v) { p->v = v; }
+template <> __device__ __forceinline__ void store_elem<feat_bf16>(feat_bf16 *p, float v) {
     p->bits = f32_to_bf16_bits(v);
 }
 
@@ -60,6 +90,12 @@ __device__ __forceinline__ f32x4 load4(const bf16_t *p) {
     r[2] = __uint_as_float(u.y << 16);
     r[3] = __uint_as_float(u.y & 0xffff0000u);
     return r;
+}
+__device__ __forceinline__ f32x4 load4(const feat_f32 *p) {
+    return load4(reinterpret_cast<const float *>(p));
+}
+__device__ __forceinline__ f32x4 load4(const feat_bf16 *p) {
+    return load4(reinterpret_cast<const bf16_t *>(p));
 }
 
 // ---- wave-level helpers ---------------------------------------------------------------------

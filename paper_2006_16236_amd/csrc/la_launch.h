@@ -8,7 +8,8 @@
 
 namespace la {
 
-// dtype: 0 = fp32, 1 = bf16 (la_dtype of the public header)
+// dtype: the la_dtype of the public header (0 fp32, 1 bf16, 2 / 3 the same with Q, K holding
+// feature values already)
 hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs &a, int nblocks,
                            hipStream_t s);
 // dQ, 1/den, delta and (a.totals) the per-segment Q, dO sums; causal or against the global sums
@@ -38,6 +39,15 @@ hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, fl
 hipError_t launch_recurrent_steps(const void *q, const void *k, const void *v, float *S, float *z,
                                   void *out, int steps, int BH, int D, int M, float eps, int dtype,
                                   hipStream_t s);
+
+#define LA_DISPATCH_T(dtype, ...)                                              \
+    do {                                                                       \
+        if ((dtype) == 0) { using TT = float; __VA_ARGS__; }                   \
+        else if ((dtype) == 1) { using TT = bf16_t; __VA_ARGS__; }             \
+        else if ((dtype) == 2) { using TT = feat_f32; __VA_ARGS__; }           \
+        else if ((dtype) == 3) { using TT = feat_bf16; __VA_ARGS__; }          \
+        else return hipErrorInvalidValue;                                      \
+    } while (0)
 
 #define LA_DISPATCH_DM(D, M, ...)                                              \
     do {                                                                       \

@@ -98,8 +98,8 @@ __global__ __launch_bounds__(256) void recurrent_step_kernel(const T *q, const T
 #pragma unroll
     for (int it = 0; it < D / RPI; ++it) {
         const int d = it * RPI + wave * RPW + rsub;
-        const float kd = phi(to_f32(kh[d]));
-        const float qd = phi(to_f32(qh[d]));
+        const float kd = feature<T>(to_f32(kh[d]));
+        const float qd = feature<T>(to_f32(qh[d]));
         f32x4 s4 = *reinterpret_cast<f32x4 *>(Sh + (size_t)d * M + col4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -182,8 +182,8 @@ __global__ __launch_bounds__(256) void recurrent_steps_kernel(const T *q, const 
         float dpart = 0.f;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            const float kd = phi(kq[0][it]);
-            const float qd = phi(kq[1][it]);
+            const float kd = feature<T>(kq[0][it]);
+            const float qd = feature<T>(kq[1][it]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 s4[it][e] = fmaf(kd, v4[e], s4[it][e]);
@@ -225,30 +225,21 @@ __global__ __launch_bounds__(256) void recurrent_steps_kernel(const T *q, const 
 hipError_t launch_recurrent_steps(const void *q, const void *k, const void *v, float *S, float *z,
                                   void *out, int steps, int BH, int D, int M, float eps, int dtype,
                                   hipStream_t s) {
-    LA_DISPATCH_DM(D, M, {
-        if (dtype == 0)
-            recurrent_steps_kernel<kD, kM, float><<<BH, 256, 0, s>>>(
-                (const float *)q, (const float *)k, (const float *)v, S, z, (float *)out, eps, steps,
-                (size_t)BH);
-        else
-            recurrent_steps_kernel<kD, kM, bf16_t><<<BH, 256, 0, s>>>(
-                (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, S, z, (bf16_t *)out, eps,
-                steps, (size_t)BH);
-    });
+    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+        recurrent_steps_kernel<kD, kM, TT><<<BH, 256, 0, s>>>((const TT *)q, (const TT *)k,
+                                                             (const TT *)v, S, z, (TT *)out, eps,
+                                                             steps, (size_t)BH);
+    }));
     return hipGetLastError();
 }
 
 hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z,
                                  void *out, int BH, int D, int M, float eps, int dtype,
                                  hipStream_t s) {
-    LA_DISPATCH_DM(D, M, {
-        if (dtype == 0)
-            recurrent_step_kernel<kD, kM, float><<<BH, 256, 0, s>>>(
-                (const float *)q, (const float *)k, (const float *)v, S, z, (float *)out, eps);
-        else
-            recurrent_step_kernel<kD, kM, bf16_t><<<BH, 256, 0, s>>>(
-                (const bf16_t *)q, (const bf16_t *)k, (const bf16_t *)v, S, z, (bf16_t *)out, eps);
-    });
+    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+        recurrent_step_kernel<kD, kM, TT><<<BH, 256, 0, s>>>((const TT *)q, (const TT *)k,
+                                                            (const TT *)v, S, z, (TT *)out, eps);
+    }));
     return hipGetLastError();
 }
 

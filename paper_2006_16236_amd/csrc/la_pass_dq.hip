@@ -5,15 +5,10 @@ namespace la {
 
 hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &a, int nblocks,
                           hipStream_t s) {
-    LA_DISPATCH_DM(D, M, {
-        if (causal) {
-            if (dtype == 0) dq_pass_kernel<kD, kM, float, true><<<nblocks, 2 * kWave, 0, s>>>(a);
-            else dq_pass_kernel<kD, kM, bf16_t, true><<<nblocks, 2 * kWave, 0, s>>>(a);
-        } else {
-            if (dtype == 0) dq_pass_kernel<kD, kM, float, false><<<nblocks, 2 * kWave, 0, s>>>(a);
-            else dq_pass_kernel<kD, kM, bf16_t, false><<<nblocks, 2 * kWave, 0, s>>>(a);
-        }
-    });
+    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+        if (causal) dq_pass_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+        else dq_pass_kernel<kD, kM, TT, false><<<nblocks, 2 * kWave, 0, s>>>(a);
+    }));
     return hipGetLastError();
 }
 

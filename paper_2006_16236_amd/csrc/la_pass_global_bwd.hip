@@ -6,15 +6,10 @@ namespace la {
 
 hipError_t launch_pass_global_bwd(int which, int D, int M, int dtype, const PassArgs &a,
                                   int nblocks, hipStream_t s) {
-    LA_DISPATCH_DM(D, M, {
-        if (which == 1) {
-            if (dtype == 0) causal_pass_kernel<kGlobalDv, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
-            else causal_pass_kernel<kGlobalDv, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
-        } else {
-            if (dtype == 0) causal_pass_kernel<kGlobalDk, kD, kM, float><<<nblocks, kWave, 0, s>>>(a);
-            else causal_pass_kernel<kGlobalDk, kD, kM, bf16_t><<<nblocks, kWave, 0, s>>>(a);
-        }
-    });
+    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+        if (which == 1) causal_pass_kernel<kGlobalDv, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
+        else causal_pass_kernel<kGlobalDk, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
+    }));
     return hipGetLastError();
 }
 

@@ -6,10 +6,9 @@ namespace la {
 
 hipError_t launch_pass_reverse(int D, int M, int dtype, const PassArgs &a, int nblocks,
                                hipStream_t s) {
-    LA_DISPATCH_DM(D, M, {
-        if (dtype == 0) reverse_pass_kernel<kD, kM, float><<<nblocks, 2 * kWave, 0, s>>>(a);
-        else reverse_pass_kernel<kD, kM, bf16_t><<<nblocks, 2 * kWave, 0, s>>>(a);
-    });
+    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+        reverse_pass_kernel<kD, kM, TT><<<nblocks, 2 * kWave, 0, s>>>(a);
+    }));
     return hipGetLastError();
 }
 

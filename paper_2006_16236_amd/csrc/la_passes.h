@@ -91,26 +91,27 @@ struct PassArgs {
     float eps;
 };
 
-enum Map { kMapId = 0, kMapPhi = 1, kMapDphi = 2, kMapScale = 3 };
+enum Map { kMapId = 0, kMapPhi = 1, kMapDphi = 2, kMapScale = 3, kMapOne = 4 };
 
 template <int MAP>
 __device__ __forceinline__ float map_value(float v, float scale) {
     if constexpr (MAP == kMapPhi) return phi(v);
     if constexpr (MAP == kMapDphi) return dphi(v);
     if constexpr (MAP == kMapScale) return v * scale;
+    if constexpr (MAP == kMapOne) return 1.0f;
     return v;
 }
-
-template <typename T> constexpr bool is_bf16 = std::is_same<T, bf16_t>::value;
 
 // Park a staged tile in LDS: apply the map; kFull = false also zeroes the rows past the end
 // of the sequence.  kRound (bf16 tensors): the mapped values phi(x) and dO/den are rounded to
 // bf16 here, once, so that every product and every sum that uses them sees the same values:
 // the numerator S and the denominator z of eq. 10-12 are then built from identical features
 // (the attention weights still sum to one), and packing them as MFMA operands is exact.
-template <int F, int MAP, bool kFull, bool kRound>
+// kFeat (the caller has applied the feature map): phi becomes the identity, phi' becomes 1.
+template <int F, int MAP_, bool kFull, bool kRound, bool kFeat>
 __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16],
                                           const float (&scale)[F / 16], int nvalid, int lane) {
+    constexpr int MAP = !kFeat ? MAP_ : MAP_ == kMapPhi ? kMapId : MAP_ == kMapDphi ? kMapOne : MAP_;
 #pragma unroll
     for (int i = 0; i < F / 16; ++i) {
         const int row = stage_row<F>(lane, i);
@@ -194,12 +195,12 @@ struct PassStager {
 
     template <bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<DX, Tr::kMapX, kFull, is_bf16<T>>(lds_x, sx, onex, nvalid, lane);
+        park_tile<DX, Tr::kMapX, kFull, is_bf16<T>, is_feat<T>>(lds_x, sx, onex, nvalid, lane);
         if constexpr (Tr::kHasYZ) {
-            park_tile<DX, Tr::kMapY, kFull, is_bf16<T>>(lds_y, sy, onex, nvalid, lane);
-            park_tile<DZ, Tr::kMapZ, kFull, is_bf16<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<DX, Tr::kMapY, kFull, is_bf16<T>, is_feat<T>>(lds_y, sy, onex, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ, kFull, is_bf16<T>, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         }
-        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, is_bf16<T>>(lds_r, sr, onez, nvalid, lane);
+        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, is_bf16<T>, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
     }
 
     template <int SLOT>
@@ -264,12 +265,12 @@ struct ReverseStager {
 
     template <int SLOT, bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<D, kMapPhi, kFull, is_bf16<T>>(lds_a, sa[SLOT], scd, nvalid, lane);
+        park_tile<D, kMapPhi, kFull, is_bf16<T>, is_feat<T>>(lds_a, sa[SLOT], scd, nvalid, lane);
         if constexpr (ROLE == 0) {
-            park_tile<M, kMapScale, kFull, is_bf16<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<M, kMapScale, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         } else {
-            park_tile<D, kMapDphi, kFull, is_bf16<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
-            park_tile<M, kMapId, kFull, is_bf16<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<D, kMapDphi, kFull, is_bf16<T>, is_feat<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
+            park_tile<M, kMapId, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         }
     }
 
@@ -601,7 +602,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     rp = fmaf(d4[r], fq[zt][r], rp);
-                    out[zt][r] = fmaf(d4[r], cz[zt][r], out[zt][r]) * dphi_from_phi(fq[zt][r]);
+                    out[zt][r] = fmaf(d4[r], cz[zt][r], out[zt][r]) * feature_slope<T>(fq[zt][r]);
                 }
                 rho[zt] += rp;
             }
@@ -841,14 +842,14 @@ struct DqStager {
         if constexpr (ROLE == 0) {
 #pragma unroll
             for (int i = 0; i < FT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
-            park_tile<F, kMapScale, kFull, is_bf16<T>>(lds_a, sa, sca, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapId, kFull, is_bf16<T>>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapScale, kFull, is_bf16<T>, is_feat<T>>(lds_a, sa, sca, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapId, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb, one, nvalid, lane);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
         } else {
-            park_tile<F, kMapPhi, kFull, is_bf16<T>>(lds_a, sa, one, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_bf16<T>>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapPhi, kFull, is_bf16<T>, is_feat<T>>(lds_a, sa, one, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb, one, nvalid, lane);
         }
     }
 
@@ -1070,11 +1071,11 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
         if (nvalid == kChunk) {
-            park_tile<D, kMapPhi, true, is_bf16<T>>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, true, is_bf16<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, true, is_bf16<T>, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, true, is_bf16<T>, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         } else {
-            park_tile<D, kMapPhi, false, is_bf16<T>>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, false, is_bf16<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, false, is_bf16<T>, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, false, is_bf16<T>, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         }
         if (ch + 1 < ch_end) fetch(ch + 1);
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass

@@ -111,6 +111,13 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert bws(*args, *tail) == b.LA_ERR_ALIGN
     assert bws(*ok16, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
 
+    # element type codes: 0..3 are known (fp32, bf16, and the same with Q, K as feature values)
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 4, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), -1, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 3, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert b.la_causal_bwd_workspace(2, 8, 4096, 64, 64, b.LA_BF16_FEATURES) == \
+        b.la_causal_bwd_workspace(2, 8, 4096, 64, 64, b.LA_BF16)
+
     glob = lib.la_global_fwd
     assert glob(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
     assert glob(p, p, null, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, p, 1 << 20, null) == b.LA_ERR_NULL

@@ -486,6 +486,109 @@ def test_random_shapes_all_entry_points(la, oracle, B, H, N, D, M, sched, eps, s
     assert max(grad_errs(gg, oracle.global_bwd_linear(Q, K, V, G, eps))) <= tol
 
 
+# ---- Q and K as feature values of a map the caller applied ---------------------------------
+
+@pytest.fixture
+def oracle_features(oracle):
+    oracle.set_feature_map(1)
+    yield oracle
+    oracle.set_feature_map(0)
+
+
+def _feature_case(seed, B, H, N, D, M):
+    """Non-negative features (some below one, some exactly zero) in place of Q and K."""
+    rng = np.random.default_rng(seed)
+    FQ = rng.gamma(1.5, 0.6, (B, H, N, D)).astype(np.float32)
+    FK = rng.gamma(1.5, 0.6, (B, H, N, D)).astype(np.float32)
+    FK[rng.random(FK.shape) < 0.1] = 0.0
+    V = rng.standard_normal((B, H, N, M)).astype(np.float32)
+    G = rng.standard_normal((B, H, N, M)).astype(np.float32)
+    return FQ, FK, V, G
+
+
+@pytest.mark.parametrize("sched", ["default", "one_segment", "three_chunk_segments"])
+@pytest.mark.parametrize("D,M,N", [(64, 64, 300), (32, 64, 77), (64, 32, 1000)])
+def test_caller_supplied_features_against_oracle(la, oracle_features, D, M, N, sched):
+    o = oracle_features
+    B, H = 2, 2
+    FQ, FK, V, G = _feature_case(1100 + N, B, H, N, D, M)
+    eps = 1e-5
+    dq, dk, dv, dg = (to_dev(x) for x in (FQ, FK, V, G))
+    with schedule(**SCHEDULES[sched]):
+        O = torch.empty_like(dv); den = torch.empty(B, H, N, device=DEV)
+        ws = la.la_causal_fwd(dq, dk, dv, O, den, eps, features=True)
+        gq, gk, gv = (torch.empty_like(x) for x in (dq, dk, dv))
+        la.la_causal_bwd(dq, dk, dv, None, den, dg, gq, gk, gv, eps, fwd_ws=ws, features=True)
+        Og = torch.empty_like(dv); deng = torch.empty(B, H, N, device=DEV)
+        wsg = la.la_global_fwd(dq, dk, dv, Og, eps, den=deng, features=True)
+        hq, hk, hv = (torch.empty_like(x) for x in (dq, dk, dv))
+        la.la_global_bwd(dq, dk, dv, None, deng, dg, hq, hk, hv, eps, fwd_ws=wsg, features=True)
+    torch.cuda.synchronize()
+    tol = tol_for(N)
+    ref, dref = o.causal_fwd_prefix(FQ, FK, V, eps, return_den=True)
+    assert rel_err(to_host(O), ref) <= tol and rel_err(den.cpu().numpy(), dref) <= tol
+    assert max(grad_errs([to_host(x) for x in (gq, gk, gv)], o.causal_bwd_linear(FQ, FK, V, G, eps))) <= tol
+    assert rel_err(to_host(Og), o.global_fwd_linear(FQ, FK, V, eps)) <= tol
+    assert max(grad_errs([to_host(x) for x in (hq, hk, hv)], o.global_bwd_linear(FQ, FK, V, G, eps))) <= tol
+
+
+def test_caller_supplied_features_decode_and_bf16(la, oracle_features):
+    o = oracle_features
+    B, H, T, D, M = 3, 2, 25, 64, 64
+    FQ, FK, V, G = _feature_case(1150, B, H, T, D, M)
+    # decode, token by token and in one launch (layout [T, B, H, .])
+    q, k, v = (np.ascontiguousarray(np.moveaxis(x, 2, 0)) for x in (FQ, FK, V))
+    dq, dk, dv = (to_dev(x) for x in (q, k, v))
+    S = torch.zeros(B, H, D, M, device=DEV); z = torch.zeros(B, H, D, device=DEV)
+    out = torch.empty(T, B, H, M, device=DEV)
+    for t in range(T):
+        la.la_recurrent_step(dq[t], dk[t], dv[t], S, z, out[t], 1e-6, features=True)
+    S2 = torch.zeros_like(S); z2 = torch.zeros_like(z); out2 = torch.empty_like(out)
+    la.la_recurrent_steps(dq, dk, dv, S2, z2, out2, 1e-6, features=True)
+    torch.cuda.synchronize()
+    ref = o.causal_fwd_prefix(FQ, FK, V, 1e-6)
+    assert rel_err(np.moveaxis(to_host(out), 0, 2), ref) <= 1e-4
+    assert torch.equal(out, out2) and torch.equal(S, S2) and torch.equal(z, z2)
+    # bf16 tensors
+    FQb, FKb, Vb, Gb = (wl.round_to_bf16(x) for x in (FQ, FK, V, G))
+    bq, bk, bv, bg = (to_dev(x, True) for x in (FQb, FKb, Vb, Gb))
+    O = torch.empty_like(bv); den = torch.empty(B, H, T, device=DEV)
+    ws = la.la_causal_fwd(bq, bk, bv, O, den, 1e-6, features=True)
+    gq, gk, gv = (torch.empty_like(x) for x in (bq, bk, bv))
+    la.la_causal_bwd(bq, bk, bv, None, den, bg, gq, gk, gv, 1e-6, fwd_ws=ws, features=True)
+    torch.cuda.synchronize()
+    assert rel_err(to_host(O), o.causal_fwd_prefix(FQb, FKb, Vb, 1e-6)) <= 2e-2
+    gref = o.causal_bwd_linear(FQb, FKb, Vb, Gb, 1e-6)
+    assert max(grad_errs([to_host(x) for x in (gq, gk, gv)], gref)) <= 2e-2
+
+
+def test_features_equal_the_elu_map_on_shifted_inputs_bit_for_bit(la):
+    """elu(x) + 1 = x + 1 with slope 1 for x > 0, and x + 1 is exact for x on a coarse grid: the
+    same call on raw x (map inside) and on features x + 1 (map outside) must agree in every bit,
+    for every entry point including the state-carrying ones."""
+    B, H, N, D, M = 2, 2, 200, 64, 64
+    rng = np.random.default_rng(1160)
+    Xq = (rng.integers(1, 256, (B, H, N, D)) / 64.0).astype(np.float32)
+    Xk = (rng.integers(1, 256, (B, H, N, D)) / 64.0).astype(np.float32)
+    _, _, V, G, S0, z0, dS1, dz1 = _state_case(1161, B, H, N, D, M)
+    res = []
+    for Qh, Kh, feat in ((Xq, Xk, False), (Xq + 1.0, Xk + 1.0, True)):
+        dq, dk, dv, dg = (to_dev(x) for x in (Qh, Kh, V, G))
+        s0, zz0, ds1, dzz1 = (to_dev(x) for x in (S0, z0, dS1, dz1))
+        O = torch.empty_like(dv); den = torch.empty(B, H, N, device=DEV)
+        S1 = torch.empty(B, H, D, M, device=DEV); z1 = torch.empty(B, H, D, device=DEV)
+        with schedule(**SCHEDULES["three_chunk_segments"]):
+            ws = la.la_causal_fwd_state(dq, dk, dv, O, den, s0, zz0, S1, z1, 1e-6, features=feat)
+            gq, gk, gv = (torch.empty_like(x) for x in (dq, dk, dv))
+            ds0 = torch.empty_like(S1); dzz0 = torch.empty_like(z1)
+            la.la_causal_bwd_state(dq, dk, dv, None, den, dg, gq, gk, gv, s0, zz0, ds1, dzz1, ds0, dzz0,
+                                   1e-6, fwd_ws=ws, features=feat)
+        torch.cuda.synchronize()
+        res.append([x.clone() for x in (O, den, S1, z1, gq, gk, gv, ds0, dzz0)])
+    for a, b in zip(*res):
+        assert torch.equal(a, b)
+
+
 def test_bitwise_determinism_and_slab_independence(la):
     B, H, N, D, M = 2, 4, 500, 64, 64
     Q, K, V, G = wl.random_case(800, B, H, N, D, M)
