@@ -48,7 +48,7 @@
  *   Tuning     Two environment variables, read at every call, override the
  *              segment schedule (for tests and experiments): LA_TARGET_WAVES
  *              (default 2048: wavefronts wanted in flight) and
- *              LA_MIN_SEG_CHUNKS (default 4: shortest segment, in 16-token
+ *              LA_MIN_SEG_CHUNKS (default 2: shortest segment, in 16-token
  *              chunks).  Sequences are not cut at all once B*H reaches half of
  *              LA_TARGET_WAVES.  The workspace query and the call must see the
  *              same values.

@@ -33,7 +33,7 @@ int env_int(const char *name, int dflt) {
 
 Plan make_plan(long BH, int N) {
     const int target_waves = env_int("LA_TARGET_WAVES", 2048);
-    const int min_chunks = env_int("LA_MIN_SEG_CHUNKS", 4);
+    const int min_chunks = env_int("LA_MIN_SEG_CHUNKS", 2);
     Plan p;
     p.nchunks = (N + la::kChunk - 1) / la::kChunk;
     long want = (target_waves + BH - 1) / BH;
