@@ -145,7 +145,7 @@ def test_aliasing_is_refused(lib):
     (fake addresses, nothing is launched)."""
     from paper_2006_16236_amd import binding as b
     f, vp, null = ctypes.c_float, ctypes.c_void_p, ctypes.c_void_p(None)
-    B, H, N, D, M = 1, 2, 64, 64, 64
+    B, H, N, D, M = 1, 2, 16, 64, 64                          # one chunk: no forward workspace
     tensor = B * H * N * D * 4
     base = 0x100000
     at = lambda i: vp(base + i * 2 * tensor)                  # disjoint, 16-byte aligned
