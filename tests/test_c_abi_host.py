@@ -180,3 +180,30 @@ def test_binding_refuses_host_tensors(lib):
         b.la_causal_fwd(x, x, x, x)
     with pytest.raises(TypeError):
         b.la_causal_fwd(x.double(), x, x, x)
+
+
+def test_header_is_plain_c_and_links_against_the_library(lib, tmp_path):
+    """include/la.h compiles as C99 and as C++11 with pedantic warnings as errors, and a plain C
+    program that calls the host-only entry points links against the shared library and runs."""
+    import subprocess
+    from paper_2006_16236_amd import binding as b
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    inc = os.path.join(root, "include")
+    src = tmp_path / "client.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "la.h"\n'
+        'int main(void) {\n'
+        '    size_t ws = la_causal_bwd_workspace(2, 8, 4096, 64, 64, LA_F32);\n'
+        '    printf("%d %s %lu\\n", la_version(), la_status_string(LA_ERR_ALIAS), (unsigned long)ws);\n'
+        '    return la_causal_fwd(0, 0, 0, 0, 0, 1, 1, 16, 64, 64, 1e-6f, LA_F32, 0, 0, 0) == LA_ERR_NULL ? 0 : 1;\n'
+        '}\n')
+    for cc, std, lang in (("gcc", "-std=c99", "c"), ("g++", "-std=c++11", "c++")):
+        subprocess.run([cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-I", inc, "-fsyntax-only",
+                        "-x", lang, str(src)], check=True)
+    exe = tmp_path / "client"
+    libdir = os.path.dirname(b.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", libdir, "-l:libla_hip.so",
+                    f"-Wl,-rpath,{libdir}"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(" ", 1)
+    assert int(out[0]) == b.la_version() and "overlaps" in out[1]
+    assert out[1].rstrip().endswith(str(b.la_causal_bwd_workspace(2, 8, 4096, 64, 64)))
