@@ -17,9 +17,10 @@ namespace {
 constexpr int kVersion = 300;   // 0.3.0
 
 // ---- schedule ---------------------------------------------------------------------------------
-// One wavefront walks one segment of one sequence.  MI355X holds 256 CUs x 4 SIMDs x 2
-// such waves; a sequence is cut into segments only as far as needed to reach that
-// many waves, and never into segments shorter than a few chunks.
+// One wavefront (forward) or one two-wave workgroup (backward) walks one segment of one
+// sequence.  MI355X holds 256 CUs x 4 SIMDs x 2 such waves; a sequence is cut into segments
+// only as far as needed to reach that many waves, never into segments shorter than a couple of
+// chunks, and not at all once the sequences alone fill half the machine.
 struct Plan {
     int nchunks, nseg, cps;
 };

@@ -27,7 +27,7 @@ hipError_t launch_segment_state(int D, int M, int dtype, const SegArgs &a, int n
 enum ScanMode { kScanForward = 0, kScanReverse = 1, kScanTotal = 2 };
 // In-place scan over the nseg slots of every sequence: exclusive prefix, exclusive
 // suffix, or the grand total written to slot 0.
-// init_S [BH, DM] / init_z [BH, stride - DM]: optional starting value of the forward prefix.
+// init_S [BH, DM] / init_z [BH, stride - DM]: optional starting value of the prefix or suffix.
 hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s,
                        const float *init_S = nullptr, const float *init_z = nullptr, int DM = 0);
 
