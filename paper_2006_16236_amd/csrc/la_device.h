@@ -62,10 +62,7 @@ __device__ __forceinline__ float to_f32(feat_f32 x) { return x.v; }
 __device__ __forceinline__ float to_f32(feat_bf16 x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {      // round to nearest even
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);   // NaN stays NaN
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));     // v_cvt_pk_bf16_f32
 }
 
 template <typename T> __device__ __forceinline__ void store_elem(T *p, float v);

@@ -102,6 +102,15 @@ __device__ __forceinline__ float map_value(float v, float scale) {
     return v;
 }
 
+// Which passes of a bf16 call run their tile products on the bf16 MFMA: the forward ones
+// (kFwd, kGlobal and the K, V segment sums).  The backward passes keep fp32 products on the
+// widened values: their results are differences of nearly equal terms (dphi(Q)_a = A_a +
+// delta_a z_a vanishes for constant V; R v + rho likewise), and with features phi(x) = 1 + x + ...
+// of small x the 8-bit mantissa of the operands would cost up to 1.5e-2 of the gradient's scale
+// (measured on inputs scaled by 1/8; worse for smaller inputs), too close to the 2e-2 gate.
+template <int PASS, typename T>
+constexpr bool bf16_products = is_bf16<T> && (PASS == kFwd || PASS == kGlobal);
+
 // Park a staged tile in LDS: apply the map; kFull = false also zeroes the rows past the end
 // of the sequence.  kRound (bf16 tensors): the mapped values phi(x) and dO/den are rounded to
 // bf16 here, once, so that every product and every sum that uses them sees the same values:
@@ -149,6 +158,7 @@ struct PassStager {
     static_assert(PASS == kFwd || PASS == kGlobal || PASS == kGlobalDv || PASS == kGlobalDk,
                   "the other passes have stagers of their own");
     static constexpr int DX = Tr::DX, DZ = Tr::DZ, XT = DX / 16, ZT = DZ / 16;
+    static constexpr bool kRound = false;
     const T *Xs, *Ys, *Zs, *Rs;
     float *lds_x, *lds_y, *lds_z, *lds_r;
     int N, lane;
@@ -195,12 +205,12 @@ struct PassStager {
 
     template <bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<DX, Tr::kMapX, kFull, is_bf16<T>, is_feat<T>>(lds_x, sx, onex, nvalid, lane);
+        park_tile<DX, Tr::kMapX, kFull, kRound, is_feat<T>>(lds_x, sx, onex, nvalid, lane);
         if constexpr (Tr::kHasYZ) {
-            park_tile<DX, Tr::kMapY, kFull, is_bf16<T>, is_feat<T>>(lds_y, sy, onex, nvalid, lane);
-            park_tile<DZ, Tr::kMapZ, kFull, is_bf16<T>, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<DX, Tr::kMapY, kFull, kRound, is_feat<T>>(lds_y, sy, onex, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ, kFull, kRound, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         }
-        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, is_bf16<T>, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
+        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, kRound, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
     }
 
     template <int SLOT>
@@ -265,12 +275,12 @@ struct ReverseStager {
 
     template <int SLOT, bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<D, kMapPhi, kFull, is_bf16<T>, is_feat<T>>(lds_a, sa[SLOT], scd, nvalid, lane);
+        park_tile<D, kMapPhi, kFull, false, is_feat<T>>(lds_a, sa[SLOT], scd, nvalid, lane);
         if constexpr (ROLE == 0) {
-            park_tile<M, kMapScale, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<M, kMapScale, kFull, false, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         } else {
-            park_tile<D, kMapDphi, kFull, is_bf16<T>, is_feat<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
-            park_tile<M, kMapId, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<D, kMapDphi, kFull, false, is_feat<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
+            park_tile<M, kMapId, kFull, false, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         }
     }
 
@@ -307,9 +317,9 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     constexpr bool kReverse = Tr::kReverse;
     constexpr bool kHasRaw = Tr::kHasRaw;
     constexpr bool kHasYZ = Tr::kHasYZ;
-    // bf16 tensors: the tile products run on the bf16 MFMA (operands rounded to bf16, fp32
-    // accumulation); the sums that ride on MFMAs against ones stay fp32
-    constexpr bool kBf = is_bf16<T>;
+    // bf16 tensors, forward passes: the tile products run on the bf16 MFMA (operands rounded to
+    // bf16, fp32 accumulation); the sums that ride on MFMAs against ones stay fp32
+    constexpr bool kBf = bf16_products<PASS, T>;
 
     const int c = lane & 15, g = lane >> 4;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
@@ -494,21 +504,15 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             float ya[XT][4];             // Y, token-lane
             lds_token_lane<DX>(lds_y, c, g, ya);
             f32x4 w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
-            if constexpr (kBf) {
+            // (fp32 products also for bf16 tensors: the row sums of the scores are the in-chunk
+            // part of the denominator, and the backward divides by it)
 #pragma unroll
-                for (int xt = 0; xt < XT; xt += 2) {
-                    w0 = mfma16_bf16(pack_bf16x4(ya[xt]), xp[xt], w0);
-                    w1 = mfma16_bf16(pack_bf16x4(ya[xt + 1]), xp[xt + 1], w1);
+            for (int xt = 0; xt < XT; xt += 2)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    w0 = mfma16(ya[xt][r], xa[xt][r], w0);
+                    w1 = mfma16(ya[xt + 1][r], xa[xt + 1][r], w1);
                 }
-            } else {
-#pragma unroll
-                for (int xt = 0; xt < XT; xt += 2)
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        w0 = mfma16(ya[xt][r], xa[xt][r], w0);
-                        w1 = mfma16(ya[xt + 1][r], xa[xt + 1][r], w1);
-                    }
-            }
             f32x4 w;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -842,14 +846,14 @@ struct DqStager {
         if constexpr (ROLE == 0) {
 #pragma unroll
             for (int i = 0; i < FT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
-            park_tile<F, kMapScale, kFull, is_bf16<T>, is_feat<T>>(lds_a, sa, sca, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapId, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapScale, kFull, false, is_feat<T>>(lds_a, sa, sca, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapId, kFull, false, is_feat<T>>(lds_b, sb, one, nvalid, lane);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
         } else {
-            park_tile<F, kMapPhi, kFull, is_bf16<T>, is_feat<T>>(lds_a, sa, one, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_bf16<T>, is_feat<T>>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapPhi, kFull, false, is_feat<T>>(lds_a, sa, one, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, false, is_feat<T>>(lds_b, sb, one, nvalid, lane);
         }
     }
 
@@ -878,7 +882,7 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const bool want = a.totals != nullptr;         // uniform
-    constexpr bool kBf = is_bf16<T>;   // see run_pass
+    constexpr bool kBf = false;        // a backward pass: fp32 products (see bf16_products)
 
     f32x4 S[XT][ZT], R[XT][ZT];                    // element (d = 16xt + 4g + r, m = 16zt + c)
 #pragma unroll
@@ -1071,11 +1075,11 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
         if (nvalid == kChunk) {
-            park_tile<D, kMapPhi, true, is_bf16<T>, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, true, is_bf16<T>, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, true, false, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, true, false, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         } else {
-            park_tile<D, kMapPhi, false, is_bf16<T>, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, false, is_bf16<T>, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, false, false, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, false, false, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         }
         if (ch + 1 < ch_end) fetch(ch + 1);
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
