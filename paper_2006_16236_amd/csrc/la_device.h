@@ -141,17 +141,6 @@ __device__ __forceinline__ bf16x4_t pack_bf16x4(const float (&x)[4]) {
     return pack_bf16x4(x[0], x[1], x[2], x[3]);
 }
 __device__ __forceinline__ bf16x4_t pack_bf16x4(f32x4 x) { return pack_bf16x4(x[0], x[1], x[2], x[3]); }
-// the four values rounded to bf16 precision (round to nearest even), still as fp32
-__device__ __forceinline__ f32x4 round_to_bf16(f32x4 x) {
-    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-    const u32x2 u = __builtin_bit_cast(u32x2, pack_bf16x4(x));
-    f32x4 r;
-    r[0] = __uint_as_float(u[0] << 16);
-    r[1] = __uint_as_float(u[0] & 0xffff0000u);
-    r[2] = __uint_as_float(u[1] << 16);
-    r[3] = __uint_as_float(u[1] & 0xffff0000u);
-    return r;
-}
 __device__ __forceinline__ f32x4 mfma16_bf16(bf16x4_t a, bf16x4_t b, f32x4 acc) {
     return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, acc, 0, 0, 0);
 }

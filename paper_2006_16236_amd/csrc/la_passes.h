@@ -112,12 +112,10 @@ template <int PASS, typename T>
 constexpr bool bf16_products = is_bf16<T> && (PASS == kFwd || PASS == kGlobal);
 
 // Park a staged tile in LDS: apply the map; kFull = false also zeroes the rows past the end
-// of the sequence.  kRound (bf16 tensors): the mapped values phi(x) and dO/den are rounded to
-// bf16 here, once, so that every product and every sum that uses them sees the same values:
-// the numerator S and the denominator z of eq. 10-12 are then built from identical features
-// (the attention weights still sum to one), and packing them as MFMA operands is exact.
+// of the sequence.  The parked values stay fp32 for every element type: a pass that multiplies
+// on the bf16 MFMA rounds them when it packs its operands.
 // kFeat (the caller has applied the feature map): phi becomes the identity, phi' becomes 1.
-template <int F, int MAP_, bool kFull, bool kRound, bool kFeat>
+template <int F, int MAP_, bool kFull, bool kFeat>
 __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16],
                                           const float (&scale)[F / 16], int nvalid, int lane) {
     constexpr int MAP = !kFeat ? MAP_ : MAP_ == kMapPhi ? kMapId : MAP_ == kMapDphi ? kMapOne : MAP_;
@@ -130,7 +128,6 @@ __device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16]
             const float m = map_value<MAP>(st[i][r], scale[i]);
             v[r] = (kFull || row < nvalid) ? m : 0.0f;
         }
-        if constexpr (kRound && (MAP == kMapPhi || MAP == kMapScale)) v = round_to_bf16(v);
         lds_store4(tile + row * tile_stride(F) + stage_col<F>(lane, i), v);
     }
 }
@@ -158,7 +155,6 @@ struct PassStager {
     static_assert(PASS == kFwd || PASS == kGlobal || PASS == kGlobalDv || PASS == kGlobalDk,
                   "the other passes have stagers of their own");
     static constexpr int DX = Tr::DX, DZ = Tr::DZ, XT = DX / 16, ZT = DZ / 16;
-    static constexpr bool kRound = false;
     const T *Xs, *Ys, *Zs, *Rs;
     float *lds_x, *lds_y, *lds_z, *lds_r;
     int N, lane;
@@ -205,12 +201,12 @@ struct PassStager {
 
     template <bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<DX, Tr::kMapX, kFull, kRound, is_feat<T>>(lds_x, sx, onex, nvalid, lane);
+        park_tile<DX, Tr::kMapX, kFull, is_feat<T>>(lds_x, sx, onex, nvalid, lane);
         if constexpr (Tr::kHasYZ) {
-            park_tile<DX, Tr::kMapY, kFull, kRound, is_feat<T>>(lds_y, sy, onex, nvalid, lane);
-            park_tile<DZ, Tr::kMapZ, kFull, kRound, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<DX, Tr::kMapY, kFull, is_feat<T>>(lds_y, sy, onex, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ, kFull, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         }
-        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, kRound, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
+        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
     }
 
     template <int SLOT>
@@ -275,12 +271,12 @@ struct ReverseStager {
 
     template <int SLOT, bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<D, kMapPhi, kFull, false, is_feat<T>>(lds_a, sa[SLOT], scd, nvalid, lane);
+        park_tile<D, kMapPhi, kFull, is_feat<T>>(lds_a, sa[SLOT], scd, nvalid, lane);
         if constexpr (ROLE == 0) {
-            park_tile<M, kMapScale, kFull, false, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<M, kMapScale, kFull, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         } else {
-            park_tile<D, kMapDphi, kFull, false, is_feat<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
-            park_tile<M, kMapId, kFull, false, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
+            park_tile<D, kMapDphi, kFull, is_feat<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
+            park_tile<M, kMapId, kFull, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         }
     }
 
@@ -846,14 +842,14 @@ struct DqStager {
         if constexpr (ROLE == 0) {
 #pragma unroll
             for (int i = 0; i < FT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
-            park_tile<F, kMapScale, kFull, false, is_feat<T>>(lds_a, sa, sca, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapId, kFull, false, is_feat<T>>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapScale, kFull, is_feat<T>>(lds_a, sa, sca, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapId, kFull, is_feat<T>>(lds_b, sb, one, nvalid, lane);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
         } else {
-            park_tile<F, kMapPhi, kFull, false, is_feat<T>>(lds_a, sa, one, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, false, is_feat<T>>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_a, sa, one, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_b, sb, one, nvalid, lane);
         }
     }
 
@@ -1075,11 +1071,11 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
         if (nvalid == kChunk) {
-            park_tile<D, kMapPhi, true, false, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, true, false, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, true, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, true, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         } else {
-            park_tile<D, kMapPhi, false, false, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
-            park_tile<M, kMapId, false, false, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<D, kMapPhi, false, is_feat<T>>(lds_y, sy, oney, nvalid, lane);
+            park_tile<M, kMapId, false, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         }
         if (ch + 1 < ch_end) fetch(ch + 1);
         __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
