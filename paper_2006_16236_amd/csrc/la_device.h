@@ -145,6 +145,61 @@ __device__ __forceinline__ f32x4 mfma16_bf16(bf16x4_t a, bf16x4_t b, f32x4 acc) 
     return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, acc, 0, 0, 0);
 }
 
+// fp32 products on the bf16 matrix pipe, to fp32 accuracy.  Every fp32 value is cut into three
+// bf16 parts, x = h + m + l exactly: h the top 8 significant bits (truncated), m the top 8 of
+// what is left, l the rest (at most 8 more).  A product keeps the six part products down to
+// 2^-16 of its size (hh, hm, mh, hl, lh, mm; what is dropped is below 2^-23), and
+// `v_mfma_f32_16x16x32_bf16` takes two part products per instruction: its 32 contraction slots
+// are the 16 of a 16x16x16 tile twice, with any pair of parts on the two halves.  Lane (c, g)
+// supplies the same four values per operand as for four mfma16 calls; three instructions of 16
+// cycles replace four of 32, and they leave the vector pipe free.
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+struct Split3 {
+    u32x2_t h, m, l;        // four bf16 each, element j in the low / high half of word j / 2
+};
+__device__ __forceinline__ Split3 split3(const float (&x)[4]) {
+    unsigned h[4], m[4], l[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        h[j] = __float_as_uint(x[j]) & 0xffff0000u;
+        const float r = x[j] - __uint_as_float(h[j]);
+        m[j] = __float_as_uint(r) & 0xffff0000u;
+        l[j] = __float_as_uint(r - __uint_as_float(m[j]));
+    }
+    Split3 s;
+    // (high half of b) << 16 | (high half of a)
+    s.h = u32x2_t{__builtin_amdgcn_perm(h[1], h[0], 0x07060302u), __builtin_amdgcn_perm(h[3], h[2], 0x07060302u)};
+    s.m = u32x2_t{__builtin_amdgcn_perm(m[1], m[0], 0x07060302u), __builtin_amdgcn_perm(m[3], m[2], 0x07060302u)};
+    s.l = u32x2_t{__builtin_amdgcn_perm(l[1], l[0], 0x07060302u), __builtin_amdgcn_perm(l[3], l[2], 0x07060302u)};
+    return s;
+}
+__device__ __forceinline__ bf16x8_t cat_parts(u32x2_t lo, u32x2_t hi) {
+    return __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], hi[0], hi[1]});
+}
+// the three operand pairs of one side, built once and reused over the other side's tiles
+struct SplitA { bf16x8_t lh, hm; };
+struct SplitB { bf16x8_t hl, mm, hh; };
+__device__ __forceinline__ SplitA split_a(const float (&x)[4]) {
+    const Split3 s = split3(x);
+    return SplitA{cat_parts(s.l, s.h), cat_parts(s.h, s.m)};
+}
+__device__ __forceinline__ SplitB split_b(const float (&x)[4]) {
+    const Split3 s = split3(x);
+    return SplitB{cat_parts(s.h, s.l), cat_parts(s.m, s.m), cat_parts(s.h, s.h)};
+}
+__device__ __forceinline__ f32x4 mfma32_bf16(bf16x8_t a, bf16x8_t b, f32x4 acc) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
+}
+// acc + sum over the four contraction steps of a * b: the small terms first
+__device__ __forceinline__ f32x4 mfma16_split(const SplitA &a, const SplitB &b, f32x4 acc) {
+    acc = mfma32_bf16(a.lh, b.hl, acc);    // lh + hl
+    acc = mfma32_bf16(a.hm, b.mm, acc);    // hm + mm
+    acc = mfma32_bf16(a.hm, b.hh, acc);    // hh + mh
+    return acc;
+}
+
 // ---- tiles ------------------------------------------------------------------------------------
 // A tile is 16 consecutive tokens x F features of one [N, F] slab, F in {32, 64}.
 //

@@ -49,6 +49,9 @@
 
 #include "la_device.h"
 
+#ifndef LA_SPLIT_SUMS
+#define LA_SPLIT_SUMS 1          // outer-product sums of the backward on split bf16 operands
+#endif
 #ifndef LA_SLEEP_AFTER_FETCH
 #define LA_SLEEP_AFTER_FETCH 1   // in units of 64 clocks
 #endif
@@ -316,6 +319,11 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     // bf16 tensors, forward passes: the tile products run on the bf16 MFMA (operands rounded to
     // bf16, fp32 accumulation); the sums that ride on MFMAs against ones stay fp32
     constexpr bool kBf = bf16_products<PASS, T>;
+    // fp32 products whose operands are tile values shared by several products (the in-chunk
+    // term, the running sum inside the chunk, the update of U) run on split bf16 operands, to
+    // fp32 accuracy (see split3); the products against U itself and the scores stay on the fp32
+    // MFMA: splitting their operands would cost more than it saves.
+    constexpr bool kSplit = !kBf && (LA_SPLIT_SUMS != 0);
 
     const int c = lane & 15, g = lane >> 4;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
@@ -482,6 +490,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         const f32x4 eps4 = {a.eps, a.eps, a.eps, a.eps};
         float zf[ZT][4];                 // Z, feature-lane
         bf16x4_t zp[ZT];                 // ... packed (bf16 path)
+        SplitB zs[ZT];                   // ... split (fp32 on the bf16 pipe)
         if constexpr (!kHasYZ) {
             if constexpr (PASS == kGlobal) {
                 float p = 0.f;
@@ -539,6 +548,14 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     zp[zt] = pack_bf16x4(zf[zt]);
                     out[zt] = mfma16_bf16(wp, zp[zt], out[zt]);
                 }
+            } else if constexpr (kSplit) {
+                const float wq[4] = {w[0], w[1], w[2], w[3]};
+                const SplitA ws = split_a(wq);
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt) {
+                    zs[zt] = split_b(zf[zt]);
+                    out[zt] = mfma16_split(ws, zs[zt], out[zt]);
+                }
             } else {
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
@@ -589,6 +606,16 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     const bf16x4_t mp = pack_bf16x4(m);
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16_bf16(mp, zp[zt], cz[zt]);
+                } else if constexpr (kSplit) {
+                    // the mask is exact in bf16: mask . (h + l) and mask . m
+                    const u32x2_t mk = {(m[0] != 0.f ? 0x3f80u : 0u) | (m[1] != 0.f ? 0x3f800000u : 0u),
+                                        (m[2] != 0.f ? 0x3f80u : 0u) | (m[3] != 0.f ? 0x3f800000u : 0u)};
+                    const bf16x8_t mm = cat_parts(mk, mk), m0 = cat_parts(mk, u32x2_t{0u, 0u});
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt) {
+                        cz[zt] = mfma32_bf16(mm, zs[zt].hl, cz[zt]);
+                        cz[zt] = mfma32_bf16(m0, zs[zt].mm, cz[zt]);
+                    }
                 } else {
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
@@ -650,6 +677,13 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                         const bf16x4_t yp = pack_bf16x4(yf[xt]);
 #pragma unroll
                         for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_bf16(yp, zp[zt], U[xt][zt]);
+                    }
+                } else if constexpr (kSplit) {
+#pragma unroll
+                    for (int xt = 0; xt < XT; ++xt) {
+                        const SplitA ys = split_a(yf[xt]);
+#pragma unroll
+                        for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_split(ys, zs[zt], U[xt][zt]);
                     }
                 } else {
 #pragma unroll
@@ -931,6 +965,16 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt) S[xt][zt] = mfma16_bf16(kp, vp[zt], S[xt][zt]);
                 }
+            } else if constexpr (LA_SPLIT_SUMS) {
+                SplitA ka[XT];
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt) ka[xt] = split_a(kf[xt]);
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt) {
+                    const SplitB vb = split_b(vf[zt]);
+#pragma unroll
+                    for (int xt = 0; xt < XT; ++xt) S[xt][zt] = mfma16_split(ka[xt], vb, S[xt][zt]);
+                }
             } else {
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
@@ -954,6 +998,16 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
                     const bf16x4_t qp = pack_bf16x4(qf[xt]);
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt) R[xt][zt] = mfma16_bf16(qp, gp[zt], R[xt][zt]);
+                }
+            } else if constexpr (LA_SPLIT_SUMS) {
+                SplitA qa[XT];
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt) qa[xt] = split_a(qf[xt]);
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt) {
+                    const SplitB gb = split_b(gf[zt]);
+#pragma unroll
+                    for (int xt = 0; xt < XT; ++xt) R[xt][zt] = mfma16_split(qa[xt], gb, R[xt][zt]);
                 }
             } else {
 #pragma unroll
@@ -1094,6 +1148,16 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
                 const bf16x4_t yp = pack_bf16x4(yf[xt]);
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_bf16(yp, zp[zt], U[xt][zt]);
+            }
+        } else if constexpr (LA_SPLIT_SUMS != 0) {
+            SplitA ys[XT];
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt) ys[xt] = split_a(yf[xt]);
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt) {
+                const SplitB zs = split_b(zf[zt]);
+#pragma unroll
+                for (int xt = 0; xt < XT; ++xt) U[xt][zt] = mfma16_split(ys[xt], zs, U[xt][zt]);
             }
         } else {
 #pragma unroll
