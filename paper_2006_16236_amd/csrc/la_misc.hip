@@ -28,8 +28,20 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg
     // the last slot in scan order holds no total (nobody reads past it): never read it
     const int klast = mode == kScanTotal ? nseg : nseg - 1;
 
+    // eight independent loads in flight per thread (a plain loop waits for each in turn)
+    constexpr int kBlock = 8;
+    const int kread = min(k1, klast);
     float total = 0.f;
-    for (int k = k0; k < min(k1, klast); ++k) total += p[(size_t)(reverse ? nseg - 1 - k : k) * stride];
+    for (int kb = k0; kb < kread; kb += kBlock) {
+        float t[kBlock];
+#pragma unroll
+        for (int j = 0; j < kBlock; ++j) {
+            const int k = min(kb + j, kread - 1);
+            t[j] = p[(size_t)(reverse ? nseg - 1 - k : k) * stride];
+        }
+#pragma unroll
+        for (int j = 0; j < kBlock; ++j) total += kb + j < kread ? t[j] : 0.f;
+    }
     // the scan starts from the caller's initial state when there is one (forward prefix only)
     float acc = 0.f;
     if (init_S != nullptr && live)
@@ -44,11 +56,21 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg
         if (part == PARTS - 1 && live) p[0] = acc + total;
         return;
     }
-    for (int k = k0; k < k1; ++k) {
-        float *slot = p + (size_t)(reverse ? nseg - 1 - k : k) * stride;
-        const float t = k < klast ? *slot : 0.f;
-        if (live) *slot = acc;
-        acc += t;
+    for (int kb = k0; kb < k1; kb += kBlock) {
+        float t[kBlock];
+#pragma unroll
+        for (int j = 0; j < kBlock; ++j) {
+            const int k = min(kb + j, k1 - 1);
+            t[j] = k < klast ? p[(size_t)(reverse ? nseg - 1 - k : k) * stride] : 0.f;
+        }
+#pragma unroll
+        for (int j = 0; j < kBlock; ++j) {
+            const int k = kb + j;
+            if (k < k1) {
+                if (live) p[(size_t)(reverse ? nseg - 1 - k : k) * stride] = acc;
+                acc += t[j];
+            }
+        }
     }
 }
 
