@@ -178,25 +178,55 @@ __device__ __forceinline__ Split3 split3(const float (&x)[4]) {
 __device__ __forceinline__ bf16x8_t cat_parts(u32x2_t lo, u32x2_t hi) {
     return __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], hi[0], hi[1]});
 }
-// the three operand pairs of one side, built once and reused over the other side's tiles
-struct SplitA { bf16x8_t lh, hm; };
-struct SplitB { bf16x8_t hl, mm, hh; };
+// The operand pairs of the two sides of a product, built once per operand quad and reused over
+// the other side's tiles.  Each side keeps its parts in one run of registers and the instructions
+// take overlapping windows of it: side A holds [l h m] (windows l|h and h|m), side B holds
+// [h m h l] (windows h|m, m|h and h|l): lh + hl, hh + mm, hm + mh are the six products.
+typedef unsigned u32x6_t __attribute__((ext_vector_type(6)));
+typedef unsigned u32x8_t __attribute__((ext_vector_type(8)));
+struct SplitA {
+    u32x6_t v;
+    __device__ __forceinline__ bf16x8_t lh() const {
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 0, 1, 2, 3));
+    }
+    __device__ __forceinline__ bf16x8_t hm() const {
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 2, 3, 4, 5));
+    }
+};
+struct SplitB {
+    u32x8_t v;
+    __device__ __forceinline__ bf16x8_t hm() const {
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 0, 1, 2, 3));
+    }
+    __device__ __forceinline__ bf16x8_t mh() const {
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 2, 3, 4, 5));
+    }
+    __device__ __forceinline__ bf16x8_t hl() const {
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 4, 5, 6, 7));
+    }
+};
 __device__ __forceinline__ SplitA split_a(const float (&x)[4]) {
     const Split3 s = split3(x);
-    return SplitA{cat_parts(s.l, s.h), cat_parts(s.h, s.m)};
+    return SplitA{u32x6_t{s.l[0], s.l[1], s.h[0], s.h[1], s.m[0], s.m[1]}};
 }
 __device__ __forceinline__ SplitB split_b(const float (&x)[4]) {
     const Split3 s = split3(x);
-    return SplitB{cat_parts(s.h, s.l), cat_parts(s.m, s.m), cat_parts(s.h, s.h)};
+    return SplitB{u32x8_t{s.h[0], s.h[1], s.m[0], s.m[1], s.h[0], s.h[1], s.l[0], s.l[1]}};
 }
 __device__ __forceinline__ f32x4 mfma32_bf16(bf16x8_t a, bf16x8_t b, f32x4 acc) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
 }
 // acc + sum over the four contraction steps of a * b: the small terms first
 __device__ __forceinline__ f32x4 mfma16_split(const SplitA &a, const SplitB &b, f32x4 acc) {
-    acc = mfma32_bf16(a.lh, b.hl, acc);    // lh + hl
-    acc = mfma32_bf16(a.hm, b.mm, acc);    // hm + mm
-    acc = mfma32_bf16(a.hm, b.hh, acc);    // hh + mh
+    acc = mfma32_bf16(a.lh(), b.hl(), acc);    // lh + hl
+    acc = mfma32_bf16(a.hm(), b.mh(), acc);    // hm + mh
+    acc = mfma32_bf16(a.hm(), b.hm(), acc);    // hh + mm
+    return acc;
+}
+// acc + mask * b for a mask of zeros and ones (exact in bf16), four bf16 per lane in `mk`
+__device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB &b, f32x4 acc) {
+    acc = mfma32_bf16(cat_parts(mk, mk), b.hl(), acc);                  // mask (h + l)
+    acc = mfma32_bf16(cat_parts(mk, u32x2_t{0u, 0u}), b.mh(), acc);     // mask m
     return acc;
 }
 

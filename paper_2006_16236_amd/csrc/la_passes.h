@@ -607,15 +607,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16_bf16(mp, zp[zt], cz[zt]);
                 } else if constexpr (kSplit) {
-                    // the mask is exact in bf16: mask . (h + l) and mask . m
-                    const u32x2_t mk = {(m[0] != 0.f ? 0x3f80u : 0u) | (m[1] != 0.f ? 0x3f800000u : 0u),
+                                        const u32x2_t mk = {(m[0] != 0.f ? 0x3f80u : 0u) | (m[1] != 0.f ? 0x3f800000u : 0u),
                                         (m[2] != 0.f ? 0x3f80u : 0u) | (m[3] != 0.f ? 0x3f800000u : 0u)};
-                    const bf16x8_t mm = cat_parts(mk, mk), m0 = cat_parts(mk, u32x2_t{0u, 0u});
 #pragma unroll
-                    for (int zt = 0; zt < ZT; ++zt) {
-                        cz[zt] = mfma32_bf16(mm, zs[zt].hl, cz[zt]);
-                        cz[zt] = mfma32_bf16(m0, zs[zt].mm, cz[zt]);
-                    }
+                    for (int zt = 0; zt < ZT; ++zt) cz[zt] = mfma16_mask(mk, zs[zt], cz[zt]);
                 } else {
 #pragma unroll
                     for (int s = 0; s < 4; ++s)
