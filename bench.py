@@ -35,11 +35,11 @@ MFMA_F32_PEAK_TFLOPS = 157.3     # MI355X dense fp32 matrix, published
 # and scaled by a copy kernel of known size (factors 2.000 / 1.000); the runs and their commands are
 # in profiles/hbm_traffic_and_pipe_counters_N65536_B2_H8_D64_f32.md.  Read + written, in bytes.
 MEASURED_TRAFFIC_BYTES = {
-    "causal_pass_fwd": (839.5 + 273.6) * 1e6,
-    "pass_dq": (1095.8 + 296.0) * 1e6,
-    "reverse_pass_dv_dk": (1101.6 + 536.9) * 1e6,
+    "causal_pass_fwd": (839.6 + 273.7) * 1e6,
+    "pass_dq": (1095.7 + 296.5) * 1e6,
+    "reverse_pass_dv_dk": (1101.7 + 536.9) * 1e6,
     "segment_state_kv": (532.8 + 33.8) * 1e6,
-    "scan_states": (35.8 + 25.6) * 1e6,
+    "scan_states": (34.5 + 25.6) * 1e6,
 }
 
 
