@@ -1,6 +1,7 @@
 // Device-side building blocks shared by the gfx950 linear-attention kernels:
 // feature map, element conversion, coalesced tile fetch, the LDS image of a tile with
-// the two MFMA operand layouts read from it, and the fp32 16x16x4 MFMA wrapper.
+// the two MFMA operand layouts read from it, and the MFMA wrappers (fp32, bf16, and fp32
+// products on the bf16 pipe through an exact operand split).
 #pragma once
 
 #include <hip/hip_runtime.h>

@@ -1,4 +1,6 @@
-// Chunked causal products on the matrix units (fp32 MFMA; bf16 MFMA for bf16 tensors).
+// Chunked causal products on the matrix units.  fp32-accurate products run on the fp32 MFMA or,
+// where one operand quad feeds several products, on the bf16 MFMA with exactly split operands
+// (split3 in la_device.h); the forward passes of bf16 tensors use plain bf16 products.
 // The forward runs one wavefront per (sequence, segment); the two kernels of the backward run
 // two wavefronts per (sequence, segment) that share one fetch of the inputs.
 //
@@ -41,7 +43,7 @@
 // Data movement per chunk: every input tile (16 tokens x 32|64 features) is fetched
 // once with fully coalesced 16-byte loads into staging registers while the previous
 // chunk is being computed, then mapped (phi, phi', 1/den scaling, zero fill of rows past
-// the end of the sequence; for bf16 tensors also rounded to bf16) and parked in LDS, from where the MFMA operands are read in
+// the end of the sequence) and parked in LDS as fp32, from where the MFMA operands are read in
 // whichever of the two layouts of la_device.h each product needs.
 #pragma once
 
@@ -50,7 +52,7 @@
 #include "la_device.h"
 
 #ifndef LA_SPLIT_SUMS
-#define LA_SPLIT_SUMS 1          // outer-product sums of the backward on split bf16 operands
+#define LA_SPLIT_SUMS 1          // 0: every fp32 product on the fp32 MFMA (for comparison)
 #endif
 #ifndef LA_SLEEP_AFTER_FETCH
 #define LA_SLEEP_AFTER_FETCH 1   // in units of 64 clocks
@@ -106,8 +108,8 @@ __device__ __forceinline__ float map_value(float v, float scale) {
 }
 
 // Which passes of a bf16 call run their tile products on the bf16 MFMA: the forward ones
-// (kFwd, kGlobal and the K, V segment sums).  The backward passes keep fp32 products on the
-// widened values: their results are differences of nearly equal terms (dphi(Q)_a = A_a +
+// (kFwd, kGlobal and the K, V segment sums).  The backward passes keep fp32-accurate products
+// on the widened values (fp32 MFMA and split operands, as for fp32 tensors): their results are differences of nearly equal terms (dphi(Q)_a = A_a +
 // delta_a z_a vanishes for constant V; R v + rho likewise), and with features phi(x) = 1 + x + ...
 // of small x the 8-bit mantissa of the operands would cost up to 1.5e-2 of the gradient's scale
 // (measured on inputs scaled by 1/8; worse for smaller inputs), too close to the 2e-2 gate.
@@ -895,7 +897,8 @@ struct DqStager {
 //        every chunk (wave 0 reads it transposed for its read-out) and then updates;
 //   R  = this segment's sum of phi(Q_b) dO_b^T/den_b (eq. 14-15 restricted to the segment), kept
 //        only when the sequences are cut, for the scan that feeds the reverse passes.
-// So the matrix work of the pass is split evenly between the two waves.
+// Both sums are outer products over the chunk's 16 tokens: 16 operand quads, split once, feed
+// 96 bf16 MFMAs.  Wave 0 keeps the products against S (fp32 MFMA) and the epilogue.
 template <int D, int M, typename T, bool kCausal, typename Stager>
 __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, const float *lds_fk,
                                             const float *lds_v, const float *lds_fq,
@@ -907,7 +910,7 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const bool want = a.totals != nullptr;         // uniform
-    constexpr bool kBf = false;        // a backward pass: fp32 products (see bf16_products)
+    constexpr bool kBf = false;        // a backward pass: fp32-accurate products (see bf16_products)
 
     f32x4 S[XT][ZT], R[XT][ZT];                    // element (d = 16xt + 4g + r, m = 16zt + c)
 #pragma unroll
