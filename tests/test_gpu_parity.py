@@ -75,6 +75,36 @@ def test_causal_fwd_bwd_all_head_sizes(la, oracle, D, M, sched):
         assert e <= tol_for(N), name
 
 
+@pytest.mark.parametrize("D,M", [(64, 64), (32, 64)])
+@pytest.mark.parametrize("sched", ["default", "many_segments"])
+def test_elements_of_widely_different_magnitude(la, oracle, D, M, sched):
+    """Every tile mixes elements from 2^-10 to 2^10 times a Gaussian.  Part of the fp32 products
+    run on bf16 matrix instructions with operands cut into three bf16 pieces; the cut is per
+    element, so the accuracy must not depend on how the magnitudes inside a tile compare."""
+    B, H, N = 2, 2, 419
+    Q, K, V, G = wl.wide_range_case(4242 + D, B, H, N, D, M)
+    eps = 1e-6
+    ref = oracle.causal_fwd_prefix(Q, K, V, eps)
+    gref = oracle.causal_bwd_linear(Q, K, V, G, eps)
+    gl_ref = oracle.global_bwd_linear(Q, K, V, G, eps)
+    with schedule(**SCHEDULES[sched]):
+        O, _ = run_fwd(la, Q, K, V, eps)
+        got = run_bwd(la, Q, K, V, G, eps)
+        dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+        Og = torch.empty_like(dv)
+        deng = torch.empty(Q.shape[:-1], dtype=torch.float32, device=DEV)
+        gws = la.la_global_fwd(dq, dk, dv, Og, eps, den=deng)
+        gq, gk, gv = torch.empty_like(dq), torch.empty_like(dk), torch.empty_like(dv)
+        la.la_global_bwd(dq, dk, dv, Og, deng, dg, gq, gk, gv, eps, fwd_ws=gws)
+        torch.cuda.synchronize()
+    assert rel_err(O, ref) <= 1e-5
+    for e, name in zip(grad_errs(got, gref), ("dQ", "dK", "dV")):
+        assert e <= 1e-5, name
+    assert rel_err(to_host(Og), oracle.global_fwd_linear(Q, K, V, eps)) <= 1e-5
+    for e, name in zip(grad_errs([to_host(x) for x in (gq, gk, gv)], gl_ref), ("dQ", "dK", "dV")):
+        assert e <= 1e-5, "non-causal " + name
+
+
 @pytest.mark.parametrize("sched", list(SCHEDULES))
 @pytest.mark.parametrize("N", EDGE_N)
 def test_causal_bwd_edge_lengths(la, oracle, N, sched):

@@ -96,6 +96,21 @@ def random_case(seed: int, B: int, H: int, N: int, D: int, M: int, scale: float 
     return qkvg(Workload(f"case{seed}", B, H, N, D, M, seed, scale=scale))
 
 
+def wide_range_case(seed: int, B: int, H: int, N: int, D: int, M: int, log2_spread: int = 10):
+    """Seeded case whose elements differ widely in magnitude inside every tile: each element of
+    the Gaussian Q, K, V, dO is multiplied by its own power of two, 2^k with k uniform in
+    [-log2_spread, 0] for Q and K (the feature map saturates large inputs anyway) and in
+    [-log2_spread, log2_spread] for V and dO."""
+    q, k, v, g = random_case(seed, B, H, N, D, M)
+    rng = np.random.default_rng(seed + 7919)
+    out = []
+    for x, lo, hi in ((q, -log2_spread, 0), (k, -log2_spread, 0), (v, -log2_spread, log2_spread),
+                      (g, -log2_spread, log2_spread)):
+        e = rng.integers(lo, hi + 1, size=x.shape)
+        out.append(np.ldexp(x, e).astype(np.float32))
+    return tuple(out)
+
+
 # ---- exact bf16 rounding of inputs (round to nearest, ties to even) -----------------------
 
 def round_to_bf16(x: np.ndarray) -> np.ndarray:
