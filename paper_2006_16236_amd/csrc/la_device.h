@@ -181,54 +181,109 @@ __device__ __forceinline__ bf16x8_t cat_parts(u32x2_t lo, u32x2_t hi) {
 }
 // The operand pairs of the two sides of a product, built once per operand quad and reused over
 // the other side's tiles.  Each side keeps its parts in one run of registers and the instructions
-// take overlapping windows of it: side A holds [l h m] (windows l|h and h|m), side B holds
-// [h m h l] (windows h|m, m|h and h|l): lh + hl, hh + mm, hm + mh are the six products.
+// take overlapping windows of it.
+//   P = 3 (fp32 accuracy): side A holds [l h m] (windows l|h and h|m), side B holds [h m h l]
+//         (windows h|m, m|h and h|l): lh + hl, hh + mm, hm + mh are the six products.
+//   P = 2 (x ~ h + m, 16 significant bits, for bf16 tensors whose results are rounded to 8):
+//         side A holds [h m], side B holds [h h m 0] (windows h|h, h|m, m|0): hh + mh and hm
+//         are the three products, two instructions.
 typedef unsigned u32x6_t __attribute__((ext_vector_type(6)));
 typedef unsigned u32x8_t __attribute__((ext_vector_type(8)));
-struct SplitA {
+template <int P> struct SplitA;
+template <int P> struct SplitB;
+#define LA_WINDOW(name, v, i0)                                                                 \
+    __device__ __forceinline__ bf16x8_t name() const {                                          \
+        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, i0, i0 + 1, i0 + 2, i0 + 3)); \
+    }
+template <> struct SplitA<3> {
     u32x6_t v;
-    __device__ __forceinline__ bf16x8_t lh() const {
-        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 0, 1, 2, 3));
-    }
-    __device__ __forceinline__ bf16x8_t hm() const {
-        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 2, 3, 4, 5));
-    }
+    LA_WINDOW(lh, v, 0)
+    LA_WINDOW(hm, v, 2)
 };
-struct SplitB {
+template <> struct SplitB<3> {
     u32x8_t v;
-    __device__ __forceinline__ bf16x8_t hm() const {
-        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 0, 1, 2, 3));
-    }
-    __device__ __forceinline__ bf16x8_t mh() const {
-        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 2, 3, 4, 5));
-    }
-    __device__ __forceinline__ bf16x8_t hl() const {
-        return __builtin_bit_cast(bf16x8_t, __builtin_shufflevector(v, v, 4, 5, 6, 7));
-    }
+    LA_WINDOW(hm, v, 0)
+    LA_WINDOW(mh, v, 2)
+    LA_WINDOW(hl, v, 4)
 };
-__device__ __forceinline__ SplitA split_a(const float (&x)[4]) {
-    const Split3 s = split3(x);
-    return SplitA{u32x6_t{s.l[0], s.l[1], s.h[0], s.h[1], s.m[0], s.m[1]}};
+template <> struct SplitA<2> {
+    u32x4_t v;
+    LA_WINDOW(hm, v, 0)
+};
+template <> struct SplitB<2> {
+    u32x8_t v;
+    LA_WINDOW(hh, v, 0)
+    LA_WINDOW(hm, v, 2)
+    LA_WINDOW(m0, v, 4)
+};
+#undef LA_WINDOW
+
+// x ~ h + m: h the top 8 significant bits, m the top 8 of the rest (both by truncation)
+struct Split2 {
+    u32x2_t h, m;
+};
+__device__ __forceinline__ Split2 split2(const float (&x)[4]) {
+    unsigned h[4], m[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        h[j] = __float_as_uint(x[j]) & 0xffff0000u;
+        m[j] = __float_as_uint(x[j] - __uint_as_float(h[j]));
+    }
+    Split2 s;
+    s.h = u32x2_t{__builtin_amdgcn_perm(h[1], h[0], 0x07060302u), __builtin_amdgcn_perm(h[3], h[2], 0x07060302u)};
+    s.m = u32x2_t{__builtin_amdgcn_perm(m[1], m[0], 0x07060302u), __builtin_amdgcn_perm(m[3], m[2], 0x07060302u)};
+    return s;
 }
-__device__ __forceinline__ SplitB split_b(const float (&x)[4]) {
-    const Split3 s = split3(x);
-    return SplitB{u32x8_t{s.h[0], s.h[1], s.m[0], s.m[1], s.h[0], s.h[1], s.l[0], s.l[1]}};
+
+__device__ __forceinline__ SplitA<2> as_a(const Split2 &s) {
+    return SplitA<2>{u32x4_t{s.h[0], s.h[1], s.m[0], s.m[1]}};
+}
+__device__ __forceinline__ SplitB<2> as_b(const Split2 &s) {
+    return SplitB<2>{u32x8_t{s.h[0], s.h[1], s.h[0], s.h[1], s.m[0], s.m[1], 0u, 0u}};
+}
+template <int P> __device__ __forceinline__ SplitA<P> split_a(const float (&x)[4]) {
+    if constexpr (P == 3) {
+        const Split3 s = split3(x);
+        return SplitA<3>{u32x6_t{s.l[0], s.l[1], s.h[0], s.h[1], s.m[0], s.m[1]}};
+    } else {
+        return as_a(split2(x));
+    }
+}
+template <int P> __device__ __forceinline__ SplitB<P> split_b(const float (&x)[4]) {
+    if constexpr (P == 3) {
+        const Split3 s = split3(x);
+        return SplitB<3>{u32x8_t{s.h[0], s.h[1], s.m[0], s.m[1], s.h[0], s.h[1], s.l[0], s.l[1]}};
+    } else {
+        return as_b(split2(x));
+    }
+}
+template <int P> __device__ __forceinline__ SplitB<P> split_b(f32x4 x) {
+    const float q[4] = {x[0], x[1], x[2], x[3]};
+    return split_b<P>(q);
 }
 __device__ __forceinline__ f32x4 mfma32_bf16(bf16x8_t a, bf16x8_t b, f32x4 acc) {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);
 }
 // acc + sum over the four contraction steps of a * b: the small terms first
-__device__ __forceinline__ f32x4 mfma16_split(const SplitA &a, const SplitB &b, f32x4 acc) {
+__device__ __forceinline__ f32x4 mfma16_split(const SplitA<3> &a, const SplitB<3> &b, f32x4 acc) {
     acc = mfma32_bf16(a.lh(), b.hl(), acc);    // lh + hl
     acc = mfma32_bf16(a.hm(), b.mh(), acc);    // hm + mh
     acc = mfma32_bf16(a.hm(), b.hm(), acc);    // hh + mm
     return acc;
 }
+__device__ __forceinline__ f32x4 mfma16_split(const SplitA<2> &a, const SplitB<2> &b, f32x4 acc) {
+    acc = mfma32_bf16(a.hm(), b.m0(), acc);    // hm
+    acc = mfma32_bf16(a.hm(), b.hh(), acc);    // hh + mh
+    return acc;
+}
 // acc + mask * b for a mask of zeros and ones (exact in bf16), four bf16 per lane in `mk`
-__device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB &b, f32x4 acc) {
+__device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB<3> &b, f32x4 acc) {
     acc = mfma32_bf16(cat_parts(mk, mk), b.hl(), acc);                  // mask (h + l)
     acc = mfma32_bf16(cat_parts(mk, u32x2_t{0u, 0u}), b.mh(), acc);     // mask m
     return acc;
+}
+__device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB<2> &b, f32x4 acc) {
+    return mfma32_bf16(cat_parts(mk, mk), b.hm(), acc);                 // mask (h + m)
 }
 
 // ---- tiles ------------------------------------------------------------------------------------

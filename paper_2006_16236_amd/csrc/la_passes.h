@@ -326,6 +326,11 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     // fp32 accuracy (see split3); the products against U itself and the scores stay on the fp32
     // MFMA: splitting their operands would cost more than it saves.
     constexpr bool kSplit = !kBf && (LA_SPLIT_SUMS != 0);
+    // bf16 tensors (backward passes; the forward ones are kBf): the results are rounded to 8
+    // significant bits, so 16-bit operands (two parts) are ample, and at 12 vector instructions
+    // per quad the split then pays for the state operand of the read-out as well
+    constexpr int kParts = is_bf16<T> ? 2 : 3;
+    constexpr bool kSplitState = kSplit && is_bf16<T>;
 
     const int c = lane & 15, g = lane >> 4;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
@@ -467,6 +472,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
         for (int zt = 0; zt < ZT; ++zt) out[zt] = f32x4{0.f, 0.f, 0.f, 0.f};
         bf16x4_t xp[XT];                 // X packed (bf16 path)
+        Split2 x2[XT];                   // X in two parts (bf16 tensors, backward passes)
         if constexpr (kBf) {
 #pragma unroll
             for (int xt = 0; xt < XT; ++xt) {
@@ -474,6 +480,15 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt)
                     out[zt] = mfma16_bf16(xp[xt], pack_bf16x4(U[xt][zt]), out[zt]);
+            }
+        } else if constexpr (kSplitState) {
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt) {
+                x2[xt] = split2(xa[xt]);
+                const SplitA<2> xs = as_a(x2[xt]);
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt)
+                    out[zt] = mfma16_split(xs, split_b<2>(U[xt][zt]), out[zt]);
             }
         } else {
 #pragma unroll
@@ -492,7 +507,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         const f32x4 eps4 = {a.eps, a.eps, a.eps, a.eps};
         float zf[ZT][4];                 // Z, feature-lane
         bf16x4_t zp[ZT];                 // ... packed (bf16 path)
-        SplitB zs[ZT];                   // ... split (fp32 on the bf16 pipe)
+        SplitB<kParts> zs[ZT];           // ... split (fp32 on the bf16 pipe)
         if constexpr (!kHasYZ) {
             if constexpr (PASS == kGlobal) {
                 float p = 0.f;
@@ -511,15 +526,23 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             float ya[XT][4];             // Y, token-lane
             lds_token_lane<DX>(lds_y, c, g, ya);
             f32x4 w0 = {0.f, 0.f, 0.f, 0.f}, w1 = {0.f, 0.f, 0.f, 0.f};
-            // (fp32 products also for bf16 tensors: the row sums of the scores are the in-chunk
-            // part of the denominator, and the backward divides by it)
+            // (never plain bf16 products: in the forward pass the row sums of the scores are the
+            // in-chunk part of the denominator, and the backward divides by it)
+            if constexpr (kSplitState) {
 #pragma unroll
-            for (int xt = 0; xt < XT; xt += 2)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    w0 = mfma16(ya[xt][r], xa[xt][r], w0);
-                    w1 = mfma16(ya[xt + 1][r], xa[xt + 1][r], w1);
+                for (int xt = 0; xt < XT; xt += 2) {
+                    w0 = mfma16_split(split_a<2>(ya[xt]), as_b(x2[xt]), w0);
+                    w1 = mfma16_split(split_a<2>(ya[xt + 1]), as_b(x2[xt + 1]), w1);
                 }
+            } else {
+#pragma unroll
+                for (int xt = 0; xt < XT; xt += 2)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        w0 = mfma16(ya[xt][r], xa[xt][r], w0);
+                        w1 = mfma16(ya[xt + 1][r], xa[xt + 1][r], w1);
+                    }
+            }
             f32x4 w;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -552,10 +575,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 }
             } else if constexpr (kSplit) {
                 const float wq[4] = {w[0], w[1], w[2], w[3]};
-                const SplitA ws = split_a(wq);
+                const SplitA<kParts> ws = split_a<kParts>(wq);
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) {
-                    zs[zt] = split_b(zf[zt]);
+                    zs[zt] = split_b<kParts>(zf[zt]);
                     out[zt] = mfma16_split(ws, zs[zt], out[zt]);
                 }
             } else {
@@ -678,7 +701,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 } else if constexpr (kSplit) {
 #pragma unroll
                     for (int xt = 0; xt < XT; ++xt) {
-                        const SplitA ys = split_a(yf[xt]);
+                        const SplitA<kParts> ys = split_a<kParts>(yf[xt]);
 #pragma unroll
                         for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_split(ys, zs[zt], U[xt][zt]);
                     }
@@ -911,6 +934,7 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const bool want = a.totals != nullptr;         // uniform
     constexpr bool kBf = false;        // a backward pass: fp32-accurate products (see bf16_products)
+    constexpr int kParts = is_bf16<T> ? 2 : 3;     // see run_pass
 
     f32x4 S[XT][ZT], R[XT][ZT];                    // element (d = 16xt + 4g + r, m = 16zt + c)
 #pragma unroll
@@ -964,12 +988,12 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
                     for (int zt = 0; zt < ZT; ++zt) S[xt][zt] = mfma16_bf16(kp, vp[zt], S[xt][zt]);
                 }
             } else if constexpr (LA_SPLIT_SUMS) {
-                SplitA ka[XT];
+                SplitA<kParts> ka[XT];
 #pragma unroll
-                for (int xt = 0; xt < XT; ++xt) ka[xt] = split_a(kf[xt]);
+                for (int xt = 0; xt < XT; ++xt) ka[xt] = split_a<kParts>(kf[xt]);
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) {
-                    const SplitB vb = split_b(vf[zt]);
+                    const SplitB<kParts> vb = split_b<kParts>(vf[zt]);
 #pragma unroll
                     for (int xt = 0; xt < XT; ++xt) S[xt][zt] = mfma16_split(ka[xt], vb, S[xt][zt]);
                 }
@@ -998,12 +1022,12 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
                     for (int zt = 0; zt < ZT; ++zt) R[xt][zt] = mfma16_bf16(qp, gp[zt], R[xt][zt]);
                 }
             } else if constexpr (LA_SPLIT_SUMS) {
-                SplitA qa[XT];
+                SplitA<kParts> qa[XT];
 #pragma unroll
-                for (int xt = 0; xt < XT; ++xt) qa[xt] = split_a(qf[xt]);
+                for (int xt = 0; xt < XT; ++xt) qa[xt] = split_a<kParts>(qf[xt]);
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) {
-                    const SplitB gb = split_b(gf[zt]);
+                    const SplitB<kParts> gb = split_b<kParts>(gf[zt]);
 #pragma unroll
                     for (int xt = 0; xt < XT; ++xt) R[xt][zt] = mfma16_split(qa[xt], gb, R[xt][zt]);
                 }
@@ -1148,12 +1172,12 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
                 for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_bf16(yp, zp[zt], U[xt][zt]);
             }
         } else if constexpr (LA_SPLIT_SUMS != 0) {
-            SplitA ys[XT];
+            SplitA<3> ys[XT];
 #pragma unroll
-            for (int xt = 0; xt < XT; ++xt) ys[xt] = split_a(yf[xt]);
+            for (int xt = 0; xt < XT; ++xt) ys[xt] = split_a<3>(yf[xt]);
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) {
-                const SplitB zs = split_b(zf[zt]);
+                const SplitB<3> zs = split_b<3>(zf[zt]);
 #pragma unroll
                 for (int xt = 0; xt < XT; ++xt) U[xt][zt] = mfma16_split(ys[xt], zs, U[xt][zt]);
             }
