@@ -534,6 +534,12 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     w0 = mfma16_split(split_a<2>(ya[xt]), as_b(x2[xt]), w0);
                     w1 = mfma16_split(split_a<2>(ya[xt + 1]), as_b(x2[xt + 1]), w1);
                 }
+            } else if constexpr (kBf) {       // 16-bit operands: den is good to 2^-16
+#pragma unroll
+                for (int xt = 0; xt < XT; xt += 2) {
+                    w0 = mfma16_split(split_a<2>(ya[xt]), split_b<2>(xa[xt]), w0);
+                    w1 = mfma16_split(split_a<2>(ya[xt + 1]), split_b<2>(xa[xt + 1]), w1);
+                }
             } else {
 #pragma unroll
                 for (int xt = 0; xt < XT; xt += 2)
