@@ -105,6 +105,23 @@ def test_elements_of_widely_different_magnitude(la, oracle, D, M, sched):
         assert e <= 1e-5, "non-causal " + name
 
 
+def test_elements_of_widely_different_magnitude_bf16(la, oracle):
+    """The same kind of input as bf16 tensors (products on 16-bit operands, two bf16 pieces per
+    value in the backward): the bf16 gate must hold whatever the spread inside a tile."""
+    B, H, N, D, M = 2, 2, 419, 64, 64
+    host = maybe_bf16(wl.wide_range_case(4343, B, H, N, D, M, log2_spread=6), True)
+    Q, K, V, G = host
+    eps = 1e-6
+    ref = oracle.causal_fwd_prefix(Q, K, V, eps)
+    gref = oracle.causal_bwd_linear(Q, K, V, G, eps)
+    with schedule(**SCHEDULES["many_segments"]):
+        O, _ = run_fwd(la, Q, K, V, eps, bf16=True)
+        got = run_bwd(la, Q, K, V, G, eps, bf16=True)
+    assert rel_err(O, ref) <= tol_for(N, True)
+    for e, name in zip(grad_errs(got, gref), ("dQ", "dK", "dV")):
+        assert e <= tol_for(N, True), name
+
+
 @pytest.mark.parametrize("sched", list(SCHEDULES))
 @pytest.mark.parametrize("N", EDGE_N)
 def test_causal_bwd_edge_lengths(la, oracle, N, sched):
