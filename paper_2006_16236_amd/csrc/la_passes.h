@@ -1108,6 +1108,11 @@ struct SegArgs {
 template <int D, int M, typename T>
 __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     constexpr int XT = D / 16, ZT = M / 16;
+    // bf16 tensors: 16-bit operands (two parts), not plain bf16 products.  These sums also
+    // serve the backward passes (as the states at the segment borders, and as the grand total
+    // of the non-causal gradient), which need S and z built from the same feature values
+    // to better than 8 bits: their results are differences of nearly equal terms.
+    constexpr int kParts = is_bf16<T> ? 2 : 3;
     __shared__ float lds_y[tile_floats(D)];
     __shared__ float lds_z[tile_floats(M)];
     const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
@@ -1167,23 +1172,13 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         float yf[XT][4], zf[ZT][4];
         lds_feature_lane<D>(lds_y, c, g, yf);
         lds_feature_lane<M>(lds_z, c, g, zf);
-        if constexpr (is_bf16<T>) {       // see run_pass
-            bf16x4_t zp[ZT];
+        if constexpr (LA_SPLIT_SUMS != 0 || is_bf16<T>) {
+            SplitA<kParts> ys[XT];
 #pragma unroll
-            for (int zt = 0; zt < ZT; ++zt) zp[zt] = pack_bf16x4(zf[zt]);
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt) {
-                const bf16x4_t yp = pack_bf16x4(yf[xt]);
-#pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = mfma16_bf16(yp, zp[zt], U[xt][zt]);
-            }
-        } else if constexpr (LA_SPLIT_SUMS != 0) {
-            SplitA<3> ys[XT];
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt) ys[xt] = split_a<3>(yf[xt]);
+            for (int xt = 0; xt < XT; ++xt) ys[xt] = split_a<kParts>(yf[xt]);
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) {
-                const SplitB<3> zs = split_b<3>(zf[zt]);
+                const SplitB<kParts> zs = split_b<kParts>(zf[zt]);
 #pragma unroll
                 for (int xt = 0; xt < XT; ++xt) U[xt][zt] = mfma16_split(ys[xt], zs, U[xt][zt]);
             }

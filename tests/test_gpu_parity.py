@@ -188,6 +188,25 @@ def run_global(la, Q, K, V, G, eps, bf16=False, reuse_fwd=True, reuse_states=Tru
     return to_host(O), den.cpu().numpy(), (to_host(gq), to_host(gk), to_host(gv))
 
 
+@pytest.mark.parametrize("B,H,N,D,M,sched,eps", [(3, 4, 14, 32, 32, "one_segment", 1e-3),
+                                                  (2, 2, 593, 32, 64, "default", 0.0),
+                                                  (1, 4, 3793, 32, 64, "many_segments", 1e-6)])
+def test_bf16_backward_on_small_inputs(la, oracle, B, H, N, D, M, sched, eps):
+    """bf16 tensors scaled by 1/8: the features are 1 + (something small) and the gradients with
+    respect to Q are differences of nearly equal terms.  The sums over K, V that the backward
+    passes start from must then be good to more than bf16's 8 bits: with plain bf16 products in
+    them these cases sat at 1.4e-2 .. 2.04e-2."""
+    host = maybe_bf16(wl.random_case(50000 + N, B, H, N, D, M, scale=0.125), True)
+    Q, K, V, G = host
+    with schedule(**SCHEDULES[sched]):
+        grads = run_bwd(la, Q, K, V, G, eps, bf16=True)
+        _, _, ggrads = run_global(la, Q, K, V, G, eps, bf16=True)
+    for e, name in zip(grad_errs(grads, oracle.causal_bwd_linear(Q, K, V, G, eps)), ("dQ", "dK", "dV")):
+        assert e <= 1e-2, name
+    for e, name in zip(grad_errs(ggrads, oracle.global_bwd_linear(Q, K, V, G, eps)), ("dQ", "dK", "dV")):
+        assert e <= 1e-2, "non-causal " + name
+
+
 @pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
 @pytest.mark.parametrize("N", [1, 15, 16, 17, 64, 257, 1000])
 def test_global_bwd_edge_lengths(la, oracle, N, sched):
