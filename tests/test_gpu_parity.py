@@ -598,6 +598,46 @@ def test_caller_supplied_features_against_oracle(la, oracle_features, D, M, N, s
     assert max(grad_errs([to_host(x) for x in (hq, hk, hv)], o.global_bwd_linear(FQ, FK, V, G, eps))) <= tol
 
 
+def test_degree_two_polynomial_kernel_through_the_feature_interface(la, oracle_features):
+    """The polynomial kernel of degree 2 (section 3.2: a finite feature map, sim(q, k) = (q . k)^2):
+    phi(x) = vec(x x^T), 64 features of an 8-vector, handed in as features (signed values).
+    The oracle on these features must equal attention with (q . k)^2 written out, and the GPU
+    must equal the oracle, forward and backward, causal and not."""
+    o = oracle_features
+    rng = np.random.default_rng(2468)
+    B, H, N, d, M = 2, 3, 333, 8, 64
+    xq, xk = (rng.standard_normal((B, H, N, d)) for _ in range(2))
+    V, G = (rng.standard_normal((B, H, N, M)).astype(np.float32) for _ in range(2))
+    FQ = np.einsum("...i,...j->...ij", xq, xq).reshape(B, H, N, d * d).astype(np.float32)
+    FK = np.einsum("...i,...j->...ij", xk, xk).reshape(B, H, N, d * d).astype(np.float32)
+    # (q . k)^2 can be arbitrarily small, and where den is tiny its rounding error in fp32 is
+    # amplified by 1/den^2 in the gradients (token 0 of a causal sequence has a single term):
+    # a sizeable eps keeps the case well conditioned; the point here is the interface
+    eps = 0.5
+    # the definition, from the float32 features' own inner products
+    A = np.einsum("bhic,bhjc->bhij", FQ.astype(np.float64), FK.astype(np.float64))
+    np.testing.assert_allclose(A, np.einsum("bhid,bhjd->bhij", xq, xk) ** 2, rtol=2e-5, atol=2e-5)
+    Ac = np.tril(A)
+    ref_c = (Ac @ V) / (Ac.sum(-1, keepdims=True) + eps)
+    ref_g = (A @ V) / (A.sum(-1, keepdims=True) + eps)
+    np.testing.assert_allclose(o.causal_fwd_prefix(FQ, FK, V, eps), ref_c, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(o.global_fwd_linear(FQ, FK, V, eps), ref_g, rtol=1e-9, atol=1e-11)
+    dq, dk, dv, dg = (to_dev(x) for x in (FQ, FK, V, G))
+    O = torch.empty_like(dv); den = torch.empty(B, H, N, device=DEV)
+    ws = la.la_causal_fwd(dq, dk, dv, O, den, eps, features=True)
+    gq, gk, gv = (torch.empty_like(x) for x in (dq, dk, dv))
+    la.la_causal_bwd(dq, dk, dv, None, den, dg, gq, gk, gv, eps, fwd_ws=ws, features=True)
+    Og = torch.empty_like(dv); deng = torch.empty(B, H, N, device=DEV)
+    wsg = la.la_global_fwd(dq, dk, dv, Og, eps, den=deng, features=True)
+    hq, hk, hv = (torch.empty_like(x) for x in (dq, dk, dv))
+    la.la_global_bwd(dq, dk, dv, None, deng, dg, hq, hk, hv, eps, fwd_ws=wsg, features=True)
+    torch.cuda.synchronize()
+    tol = tol_for(N)
+    assert rel_err(to_host(O), ref_c) <= tol and rel_err(to_host(Og), ref_g) <= tol
+    assert max(grad_errs([to_host(x) for x in (gq, gk, gv)], o.causal_bwd_linear(FQ, FK, V, G, eps))) <= tol
+    assert max(grad_errs([to_host(x) for x in (hq, hk, hv)], o.global_bwd_linear(FQ, FK, V, G, eps))) <= tol
+
+
 def test_caller_supplied_features_decode_and_bf16(la, oracle_features):
     o = oracle_features
     B, H, T, D, M = 3, 2, 25, 64, 64
