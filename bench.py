@@ -99,6 +99,12 @@ class FwdBwd:
         self.la.la_causal_fwd(self.Q, self.K, self.V, self.O, self.den, self.w.eps, ws=self.ws_f)
 
 
+# The GPU needs some tens of milliseconds of back-to-back work to settle its clocks: the first
+# 20 steps after a pause run ~7 % slower than the following ones.  Hence the default warm-up of the
+# headline run (--warmup 50) and of every row of the table.
+TABLE_WARMUP = 30
+
+
 def time_steps(fn, steps, warmup, torch):
     for _ in range(warmup):
         fn()
@@ -221,8 +227,8 @@ def run_table(args):
 
     def fwdbwd_row(w, bf16=False, steps=20):
         fb = FwdBwd(w, bf16)
-        sec = time_steps(fb.step, steps, 5, torch)
-        secf = time_steps(fb.fwd_only, steps, 5, torch)
+        sec = time_steps(fb.step, steps, TABLE_WARMUP, torch)
+        secf = time_steps(fb.fwd_only, steps, TABLE_WARMUP, torch)
         prof = profile_kernels(la, fb.step, 3, torch)
         e = 2 if bf16 else 4
         ceiling = HBM_PEAK_GBS * 1e9 / (w.H * e * (6 * w.D + 6 * w.M)) / 1e6
@@ -248,7 +254,7 @@ def run_table(args):
         # the non-causal forward on the same tensors
         ws = torch.empty(la.la_global_fwd_workspace(w.B, w.H, w.N, w.D, w.M), dtype=torch.uint8,
                          device="cuda:0")
-        sec = time_steps(lambda: la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws), 20, 5, torch)
+        sec = time_steps(lambda: la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws), 20, TABLE_WARMUP, torch)
         rows.append({"workload": w.name + "_global_fwd", "tokens": w.B * w.N, "fwd_ms": sec * 1e3,
                      "fwd_mtok_s": w.B * w.N / sec / 1e6,
                      "hbm_ceiling_mtok_s": HBM_PEAK_GBS * 1e9 / (w.H * 4 * (2 * w.D + 2 * w.M)) / 1e6})
@@ -262,7 +268,7 @@ def run_table(args):
             la.la_global_fwd(fb.Q, fb.K, fb.V, fb.O, w.eps, ws=ws, den=deng)
             la.la_global_bwd(fb.Q, fb.K, fb.V, fb.O, deng, fb.G, fb.dQ, fb.dK, fb.dV, w.eps, ws=wsb,
                              fwd_ws=ws)
-        sec = time_steps(global_step, 20, 5, torch)
+        sec = time_steps(global_step, 20, TABLE_WARMUP, torch)
         prof = profile_kernels(la, global_step, 3, torch)
         rows.append({"workload": w.name + "_global_fwd_bwd", "tokens": w.B * w.N,
                      "fwd_bwd_ms": sec * 1e3, "fwd_bwd_mtok_s": w.B * w.N / sec / 1e6,
@@ -336,8 +342,8 @@ def run_table(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=65536)
     ap.add_argument("--table", metavar="PATH", default=None,
