@@ -1,6 +1,7 @@
-// Chunked causal products on the matrix units.  fp32-accurate products run on the fp32 MFMA or,
-// where one operand quad feeds several products, on the bf16 MFMA with exactly split operands
-// (split3 in la_device.h); the forward passes of bf16 tensors use plain bf16 products.
+// Chunked causal products on the matrix units.  For fp32 tensors the products run on the fp32
+// MFMA or, where one operand quad feeds several products, on the bf16 MFMA with exactly split
+// operands (split3 in la_device.h).  For bf16 tensors the forward passes use plain bf16 products
+// and the backward passes (and the segment sums they start from) 16-bit operands in two parts.
 // The forward runs one wavefront per (sequence, segment); the two kernels of the backward run
 // two wavefronts per (sequence, segment) that share one fetch of the inputs.
 //
@@ -107,12 +108,13 @@ __device__ __forceinline__ float map_value(float v, float scale) {
     return v;
 }
 
-// Which passes of a bf16 call run their tile products on the bf16 MFMA: the forward ones
-// (kFwd, kGlobal and the K, V segment sums).  The backward passes keep fp32-accurate products
-// on the widened values (fp32 MFMA and split operands, as for fp32 tensors): their results are differences of nearly equal terms (dphi(Q)_a = A_a +
-// delta_a z_a vanishes for constant V; R v + rho likewise), and with features phi(x) = 1 + x + ...
-// of small x the 8-bit mantissa of the operands would cost up to 1.5e-2 of the gradient's scale
-// (measured on inputs scaled by 1/8; worse for smaller inputs), too close to the 2e-2 gate.
+// Which passes of a bf16 call run their tile products as plain bf16 products (operands rounded
+// to 8 significant bits): the forward ones, kFwd and kGlobal.  The backward passes carry every
+// operand to 16 bits (two bf16 parts, see run_pass): their results are differences of nearly equal
+// terms (dphi(Q)_a = A_a + delta_a z_a vanishes for constant V; R v + rho likewise), and with
+// features phi(x) = 1 + x + ... of small x an 8-bit mantissa of the operands would cost up to
+// 1.5e-2 of the gradient's scale (measured on inputs scaled by 1/8; worse for smaller inputs),
+// too close to the 2e-2 gate.
 template <int PASS, typename T>
 constexpr bool bf16_products = is_bf16<T> && (PASS == kFwd || PASS == kGlobal);
 
