@@ -67,7 +67,7 @@ def kernel_flops(name: str, D: int, M: int) -> float:
 class FwdBwd:
     """Device buffers and the step function for one workload."""
 
-    def __init__(self, w, bf16=False):
+    def __init__(self, w, bf16=False, token_major=False):
         import torch
 
         import paper_2006_16236_amd as la
@@ -80,6 +80,10 @@ class FwdBwd:
         self.host = host
         dt = torch.bfloat16 if bf16 else torch.float32
         self.Q, self.K, self.V, self.G = (torch.from_numpy(x).to(dev).to(dt) for x in host)
+        self.token_major = token_major
+        if token_major:      # [B, H, N, .] -> [B, N, H, .], the entry points for that layout
+            self.Q, self.K, self.V, self.G = (x.transpose(1, 2).contiguous()
+                                              for x in (self.Q, self.K, self.V, self.G))
         self.O = torch.empty_like(self.V)
         self.den = torch.empty(w.B, w.H, w.N, dtype=torch.float32, device=dev)
         self.dQ, self.dK, self.dV = (torch.empty_like(x) for x in (self.Q, self.K, self.V))
@@ -91,12 +95,15 @@ class FwdBwd:
 
     def step(self):
         la, w = self.la, self.w
-        la.la_causal_fwd(self.Q, self.K, self.V, self.O, self.den, w.eps, ws=self.ws_f)
-        la.la_causal_bwd(self.Q, self.K, self.V, self.O, self.den, self.G, self.dQ, self.dK,
-                         self.dV, w.eps, ws=self.ws_b, fwd_ws=self.ws_f)
+        fwd = la.la_causal_fwd_bnhd if self.token_major else la.la_causal_fwd
+        bwd = la.la_causal_bwd_bnhd if self.token_major else la.la_causal_bwd
+        fwd(self.Q, self.K, self.V, self.O, self.den, w.eps, ws=self.ws_f)
+        bwd(self.Q, self.K, self.V, self.O, self.den, self.G, self.dQ, self.dK,
+            self.dV, w.eps, ws=self.ws_b, fwd_ws=self.ws_f)
 
     def fwd_only(self):
-        self.la.la_causal_fwd(self.Q, self.K, self.V, self.O, self.den, self.w.eps, ws=self.ws_f)
+        fwd = self.la.la_causal_fwd_bnhd if self.token_major else self.la.la_causal_fwd
+        fwd(self.Q, self.K, self.V, self.O, self.den, self.w.eps, ws=self.ws_f)
 
 
 # The GPU needs some tens of milliseconds of back-to-back work to settle its clocks: the first
@@ -225,19 +232,20 @@ def run_table(args):
     import workloads as wl
     rows = []
 
-    def fwdbwd_row(w, bf16=False, steps=20):
-        fb = FwdBwd(w, bf16)
+    def fwdbwd_row(w, bf16=False, steps=20, token_major=False):
+        fb = FwdBwd(w, bf16, token_major)
         sec = time_steps(fb.step, steps, TABLE_WARMUP, torch)
         secf = time_steps(fb.fwd_only, steps, TABLE_WARMUP, torch)
         prof = profile_kernels(la, fb.step, 3, torch)
         e = 2 if bf16 else 4
         ceiling = HBM_PEAK_GBS * 1e9 / (w.H * e * (6 * w.D + 6 * w.M)) / 1e6
-        rows.append({"workload": w.name + ("_bf16" if bf16 else ""), "tokens": w.B * w.N,
+        rows.append({"workload": w.name + ("_bf16" if bf16 else "") + ("_layout_BNHD" if token_major else ""),
+                     "tokens": w.B * w.N,
                      "fwd_bwd_ms": sec * 1e3, "fwd_ms": secf * 1e3,
                      "fwd_bwd_mtok_s": w.B * w.N / sec / 1e6, "fwd_mtok_s": w.B * w.N / secf / 1e6,
                      "hbm_ceiling_mtok_s": ceiling, "frac": w.B * w.N / sec / 1e6 / ceiling,
                      "kernels_ms": {k: round(ms * n, 4) for k, (ms, n) in prof.items()}})
-        if not args.no_cpu_baseline:      # the oracle on the same inputs, beside it
+        if not args.no_cpu_baseline and not token_major:      # the oracle on the same inputs, beside it
             cb = cpu_baseline(w, fb.host, w.N)
             rows[-1]["oracle_mtok_s"] = cb["value"]
             rows[-1]["oracle_cores"] = cb["cores"]
@@ -248,6 +256,8 @@ def run_table(args):
         fwdbwd_row(w, steps=200)
     fwdbwd_row(wl.CFG3, bf16=True, steps=200)
     fwdbwd_row(wl.sweep_point(16), bf16=True)
+    fwdbwd_row(wl.sweep_point(16), token_major=True)
+    fwdbwd_row(wl.sweep_point(16), bf16=True, token_major=True)
     for n in range(9, 17):
         w = wl.sweep_point(n)
         fb = fwdbwd_row(w)

@@ -170,6 +170,25 @@ int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float
                         float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * la_causal_fwd and la_causal_bwd on tensors laid out [B,N,H,.] (token-major, the heads of a
+ * token side by side: what a fused projection x W_Q of eq. 1 / eq. 20 produces and what the
+ * output projection consumes), so that a model need not transpose Q, K, V, O and their
+ * gradients into [B,H,N,.] and back.  Q, K, dQ, dK [B,N,H,D]; V, O, dO, dV [B,N,H,M].  The
+ * per-token scalars keep their layout: den [B,H,N] fp32.  Everything else (meaning of the
+ * arguments, workspace sizes and queries, fwd_ws, O not read, errors) as for la_causal_fwd /
+ * la_causal_bwd; a forward and its backward must use the same layout.  A row of one head is
+ * D (or M) contiguous elements, rows of a sequence are H * D elements apart: the kernels
+ * fetch the same 16-token tiles as 16 such rows.
+ */
+int la_causal_fwd_bnhd(const void *Q, const void *K, const void *V, void *O, float *den,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream);
+int la_causal_bwd_bnhd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                       const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Non-causal linear attention, forward (eq. 5-6): the sums over all N keys are
  * formed once and reused for every query,
  *   O_i = phi(Q_i)^T (sum_j phi(K_j) V_j^T) / (phi(Q_i) . sum_j phi(K_j) + eps).

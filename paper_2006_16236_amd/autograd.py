@@ -15,21 +15,27 @@ from . import binding as _b
 
 class _CausalLinearAttention(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, Q, K, V, eps):
+    def forward(ctx, Q, K, V, eps, token_major):
         Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
         O = torch.empty_like(V)
-        den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
-        ws = _b.la_causal_fwd(Q, K, V, O, den, eps)
+        if token_major:     # [B, N, H, .]
+            B, N, H = Q.shape[:3]
+            den = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+            ws = _b.la_causal_fwd_bnhd(Q, K, V, O, den, eps)
+        else:
+            den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
+            ws = _b.la_causal_fwd(Q, K, V, O, den, eps)
         ctx.save_for_backward(Q, K, V, den, ws)
-        ctx.eps = eps
+        ctx.eps, ctx.token_major = eps, token_major
         return O
 
     @staticmethod
     def backward(ctx, dO):
         Q, K, V, den, ws = ctx.saved_tensors
         dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
-        _b.la_causal_bwd(Q, K, V, None, den, dO.contiguous(), dQ, dK, dV, ctx.eps, fwd_ws=ws)
-        return dQ, dK, dV, None
+        bwd = _b.la_causal_bwd_bnhd if ctx.token_major else _b.la_causal_bwd
+        bwd(Q, K, V, None, den, dO.contiguous(), dQ, dK, dV, ctx.eps, fwd_ws=ws)
+        return dQ, dK, dV, None, None
 
 
 class _LinearAttention(torch.autograd.Function):
@@ -51,10 +57,13 @@ class _LinearAttention(torch.autograd.Function):
         return dQ, dK, dV, None
 
 
-def causal_linear_attention(Q, K, V, eps: float = 1e-6):
+def causal_linear_attention(Q, K, V, eps: float = 1e-6, layout: str = "bhnd"):
     """Causal linear attention (eq. 9-12) of Q, K [B, H, N, D], V [B, H, N, M] with
-    phi(x) = elu(x) + 1; differentiable with respect to Q, K, V."""
-    return _CausalLinearAttention.apply(Q, K, V, float(eps))
+    phi(x) = elu(x) + 1; differentiable with respect to Q, K, V.  layout="bnhd": the tensors
+    (and the result) are [B, N, H, .], as a fused projection produces them; nothing is transposed."""
+    if layout not in ("bhnd", "bnhd"):
+        raise ValueError("layout must be 'bhnd' or 'bnhd'")
+    return _CausalLinearAttention.apply(Q, K, V, float(eps), layout == "bnhd")
 
 
 def linear_attention(Q, K, V, eps: float = 1e-6):

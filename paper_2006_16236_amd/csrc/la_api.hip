@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kVersion = 300;   // 0.3.0
+constexpr int kVersion = 310;   // 0.3.1
 
 // ---- schedule ---------------------------------------------------------------------------------
 // One wavefront (forward) or one two-wave workgroup (backward) walks one segment of one
@@ -153,19 +153,22 @@ struct ProfScope {
     } while (0)
 
 // forward on already-validated arguments; `states` holds states_bytes() when p.nseg > 1
+// heads / tok_heads: the layout of the [., N, .] tensors (see la::PassArgs); 0, 0 = [B, H, N, .]
 int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den, long BH, int N,
                    int D, int M, float eps, la_dtype t, const Plan &p, float *states,
                    hipStream_t s, const float *S0 = nullptr, const float *z0 = nullptr,
-                   float *S1 = nullptr, float *z1 = nullptr) {
+                   float *S1 = nullptr, float *z1 = nullptr, int heads = 0, int tok_heads = 0) {
     const int nblocks = (int)(BH * p.nseg);
     if (p.nseg > 1) {
         la::SegArgs sa{};
         sa.Y = K; sa.Z = V; sa.state = states;
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = p.nseg - 1;
+        sa.heads = heads; sa.tok_heads = tok_heads;
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
     la::PassArgs a{};
+    a.heads = heads; a.tok_heads = tok_heads;
     a.Q = Q; a.K = K; a.V = V; a.G = nullptr; a.rden = nullptr; a.delta = nullptr;
     a.out = O; a.den = den; a.state = p.nseg > 1 ? states : nullptr;
     a.init_S = S0; a.init_z = z0; a.final_S = S1; a.final_z = z1;
@@ -245,9 +248,9 @@ size_t la_global_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     return bytes;
 }
 
-int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
-                  int B, int H, int N, int D, int M, float eps, la_dtype t,
-                  void *ws, size_t ws_bytes, void *stream) {
+static int causal_fwd_impl(const void *Q, const void *K, const void *V, void *O, float *den,
+                           int B, int H, int N, int D, int M, float eps, la_dtype t,
+                           void *ws, size_t ws_bytes, void *stream, int tok_heads) {
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
@@ -262,7 +265,21 @@ int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *d
     const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e}};
     if (aliased(outs, ins)) return LA_ERR_ALIAS;
     return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
-                          static_cast<hipStream_t>(stream));
+                          static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, nullptr, H,
+                          tok_heads);
+}
+
+int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream) {
+    return causal_fwd_impl(Q, K, V, O, den, B, H, N, D, M, eps, t, ws, ws_bytes, stream, 0);
+}
+
+int la_causal_fwd_bnhd(const void *Q, const void *K, const void *V, void *O, float *den,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream) {
+    return causal_fwd_impl(Q, K, V, O, den, B, H, N, D, M, eps, t, ws, ws_bytes, stream,
+                           H > 1 ? H : 0);
 }
 
 int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float *S0,
@@ -294,7 +311,8 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
                            const float *z0, const void *O, const float *den, const void *fwd_ws,
                            const void *dO, const float *dS1, const float *dz1, void *dQ, void *dK,
                            void *dV, float *dS0, float *dz0, int B, int H, int N, int D, int M,
-                           float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream) {
+                           float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream,
+                           int tok_heads = 0) {
     if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr ||
         dK == nullptr || dV == nullptr)
         return LA_ERR_NULL;
@@ -341,7 +359,8 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     if (recompute_fwd) {                       // recompute the forward's denominators
         void *Otmp = cv.take(rows * M * esize(t));
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
-        const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s, S0, z0);
+        const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s, S0, z0,
+                                      nullptr, nullptr, H, tok_heads);
         if (fs != LA_OK) return fs;
         den = dentmp;
     }
@@ -351,6 +370,7 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps;
         sa.Y = K; sa.Z = V; sa.state = stS;
         sa.skip_seg = p.nseg - 1;
+        sa.heads = H; sa.tok_heads = tok_heads;
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
@@ -366,6 +386,7 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     // forward direction: dQ; on the way 1/den and delta per token and, when the sequences
     // are cut, the per-segment sums that the reverse direction starts from
     la::PassArgs a{};
+    a.heads = H; a.tok_heads = tok_heads;
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
     a.den_in = den; a.rden_out = rden; a.delta_out = delta; a.totals = pb.nseg > 1 ? stR : nullptr;
     a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
@@ -387,6 +408,15 @@ int la_causal_bwd(const void *Q, const void *K, const void *V, const void *O, co
                   void *ws, size_t ws_bytes, void *stream) {
     return causal_bwd_impl(Q, K, V, nullptr, nullptr, O, den, fwd_ws, dO, nullptr, nullptr, dQ, dK,
                            dV, nullptr, nullptr, B, H, N, D, M, eps, t, ws, ws_bytes, stream);
+}
+
+int la_causal_bwd_bnhd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                       const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream) {
+    return causal_bwd_impl(Q, K, V, nullptr, nullptr, O, den, fwd_ws, dO, nullptr, nullptr, dQ, dK,
+                           dV, nullptr, nullptr, B, H, N, D, M, eps, t, ws, ws_bytes, stream,
+                           H > 1 ? H : 0);
 }
 
 int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float *S0,

@@ -296,17 +296,19 @@ __device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB<2> &b, f32
 template <int F> __device__ __forceinline__ int stage_row(int lane, int i) { return (4 * (lane + 64 * i)) / F; }
 template <int F> __device__ __forceinline__ int stage_col(int lane, int i) { return (4 * (lane + 64 * i)) % F; }
 
-// kFull: all 16 rows exist (the common case): one lane offset for the whole kernel plus an
-// immediate per load, no clamping.
+// kFull: all 16 rows exist (the common case): no clamping.  `ts` is the distance between
+// consecutive tokens in elements: F when the sequence is contiguous ([B, H, N, F] tensors, the
+// tile is then one run of 16 * F elements), H * F for [B, N, H, F] tensors.
 template <int F, bool kFull, typename T>
-__device__ __forceinline__ void stage_load(const T *base, int nvalid, int lane, f32x4 (&st)[F / 16]) {
+__device__ __forceinline__ void stage_load(const T *base, int ts, int nvalid, int lane, f32x4 (&st)[F / 16]) {
+    const T *lane_base = base + (size_t)stage_row<F>(lane, 0) * ts + stage_col<F>(lane, 0);
 #pragma unroll
     for (int i = 0; i < F / 16; ++i) {
         if constexpr (kFull) {
-            st[i] = load4(base + 4 * lane + 256 * i);
+            st[i] = load4(lane_base + (size_t)(i * (256 / F)) * ts);
         } else {
             const int row = min(stage_row<F>(lane, i), nvalid - 1);
-            st[i] = load4(base + (size_t)row * F + stage_col<F>(lane, i));
+            st[i] = load4(base + (size_t)row * ts + stage_col<F>(lane, i));
         }
     }
 }

@@ -5,8 +5,10 @@ namespace la {
 
 hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs &a, int nblocks,
                            hipStream_t s) {
+    if (a.tok_heads > 1 && global) return hipErrorInvalidValue;     // [B, N, H, .] is causal-only
     LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
         if (global) causal_pass_kernel<kGlobal, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
+        else if (a.tok_heads > 1) causal_pass_kernel<kFwd, kD, kM, TT, true><<<nblocks, kWave, 0, s>>>(a);
         else causal_pass_kernel<kFwd, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
     }));
     return hipGetLastError();
@@ -15,7 +17,8 @@ hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs 
 hipError_t launch_segment_state(int D, int M, int dtype, const SegArgs &a, int nblocks,
                                 hipStream_t s) {
     LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
-        segment_state_kernel<kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
+        if (a.tok_heads > 1) segment_state_kernel<kD, kM, TT, true><<<nblocks, kWave, 0, s>>>(a);
+        else segment_state_kernel<kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
     }));
     return hipGetLastError();
 }

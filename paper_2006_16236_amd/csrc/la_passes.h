@@ -95,7 +95,27 @@ struct PassArgs {
     float *final_S, *final_z;      // same shapes; may be null
     int N, nseg, chunks_per_seg;
     float eps;
+    // Layout of the [., N, .] tensors (Q, K, V, dO and the outputs; not the [BH, N] scalars):
+    // tok_heads <= 1: [B, H, N, F], every sequence contiguous (kernels with kStrided = false);
+    // tok_heads = H = heads: [B, N, H, F], consecutive tokens of a sequence H * F elements
+    // apart (kernels with kStrided = true).
+    int heads, tok_heads;
 };
+
+// element offset of token 0 of sequence bh in a tensor of row width F, and the distance
+// between consecutive tokens, for the two layouts
+// (kStrided is a template parameter of the kernels: the contiguous layout keeps compile-time
+// strides, which matters for the instruction-bound bf16 kernels)
+template <bool kStrided>
+__device__ __forceinline__ size_t seq_base(int N, int heads, int bh, int F) {
+    if constexpr (!kStrided) return (size_t)bh * N * F;
+    else return ((size_t)(bh / heads) * N * heads + (size_t)(bh % heads)) * F;
+}
+template <bool kStrided>
+__device__ __forceinline__ int tok_stride(int tok_heads, int F) {
+    if constexpr (!kStrided) return F;
+    else return tok_heads * F;
+}
 
 enum Map { kMapId = 0, kMapPhi = 1, kMapDphi = 2, kMapScale = 3, kMapOne = 4 };
 
@@ -156,8 +176,9 @@ struct PassTraits {
 
 // Staging of a pass run by one wave on its own (kFwd and the read-out-only passes kGlobal,
 // kGlobalDv, kGlobalDk): the wave fetches and parks all its tiles.
-template <int PASS, int D, int M, typename T>
+template <int PASS, int D, int M, typename T, bool kStrided = false>
 struct PassStager {
+    static constexpr bool kStridedLayout = kStrided;
     using Tr = PassTraits<PASS, D, M>;
     static_assert(PASS == kFwd || PASS == kGlobal || PASS == kGlobalDv || PASS == kGlobalDk,
                   "the other passes have stagers of their own");
@@ -165,18 +186,22 @@ struct PassStager {
     const T *Xs, *Ys, *Zs, *Rs;
     float *lds_x, *lds_y, *lds_z, *lds_r;
     int N, lane;
+    int tsx, tsz;                       // token strides of the DX-wide and DZ-wide tensors
     f32x4 sx[XT], sy[XT], sz[ZT], sr[ZT];
     float onex[XT], onez[ZT];
     float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
 
-    __device__ __forceinline__ PassStager(const PassArgs &a, size_t rowbase, int lane_, float *lx,
+    __device__ __forceinline__ PassStager(const PassArgs &a, int bh, int lane_, float *lx,
                                           float *ly, float *lz, float *lr)
-        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_) {
+        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_),
+          tsx(tok_stride<kStrided>(a.tok_heads, DX)), tsz(tok_stride<kStrided>(a.tok_heads, DZ)) {
         constexpr int BP = Tr::BP;
-        Xs = static_cast<const T *>(BP == kFwd ? a.Q : BP == kDv ? a.K : a.V) + rowbase * DX;
-        Ys = static_cast<const T *>(a.K) + rowbase * DX;      // kFwd
-        Zs = static_cast<const T *>(a.V) + rowbase * DZ;      // kFwd
-        Rs = static_cast<const T *>(a.K) + rowbase * DZ;      // kGlobalDk
+        const size_t bx = seq_base<kStrided>(a.N, a.heads, bh, DX);
+        const size_t bz = seq_base<kStrided>(a.N, a.heads, bh, DZ);
+        Xs = static_cast<const T *>(BP == kFwd ? a.Q : BP == kDv ? a.K : a.V) + bx;
+        Ys = static_cast<const T *>(a.K) + bx;      // kFwd
+        Zs = static_cast<const T *>(a.V) + bz;      // kFwd
+        Rs = static_cast<const T *>(a.K) + bz;      // kGlobalDk
         dl1 = 0.f;
 #pragma unroll
         for (int s = 0; s < 4; ++s) dl4[s] = 0.f;
@@ -190,12 +215,12 @@ struct PassStager {
 
     template <bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        stage_load<DX, kFull>(Xs + (size_t)t0 * DX, nvalid, lane, sx);
+        stage_load<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx);
         if constexpr (Tr::kHasYZ) {
-            stage_load<DX, kFull>(Ys + (size_t)t0 * DX, nvalid, lane, sy);
-            stage_load<DZ, kFull>(Zs + (size_t)t0 * DZ, nvalid, lane, sz);
+            stage_load<DX, kFull>(Ys + (size_t)t0 * tsx, tsx, nvalid, lane, sy);
+            stage_load<DZ, kFull>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
         }
-        if constexpr (Tr::kHasRaw) stage_load<DZ, kFull>(Rs + (size_t)t0 * DZ, nvalid, lane, sr);
+        if constexpr (Tr::kHasRaw) stage_load<DZ, kFull>(Rs + (size_t)t0 * tsz, tsz, nvalid, lane, sr);
     }
 
     template <int SLOT>
@@ -226,24 +251,28 @@ struct PassStager {
 // Staging of the two reverse passes run side by side by the two waves of one workgroup:
 // the four input tiles are fetched once and shared.  Wave 0 (the kDv role) brings Q and
 // dO, wave 1 (the kDk role) brings K (parked twice, as phi and as phi') and V.
-template <int ROLE, int D, int M, typename T>
+template <int ROLE, int D, int M, typename T, bool kStrided = false>
 struct ReverseStager {
+    static constexpr bool kStridedLayout = kStrided;
     static constexpr int DT = D / 16, MT = M / 16;
     static constexpr int kDepth = 1;    // chunks in flight = sets of staging registers (1 or 2)
     const T *As, *Bs;                   // role 0: Q, dO; role 1: K, V
     const float *rden, *delta;
     float *lds_a, *lds_a2, *lds_b;      // role 0: phi(Q), -, dO/den; role 1: phi(K), phi'(K), V
     int N, lane, g;
+    int tsd, tsm;                       // token strides of the D-wide and M-wide tensors
     f32x4 sa[kDepth][DT], sb[kDepth][MT];
     float scd[DT], scb[kDepth][MT];
     float n_dl4[kDepth][4];
     float dl1, dl4[4];
 
-    __device__ __forceinline__ ReverseStager(const PassArgs &a, size_t rowbase, int lane_, float *la,
+    __device__ __forceinline__ ReverseStager(const PassArgs &a, int bh, int lane_, float *la,
                                              float *la2, float *lb)
-        : lds_a(la), lds_a2(la2), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4) {
-        As = static_cast<const T *>(ROLE == 0 ? a.Q : a.K) + rowbase * D;
-        Bs = static_cast<const T *>(ROLE == 0 ? a.G : a.V) + rowbase * M;
+        : lds_a(la), lds_a2(la2), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4),
+          tsd(tok_stride<kStrided>(a.tok_heads, D)), tsm(tok_stride<kStrided>(a.tok_heads, M)) {
+        const size_t rowbase = (size_t)bh * a.N;
+        As = static_cast<const T *>(ROLE == 0 ? a.Q : a.K) + seq_base<kStrided>(a.N, a.heads, bh, D);
+        Bs = static_cast<const T *>(ROLE == 0 ? a.G : a.V) + seq_base<kStrided>(a.N, a.heads, bh, M);
         rden = a.rden + rowbase;
         delta = a.delta + rowbase;
         dl1 = 0.f;
@@ -262,8 +291,8 @@ struct ReverseStager {
 
     template <int SLOT, bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        stage_load<D, kFull>(As + (size_t)t0 * D, nvalid, lane, sa[SLOT]);
-        stage_load<M, kFull>(Bs + (size_t)t0 * M, nvalid, lane, sb[SLOT]);
+        stage_load<D, kFull>(As + (size_t)t0 * tsd, tsd, nvalid, lane, sa[SLOT]);
+        stage_load<M, kFull>(Bs + (size_t)t0 * tsm, tsm, nvalid, lane, sb[SLOT]);
         if constexpr (ROLE == 0) stage_rows<M, kFull>(rden + t0, nvalid, lane, scb[SLOT]);
         else rows4<kFull>(delta + t0, nvalid, g, n_dl4[SLOT]);
     }
@@ -340,7 +369,9 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
     const int count = ch_end - ch_begin;
     const size_t rowbase = (size_t)bh * a.N;
-    T *outs = static_cast<T *>(out_tensor) + rowbase * DZ;
+    constexpr bool kStrided = Stager::kStridedLayout;
+    const int tso = tok_stride<kStrided>(a.tok_heads, DZ);
+    T *outs = static_cast<T *>(out_tensor) + seq_base<kStrided>(a.N, a.heads, bh, DZ);
 
     // ---- carried state --------------------------------------------------------------------
     f32x4 U[XT][ZT];
@@ -677,19 +708,19 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 for (int r = 0; r < 4; ++r) out[zt][r] *= dp[zt][r];
         }
         // uniform chunk base + one lane offset; the 16 stores differ by constants only
-        T *lane_out = outs + (size_t)t0 * DZ + (4 * g * DZ + c);
+        T *lane_out = outs + (size_t)t0 * tso + (4 * g * tso + c);
         if (nvalid == kChunk) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) store_elem(lane_out + (r * DZ + 16 * zt), out[zt][r]);
+                for (int zt = 0; zt < ZT; ++zt) store_elem(lane_out + (r * tso + 16 * zt), out[zt][r]);
         } else {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 if (4 * g + r < nvalid) {
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt)
-                        store_elem(lane_out + (r * DZ + 16 * zt), out[zt][r]);
+                        store_elem(lane_out + (r * tso + 16 * zt), out[zt][r]);
                 }
         }
 
@@ -806,7 +837,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     }
 }
 
-template <int PASS, int D, int M, typename T>
+template <int PASS, int D, int M, typename T, bool kStrided = false>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void causal_pass_kernel(
     const PassArgs a) {
     using Tr = PassTraits<PASS, D, M>;
@@ -816,7 +847,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
     __shared__ float lds_r[Tr::kHasRaw ? tile_floats(Tr::DZ) : 4];
     const int lane = threadIdx.x;
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
-    PassStager<PASS, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_x, lds_y, lds_z, lds_r);
+    PassStager<PASS, D, M, T, kStrided> stg(a, bh, lane, lds_x, lds_y, lds_z, lds_r);
     run_pass<PASS, D, M, T>(a, stg, lds_x, lds_y, lds_z, lds_r, a.out, bh, seg, lane);
 }
 
@@ -824,7 +855,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
 // wave 0 produces dV (a.out), wave 1 produces dK (a.out2).  Wave 0 carries the reverse state R
 // (D x M) and republishes it in LDS before every chunk; wave 1, whose read-out needs R^T, reads
 // it from there transposed instead of keeping (and updating) a second copy.
-template <int D, int M, typename T>
+template <int D, int M, typename T, bool kStrided = false>
 __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void reverse_pass_kernel(
     const PassArgs a) {
     __shared__ float lds_fq[tile_floats(D)];    // phi(Q)
@@ -837,11 +868,11 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
-        ReverseStager<0, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fq, nullptr, lds_g);
+        ReverseStager<0, D, M, T, kStrided> stg(a, bh, lane, lds_fq, nullptr, lds_g);
         run_pass<kDv, D, M, T, kPublishState>(a, stg, lds_fk, lds_fq, lds_g, nullptr, a.out, bh, seg,
                                               lane, lds_R);
     } else {
-        ReverseStager<1, D, M, T> stg(a, (size_t)bh * a.N, lane, lds_fk, lds_dk, lds_v);
+        ReverseStager<1, D, M, T, kStrided> stg(a, bh, lane, lds_fk, lds_dk, lds_v);
         run_pass<kDk, D, M, T, kBorrowState>(a, stg, lds_v, lds_g, lds_fq, lds_dk, a.out2, bh, seg,
                                              lane, lds_R);
     }
@@ -851,26 +882,28 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 // brings dO (parked as dO/den, den being the forward's denominator) and V; wave 1 brings Q
 // and K, both parked as phi.  The non-causal pass (kCausal = false) has no in-chunk part and
 // no running sum: V and K are not needed.
-template <int ROLE, int D, int M, typename T, bool kCausal>
+template <int ROLE, int D, int M, typename T, bool kCausal, bool kStrided = false>
 struct DqStager {
+    static constexpr bool kStridedLayout = kStrided;
     static constexpr int F = ROLE == 0 ? M : D;
     static constexpr int FT = F / 16;
     static constexpr int kDepth = 1;
     const T *As, *Bs;                   // role 0: dO, V; role 1: Q, K
     const float *den;
     float *lds_a, *lds_b;               // role 0: dO/den, V; role 1: phi(Q), phi(K)
-    int N, lane, g;
+    int N, lane, g, ts;                 // ts: token stride of this role's tensors
     f32x4 sa[FT], sb[FT];
     float sca[FT], one[FT];
     float n_den4[4];
     float dl1, dl4[4];                  // unused by this pass (interface of run_pass)
     float rd4[4];                       // 1/den of tokens 4g + s of the parked chunk, 0 past the end
 
-    __device__ __forceinline__ DqStager(const PassArgs &a, size_t rowbase, int lane_, float *la,
+    __device__ __forceinline__ DqStager(const PassArgs &a, int bh, int lane_, float *la,
                                         float *lb)
-        : lds_a(la), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4) {
-        As = static_cast<const T *>(ROLE == 0 ? a.G : a.Q) + rowbase * F;
-        Bs = static_cast<const T *>(ROLE == 0 ? a.V : a.K) + rowbase * F;
+        : lds_a(la), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4), ts(tok_stride<kStrided>(a.tok_heads, F)) {
+        const size_t rowbase = (size_t)bh * a.N;
+        As = static_cast<const T *>(ROLE == 0 ? a.G : a.Q) + seq_base<kStrided>(a.N, a.heads, bh, F);
+        Bs = static_cast<const T *>(ROLE == 0 ? a.V : a.K) + seq_base<kStrided>(a.N, a.heads, bh, F);
         den = a.den_in + rowbase;
         dl1 = 0.f;
 #pragma unroll
@@ -881,8 +914,8 @@ struct DqStager {
 
     template <bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        stage_load<F, kFull>(As + (size_t)t0 * F, nvalid, lane, sa);
-        if constexpr (kCausal) stage_load<F, kFull>(Bs + (size_t)t0 * F, nvalid, lane, sb);
+        stage_load<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa);
+        if constexpr (kCausal) stage_load<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb);
         if constexpr (ROLE == 0) {
             stage_rows<F, kFull>(den + t0, nvalid, lane, sca);      // den of the staged rows
 #pragma unroll
@@ -1070,7 +1103,7 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
 // kCausal = false is the same step of the non-causal backward: the read-out is against the sum
 // over the whole sequence (a.state, slot 0), wave 0 keeps it in registers, and there is no
 // in-chunk part; only Q, dO and the denominators are read.
-template <int D, int M, typename T, bool kCausal>
+template <int D, int M, typename T, bool kCausal, bool kStrided = false>
 __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void dq_pass_kernel(
     const PassArgs a) {
     __shared__ float lds_g[tile_floats(M)];                       // dO / den
@@ -1082,7 +1115,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
-        DqStager<0, D, M, T, kCausal> stg(a, (size_t)bh * a.N, lane, lds_g, lds_v);
+        DqStager<0, D, M, T, kCausal, kStrided> stg(a, bh, lane, lds_g, lds_v);
         if constexpr (kCausal)
             run_pass<kDq, D, M, T, kBorrowState>(a, stg, lds_g, lds_v, lds_fk, lds_fq, a.out, bh,
                                                  seg, lane, lds_S);
@@ -1090,7 +1123,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             run_pass<kGlobalDq, D, M, T>(a, stg, lds_g, nullptr, nullptr, lds_fq, a.out, bh, seg,
                                          lane);
     } else {
-        DqStager<1, D, M, T, kCausal> stg(a, (size_t)bh * a.N, lane, lds_fq, lds_fk);
+        DqStager<1, D, M, T, kCausal, kStrided> stg(a, bh, lane, lds_fq, lds_fk);
         run_dq_sums<D, M, T, kCausal>(a, stg, lds_fk, lds_v, lds_fq, lds_g, lds_S, bh, seg, lane);
     }
 }
@@ -1105,9 +1138,10 @@ struct SegArgs {
     float *state;         // [BH, nseg, state_stride]
     int N, nseg, chunks_per_seg;
     int skip_seg;         // segment whose total nobody reads (-1: none)
+    int heads, tok_heads; // layout of K and V, as in PassArgs
 };
 
-template <int D, int M, typename T>
+template <int D, int M, typename T, bool kStrided = false>
 __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     constexpr int XT = D / 16, ZT = M / 16;
     // bf16 tensors: 16-bit operands (two parts), not plain bf16 products.  These sums also
@@ -1123,9 +1157,9 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     const int nchunks = (a.N + kChunk - 1) / kChunk;
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
-    const size_t rowbase = (size_t)bh * a.N;
-    const T *Ys = static_cast<const T *>(a.Y) + rowbase * D;
-    const T *Zs = static_cast<const T *>(a.Z) + rowbase * M;
+    const int tsy = tok_stride<kStrided>(a.tok_heads, D), tsz = tok_stride<kStrided>(a.tok_heads, M);
+    const T *Ys = static_cast<const T *>(a.Y) + seq_base<kStrided>(a.N, a.heads, bh, D);
+    const T *Zs = static_cast<const T *>(a.Z) + seq_base<kStrided>(a.N, a.heads, bh, M);
 
     f32x4 U[XT][ZT];
     float ec[XT];
@@ -1147,11 +1181,11 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
         if (nvalid == kChunk) {
-            stage_load<D, true>(Ys + (size_t)t0 * D, nvalid, lane, sy);
-            stage_load<M, true>(Zs + (size_t)t0 * M, nvalid, lane, sz);
+            stage_load<D, true>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
+            stage_load<M, true>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
         } else {
-            stage_load<D, false>(Ys + (size_t)t0 * D, nvalid, lane, sy);
-            stage_load<M, false>(Zs + (size_t)t0 * M, nvalid, lane, sz);
+            stage_load<D, false>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
+            stage_load<M, false>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
         }
     };
 

@@ -77,6 +77,15 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert fwd(p, p, p, p, null, 1, 1, 16, 64, 128, f(1e-6), 0, null, 0, null) == b.LA_ERR_UNSUPPORTED
     assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 7, null, 0, null) == b.LA_ERR_UNSUPPORTED
     assert fwd(p, odd, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_ALIGN
+    # the token-major entry points validate the same way
+    fwd_t, bwd_t = lib.la_causal_fwd_bnhd, lib.la_causal_bwd_bnhd
+    assert fwd_t(null, p, p, p, null, 1, 4, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_NULL
+    assert fwd_t(p, p, p, p, null, 1, 4, 16, 48, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd_t(p, p, odd, p, null, 1, 4, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_ALIGN
+    assert bwd_t(p, p, p, null, p, null, null, p, p, p, 1, 4, 16, 64, 64, f(1e-6), 0, p, 1 << 30,
+                 null) == b.LA_ERR_NULL
+    assert bwd_t(p, p, p, null, p, null, p, p, p, p, 1, 4, 16, 64, 64, f(1e-6), 0, null, 0,
+                 null) == b.LA_ERR_WORKSPACE
     # a long sequence needs a workspace
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, p, 1024, null) == b.LA_ERR_WORKSPACE

@@ -552,6 +552,66 @@ def test_random_shapes_all_entry_points(la, oracle, B, H, N, D, M, sched, eps, s
     assert max(grad_errs(gg, oracle.global_bwd_linear(Q, K, V, G, eps))) <= tol
 
 
+# ---- token-major tensors [B, N, H, .] --------------------------------------------------------
+
+def _token_major(x, bf16=False):
+    """[B, H, N, F] host array -> contiguous [B, N, H, F] device tensor."""
+    return to_dev(np.ascontiguousarray(np.transpose(x, (0, 2, 1, 3))), bf16)
+
+
+def _head_major(t):
+    return to_host(t).transpose(0, 2, 1, 3)
+
+
+@pytest.mark.parametrize("B,H,N,D,M,bf16,sched,reuse", [
+    (2, 3, 333, 64, 64, False, "default", "all"),
+    (1, 8, 1000, 64, 32, False, "many_segments", "den"),
+    (3, 2, 77, 32, 64, False, "three_chunk_segments", "none"),
+    (2, 5, 16, 32, 32, False, "one_segment", "all"),
+    (2, 1, 129, 64, 64, False, "default", "all"),
+    (2, 4, 500, 64, 64, True, "default", "all"),
+    (1, 6, 47, 32, 64, True, "many_segments", "den"),
+])
+def test_token_major_layout(la, oracle, B, H, N, D, M, bf16, sched, reuse):
+    """la_causal_fwd_bnhd / la_causal_bwd_bnhd on [B, N, H, .] tensors: against the oracle, and
+    bit for bit against the [B, H, N, .] entry points (same arithmetic, other addresses)."""
+    host = maybe_bf16(wl.random_case(8800 + N, B, H, N, D, M), bf16)
+    Q, K, V, G = host
+    eps = 1e-6
+    tq, tk, tv, tg = (_token_major(x, bf16) for x in host)
+    with schedule(**SCHEDULES[sched]):
+        O = torch.full_like(tv, float("nan"))
+        den = torch.full((B, H, N), float("nan"), dtype=torch.float32, device=DEV)
+        ws = la.la_causal_fwd_bnhd(tq, tk, tv, O, den, eps)
+        gq, gk, gv = (torch.full_like(x, float("nan")) for x in (tq, tk, tv))
+        la.la_causal_bwd_bnhd(tq, tk, tv, None, den if reuse != "none" else None, tg, gq, gk, gv, eps,
+                              fwd_ws=ws if reuse == "all" else None)
+        torch.cuda.synchronize()
+        O2, den2 = run_fwd(la, Q, K, V, eps, bf16=bf16)
+        g2 = run_bwd(la, Q, K, V, G, eps, bf16=bf16, reuse_fwd=reuse != "none",
+                     reuse_states=reuse == "all")
+    tol = tol_for(N, bf16)
+    ref, dref = oracle.causal_fwd_prefix(Q, K, V, eps, return_den=True)
+    assert rel_err(_head_major(O), ref) <= tol and rel_err(den.cpu().numpy(), dref) <= tol
+    got = [_head_major(x) for x in (gq, gk, gv)]
+    assert max(grad_errs(got, oracle.causal_bwd_linear(Q, K, V, G, eps))) <= tol
+    assert np.array_equal(_head_major(O), O2) and np.array_equal(den.cpu().numpy(), den2)
+    for a, b in zip(got, g2):
+        assert np.array_equal(a, b)
+
+
+def test_token_major_autograd(la, oracle):
+    B, H, N, D, M = 2, 4, 210, 64, 64
+    Q, K, V, G = wl.random_case(8899, B, H, N, D, M)
+    tq, tk, tv = (_token_major(x).requires_grad_() for x in (Q, K, V))
+    O = la.causal_linear_attention(tq, tk, tv, 1e-6, layout="bnhd")
+    O.backward(_token_major(G))
+    torch.cuda.synchronize()
+    assert rel_err(_head_major(O), oracle.causal_fwd_prefix(Q, K, V, 1e-6)) <= tol_for(N)
+    got = [_head_major(x.grad) for x in (tq, tk, tv)]
+    assert max(grad_errs(got, oracle.causal_bwd_linear(Q, K, V, G, 1e-6))) <= tol_for(N)
+
+
 # ---- Q and K as feature values of a map the caller applied ---------------------------------
 
 @pytest.fixture
