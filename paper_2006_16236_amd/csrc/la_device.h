@@ -276,6 +276,18 @@ __device__ __forceinline__ f32x4 mfma16_split(const SplitA<2> &a, const SplitB<2
     acc = mfma32_bf16(a.hm(), b.hh(), acc);    // hh + mh
     return acc;
 }
+// the same product with the sides exchanged: `x` (kept in side-B form) is the first operand of
+// the MFMA, `u` (kept in the narrower side-A form) the second
+__device__ __forceinline__ f32x4 mfma16_split_ba(const SplitB<3> &x, const SplitA<3> &u, f32x4 acc) {
+    acc = mfma32_bf16(x.hl(), u.lh(), acc);    // hl + lh
+    acc = mfma32_bf16(x.mh(), u.hm(), acc);    // mh + hm
+    acc = mfma32_bf16(x.hm(), u.hm(), acc);    // hh + mm
+    return acc;
+}
+template <int P> __device__ __forceinline__ SplitA<P> split_a(f32x4 x) {
+    const float q[4] = {x[0], x[1], x[2], x[3]};
+    return split_a<P>(q);
+}
 // acc + mask * b for a mask of zeros and ones (exact in bf16), four bf16 per lane in `mk`
 __device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB<3> &b, f32x4 acc) {
     acc = mfma32_bf16(cat_parts(mk, mk), b.hl(), acc);                  // mask (h + l)

@@ -443,6 +443,18 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         }
     }
 
+    // Read-out-only passes of fp32 tensors: U never changes, so it is cut into its three bf16
+    // parts once, here, and every chunk's read-out runs on the bf16 pipe (section on split3 in
+    // la_device.h); only the chunk's own operand is split per chunk.
+    constexpr bool kConstState = !kHasYZ && kSplit && !is_bf16<T>;
+    SplitA<3> us[XT][ZT];
+    if constexpr (kConstState) {
+#pragma unroll
+        for (int xt = 0; xt < XT; ++xt)
+#pragma unroll
+            for (int zt = 0; zt < ZT; ++zt) us[xt][zt] = split_a<3>(U[xt][zt]);
+    }
+
     // Chunks are visited in steps of `dir`; the stager keeps kDepth chunks in flight, each in
     // its own set of staging registers (the set is a compile-time index, hence the tag).
     constexpr int kDepth = Stager::kDepth;
@@ -513,6 +525,13 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt)
                     out[zt] = mfma16_bf16(xp[xt], pack_bf16x4(U[xt][zt]), out[zt]);
+            }
+        } else if constexpr (kConstState) {
+#pragma unroll
+            for (int xt = 0; xt < XT; ++xt) {
+                const SplitB<3> xs = split_b<3>(xa[xt]);
+#pragma unroll
+                for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16_split_ba(xs, us[xt][zt], out[zt]);
             }
         } else if constexpr (kSplitState) {
 #pragma unroll
