@@ -221,6 +221,19 @@ int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, co
                   void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * la_global_fwd and la_global_bwd on token-major tensors [B,N,H,.] (see la_causal_fwd_bnhd):
+ * Q, K, dQ, dK [B,N,H,D]; V, O, dO, dV [B,N,H,M]; den [B,H,N] fp32.  Everything else as for
+ * la_global_fwd / la_global_bwd.
+ */
+int la_global_fwd_bnhd(const void *Q, const void *K, const void *V, void *O, float *den,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream);
+int la_global_bwd_bnhd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                       const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream);
+
+/*
  * One recurrent decode step for B*H heads (eq. 16-20): update, then read.
  *   S <- S + phi(k) v^T,  z <- z + phi(k),  out = phi(q)^T S / (phi(q) . z + eps).
  * q, k [B,H,D] in; v [B,H,M] in; S [B,H,D,M] fp32 and z [B,H,D] fp32 in/out

@@ -40,21 +40,27 @@ class _CausalLinearAttention(torch.autograd.Function):
 
 class _LinearAttention(torch.autograd.Function):
     @staticmethod
-    def forward(ctx, Q, K, V, eps):
+    def forward(ctx, Q, K, V, eps, token_major):
         Q, K, V = Q.contiguous(), K.contiguous(), V.contiguous()
         O = torch.empty_like(V)
-        den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
-        ws = _b.la_global_fwd(Q, K, V, O, eps, den=den)
+        if token_major:     # [B, N, H, .]
+            B, N, H = Q.shape[:3]
+            den = torch.empty((B, H, N), dtype=torch.float32, device=Q.device)
+            ws = _b.la_global_fwd_bnhd(Q, K, V, O, eps, den=den)
+        else:
+            den = torch.empty(Q.shape[:-1], dtype=torch.float32, device=Q.device)
+            ws = _b.la_global_fwd(Q, K, V, O, eps, den=den)
         ctx.save_for_backward(Q, K, V, den, ws)
-        ctx.eps = eps
+        ctx.eps, ctx.token_major = eps, token_major
         return O
 
     @staticmethod
     def backward(ctx, dO):
         Q, K, V, den, ws = ctx.saved_tensors
         dQ, dK, dV = torch.empty_like(Q), torch.empty_like(K), torch.empty_like(V)
-        _b.la_global_bwd(Q, K, V, None, den, dO.contiguous(), dQ, dK, dV, ctx.eps, fwd_ws=ws)
-        return dQ, dK, dV, None
+        bwd = _b.la_global_bwd_bnhd if ctx.token_major else _b.la_global_bwd
+        bwd(Q, K, V, None, den, dO.contiguous(), dQ, dK, dV, ctx.eps, fwd_ws=ws)
+        return dQ, dK, dV, None, None
 
 
 def causal_linear_attention(Q, K, V, eps: float = 1e-6, layout: str = "bhnd"):
@@ -66,6 +72,9 @@ def causal_linear_attention(Q, K, V, eps: float = 1e-6, layout: str = "bhnd"):
     return _CausalLinearAttention.apply(Q, K, V, float(eps), layout == "bnhd")
 
 
-def linear_attention(Q, K, V, eps: float = 1e-6):
-    """Non-causal linear attention (eq. 4-6); differentiable with respect to Q, K, V."""
-    return _LinearAttention.apply(Q, K, V, float(eps))
+def linear_attention(Q, K, V, eps: float = 1e-6, layout: str = "bhnd"):
+    """Non-causal linear attention (eq. 4-6); differentiable with respect to Q, K, V.
+    layout as for causal_linear_attention."""
+    if layout not in ("bhnd", "bnhd"):
+        raise ValueError("layout must be 'bhnd' or 'bnhd'")
+    return _LinearAttention.apply(Q, K, V, float(eps), layout == "bnhd")

@@ -21,7 +21,7 @@ LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN, LA_ERR_ALIAS = -4, -5, -6, -7
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
            "la_global_fwd_workspace", "la_global_bwd_workspace", "la_causal_fwd", "la_causal_fwd_state",
            "la_causal_bwd", "la_causal_bwd_state", "la_causal_fwd_bnhd", "la_causal_bwd_bnhd",
-           "la_global_fwd", "la_global_bwd",
+           "la_global_fwd", "la_global_bwd", "la_global_fwd_bnhd", "la_global_bwd_bnhd",
            "la_recurrent_step", "la_recurrent_steps", "la_kernel_name", "la_profile_begin",
            "la_profile_end")
 LA_K_COUNT = 8
@@ -68,6 +68,10 @@ def _load() -> ctypes.CDLL:
     lib.la_global_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_global_bwd.restype = i
     lib.la_global_bwd.argtypes = [vp] * 10 + [i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_global_fwd_bnhd.restype = i
+    lib.la_global_fwd_bnhd.argtypes = lib.la_global_fwd.argtypes
+    lib.la_global_bwd_bnhd.restype = i
+    lib.la_global_bwd_bnhd.argtypes = lib.la_global_bwd.argtypes
     lib.la_recurrent_step.restype = i
     lib.la_recurrent_step.argtypes = [vp] * 6 + [i, i, i, i, f, i, vp]
     lib.la_recurrent_steps.restype = i
@@ -252,6 +256,31 @@ def la_global_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=Non
     _check(_lib.la_global_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
                               _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
                               wp, wb, _stream(stream)), "la_global_bwd")
+    return ws
+
+
+def la_global_fwd_bnhd(Q, K, V, O, eps=1e-6, ws=None, stream=None, den=None, features=False):
+    """la_global_fwd on token-major tensors: Q, K [B,N,H,D], V, O [B,N,H,M]; den stays [B,H,N]."""
+    B, N, H, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q, features)
+    ws, wp, wb = _ws(ws, la_global_fwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_global_fwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
+                                   float(eps), t, wp, wb, _stream(stream)), "la_global_fwd_bnhd")
+    return ws
+
+
+def la_global_bwd_bnhd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=None, fwd_ws=None,
+                       features=False):
+    """la_global_bwd on token-major tensors ([B,N,H,.]; den [B,H,N]); fwd_ws from
+    la_global_fwd_bnhd."""
+    B, N, H, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q, features)
+    ws, wp, wb = _ws(ws, la_global_bwd_workspace(B, H, N, D, M, t), Q.device)
+    _check(_lib.la_global_bwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
+                                   _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M,
+                                   float(eps), t, wp, wb, _stream(stream)), "la_global_bwd_bnhd")
     return ws
 
 

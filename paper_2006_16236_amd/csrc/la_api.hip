@@ -180,15 +180,17 @@ int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *
 // eq. 5-6: the K, V grand total (left in slot 0 of `states`), then the read-out
 int run_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den, long BH,
                    int N, int D, int M, float eps, la_dtype t, const Plan &p, float *states,
-                   hipStream_t s) {
+                   hipStream_t s, int heads = 0, int tok_heads = 0) {
     const int nblocks = (int)(BH * p.nseg);
     la::SegArgs sa{};
+    sa.heads = heads; sa.tok_heads = tok_heads;
     sa.Y = K; sa.Z = V; sa.state = states;
     sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
     { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
     if (p.nseg > 1)
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
     la::PassArgs a{};
+    a.heads = heads; a.tok_heads = tok_heads;
     a.Q = Q; a.K = K; a.V = V; a.out = O; a.den = den; a.state = states;
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
     { ProfScope ps(LA_K_GLOBAL, s); LA_TRY(la::launch_pass_fwd(true, D, M, (int)t, a, nblocks, s)); }
@@ -428,9 +430,9 @@ int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float
                            N, D, M, eps, t, ws, ws_bytes, stream);
 }
 
-int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
-                  int B, int H, int N, int D, int M, float eps, la_dtype t,
-                  void *ws, size_t ws_bytes, void *stream) {
+static int global_fwd_impl(const void *Q, const void *K, const void *V, void *O, float *den,
+                           int B, int H, int N, int D, int M, float eps, la_dtype t,
+                           void *ws, size_t ws_bytes, void *stream, int tok_heads) {
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
@@ -445,13 +447,26 @@ int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *d
     const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e}};
     if (aliased(outs, ins)) return LA_ERR_ALIAS;
     return run_global_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
-                          static_cast<hipStream_t>(stream));
+                          static_cast<hipStream_t>(stream), H, tok_heads);
 }
 
-int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
-                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
                   int B, int H, int N, int D, int M, float eps, la_dtype t,
                   void *ws, size_t ws_bytes, void *stream) {
+    return global_fwd_impl(Q, K, V, O, den, B, H, N, D, M, eps, t, ws, ws_bytes, stream, 0);
+}
+
+int la_global_fwd_bnhd(const void *Q, const void *K, const void *V, void *O, float *den,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream) {
+    return global_fwd_impl(Q, K, V, O, den, B, H, N, D, M, eps, t, ws, ws_bytes, stream,
+                           H > 1 ? H : 0);
+}
+
+static int global_bwd_impl(const void *Q, const void *K, const void *V, const void *O,
+                           const float *den, const void *fwd_ws, const void *dO, void *dQ,
+                           void *dK, void *dV, int B, int H, int N, int D, int M, float eps,
+                           la_dtype t, void *ws, size_t ws_bytes, void *stream, int tok_heads) {
     if (Q == nullptr || K == nullptr || V == nullptr || dO == nullptr || dQ == nullptr ||
         dK == nullptr || dV == nullptr)
         return LA_ERR_NULL;
@@ -483,13 +498,15 @@ int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, co
     if (den == nullptr) {                      // recompute the forward's denominators;
         void *Otmp = cv.take(rows * M * esize(t));     // also leaves the K, V total in slot 0 of stS
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
-        const int fs = run_global_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s);
+        const int fs = run_global_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s, H,
+                                      tok_heads);
         if (fs != LA_OK) return fs;
         den = dentmp;
     } else if (fwd_ws != nullptr) {            // the forward's workspace still holds that total
         stS = const_cast<float *>(static_cast<const float *>(fwd_ws));
     } else {
         la::SegArgs sa{};
+        sa.heads = H; sa.tok_heads = tok_heads;
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
         sa.Y = K; sa.Z = V; sa.state = stS;
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
@@ -504,6 +521,7 @@ int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, co
         pb.nseg = (p.nchunks + pb.cps - 1) / pb.cps;
     }
     la::PassArgs a{};
+    a.heads = H; a.tok_heads = tok_heads;
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.den_in = den; a.totals = stR;
     a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
     a.out = dQ; a.state = stS; a.state_nseg = p.nseg;
@@ -519,6 +537,22 @@ int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, co
     a.out = dK;
     LA_TRY(la::launch_pass_global_bwd(2, D, M, (int)t, a, nblocks, s));
     return LA_OK;
+}
+
+int la_global_bwd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                  const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+                  int B, int H, int N, int D, int M, float eps, la_dtype t,
+                  void *ws, size_t ws_bytes, void *stream) {
+    return global_bwd_impl(Q, K, V, O, den, fwd_ws, dO, dQ, dK, dV, B, H, N, D, M, eps, t, ws,
+                           ws_bytes, stream, 0);
+}
+
+int la_global_bwd_bnhd(const void *Q, const void *K, const void *V, const void *O, const float *den,
+                       const void *fwd_ws, const void *dO, void *dQ, void *dK, void *dV,
+                       int B, int H, int N, int D, int M, float eps, la_dtype t,
+                       void *ws, size_t ws_bytes, void *stream) {
+    return global_bwd_impl(Q, K, V, O, den, fwd_ws, dO, dQ, dK, dV, B, H, N, D, M, eps, t, ws,
+                           ws_bytes, stream, H > 1 ? H : 0);
 }
 
 int la_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z, void *out,

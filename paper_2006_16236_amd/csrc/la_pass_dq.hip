@@ -5,11 +5,14 @@ namespace la {
 
 hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &a, int nblocks,
                           hipStream_t s) {
-    if (a.tok_heads > 1 && !causal) return hipErrorInvalidValue;    // [B, N, H, .] is causal-only
     LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
-        if (!causal) dq_pass_kernel<kD, kM, TT, false><<<nblocks, 2 * kWave, 0, s>>>(a);
-        else if (a.tok_heads > 1) dq_pass_kernel<kD, kM, TT, true, true><<<nblocks, 2 * kWave, 0, s>>>(a);
-        else dq_pass_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+        if (a.tok_heads > 1) {
+            if (causal) dq_pass_kernel<kD, kM, TT, true, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+            else dq_pass_kernel<kD, kM, TT, false, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+        } else {
+            if (causal) dq_pass_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+            else dq_pass_kernel<kD, kM, TT, false><<<nblocks, 2 * kWave, 0, s>>>(a);
+        }
     }));
     return hipGetLastError();
 }

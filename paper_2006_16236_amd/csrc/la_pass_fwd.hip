@@ -5,11 +5,14 @@ namespace la {
 
 hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs &a, int nblocks,
                            hipStream_t s) {
-    if (a.tok_heads > 1 && global) return hipErrorInvalidValue;     // [B, N, H, .] is causal-only
     LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
-        if (global) causal_pass_kernel<kGlobal, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
-        else if (a.tok_heads > 1) causal_pass_kernel<kFwd, kD, kM, TT, true><<<nblocks, kWave, 0, s>>>(a);
-        else causal_pass_kernel<kFwd, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
+        if (a.tok_heads > 1) {
+            if (global) causal_pass_kernel<kGlobal, kD, kM, TT, true><<<nblocks, kWave, 0, s>>>(a);
+            else causal_pass_kernel<kFwd, kD, kM, TT, true><<<nblocks, kWave, 0, s>>>(a);
+        } else {
+            if (global) causal_pass_kernel<kGlobal, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
+            else causal_pass_kernel<kFwd, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
+        }
     }));
     return hipGetLastError();
 }

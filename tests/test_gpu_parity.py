@@ -600,6 +600,33 @@ def test_token_major_layout(la, oracle, B, H, N, D, M, bf16, sched, reuse):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("B,H,N,D,M,bf16,sched", [
+    (2, 3, 333, 64, 64, False, "default"),
+    (1, 8, 1000, 64, 32, False, "many_segments"),
+    (3, 2, 77, 32, 64, True, "one_segment"),
+])
+def test_token_major_layout_non_causal(la, oracle, B, H, N, D, M, bf16, sched):
+    host = maybe_bf16(wl.random_case(8700 + N, B, H, N, D, M), bf16)
+    Q, K, V, G = host
+    eps = 1e-6
+    tq, tk, tv, tg = (_token_major(x, bf16) for x in host)
+    with schedule(**SCHEDULES[sched]):
+        O = torch.full_like(tv, float("nan"))
+        den = torch.full((B, H, N), float("nan"), dtype=torch.float32, device=DEV)
+        ws = la.la_global_fwd_bnhd(tq, tk, tv, O, eps, den=den)
+        gq, gk, gv = (torch.full_like(x, float("nan")) for x in (tq, tk, tv))
+        la.la_global_bwd_bnhd(tq, tk, tv, None, den, tg, gq, gk, gv, eps, fwd_ws=ws)
+        torch.cuda.synchronize()
+        O2, den2, g2 = run_global(la, Q, K, V, G, eps, bf16=bf16)
+    tol = tol_for(N, bf16)
+    assert rel_err(_head_major(O), oracle.global_fwd_linear(Q, K, V, eps)) <= tol
+    got = [_head_major(x) for x in (gq, gk, gv)]
+    assert max(grad_errs(got, oracle.global_bwd_linear(Q, K, V, G, eps))) <= tol
+    assert np.array_equal(_head_major(O), O2) and np.array_equal(den.cpu().numpy(), den2)
+    for a, b in zip(got, g2):
+        assert np.array_equal(a, b)
+
+
 def test_token_major_autograd(la, oracle):
     B, H, N, D, M = 2, 4, 210, 64, 64
     Q, K, V, G = wl.random_case(8899, B, H, N, D, M)
@@ -610,6 +637,14 @@ def test_token_major_autograd(la, oracle):
     assert rel_err(_head_major(O), oracle.causal_fwd_prefix(Q, K, V, 1e-6)) <= tol_for(N)
     got = [_head_major(x.grad) for x in (tq, tk, tv)]
     assert max(grad_errs(got, oracle.causal_bwd_linear(Q, K, V, G, 1e-6))) <= tol_for(N)
+    for x in (tq, tk, tv):
+        x.grad = None
+    O = la.linear_attention(tq, tk, tv, 1e-6, layout="bnhd")
+    O.backward(_token_major(G))
+    torch.cuda.synchronize()
+    assert rel_err(_head_major(O), oracle.global_fwd_linear(Q, K, V, 1e-6)) <= tol_for(N)
+    got = [_head_major(x.grad) for x in (tq, tk, tv)]
+    assert max(grad_errs(got, oracle.global_bwd_linear(Q, K, V, G, 1e-6))) <= tol_for(N)
 
 
 # ---- Q and K as feature values of a map the caller applied ---------------------------------
