@@ -77,7 +77,8 @@ typedef enum {
     LA_ERR_WORKSPACE = -4,    /* ws is NULL or ws_bytes is smaller than the query   */
     LA_ERR_HIP = -5,          /* a HIP call or kernel launch failed                 */
     LA_ERR_ALIGN = -6,        /* a tensor pointer is not 16-byte aligned            */
-    LA_ERR_ALIAS = -7         /* a written buffer overlaps another buffer of the call */
+    LA_ERR_ALIAS = -7,        /* a written buffer overlaps another buffer of the call */
+    LA_ERR_SCRATCH = -8       /* la_causal_fwd_noalloc: the sizes need more than the built-in scratch */
 } la_status;
 
 /* Static, NUL-terminated description of a status code. */
@@ -111,6 +112,25 @@ size_t la_global_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
 int la_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
                   int B, int H, int N, int D, int M, float eps, la_dtype t,
                   void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * la_causal_fwd for callers that cannot allocate device memory or must not call anything that
+ * does: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, results (bit for bit) and schedule as la_causal_fwd, minus the workspace:
+ * the per-segment running sums live in an array of LA_NOALLOC_SCRATCH_BYTES that is part of
+ * the library's own device code (every GPU the library runs on holds one copy until the
+ * process ends).  The call itself allocates and frees nothing and calls no allocating routine;
+ * the first call on a device looks the array's address up (make that call outside a graph
+ * capture).  Sizes whose la_causal_fwd_workspace() exceeds LA_NOALLOC_SCRATCH_BYTES are refused
+ * with LA_ERR_SCRATCH before anything is launched (the metric's shape, B=2, H=8, N=65536,
+ * D=M=64, needs 32.5 MiB and fits).  All calls on one GPU share that GPU's array, which keeps
+ * whatever the last call left in it (nothing in it needs clearing: a call writes every slot
+ * before reading it): calls that overlap in time on one GPU, from any thread or stream, race;
+ * serialise them on one stream or with events.  The caller still owns Q, K, V, O, den.
+ */
+#define LA_NOALLOC_SCRATCH_BYTES ((size_t)40 << 20)
+int la_causal_fwd_noalloc(const void *Q, const void *K, const void *V, void *O, float *den,
+                          int B, int H, int N, int D, int M, float eps, la_dtype t, void *stream);
 
 /*
  * The same forward with the recurrent state handed in and out (eq. 16-19 seen from the

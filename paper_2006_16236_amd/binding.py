@@ -16,13 +16,14 @@ LIB_PATH = os.path.join(_HERE, "libla_hip.so")
 
 LA_F32, LA_BF16, LA_F32_FEATURES, LA_BF16_FEATURES = 0, 1, 2, 3
 LA_OK, LA_ERR_NULL, LA_ERR_SHAPE, LA_ERR_UNSUPPORTED = 0, -1, -2, -3
-LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN, LA_ERR_ALIAS = -4, -5, -6, -7
+LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN, LA_ERR_ALIAS, LA_ERR_SCRATCH = -4, -5, -6, -7, -8
+LA_NOALLOC_SCRATCH_BYTES = 40 << 20
 
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
            "la_global_fwd_workspace", "la_global_bwd_workspace", "la_causal_fwd", "la_causal_fwd_state",
            "la_causal_bwd", "la_causal_bwd_state", "la_causal_fwd_bnhd", "la_causal_bwd_bnhd",
            "la_global_fwd", "la_global_bwd", "la_global_fwd_bnhd", "la_global_bwd_bnhd",
-           "la_recurrent_step", "la_recurrent_steps", "la_kernel_name", "la_profile_begin",
+           "la_recurrent_step", "la_recurrent_steps", "la_causal_fwd_noalloc", "la_kernel_name", "la_profile_begin",
            "la_profile_end")
 LA_K_COUNT = 8
 
@@ -54,6 +55,8 @@ def _load() -> ctypes.CDLL:
         fn.argtypes = [i, i, i, i, i, i]
     lib.la_causal_fwd.restype = i
     lib.la_causal_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_causal_fwd_noalloc.restype = i
+    lib.la_causal_fwd_noalloc.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp]
     lib.la_causal_fwd_state.restype = i
     lib.la_causal_fwd_state.argtypes = [vp] * 9 + [i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_causal_bwd.restype = i
@@ -158,6 +161,16 @@ def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None, features
     _check(_lib.la_causal_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
                               float(eps), t, wp, wb, _stream(stream)), "la_causal_fwd")
     return ws
+
+
+def la_causal_fwd_noalloc(Q, K, V, O, den=None, eps=1e-6, stream=None, features=False):
+    """la_causal_fwd without a workspace argument: the segment states live in the library's
+    built-in scratch array (LA_NOALLOC_SCRATCH_BYTES); nothing is allocated by the call."""
+    B, H, N, D = Q.shape
+    M = V.shape[-1]
+    t = _dtype_code(Q, features)
+    _check(_lib.la_causal_fwd_noalloc(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D,
+                                      M, float(eps), t, _stream(stream)), "la_causal_fwd_noalloc")
 
 
 def la_causal_fwd_state(Q, K, V, O, den=None, S0=None, z0=None, S1=None, z1=None, eps=1e-6, ws=None,

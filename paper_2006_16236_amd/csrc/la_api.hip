@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kVersion = 310;   // 0.3.1
+constexpr int kVersion = 400;   // 0.4.0
 
 // ---- schedule ---------------------------------------------------------------------------------
 // One wavefront (forward) or one two-wave workgroup (backward) walks one segment of one
@@ -104,6 +104,33 @@ struct Carver {
 };
 
 int hip_status(hipError_t e) { return e == hipSuccess ? LA_OK : LA_ERR_HIP; }
+
+// ---- built-in scratch of la_causal_fwd_noalloc --------------------------------------------------
+// Device memory that belongs to the library's code object: every GPU the library runs on holds
+// its own copy at its own address from the moment the code object is loaded there until the
+// process ends.  In host code the array's name is only a stand-in for those copies; the address
+// on the current device comes from hipGetSymbolAddress, once per device, and is what the
+// kernels are handed.
+constexpr size_t kScratchBytes = (size_t)40 << 20;       // 40 MiB
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};                    // guarded by g_scratch_mu
+
+int scratch_on_current_device(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LA_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_scratch_mu);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr)
+            return LA_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return LA_OK;
+}
 
 // ---- optional profiling hook: HIP events around selected launches ----------------------------
 struct ProfRec {
@@ -210,6 +237,7 @@ const char *la_status_string(int status) {
         case LA_ERR_HIP: return "a HIP call or kernel launch failed";
         case LA_ERR_ALIGN: return "a tensor pointer is not 16-byte aligned";
         case LA_ERR_ALIAS: return "an output or workspace buffer overlaps another buffer of the call";
+        case LA_ERR_SCRATCH: return "the call needs more scratch memory than the library's built-in array holds";
         default: return "unknown status";
     }
 }
@@ -282,6 +310,31 @@ int la_causal_fwd_bnhd(const void *Q, const void *K, const void *V, void *O, flo
                        void *ws, size_t ws_bytes, void *stream) {
     return causal_fwd_impl(Q, K, V, O, den, B, H, N, D, M, eps, t, ws, ws_bytes, stream,
                            H > 1 ? H : 0);
+}
+
+int la_causal_fwd_noalloc(const void *Q, const void *K, const void *V, void *O, float *den,
+                          int B, int H, int N, int D, int M, float eps, la_dtype t, void *stream) {
+    if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
+    const int st = check_dims(B, H, N, D, M, eps, t);
+    if (st != LA_OK) return st;
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return LA_ERR_ALIGN;
+    const long BH = (long)B * H;
+    const Plan p = make_plan(BH, N);
+    const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+    if (need > kScratchBytes) return LA_ERR_SCRATCH;
+    const size_t rows = (size_t)BH * N, e = esize(t);
+    const Span outs[] = {{O, rows * M * e}, {den, rows * 4}};
+    const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e}};
+    if (aliased(outs, ins)) return LA_ERR_ALIAS;
+    void *states = nullptr;
+    if (need > 0) {
+        // the states are written (segment sums), scanned and read within this call: nothing in
+        // the array has to start at zero, whatever the call before left there
+        const int ss = scratch_on_current_device(&states);
+        if (ss != LA_OK) return ss;
+    }
+    return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(states),
+                          static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, nullptr, H, 0);
 }
 
 int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float *S0,

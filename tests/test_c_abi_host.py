@@ -38,7 +38,7 @@ def test_version_and_status_strings(lib):
     from paper_2006_16236_amd import binding
     assert binding.la_version() >= 100
     seen = set()
-    for st in range(0, -8, -1):
+    for st in range(0, -9, -1):
         s = binding.status_string(st)
         assert s and s != "unknown status" and s not in seen
         seen.add(s)
@@ -89,6 +89,17 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     # a long sequence needs a workspace
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 0, p, 1024, null) == b.LA_ERR_WORKSPACE
+
+    # the forward without a workspace argument: same validation; sizes beyond its built-in
+    # scratch array are refused before any GPU call
+    fna = lib.la_causal_fwd_noalloc
+    assert fna(null, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null) == b.LA_ERR_NULL
+    assert fna(p, p, p, p, null, 1, 1, 16, 48, 64, f(1e-6), 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fna(p, odd, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null) == b.LA_ERR_ALIGN
+    # (1000 sequences cut in three: 3000 states of 16.6 KB)
+    assert b.la_causal_fwd_workspace(125, 8, 4096, 64, 64) > b.LA_NOALLOC_SCRATCH_BYTES
+    assert fna(p, p, p, p, null, 125, 8, 4096, 64, 64, f(1e-6), 0, null) == b.LA_ERR_SCRATCH
+    assert b.la_causal_fwd_workspace(2, 8, 1 << 16, 64, 64) <= b.LA_NOALLOC_SCRATCH_BYTES
 
     fws = lib.la_causal_fwd_state
     assert fws(p, p, p, p, null, p, null, null, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_NULL
