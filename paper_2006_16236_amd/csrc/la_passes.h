@@ -1147,6 +1147,320 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     }
 }
 
+// The causal dQ pass for fp32 tensors, organised so that neither wave waits long for the other.
+// (dq_pass_kernel above hands the whole running sum S from one wave to the other through LDS
+// every chunk, 16 KB, and its first wave then carries 84 fp32 MFMAs in one dependent chain
+// while the second idles at the barrier: measured, that chain sets the pace of the kernel.)
+// Here the work of a chunk is cut along the data flow instead:
+//   wave 1 ("state wave") owns S^T (M x D) in accumulators.  It reads out A0 = (dO/den) S^T (the
+//          part of eq. 13 that comes from the tokens before the chunk, 64 fp32 MFMAs), hands
+//          the 16 x D result to wave 0 through LDS (4 KB), then adds the chunk's V^T phi(K) to S^T
+//          and, when the sequences are cut, phi(Q)^T dO/den to this segment's sum for the reverse
+//          passes (96 bf16 MFMAs on split operands);
+//   wave 0 ("chunk wave") forms the masked scores (dO/den) V^T, their product with phi(K), the
+//          running sum of phi(K) for the ones column, and after adding A0 finishes dQ: delta,
+//          the chain rule through phi, the stores.
+// The input tiles are double-buffered in LDS: each wave parks its two tiles of the next chunk
+// while the other is still reading the current ones, so a chunk costs two barriers and the
+// feature map (32 exponentials per lane and chunk, wave 0) is off the critical path.
+template <int D, int M, typename T, bool kStrided = false>
+__global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void dq_causal_kernel(
+    const PassArgs a) {
+    static_assert(!is_bf16<T>, "fp32 tensors only; bf16 tensors use dq_pass_kernel");
+    constexpr int DT = D / 16, MT = M / 16;
+    __shared__ float lds_g[2][tile_floats(M)];       // dO / den
+    __shared__ float lds_v[2][tile_floats(M)];       // V
+    __shared__ float lds_fk[2][tile_floats(D)];      // phi(K)
+    __shared__ float lds_fq[2][tile_floats(D)];      // phi(Q)
+    __shared__ __attribute__((aligned(16))) float lds_a0[DT][kWave][4];   // A0, in wave 1's register layout
+    const int lane = threadIdx.x & (kWave - 1), c = lane & 15, g = lane >> 4;
+    const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
+    const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
+    const int nchunks = (a.N + kChunk - 1) / kChunk;
+    const int ch_begin = seg * a.chunks_per_seg;
+    const int count = min(ch_begin + a.chunks_per_seg, nchunks) - ch_begin;
+    const size_t rowbase = (size_t)bh * a.N;
+    // the sums before this segment: from the scan (possibly laid out for a finer cut), else the
+    // caller's initial state, else zero
+    const size_t slot = (size_t)bh * (a.state_nseg != 0 ? a.state_nseg : a.nseg) +
+                        (size_t)seg * (a.state_step != 0 ? a.state_step : 1);
+    const float *st = a.state != nullptr ? a.state + slot * state_stride(D, M) : nullptr;
+    const float *s0 = st != nullptr ? st : (a.init_S != nullptr ? a.init_S + (size_t)bh * D * M : nullptr);
+    const float *z0 = st != nullptr ? st + D * M : (a.init_z != nullptr ? a.init_z + (size_t)bh * D : nullptr);
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    if (role == 0) {
+        // ---- chunk wave: brings Q and K --------------------------------------------------------
+        const int ts = tok_stride<kStrided>(a.tok_heads, D);
+        const T *Qs = static_cast<const T *>(a.Q) + seq_base<kStrided>(a.N, a.heads, bh, D);
+        const T *Ks = static_cast<const T *>(a.K) + seq_base<kStrided>(a.N, a.heads, bh, D);
+        T *outs = static_cast<T *>(a.out) + seq_base<kStrided>(a.N, a.heads, bh, D);
+        const float *den = a.den_in + rowbase;
+        f32x4 sq[DT], sk[DT];
+        float one[DT], nden[4], rd4[4];
+        float ecp[DT];     // z[16zt + c] before the chunk, as four per-lane partial sums (lanes (c, g = 0..3))
+        float rho[DT];     // this segment's sum of delta_b phi(Q_b)[16zt + c], same partial form
+#pragma unroll
+        for (int zt = 0; zt < DT; ++zt) {
+            one[zt] = 1.0f;
+            rho[zt] = 0.f;
+            ecp[zt] = (z0 != nullptr && g == 0) ? z0[16 * zt + c] : 0.f;
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) nden[s] = 1.f, rd4[s] = 0.f;
+        // constant lower-triangular mask (token 4g + s <= token c) as bf16 ones
+        const u32x2_t mk = {((4 * g + 0) <= c ? 0x3f80u : 0u) | ((4 * g + 1) <= c ? 0x3f800000u : 0u),
+                            ((4 * g + 2) <= c ? 0x3f80u : 0u) | ((4 * g + 3) <= c ? 0x3f800000u : 0u)};
+
+        auto fetch = [&](const int ch) {
+            const int t0 = ch * kChunk;
+            const int nvalid = min(kChunk, a.N - t0);
+            if (nvalid == kChunk) {
+                stage_load<D, true>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
+                stage_load<D, true>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
+            } else {
+                stage_load<D, false>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
+                stage_load<D, false>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) nden[s] = den[t0 + min(4 * g + s, nvalid - 1)];
+        };
+        auto park = [&](const int ch, const int buf) {
+            const int nvalid = min(kChunk, a.N - ch * kChunk);
+            if (nvalid == kChunk) {
+                park_tile<D, kMapPhi, true, is_feat<T>>(lds_fq[buf], sq, one, nvalid, lane);
+                park_tile<D, kMapPhi, true, is_feat<T>>(lds_fk[buf], sk, one, nvalid, lane);
+            } else {
+                park_tile<D, kMapPhi, false, is_feat<T>>(lds_fq[buf], sq, one, nvalid, lane);
+                park_tile<D, kMapPhi, false, is_feat<T>>(lds_fk[buf], sk, one, nvalid, lane);
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) rd4[s] = 4 * g + s < nvalid ? __builtin_amdgcn_rcpf(nden[s]) : 0.f;
+        };
+
+        if (count > 0) {
+            fetch(ch_begin);
+            park(ch_begin, 0);
+            if (count > 1) fetch(ch_begin + 1);
+        }
+        for (int n = 0; n < count; ++n) {
+            const int buf = n & 1, ch = ch_begin + n, t0 = ch * kChunk;
+            const int nvalid = min(kChunk, a.N - t0);
+            __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();                 // the tiles of this chunk are parked (both waves)
+
+            // scores W[a][b] = (dO_a/den_a) . V_b: lane (c = a, g), register r: b = 4g + r
+            float xa[MT][4], ya[MT][4];
+            lds_token_lane<M>(lds_g[buf], c, g, xa);
+            lds_token_lane<M>(lds_v[buf], c, g, ya);
+            f32x4 w0 = zero4, w1 = zero4;
+#pragma unroll
+            for (int xt = 0; xt < MT; xt += 2)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    w0 = mfma16(ya[xt][r], xa[xt][r], w0);
+                    w1 = mfma16(ya[xt + 1][r], xa[xt + 1][r], w1);
+                }
+            float wq[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) wq[r] = (4 * g + r) <= c ? w0[r] + w1[r] : 0.f;   // select, never multiply
+            // in-chunk part of eq. 13: W phi(K); and z_a = z + running sum of phi(K) up to token a
+            float zf[DT][4];
+            lds_feature_lane<D>(lds_fk[buf], c, g, zf);
+            const SplitA<3> ws = split_a<3>(wq);
+            f32x4 out[DT], cz[DT];
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) {
+                const SplitB<3> zs = split_b<3>(zf[zt]);
+                out[zt] = mfma16_split(ws, zs, zero4);
+                cz[zt] = mfma16_mask(mk, zs, mfma16(1.0f, ecp[zt], zero4));
+            }
+            float fq[DT][4];                 // phi(Q): token 4g + r, feature 16zt + c
+            lds_feature_lane<D>(lds_fq[buf], c, g, fq);
+            __syncthreads();                 // wave 1 has put A0 into LDS
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) out[zt] += *reinterpret_cast<const f32x4 *>(&lds_a0[zt][lane][0]);
+
+            // delta_a = -(phi(Q_a) . A_a)/den_a, then dphi(Q)_a = A_a + delta_a z_a, times phi'(Q_a)
+            float d4[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                float p = out[0][r] * fq[0][r];
+#pragma unroll
+                for (int zt = 1; zt < DT; ++zt) p = fmaf(out[zt][r], fq[zt][r], p);
+                d4[r] = -row_sum16(p) * rd4[r];
+            }
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) {
+                float rp = 0.f;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    rp = fmaf(d4[r], fq[zt][r], rp);
+                    out[zt][r] = fmaf(d4[r], cz[zt][r], out[zt][r]) * feature_slope<T>(fq[zt][r]);
+                }
+                rho[zt] += rp;
+                ecp[zt] += (zf[zt][0] + zf[zt][1]) + (zf[zt][2] + zf[zt][3]);
+            }
+            const int tso = ts;
+            T *lane_out = outs + (size_t)t0 * tso + (4 * g * tso + c);
+            if (nvalid == kChunk) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int zt = 0; zt < DT; ++zt) store_elem(lane_out + (r * tso + 16 * zt), out[zt][r]);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (4 * g + r < nvalid) {
+#pragma unroll
+                        for (int zt = 0; zt < DT; ++zt) store_elem(lane_out + (r * tso + 16 * zt), out[zt][r]);
+                    }
+            }
+            // lanes c < 4 of each group write 1/den and delta of token 4g + c
+            const float dsel = c == 0 ? d4[0] : c == 1 ? d4[1] : c == 2 ? d4[2] : d4[3];
+            const float rsel = c == 0 ? rd4[0] : c == 1 ? rd4[1] : c == 2 ? rd4[2] : rd4[3];
+            if (a.delta_out != nullptr && c < 4 && 4 * g + c < nvalid) {
+                a.delta_out[rowbase + t0 + 4 * g + c] = dsel;
+                a.rden_out[rowbase + t0 + 4 * g + c] = rsel;
+            }
+            // the next chunk's tiles go into the other buffer (nobody reads it any more)
+            if (n + 1 < count) {
+                park(ch + 1, buf ^ 1);
+                if (n + 2 < count) fetch(ch + 2);
+            }
+        }
+        if (a.totals != nullptr) {          // this segment's sum of delta_b phi(Q_b)
+            float *tot = a.totals + ((size_t)bh * a.nseg + seg) * state_stride(D, M) + D * M;
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) {
+                const float e = sum_over_groups(rho[zt]);
+                if (g == 0) tot[16 * zt + c] = e;
+            }
+        }
+    } else {
+        // ---- state wave: brings dO (parked as dO/den) and V --------------------------------------
+        const int ts = tok_stride<kStrided>(a.tok_heads, M);
+        const T *Gs = static_cast<const T *>(a.G) + seq_base<kStrided>(a.N, a.heads, bh, M);
+        const T *Vs = static_cast<const T *>(a.V) + seq_base<kStrided>(a.N, a.heads, bh, M);
+        const float *den = a.den_in + rowbase;
+        const bool want = a.totals != nullptr;         // uniform
+        f32x4 sg[MT], sv[MT];
+        float sca[MT], one[MT];
+        f32x4 U[MT][DT];      // S^T: element (m = 16xt + 4g + r, d = 16zt + c)
+        f32x4 R[DT][MT];      // this segment's phi(Q)^T dO/den: element (d = 16xt + 4g + r, m = 16zt + c)
+#pragma unroll
+        for (int xt = 0; xt < MT; ++xt) {
+            sca[xt] = one[xt] = 1.0f;
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) {
+                U[xt][zt] = s0 != nullptr ? load4(s0 + (16 * zt + c) * M + 16 * xt + 4 * g) : zero4;
+                R[zt][xt] = zero4;
+            }
+        }
+        auto fetch = [&](const int ch) {
+            const int t0 = ch * kChunk;
+            const int nvalid = min(kChunk, a.N - t0);
+            if (nvalid == kChunk) {
+                stage_load<M, true>(Gs + (size_t)t0 * ts, ts, nvalid, lane, sg);
+                stage_load<M, true>(Vs + (size_t)t0 * ts, ts, nvalid, lane, sv);
+                stage_rows<M, true>(den + t0, nvalid, lane, sca);
+            } else {
+                stage_load<M, false>(Gs + (size_t)t0 * ts, ts, nvalid, lane, sg);
+                stage_load<M, false>(Vs + (size_t)t0 * ts, ts, nvalid, lane, sv);
+                stage_rows<M, false>(den + t0, nvalid, lane, sca);
+            }
+        };
+        auto park = [&](const int ch, const int buf) {
+            const int nvalid = min(kChunk, a.N - ch * kChunk);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
+            if (nvalid == kChunk) {
+                park_tile<M, kMapScale, true, is_feat<T>>(lds_g[buf], sg, sca, nvalid, lane);
+                park_tile<M, kMapId, true, is_feat<T>>(lds_v[buf], sv, one, nvalid, lane);
+            } else {
+                park_tile<M, kMapScale, false, is_feat<T>>(lds_g[buf], sg, sca, nvalid, lane);
+                park_tile<M, kMapId, false, is_feat<T>>(lds_v[buf], sv, one, nvalid, lane);
+            }
+        };
+
+        if (count > 0) {
+            fetch(ch_begin);
+            park(ch_begin, 0);
+            if (count > 1) fetch(ch_begin + 1);
+        }
+        for (int n = 0; n < count; ++n) {
+            const int buf = n & 1, ch = ch_begin + n;
+            __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);    // see run_pass
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();                 // the tiles of this chunk are parked (both waves)
+
+            // A0 = (dO/den) S^T: lane (c, g), register r: token 4g + r, feature 16zt + c
+            float xa[MT][4];
+            lds_token_lane<M>(lds_g[buf], c, g, xa);
+            f32x4 out[DT];
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) out[zt] = zero4;
+#pragma unroll
+            for (int xt = 0; xt < MT; ++xt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int zt = 0; zt < DT; ++zt) out[zt] = mfma16(xa[xt][r], U[xt][zt][r], out[zt]);
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) lds_store4(&lds_a0[zt][lane][0], out[zt]);
+            __syncthreads();                 // A0 is there for wave 0
+
+            if (n + 1 < count) {
+                park(ch + 1, buf ^ 1);
+                if (n + 2 < count) fetch(ch + 2);
+                __builtin_amdgcn_s_sleep(LA_SLEEP_AFTER_FETCH);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            // S^T += V^T phi(K) over the chunk's tokens (eq. 10)
+            float yf[MT][4], zf[DT][4];
+            lds_feature_lane<M>(lds_v[buf], c, g, yf);
+            lds_feature_lane<D>(lds_fk[buf], c, g, zf);
+            {
+                SplitB<3> zs[DT];
+#pragma unroll
+                for (int zt = 0; zt < DT; ++zt) zs[zt] = split_b<3>(zf[zt]);
+#pragma unroll
+                for (int xt = 0; xt < MT; ++xt) {
+                    const SplitA<3> ys = split_a<3>(yf[xt]);
+#pragma unroll
+                    for (int zt = 0; zt < DT; ++zt) U[xt][zt] = mfma16_split(ys, zs[zt], U[xt][zt]);
+                }
+            }
+            // this segment's phi(Q)^T dO/den (eq. 14-15 restricted to the segment)
+            if (want) {
+                float qf[DT][4], gf[MT][4];
+                lds_feature_lane<D>(lds_fq[buf], c, g, qf);
+                lds_feature_lane<M>(lds_g[buf], c, g, gf);
+                SplitA<3> qa[DT];
+#pragma unroll
+                for (int xt = 0; xt < DT; ++xt) qa[xt] = split_a<3>(qf[xt]);
+#pragma unroll
+                for (int zt = 0; zt < MT; ++zt) {
+                    const SplitB<3> gb = split_b<3>(gf[zt]);
+#pragma unroll
+                    for (int xt = 0; xt < DT; ++xt) R[xt][zt] = mfma16_split(qa[xt], gb, R[xt][zt]);
+                }
+            }
+        }
+        if (want) {
+            float *tot = a.totals + ((size_t)bh * a.nseg + seg) * state_stride(D, M);
+#pragma unroll
+            for (int xt = 0; xt < DT; ++xt)
+#pragma unroll
+                for (int zt = 0; zt < MT; ++zt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        tot[(16 * xt + 4 * g + r) * M + 16 * zt + c] = R[xt][zt][r];
+        }
+    }
+}
+
 // ---- per-segment totals (first phase of the segment scan) ---------------------------------
 // S = sum phi(K_b)^T V_b, z = sum phi(K_b) over the tokens of one segment (eq. 10-11), written
 // as [D][M] row-major followed by the D-vector.  (The matching sums of the backward, over Q and
