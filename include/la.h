@@ -45,13 +45,16 @@
  *   Threads    No global mutable state apart from the optional profiling hook
  *              at the end of this file; calls from several host threads are
  *              safe as long as they do not share output or workspace buffers.
- *   Tuning     Two environment variables, read at every call, override the
+ *   Tuning     Three environment variables, read at every call, override the
  *              segment schedule (for tests and experiments): LA_TARGET_WAVES
- *              (default 2048: wavefronts wanted in flight) and
- *              LA_MIN_SEG_CHUNKS (default 2: shortest segment, in 16-token
- *              chunks).  Sequences are not cut at all once B*H reaches half of
- *              LA_TARGET_WAVES.  The workspace query and the call must see the
- *              same values.
+ *              (default 2048: wavefronts wanted in flight), LA_MIN_SEG_CHUNKS
+ *              (default 2: shortest segment, in 16-token chunks) and
+ *              LA_FOLD_MAX_SEGS (default 8: up to this many segments per
+ *              sequence the passes add up the segment totals themselves and no
+ *              scan kernel runs).  Sequences are not cut at all once B*H
+ *              reaches half of LA_TARGET_WAVES.  The workspace query, a forward
+ *              and the backward that is handed its workspace must see the same
+ *              values.
  */
 #ifndef LA_H_
 #define LA_H_

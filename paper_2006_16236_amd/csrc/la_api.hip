@@ -23,6 +23,8 @@ constexpr int kVersion = 400;   // 0.4.0
 // chunks, and not at all once the sequences alone fill half the machine.
 struct Plan {
     int nchunks, nseg, cps;
+    bool fold;      // few segments per sequence: no scan launch, every pass adds up the
+                    // segment totals before (after) its own segment itself
 };
 
 int env_int(const char *name, int dflt) {
@@ -46,6 +48,7 @@ Plan make_plan(long BH, int N) {
     if (2 * BH >= target_waves) nseg = 1;
     p.cps = (int)((p.nchunks + nseg - 1) / nseg);
     p.nseg = (p.nchunks + p.cps - 1) / p.cps;
+    p.fold = p.nseg > 1 && p.nseg <= env_int("LA_FOLD_MAX_SEGS", 8);
     return p;
 }
 
@@ -192,13 +195,15 @@ int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = p.nseg - 1;
         sa.heads = heads; sa.tok_heads = tok_heads;
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
+        if (!p.fold)
+            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
+    const bool scanned = p.nseg > 1 && !p.fold;      // the scan has added the caller's state already
     la::PassArgs a{};
     a.heads = heads; a.tok_heads = tok_heads;
     a.Q = Q; a.K = K; a.V = V; a.G = nullptr; a.rden = nullptr; a.delta = nullptr;
-    a.out = O; a.den = den; a.state = p.nseg > 1 ? states : nullptr;
-    a.init_S = S0; a.init_z = z0; a.final_S = S1; a.final_z = z1;
+    a.out = O; a.den = den; a.state = p.nseg > 1 ? states : nullptr; a.fold = p.fold;
+    a.init_S = scanned ? nullptr : S0; a.init_z = scanned ? nullptr : z0; a.final_S = S1; a.final_z = z1;
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
     { ProfScope ps(LA_K_FWD, s); LA_TRY(la::launch_pass_fwd(false, D, M, (int)t, a, nblocks, s)); }
     return LA_OK;
@@ -214,11 +219,11 @@ int run_global_fwd(const void *Q, const void *K, const void *V, void *O, float *
     sa.Y = K; sa.Z = V; sa.state = states;
     sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
     { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
-    if (p.nseg > 1)
+    if (p.nseg > 1 && !p.fold)
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(states, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
     la::PassArgs a{};
     a.heads = heads; a.tok_heads = tok_heads;
-    a.Q = Q; a.K = K; a.V = V; a.out = O; a.den = den; a.state = states;
+    a.Q = Q; a.K = K; a.V = V; a.out = O; a.den = den; a.state = states; a.fold = p.fold;
     a.N = N; a.nseg = p.nseg; a.chunks_per_seg = p.cps; a.eps = eps;
     { ProfScope ps(LA_K_GLOBAL, s); LA_TRY(la::launch_pass_fwd(true, D, M, (int)t, a, nblocks, s)); }
     return LA_OK;
@@ -427,7 +432,8 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
         sa.skip_seg = p.nseg - 1;
         sa.heads = H; sa.tok_heads = tok_heads;
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
+        if (!p.fold)
+            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
     }
     // The two kernels of the backward run two waves per workgroup, so half as many workgroups
     // fill the machine: they take the forward's segments in pairs.  The prefix states (laid out
@@ -445,14 +451,18 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.rden = rden; a.delta = delta; a.den = nullptr;
     a.den_in = den; a.rden_out = rden; a.delta_out = delta; a.totals = pb.nseg > 1 ? stR : nullptr;
     a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
-    a.out = dQ; a.state = stS; a.state_nseg = p.nseg; a.state_step = 2;
-    a.init_S = S0; a.init_z = z0;            // read only where the sequences are not cut
+    a.out = dQ; a.state = stS; a.state_nseg = p.nseg; a.state_step = 2; a.fold = p.fold;
+    // the caller's state: the scan has added it to the prefix states already, if there was one
+    const bool scanned = p.nseg > 1 && !p.fold;
+    a.init_S = scanned ? nullptr : S0; a.init_z = scanned ? nullptr : z0;
     { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(true, D, M, (int)t, a, nblocks_b, s)); }
-    if (pb.nseg > 1)
+    const bool scanned_b = pb.nseg > 1 && !p.fold;
+    if (scanned_b)
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
     a.out = dV; a.out2 = dK; a.state = pb.nseg > 1 ? stR : nullptr;
     a.state_nseg = 0; a.state_step = 0;      // stR is laid out for this very cut
-    a.init_S = dS1; a.init_z = dz1; a.final_S = dS0; a.final_z = dz0;
+    a.init_S = scanned_b ? nullptr : dS1; a.init_z = scanned_b ? nullptr : dz1;
+    a.final_S = dS0; a.final_z = dz0;
     { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks_b, s)); }
     return LA_OK;
 }
@@ -563,7 +573,7 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
         sa.Y = K; sa.Z = V; sa.state = stS;
         { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
-        if (p.nseg > 1)
+        if (p.nseg > 1 && !p.fold)
             { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
     }
     // dQ against the K, V total; on the way the per-segment Q, dO sums.  A kernel with two
@@ -577,9 +587,9 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
     a.heads = H; a.tok_heads = tok_heads;
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.den_in = den; a.totals = stR;
     a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
-    a.out = dQ; a.state = stS; a.state_nseg = p.nseg;
+    a.out = dQ; a.state = stS; a.state_nseg = p.nseg; a.fold = p.fold;
     { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(false, D, M, (int)t, a, (int)(BH * pb.nseg), s)); }
-    if (pb.nseg > 1)
+    if (pb.nseg > 1 && !p.fold)
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
     // dV and dK against the Q, dO total
     a.totals = nullptr; a.nseg = p.nseg; a.chunks_per_seg = p.cps;

@@ -87,6 +87,12 @@ struct PassArgs {
     // `state` may have been laid out for a finer cut: state_nseg segments per sequence (0: nseg),
     // of which this pass's segment `seg` starts at segment seg * state_step (0: step 1)
     int state_nseg, state_step;
+    // fold = 0: every slot of `state` holds a finished sum (the scan kernel has run): a pass reads
+    //           the one slot it starts from;
+    // fold = 1: the slots hold per-segment totals and each pass adds up the ones before (after)
+    //           its segment itself, in slot order.  Pays when a sequence has few segments: one
+    //           launch and one sweep over the states less.
+    int fold;
     // State at the end a pass starts from, used when the sequences are not cut (nseg == 1),
     // [BH, D, M] / [BH, D], may be null: kFwd, kDq the sums before token 0; kDv (matrix) and
     // kDk (vector) the gradient that arrives at the state after the last token.
@@ -115,6 +121,25 @@ template <bool kStrided>
 __device__ __forceinline__ int tok_stride(int tok_heads, int F) {
     if constexpr (!kStrided) return F;
     else return tok_heads * F;
+}
+
+// Which slots of a sequence's state array a pass adds up to get the sum it starts from:
+// the tokens before its segment, the tokens after it, or all of them.
+enum StateKind { kStatePrefix = 0, kStateSuffix = 1, kStateTotal = 2 };
+__device__ __forceinline__ void state_slots(const PassArgs &a, const int seg, const int kind,
+                                            int &nslots, int &lo, int &hi) {
+    nslots = a.state_nseg != 0 ? a.state_nseg : a.nseg;
+    const int at = seg * (a.state_step != 0 ? a.state_step : 1);
+    if (a.fold == 0) {
+        lo = kind == kStateTotal ? 0 : at;
+        hi = lo + 1;
+    } else if (kind == kStatePrefix) {
+        lo = 0, hi = at;
+    } else if (kind == kStateSuffix) {
+        lo = at + 1, hi = nslots;
+    } else {
+        lo = 0, hi = nslots;
+    }
 }
 
 enum Map { kMapId = 0, kMapPhi = 1, kMapDphi = 2, kMapScale = 3, kMapOne = 4 };
@@ -388,10 +413,10 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
 #pragma unroll
     for (int zt = 0; zt < ZT; ++zt) ecp[zt] = rho[zt] = 0.f;
 
-    if (a.state != nullptr) {
-        const size_t slot = (size_t)bh * (a.state_nseg != 0 ? a.state_nseg : a.nseg) +
-                            (kHasYZ ? (size_t)seg * (a.state_step != 0 ? a.state_step : 1) : 0);
-        const float *st = a.state + slot * state_stride(D, M);
+    // The sum the pass starts from: the caller's state at that end (if any) plus the slots of
+    // the state array that state_slots() names (one finished sum, or the totals to add up).
+    // sm: [D][M] matrix, sv: the D-vector of the ones column.
+    auto add_state = [&](const float *sm, const float *sv) {
 #pragma unroll
         for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
@@ -400,46 +425,29 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 if constexpr (kXisD) {        // U[d][m], d = 16xt + 4g + r, m = 16zt + c
 #pragma unroll
                     for (int r = 0; r < 4; ++r)
-                        U[xt][zt][r] = st[(16 * xt + 4 * g + r) * M + 16 * zt + c];
+                        U[xt][zt][r] += sm[(16 * xt + 4 * g + r) * M + 16 * zt + c];
                 } else {                      // U[m][d] = S[d][m], m = 16xt + 4g + r, d = 16zt + c
-                    U[xt][zt] = load4(st + (16 * zt + c) * M + 16 * xt + 4 * g);
+                    U[xt][zt] += load4(sm + (16 * zt + c) * M + 16 * xt + 4 * g);
                 }
             }
         if constexpr (PASS == kFwd || PASS == kGlobal) {
 #pragma unroll
-            for (int xt = 0; xt < XT; ++xt) zg[xt] = load4(st + D * M + 16 * xt + 4 * g);
+            for (int xt = 0; xt < XT; ++xt) zg[xt] += load4(sv + 16 * xt + 4 * g);
         }
         if constexpr (Tr::BP == kDq || Tr::BP == kDk) {
 #pragma unroll
-            for (int zt = 0; zt < ZT; ++zt) ecp[zt] = g == 0 ? st[D * M + 16 * zt + c] : 0.f;
+            for (int zt = 0; zt < ZT; ++zt) ecp[zt] += g == 0 ? sv[16 * zt + c] : 0.f;
         }
-    }
-
+    };
     if constexpr (kHasYZ) {
-        // caller-supplied state at the end the pass starts from (sequences that are not cut;
-        // otherwise the scan has already folded it into the segment states): [D][M] and [D]
-        if (a.state == nullptr && a.init_S != nullptr) {
-            const float *s0 = a.init_S + (size_t)bh * D * M;
-            const float *z0 = a.init_z + (size_t)bh * D;
-#pragma unroll
-            for (int xt = 0; xt < XT; ++xt) {
-#pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) {
-                    if constexpr (kStateMode == kBorrowState) continue;
-                    if constexpr (kXisD) {
-#pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            U[xt][zt][r] = s0[(16 * xt + 4 * g + r) * M + 16 * zt + c];
-                    } else {
-                        U[xt][zt] = load4(s0 + (16 * zt + c) * M + 16 * xt + 4 * g);
-                    }
-                }
-                if constexpr (PASS == kFwd) zg[xt] = load4(z0 + 16 * xt + 4 * g);
-            }
-            if constexpr (PASS == kDq || PASS == kDk) {
-#pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) ecp[zt] = g == 0 ? z0[16 * zt + c] : 0.f;
-            }
+        if (a.init_S != nullptr) add_state(a.init_S + (size_t)bh * D * M, a.init_z + (size_t)bh * D);
+    }
+    if (a.state != nullptr) {
+        int nslots, lo, hi;
+        state_slots(a, seg, !kHasYZ ? kStateTotal : kReverse ? kStateSuffix : kStatePrefix, nslots, lo, hi);
+        for (int j = lo; j < hi; ++j) {
+            const float *st = a.state + ((size_t)bh * nslots + j) * state_stride(D, M);
+            add_state(st, st + D * M);
         }
     }
 
@@ -1001,19 +1009,22 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
     for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
         for (int zt = 0; zt < ZT; ++zt) S[xt][zt] = R[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    const size_t slot = a.state_step != 0 ? (size_t)bh * a.state_nseg + (size_t)seg * a.state_step
-                                          : (size_t)bh * a.nseg + seg;
-    const float *s0 = a.state != nullptr
-                          ? a.state + slot * state_stride(D, M)
-                          : (a.init_S != nullptr ? a.init_S + (size_t)bh * D * M : nullptr);
-    if (kCausal && s0 != nullptr) {
+    if constexpr (kCausal) {
+        auto add_state = [&](const float *sm) {
 #pragma unroll
-        for (int xt = 0; xt < XT; ++xt)
+            for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
-            for (int zt = 0; zt < ZT; ++zt)
+                for (int zt = 0; zt < ZT; ++zt)
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    S[xt][zt][r] = s0[(16 * xt + 4 * g + r) * M + 16 * zt + c];
+                    for (int r = 0; r < 4; ++r)
+                        S[xt][zt][r] += sm[(16 * xt + 4 * g + r) * M + 16 * zt + c];
+        };
+        if (a.init_S != nullptr) add_state(a.init_S + (size_t)bh * D * M);
+        if (a.state != nullptr) {
+            int nslots, lo, hi;
+            state_slots(a, seg, kStatePrefix, nslots, lo, hi);
+            for (int j = lo; j < hi; ++j) add_state(a.state + ((size_t)bh * nslots + j) * state_stride(D, M));
+        }
     }
 
     if (ch_begin < ch_end) stg.template fetch<0>(ch_begin);
@@ -1180,13 +1191,11 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int ch_begin = seg * a.chunks_per_seg;
     const int count = min(ch_begin + a.chunks_per_seg, nchunks) - ch_begin;
     const size_t rowbase = (size_t)bh * a.N;
-    // the sums before this segment: from the scan (possibly laid out for a finer cut), else the
-    // caller's initial state, else zero
-    const size_t slot = (size_t)bh * (a.state_nseg != 0 ? a.state_nseg : a.nseg) +
-                        (size_t)seg * (a.state_step != 0 ? a.state_step : 1);
-    const float *st = a.state != nullptr ? a.state + slot * state_stride(D, M) : nullptr;
-    const float *s0 = st != nullptr ? st : (a.init_S != nullptr ? a.init_S + (size_t)bh * D * M : nullptr);
-    const float *z0 = st != nullptr ? st + D * M : (a.init_z != nullptr ? a.init_z + (size_t)bh * D : nullptr);
+    // the sums before this segment: the caller's initial state (if any) plus the slots of the
+    // state array that state_slots() names
+    int nslots = 0, slot_lo = 0, slot_hi = 0;
+    if (a.state != nullptr) state_slots(a, seg, kStatePrefix, nslots, slot_lo, slot_hi);
+    const float *slots = a.state != nullptr ? a.state + (size_t)bh * nslots * state_stride(D, M) : nullptr;
     const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
 
     if (role == 0) {
@@ -1204,7 +1213,12 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         for (int zt = 0; zt < DT; ++zt) {
             one[zt] = 1.0f;
             rho[zt] = 0.f;
-            ecp[zt] = (z0 != nullptr && g == 0) ? z0[16 * zt + c] : 0.f;
+            ecp[zt] = (a.init_z != nullptr && g == 0) ? a.init_z[(size_t)bh * D + 16 * zt + c] : 0.f;
+        }
+        for (int j = slot_lo; j < slot_hi; ++j) {
+            const float *sv = slots + (size_t)j * state_stride(D, M) + D * M;
+#pragma unroll
+            for (int zt = 0; zt < DT; ++zt) ecp[zt] += g == 0 ? sv[16 * zt + c] : 0.f;
         }
 #pragma unroll
         for (int s = 0; s < 4; ++s) nden[s] = 1.f, rd4[s] = 0.f;
@@ -1353,11 +1367,16 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         for (int xt = 0; xt < MT; ++xt) {
             sca[xt] = one[xt] = 1.0f;
 #pragma unroll
-            for (int zt = 0; zt < DT; ++zt) {
-                U[xt][zt] = s0 != nullptr ? load4(s0 + (16 * zt + c) * M + 16 * xt + 4 * g) : zero4;
-                R[zt][xt] = zero4;
-            }
+            for (int zt = 0; zt < DT; ++zt) U[xt][zt] = R[zt][xt] = zero4;
         }
+        auto add_state = [&](const float *sm) {     // sm: S as [D][M]
+#pragma unroll
+            for (int xt = 0; xt < MT; ++xt)
+#pragma unroll
+                for (int zt = 0; zt < DT; ++zt) U[xt][zt] += load4(sm + (16 * zt + c) * M + 16 * xt + 4 * g);
+        };
+        if (a.init_S != nullptr) add_state(a.init_S + (size_t)bh * D * M);
+        for (int j = slot_lo; j < slot_hi; ++j) add_state(slots + (size_t)j * state_stride(D, M));
         auto fetch = [&](const int ch) {
             const int t0 = ch * kChunk;
             const int nvalid = min(kChunk, a.N - t0);

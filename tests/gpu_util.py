@@ -51,9 +51,10 @@ def to_host(t):
 
 
 @contextlib.contextmanager
-def schedule(target_waves=None, min_seg_chunks=None):
-    """Force the segment schedule of the library through its two environment knobs."""
-    keys = {"LA_TARGET_WAVES": target_waves, "LA_MIN_SEG_CHUNKS": min_seg_chunks}
+def schedule(target_waves=None, min_seg_chunks=None, fold_max_segs=None):
+    """Force the segment schedule of the library through its environment knobs."""
+    keys = {"LA_TARGET_WAVES": target_waves, "LA_MIN_SEG_CHUNKS": min_seg_chunks,
+            "LA_FOLD_MAX_SEGS": fold_max_segs}
     old = {k: os.environ.get(k) for k in keys}
     try:
         for k, v in keys.items():
@@ -75,6 +76,10 @@ SCHEDULES = {
     "one_segment": dict(target_waves=1),
     "many_segments": dict(target_waves=1 << 20, min_seg_chunks=1),
     "three_chunk_segments": dict(target_waves=1 << 20, min_seg_chunks=3),
+    # few segments per sequence, their totals added up by the consumers (no scan kernel) ...
+    "folded_totals": dict(target_waves=24, min_seg_chunks=1, fold_max_segs=64),
+    # ... and the same few segments through the scan kernel
+    "few_segments_scanned": dict(target_waves=24, min_seg_chunks=1, fold_max_segs=1),
 }
 
 

@@ -60,7 +60,7 @@ def test_causal_fwd_edge_lengths(la, oracle, N, sched):
 
 
 @pytest.mark.parametrize("D,M", [(32, 32), (32, 64), (64, 32), (64, 64)])
-@pytest.mark.parametrize("sched", ["default", "many_segments"])
+@pytest.mark.parametrize("sched", ["default", "many_segments", "folded_totals"])
 def test_causal_fwd_bwd_all_head_sizes(la, oracle, D, M, sched):
     B, H, N = 2, 2, 203
     Q, K, V, G = wl.random_case(200 + D + 2 * M, B, H, N, D, M)
@@ -159,7 +159,7 @@ def test_eps_values(la, oracle, eps):
     assert max(grad_errs(run_bwd(la, Q, K, V, G, eps), gref)) <= tol_for(N)
 
 
-@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments", "folded_totals"])
 @pytest.mark.parametrize("N", [1, 17, 64, 257, 1000])
 def test_global_fwd(la, oracle, N, sched):
     B, H, D, M = 2, 2, 64, 64
@@ -207,7 +207,7 @@ def test_bf16_backward_on_small_inputs(la, oracle, B, H, N, D, M, sched, eps):
         assert e <= 1e-2, "non-causal " + name
 
 
-@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments", "folded_totals"])
 @pytest.mark.parametrize("N", [1, 15, 16, 17, 64, 257, 1000])
 def test_global_bwd_edge_lengths(la, oracle, N, sched):
     B, H, D, M = 2, 2, 64, 64
@@ -344,7 +344,7 @@ def test_multi_step_decode_equals_single_steps_bit_for_bit(la, oracle, D, M, bf1
     assert rel_err(S2.cpu().numpy(), So) <= 1e-4
 
 
-@pytest.mark.parametrize("sched", ["default", "many_segments"])
+@pytest.mark.parametrize("sched", ["default", "many_segments", "folded_totals"])
 def test_bf16_tensors_fp32_state(la, oracle, sched):
     B, H, N, D, M = 2, 2, 300, 64, 64
     Q, K, V, G = maybe_bf16(wl.random_case(700, B, H, N, D, M, scale=0.125), True)
@@ -360,7 +360,7 @@ def test_bf16_tensors_fp32_state(la, oracle, sched):
         assert e <= tol_for(N, True), name
 
 
-@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments", "folded_totals"])
 def test_forward_with_state_in_and_out(la, oracle, sched):
     """A sequence processed in two pieces through la_causal_fwd_state, then continued token by
     token with la_recurrent_step, reproduces the one-shot causal forward (eq. 12 == eq. 20)."""
@@ -455,7 +455,7 @@ def test_backward_with_state_head_sizes_and_recompute(la, oracle, D, M, reuse):
         assert rel_err(got[3], ref[3]) <= tol_for(N) and rel_err(got[4], ref[4]) <= tol_for(N), sched
 
 
-@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments"])
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments", "folded_totals"])
 def test_backward_chained_over_two_pieces_equals_the_uncut_sequence(la, oracle, sched):
     """Forward piece by piece through the state, backward piece by piece in reverse through the
     state gradient: the gradients equal those of the uncut sequence (oracle: Algorithm 1 backward
