@@ -18,7 +18,9 @@
  *   recurrent_step                   eq. 16-20 (s_i, z_i update, then read-out)
  *   global_fwd_quadratic             eq. 3 with the same sim                    (definition)
  *   global_fwd_linear                eq. 5 / eq. 6
- *   causal_numerator_fwd / _bwd      Algorithm 1, forward and backward, as printed
+ *   causal_numerator_fwd / _bwd      the numerator of eq. 9 and its gradients eq. 13-15
+ *                                    (what Algorithm 1 computes), each as a cumulative
+ *                                    sum of outer products applied per position
  *                                    (takes already-mapped phi(Q), phi(K))
  *   causal_bwd_quadratic             gradient of eq. 8 by brute force           (definition)
  *   global_bwd_quadratic             gradient of eq. 3 by brute force           (definition)
@@ -30,8 +32,8 @@
  *                                    section 3.4 with its hidden state handed in and out
  *   causal_bwd_state                 backpropagation through time for that RNN: the
  *                                    loss gradient also arrives at (S_N, Z_N) and leaves
- *                                    at (S_0, Z_0); same two loops as Algorithm 1 backward
- *   causal_bwd_linear                Algorithm 1 backward applied to values
+ *                                    at (S_0, Z_0); one sweep forward in time, one backward
+ *   causal_bwd_linear                eq. 13-15 applied to values
  *                                    augmented with a column of ones, then the
  *                                    chain rule through phi (the paper leaves the
  *                                    denominator and the fraction to autograd,
@@ -51,7 +53,7 @@
  * Layout: every tensor is row-major [BH, N, feature]; the BH slabs (one per
  * batch element and head) are independent problems.  OpenMP runs over slabs
  * only; inside a slab all sums run in ascending token order (descending for
- * the reverse loop of Algorithm 1).
+ * the sums over j >= i).
  *
  * Pins (tests/test_oracle_*.py): prefix == quadratic == stepwise; linear
  * backward == brute-force backward == central finite differences == autograd
@@ -288,59 +290,59 @@ void la_oracle_global_fwd_linear(const double *Q, const double *K, const double 
 }
 
 /* ------------------------------------------------------------------------ */
-/* Algorithm 1, forward: S <- S + phi(K_i) V_i^T ; Vbar_i <- phi(Q_i) S.      */
+/* The numerator of eq. 9 and its three gradients (eq. 13, 14, 15) are all   */
+/* of one form: a cumulative sum of outer products, applied at every         */
+/* position to a vector of that position,                                     */
+/*     T_i = sum over j on one side of i (i included) of a_j b_j^T  (C x M),  */
+/*     out_i = T_i^T x_i  (length M)   or   out_i = T_i x_i  (length C).       */
+/* This routine is that form and nothing else: it keeps the running T,       */
+/* walks the positions upwards (j <= i) or downwards (j >= i), adds a_i b_i^T */
+/* first (the sums are inclusive) and then applies T.  One slab.              */
+enum { SUM_UP_TO_I = 0, SUM_FROM_I_ON = 1 };
+enum { APPLY_T_TRANSPOSED = 0, APPLY_T = 1 };
+static void cumulative_outer_apply(const double *a, const double *b, const double *x,
+                                   double *out, int N, int C, int M, int side, int how) {
+    double *T = (double *)calloc((size_t)C * M, sizeof(double));
+    for (int step = 0; step < N; ++step) {
+        const int i = side == SUM_UP_TO_I ? step : N - 1 - step;
+        for (int d = 0; d < C; ++d)
+            for (int e = 0; e < M; ++e)
+                T[(size_t)d * M + e] += a[(size_t)i * C + d] * b[(size_t)i * M + e];
+        if (how == APPLY_T_TRANSPOSED) {         /* x_i has C entries, out_i has M */
+            for (int e = 0; e < M; ++e) {
+                double acc = 0.0;
+                for (int d = 0; d < C; ++d) acc += x[(size_t)i * C + d] * T[(size_t)d * M + e];
+                out[(size_t)i * M + e] = acc;
+            }
+        } else {                                 /* x_i has M entries, out_i has C */
+            for (int d = 0; d < C; ++d) {
+                double acc = 0.0;
+                for (int e = 0; e < M; ++e) acc += x[(size_t)i * M + e] * T[(size_t)d * M + e];
+                out[(size_t)i * C + d] = acc;
+            }
+        }
+    }
+    free(T);
+}
+
+/* eq. 9, numerator: Vbar_i = (sum_{j<=i} phi(K_j) V_j^T)^T phi(Q_i).          */
 /* Inputs are already mapped (fQ = phi(Q), fK = phi(K)); one slab.            */
 static void numerator_fwd_slab(const double *fQ, const double *fK, const double *V,
                                double *Vbar, int N, int C, int M) {
-    double *S = (double *)calloc((size_t)C * M, sizeof(double));
-    for (int i = 0; i < N; ++i) {
-        for (int d = 0; d < C; ++d)
-            for (int e = 0; e < M; ++e)
-                S[(size_t)d * M + e] += fK[(size_t)i * C + d] * V[(size_t)i * M + e];
-        for (int e = 0; e < M; ++e) {
-            double a = 0.0;
-            for (int d = 0; d < C; ++d) a += fQ[(size_t)i * C + d] * S[(size_t)d * M + e];
-            Vbar[(size_t)i * M + e] = a;
-        }
-    }
-    free(S);
+    cumulative_outer_apply(fK, V, fQ, Vbar, N, C, M, SUM_UP_TO_I, APPLY_T_TRANSPOSED);
 }
 
-/* Algorithm 1, backward.  First loop, i = 1..N: rebuild S, emit the gradient */
-/* for phi(Q_i) = G_i S^T (eq. 13).  Second loop, i = N..1: S <- S + phi(Q_i) */
-/* G_i^T, then emit grad V_i = S^T phi(K_i) (eq. 15) and grad phi(K_i) = S V_i */
-/* (eq. 14); the update comes first because both sums start at j = i.         */
+/* Its gradients for an upstream G = dL/dVbar:                               */
+/*   eq. 13  grad phi(Q_i) = (sum_{j<=i} phi(K_j) V_j^T) G_i                  */
+/*   eq. 14  grad phi(K_i) = (sum_{j>=i} phi(Q_j) G_j^T) V_i                  */
+/*   eq. 15  grad V_i      = (sum_{j>=i} phi(Q_j) G_j^T)^T phi(K_i)           */
+/* (each sum rebuilt by its own sweep: nothing is stored per position).      */
 static void numerator_bwd_slab(const double *fQ, const double *fK, const double *V,
                                const double *G, double *gQ, double *gK, double *gV,
                                int N, int C, int M) {
-    double *S = (double *)calloc((size_t)C * M, sizeof(double));
-    for (int i = 0; i < N; ++i) {
-        for (int d = 0; d < C; ++d)
-            for (int e = 0; e < M; ++e)
-                S[(size_t)d * M + e] += fK[(size_t)i * C + d] * V[(size_t)i * M + e];
-        for (int d = 0; d < C; ++d) {
-            double a = 0.0;
-            for (int e = 0; e < M; ++e) a += G[(size_t)i * M + e] * S[(size_t)d * M + e];
-            gQ[(size_t)i * C + d] = a;
-        }
-    }
-    memset(S, 0, sizeof(double) * (size_t)C * M);
-    for (int i = N - 1; i >= 0; --i) {
-        for (int d = 0; d < C; ++d)
-            for (int e = 0; e < M; ++e)
-                S[(size_t)d * M + e] += fQ[(size_t)i * C + d] * G[(size_t)i * M + e];
-        for (int e = 0; e < M; ++e) {
-            double a = 0.0;
-            for (int d = 0; d < C; ++d) a += S[(size_t)d * M + e] * fK[(size_t)i * C + d];
-            gV[(size_t)i * M + e] = a;
-        }
-        for (int d = 0; d < C; ++d) {
-            double a = 0.0;
-            for (int e = 0; e < M; ++e) a += S[(size_t)d * M + e] * V[(size_t)i * M + e];
-            gK[(size_t)i * C + d] = a;
-        }
-    }
-    free(S);
+    cumulative_outer_apply(fK, V, G, gQ, N, C, M, SUM_UP_TO_I, APPLY_T);
+    cumulative_outer_apply(fQ, G, V, gK, N, C, M, SUM_FROM_I_ON, APPLY_T);
+    cumulative_outer_apply(fQ, G, fK, gV, N, C, M, SUM_FROM_I_ON, APPLY_T_TRANSPOSED);
 }
 
 void la_oracle_causal_numerator_fwd(const double *fQ, const double *fK, const double *V,
@@ -417,10 +419,10 @@ void la_oracle_causal_bwd_quadratic(const double *Q, const double *K, const doub
 
 /* Linear-time gradient.  Write the fraction as num_i / den_i with            */
 /*   [num_i, den_i - eps] = phi(Q_i)^T sum_{j<=i} phi(K_j) [V_j, 1]^T,         */
-/* i.e. the numerator of Algorithm 1 on values augmented with a ones column.  */
+/* i.e. the numerator of eq. 9 on values augmented with a ones column.        */
 /* Its upstream gradient is Gt_i = [G_i / den_i, -(G_i . O_i) / den_i]         */
-/* (quotient rule).  Algorithm 1 backward on (phi(Q), phi(K), [V,1], Gt) then  */
-/* gives the gradients for phi(Q), phi(K) and the augmented values; the ones  */
+/* (quotient rule).  eq. 13-15 on (phi(Q), phi(K), [V,1], Gt) then              */
+/* give the gradients for phi(Q), phi(K) and the augmented values; the ones   */
 /* column's own gradient is dropped, and the chain rule through phi finishes. */
 void la_oracle_causal_bwd_linear(const double *Q, const double *K, const double *V,
                                  const double *G, double *dQ, double *dK, double *dV,

@@ -156,7 +156,7 @@ def global_fwd_linear(Q, K, V, eps=1e-6):
 
 
 def causal_numerator_fwd(fQ, fK, V):
-    """Algorithm 1 forward on already-mapped phi(Q), phi(K): the numerator."""
+    """The numerator of eq. 9 on already-mapped phi(Q), phi(K) (what Algorithm 1's forward returns)."""
     lib = _load()
     BH, N, C, M = _slabs(fQ, V)
     fQ, pq = _c(fQ); fK, pk = _c(fK); V, pv = _c(V)
@@ -167,7 +167,7 @@ def causal_numerator_fwd(fQ, fK, V):
 
 
 def causal_numerator_bwd(fQ, fK, V, G):
-    """Algorithm 1 backward: gradients of the numerator for phi(Q), phi(K), V."""
+    """eq. 13-15: gradients of that numerator for phi(Q), phi(K), V."""
     lib = _load()
     BH, N, C, M = _slabs(fQ, V)
     fQ, pq = _c(fQ); fK, pk = _c(fK); V, pv = _c(V); G, pg = _c(G)
@@ -200,7 +200,7 @@ def causal_bwd_quadratic(Q, K, V, G, eps=1e-6):
 
 
 def causal_bwd_linear(Q, K, V, G, eps=1e-6):
-    """Algorithm 1 backward on ones-augmented values + chain rule; O(N D M)."""
+    """eq. 13-15 on ones-augmented values + chain rule; O(N D M)."""
     return _bwd("la_oracle_causal_bwd_linear", Q, K, V, G, eps)
 
 
