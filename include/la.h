@@ -28,7 +28,11 @@
  *   Sizes      B, H, N >= 1.  N needs no alignment.  D and M must each be 32 or
  *              64 (LA_ERR_UNSUPPORTED otherwise).  B*H*N*max(D,M) < 2^40.
  *   eps        den_i = phi(Q_i) . Z_i + eps, added once to the finished dot
- *              product; eps >= 0 (0 is legal: phi > 0 keeps den positive).
+ *              product; eps >= 0.  With eps = 0 a denominator can still be exactly
+ *              0 in fp32: phi(x) = exp(x) underflows to 0 for x below about -87, and
+ *              if that holds for every key up to a token (or for all of its
+ *              queries), its output and the gradients that pass through it are
+ *              not finite.  Pass eps > 0 where inputs that negative can occur.
  *   Stream     `stream` is a hipStream_t passed as void*; NULL is the default
  *              stream.  Every call only enqueues work and returns without
  *              synchronising.
@@ -42,9 +46,9 @@
  *              the argument checks.
  *   Determinism No floating-point atomics: the same call on the same inputs
  *              gives bit-identical results.
- *   Threads    No global mutable state apart from the optional profiling hook
- *              at the end of this file; calls from several host threads are
- *              safe as long as they do not share output or workspace buffers.
+ *   Threads    No global mutable state (la_causal_fwd_noalloc's built-in scratch
+ *              array aside); calls from several host threads are safe as long as
+ *              they do not share output or workspace buffers.
  *   Tuning     Three environment variables, read at every call, override the
  *              segment schedule (for tests and experiments): LA_TARGET_WAVES
  *              (default 2048: wavefronts wanted in flight), LA_MIN_SEG_CHUNKS
@@ -96,8 +100,9 @@ int la_version(void);
  * possible: then ws may be NULL), or 0 for invalid sizes (the entry point
  * itself reports the error).  The workspace holds per-segment partial states
  * (the running sums of eq. 10-11 cut at segment borders, so that one long
- * sequence can occupy many compute units) and, for the backward, two fp32
- * scalars per token.
+ * sequence can occupy many compute units) and, for the backward, three fp32
+ * scalars per token (1/den, the gradient that reaches den, and room for den
+ * itself when the caller does not pass it): no N x M buffer.
  */
 size_t la_causal_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
 size_t la_causal_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t);
@@ -146,6 +151,12 @@ int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float
                         const float *z0, void *O, float *den, float *S1, float *z1,
                         int B, int H, int N, int D, int M, float eps, la_dtype t,
                         void *ws, size_t ws_bytes, void *stream);
+/* The same on token-major tensors (see la_causal_fwd_bnhd): Q, K [B,N,H,D], V, O [B,N,H,M];
+ * den [B,H,N] and the states [B,H,D,M], [B,H,D] keep their layouts. */
+int la_causal_fwd_state_bnhd(const void *Q, const void *K, const void *V, const float *S0,
+                             const float *z0, void *O, float *den, float *S1, float *z1,
+                             int B, int H, int N, int D, int M, float eps, la_dtype t,
+                             void *ws, size_t ws_bytes, void *stream);
 
 /*
  * Causal linear attention, backward (eq. 13-15 / Algorithm 1 applied to the
@@ -191,6 +202,13 @@ int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float
                         const void *dO, const float *dS1, const float *dz1, void *dQ, void *dK,
                         void *dV, float *dS0, float *dz0, int B, int H, int N, int D, int M,
                         float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream);
+/* The same on token-major tensors: Q, K, dQ, dK [B,N,H,D]; V, O, dO, dV [B,N,H,M]; den and
+ * the state tensors keep their layouts; O, den, fwd_ws from la_causal_fwd_state_bnhd. */
+int la_causal_bwd_state_bnhd(const void *Q, const void *K, const void *V, const float *S0,
+                             const float *z0, const void *O, const float *den, const void *fwd_ws,
+                             const void *dO, const float *dS1, const float *dz1, void *dQ, void *dK,
+                             void *dV, float *dS0, float *dz0, int B, int H, int N, int D, int M,
+                             float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream);
 
 /*
  * la_causal_fwd and la_causal_bwd on tensors laid out [B,N,H,.] (token-major, the heads of a
@@ -280,15 +298,17 @@ int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, fl
                        int T, int B, int H, int D, int M, float eps, la_dtype t, void *stream);
 
 /*
- * Optional profiling hook (measurement aid, not part of the method).  Between
- * la_profile_begin(mask) and la_profile_end() every launch of a kernel whose
- * bit (1u << la_kernel_id) is set in `mask` is bracketed by two HIP events on
- * the stream it is launched on.  la_profile_end waits for those events, adds
- * the elapsed milliseconds per kernel into ms_total[LA_K_COUNT] and the number
- * of launches into launches[LA_K_COUNT] (either may be NULL), and switches the
- * hook off.  Process-wide, guarded by a mutex; at most 8192 launches are
- * recorded per window.  Both return LA_OK or LA_ERR_HIP.
+ * Optional profiling hook (measurement aid, not part of the method).  The caller creates a
+ * la_profile object and owns it.  Between la_profile_begin(p, mask) and la_profile_end(p, ...)
+ * every launch that THE CALLING THREAD makes of a kernel whose bit (1u << la_kernel_id) is set
+ * in `mask` is bracketed by two HIP events on the stream it is launched on.  la_profile_end
+ * waits for those events, adds the elapsed milliseconds per kernel into ms_total[LA_K_COUNT]
+ * and the number of launches into launches[LA_K_COUNT] (either may be NULL), and detaches the
+ * object from the thread.  At most 8192 launches are recorded per window.  Nothing is shared
+ * between threads or objects; an object must be used by one thread at a time.  begin / end
+ * return LA_OK, LA_ERR_NULL or LA_ERR_HIP; la_profile_create returns NULL when out of memory.
  */
+typedef struct la_profile la_profile;
 typedef enum {
     LA_K_SEG_KV = 0,   /* per-segment sums of phi(K)^T V and phi(K)            */
     LA_K_SCAN = 1,     /* scan over the segment sums                           */
@@ -302,8 +322,10 @@ typedef enum {
 } la_kernel_id;
 
 const char *la_kernel_name(int kernel_id);
-int la_profile_begin(unsigned mask);
-int la_profile_end(float *ms_total, int *launches);
+la_profile *la_profile_create(void);
+void la_profile_destroy(la_profile *p);
+int la_profile_begin(la_profile *p, unsigned mask);
+int la_profile_end(la_profile *p, float *ms_total, int *launches);
 
 #ifdef __cplusplus
 }

@@ -22,6 +22,7 @@ LA_NOALLOC_SCRATCH_BYTES = 40 << 20
 EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_causal_bwd_workspace",
            "la_global_fwd_workspace", "la_global_bwd_workspace", "la_causal_fwd", "la_causal_fwd_state",
            "la_causal_bwd", "la_causal_bwd_state", "la_causal_fwd_bnhd", "la_causal_bwd_bnhd",
+           "la_causal_fwd_state_bnhd", "la_causal_bwd_state_bnhd", "la_profile_create", "la_profile_destroy",
            "la_global_fwd", "la_global_bwd", "la_global_fwd_bnhd", "la_global_bwd_bnhd",
            "la_recurrent_step", "la_recurrent_steps", "la_causal_fwd_noalloc", "la_kernel_name", "la_profile_begin",
            "la_profile_end")
@@ -67,6 +68,10 @@ def _load() -> ctypes.CDLL:
     lib.la_causal_bwd_bnhd.argtypes = lib.la_causal_bwd.argtypes
     lib.la_causal_bwd_state.restype = i
     lib.la_causal_bwd_state.argtypes = [vp] * 16 + [i, i, i, i, i, f, i, vp, sz, vp]
+    lib.la_causal_fwd_state_bnhd.restype = i
+    lib.la_causal_fwd_state_bnhd.argtypes = lib.la_causal_fwd_state.argtypes
+    lib.la_causal_bwd_state_bnhd.restype = i
+    lib.la_causal_bwd_state_bnhd.argtypes = lib.la_causal_bwd_state.argtypes
     lib.la_global_fwd.restype = i
     lib.la_global_fwd.argtypes = [vp, vp, vp, vp, vp, i, i, i, i, i, f, i, vp, sz, vp]
     lib.la_global_bwd.restype = i
@@ -81,10 +86,14 @@ def _load() -> ctypes.CDLL:
     lib.la_recurrent_steps.argtypes = [vp] * 6 + [i, i, i, i, i, f, i, vp]
     lib.la_kernel_name.restype = ctypes.c_char_p
     lib.la_kernel_name.argtypes = [i]
+    lib.la_profile_create.restype = vp
+    lib.la_profile_create.argtypes = []
+    lib.la_profile_destroy.restype = None
+    lib.la_profile_destroy.argtypes = [vp]
     lib.la_profile_begin.restype = i
-    lib.la_profile_begin.argtypes = [ctypes.c_uint]
+    lib.la_profile_begin.argtypes = [vp, ctypes.c_uint]
     lib.la_profile_end.restype = i
-    lib.la_profile_end.argtypes = [ctypes.POINTER(f), ctypes.POINTER(i)]
+    lib.la_profile_end.argtypes = [vp, ctypes.POINTER(f), ctypes.POINTER(i)]
     return lib
 
 
@@ -151,39 +160,128 @@ def la_global_bwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
     return int(_lib.la_global_bwd_workspace(B, H, N, D, M, dtype_code))
 
 
+# ---- argument checks -----------------------------------------------------------------------------
+# The C ABI sees pointers and sizes only: a tensor that is shorter, of another element type or on
+# another device than the sizes imply would make a kernel read or write past its allocation.
+# Every wrapper therefore derives the sizes from Q and V and checks every other tensor against
+# them before the call (ValueError / TypeError, nothing is launched).
+
+def _like(name, t, shape, dtype, device, optional=False):
+    if t is None:
+        if optional:
+            return
+        raise ValueError(f"{name} is required")
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name} must be a torch.Tensor")
+    if tuple(t.shape) != tuple(shape):
+        raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
+    if t.dtype != dtype:
+        raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
+    if t.device != device:
+        raise ValueError(f"{name}: device {t.device}, expected {device}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+
+
+def _bytes(name, t, device):
+    """A workspace: any contiguous tensor on the same device (its size is passed along)."""
+    if t is None:
+        return
+    if not isinstance(t, torch.Tensor) or t.device != device or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous tensor on {device}")
+
+
+class _Sizes:
+    """B, H, N, D, M and the shapes that follow from Q and V ([B,H,N,.], or [B,N,H,.] when
+    token_major); `features` selects the element-type code."""
+
+    def __init__(self, Q, V, token_major=False, features=False):
+        if not isinstance(Q, torch.Tensor) or not isinstance(V, torch.Tensor):
+            raise TypeError("Q and V must be torch.Tensors")
+        if Q.dim() != 4 or V.dim() != 4:
+            raise ValueError("Q and V must have four dimensions")
+        self.t = _dtype_code(Q, features)
+        if token_major:
+            self.B, self.N, self.H, self.D = Q.shape
+        else:
+            self.B, self.H, self.N, self.D = Q.shape
+        self.M = V.shape[-1]
+        self.qk = tuple(Q.shape)
+        self.v = tuple(Q.shape[:-1]) + (self.M,)
+        self.rows = (self.B, self.H, self.N)              # den: always [B, H, N]
+        self.S, self.z = (self.B, self.H, self.D, self.M), (self.B, self.H, self.D)
+        self.dtype, self.dev = Q.dtype, Q.device
+        self.dims = (self.B, self.H, self.N, self.D, self.M)
+
+    def inputs(self, Q, K, V):
+        _like("Q", Q, self.qk, self.dtype, self.dev)
+        _like("K", K, self.qk, self.dtype, self.dev)
+        _like("V", V, self.v, self.dtype, self.dev)
+
+    def forward(self, Q, K, V, O, den):
+        self.inputs(Q, K, V)
+        _like("O", O, self.v, self.dtype, self.dev)
+        _like("den", den, self.rows, torch.float32, self.dev, optional=True)
+
+    def backward(self, Q, K, V, O, den, dO, dQ, dK, dV, fwd_ws):
+        self.inputs(Q, K, V)
+        _like("O", O, self.v, self.dtype, self.dev, optional=True)
+        _like("den", den, self.rows, torch.float32, self.dev, optional=True)
+        _like("dO", dO, self.v, self.dtype, self.dev)
+        _like("dQ", dQ, self.qk, self.dtype, self.dev)
+        _like("dK", dK, self.qk, self.dtype, self.dev)
+        _like("dV", dV, self.v, self.dtype, self.dev)
+        _bytes("fwd_ws", fwd_ws, self.dev)
+
+    def state(self, **pairs):
+        """fp32 state tensors by name: S-like [B,H,D,M] for names starting with S / dS, z-like
+        [B,H,D] otherwise; all optional."""
+        for name, t in pairs.items():
+            shape = self.S if name.lstrip("d").startswith("S") else self.z
+            _like(name, t, shape, torch.float32, self.dev, optional=True)
+
+
+def _fwd_ws_bytes(fwd_ws, need, name):
+    """A forward workspace handed to a backward must be at least as large as the forward's query."""
+    if fwd_ws is not None and fwd_ws.numel() * fwd_ws.element_size() < need:
+        raise ValueError(f"{name}: fwd_ws holds {fwd_ws.numel() * fwd_ws.element_size()} bytes, the forward "
+                         f"of these sizes uses {need}")
+
+
 def la_causal_fwd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None, features=False):
     """O [B,H,N,M] <- causal linear attention of Q, K [B,H,N,D], V [B,H,N,M]; den [B,H,N] fp32
     (optional) receives the denominators.  Enqueues on `stream` (default: torch's current)."""
-    B, H, N, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_causal_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
-                              float(eps), t, wp, wb, _stream(stream)), "la_causal_fwd")
+    sz = _Sizes(Q, V, features=features)
+    sz.forward(Q, K, V, O, den)
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(*sz.dims, sz.t), Q.device)
+    _check(_lib.la_causal_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), *sz.dims,
+                              float(eps), sz.t, wp, wb, _stream(stream)), "la_causal_fwd")
     return ws
 
 
 def la_causal_fwd_noalloc(Q, K, V, O, den=None, eps=1e-6, stream=None, features=False):
     """la_causal_fwd without a workspace argument: the segment states live in the library's
     built-in scratch array (LA_NOALLOC_SCRATCH_BYTES); nothing is allocated by the call."""
-    B, H, N, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    _check(_lib.la_causal_fwd_noalloc(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D,
-                                      M, float(eps), t, _stream(stream)), "la_causal_fwd_noalloc")
+    sz = _Sizes(Q, V, features=features)
+    sz.forward(Q, K, V, O, den)
+    _check(_lib.la_causal_fwd_noalloc(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), *sz.dims,
+                                      float(eps), sz.t, _stream(stream)), "la_causal_fwd_noalloc")
 
 
 def la_causal_fwd_state(Q, K, V, O, den=None, S0=None, z0=None, S1=None, z1=None, eps=1e-6, ws=None,
-                        stream=None, features=False):
+                        stream=None, features=False, token_major=False):
     """Causal forward that starts from the state (S0, z0) (None: zero) and returns the state
-    after the last token in (S1, z1) (None: not wanted); all four fp32 [B,H,D,M] / [B,H,D]."""
-    B, H, N, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_causal_fwd_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O),
-                                    _ptr(den), _ptr(S1), _ptr(z1), B, H, N, D, M, float(eps), t,
-                                    wp, wb, _stream(stream)), "la_causal_fwd_state")
+    after the last token in (S1, z1) (None: not wanted); all four fp32 [B,H,D,M] / [B,H,D].
+    token_major: Q, K, V, O are [B,N,H,.] (la_causal_fwd_state_bnhd)."""
+    sz = _Sizes(Q, V, token_major=token_major, features=features)
+    sz.forward(Q, K, V, O, den)
+    sz.state(S0=S0, z0=z0, S1=S1, z1=z1)
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(*sz.dims, sz.t), Q.device)
+    fn = _lib.la_causal_fwd_state_bnhd if token_major else _lib.la_causal_fwd_state
+    _check(fn(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O), _ptr(den), _ptr(S1), _ptr(z1),
+              *sz.dims, float(eps), sz.t, wp, wb, _stream(stream)), "la_causal_fwd_state")
     return ws
 
 
@@ -192,24 +290,25 @@ def la_causal_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=Non
     """dQ, dK, dV <- gradients of causal linear attention for upstream dO; O and den are the
     forward results (den None: recomputed; O is not read and may be None).  fwd_ws (optional) is
     the workspace tensor la_causal_fwd returned for the same call: its segment states are reused."""
-    B, H, N, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
+    sz = _Sizes(Q, V, features=features)
+    sz.backward(Q, K, V, O, den, dO, dQ, dK, dV, fwd_ws)
+    _fwd_ws_bytes(fwd_ws, la_causal_fwd_workspace(*sz.dims, sz.t), "la_causal_bwd")
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(*sz.dims, sz.t), Q.device)
     _check(_lib.la_causal_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
-                              _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
+                              _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), *sz.dims, float(eps), sz.t,
                               wp, wb, _stream(stream)), "la_causal_bwd")
     return ws
 
 
 def la_causal_fwd_bnhd(Q, K, V, O, den=None, eps=1e-6, ws=None, stream=None, features=False):
     """la_causal_fwd on token-major tensors: Q, K [B,N,H,D], V, O [B,N,H,M]; den stays [B,H,N]."""
-    B, N, H, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_causal_fwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
-                                   float(eps), t, wp, wb, _stream(stream)), "la_causal_fwd_bnhd")
+    sz = _Sizes(Q, V, token_major=True, features=features)
+    sz.forward(Q, K, V, O, den)
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_causal_fwd_workspace(*sz.dims, sz.t), Q.device)
+    _check(_lib.la_causal_fwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), *sz.dims,
+                                   float(eps), sz.t, wp, wb, _stream(stream)), "la_causal_fwd_bnhd")
     return ws
 
 
@@ -217,43 +316,46 @@ def la_causal_bwd_bnhd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, strea
                        features=False):
     """la_causal_bwd on token-major tensors ([B,N,H,.]; den [B,H,N]); fwd_ws from
     la_causal_fwd_bnhd."""
-    B, N, H, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
+    sz = _Sizes(Q, V, token_major=True, features=features)
+    sz.backward(Q, K, V, O, den, dO, dQ, dK, dV, fwd_ws)
+    _fwd_ws_bytes(fwd_ws, la_causal_fwd_workspace(*sz.dims, sz.t), "la_causal_bwd_bnhd")
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(*sz.dims, sz.t), Q.device)
     _check(_lib.la_causal_bwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
-                                   _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M,
-                                   float(eps), t, wp, wb, _stream(stream)), "la_causal_bwd_bnhd")
+                                   _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), *sz.dims,
+                                   float(eps), sz.t, wp, wb, _stream(stream)), "la_causal_bwd_bnhd")
     return ws
 
 
 def la_causal_bwd_state(Q, K, V, O, den, dO, dQ, dK, dV, S0=None, z0=None, dS1=None, dz1=None,
                         dS0=None, dz0=None, eps=1e-6, ws=None, stream=None, fwd_ws=None,
-                        features=False):
+                        features=False, token_major=False):
     """la_causal_bwd for a piece whose forward started from (S0, z0): (dS1, dz1) is the gradient
     arriving at the state after the last token (None: zero), (dS0, dz0) receives the gradient
-    for (S0, z0) (None: not wanted); all fp32 [B,H,D,M] / [B,H,D]."""
-    B, H, N, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_causal_bwd_state(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O),
-                                    _ptr(den), _ptr(fwd_ws), _ptr(dO), _ptr(dS1), _ptr(dz1),
-                                    _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dS0), _ptr(dz0), B, H, N, D,
-                                    M, float(eps), t, wp, wb, _stream(stream)),
-           "la_causal_bwd_state")
+    for (S0, z0) (None: not wanted); all fp32 [B,H,D,M] / [B,H,D].  token_major: the N-sized
+    tensors are [B,N,H,.] (la_causal_bwd_state_bnhd)."""
+    sz = _Sizes(Q, V, token_major=token_major, features=features)
+    sz.backward(Q, K, V, O, den, dO, dQ, dK, dV, fwd_ws)
+    sz.state(S0=S0, z0=z0, dS1=dS1, dz1=dz1, dS0=dS0, dz0=dz0)
+    _fwd_ws_bytes(fwd_ws, la_causal_fwd_workspace(*sz.dims, sz.t), "la_causal_bwd_state")
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_causal_bwd_workspace(*sz.dims, sz.t), Q.device)
+    fn = _lib.la_causal_bwd_state_bnhd if token_major else _lib.la_causal_bwd_state
+    _check(fn(_ptr(Q), _ptr(K), _ptr(V), _ptr(S0), _ptr(z0), _ptr(O), _ptr(den), _ptr(fwd_ws),
+              _ptr(dO), _ptr(dS1), _ptr(dz1), _ptr(dQ), _ptr(dK), _ptr(dV), _ptr(dS0), _ptr(dz0),
+              *sz.dims, float(eps), sz.t, wp, wb, _stream(stream)), "la_causal_bwd_state")
     return ws
 
 
 def la_global_fwd(Q, K, V, O, eps=1e-6, ws=None, stream=None, den=None, features=False):
     """O <- non-causal linear attention (every query sees every key); den [B,H,N] fp32
     (optional) receives the denominators."""
-    B, H, N, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_global_fwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_global_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
-                              float(eps), t, wp, wb, _stream(stream)), "la_global_fwd")
+    sz = _Sizes(Q, V, features=features)
+    sz.forward(Q, K, V, O, den)
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_global_fwd_workspace(*sz.dims, sz.t), Q.device)
+    _check(_lib.la_global_fwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), *sz.dims,
+                              float(eps), sz.t, wp, wb, _stream(stream)), "la_global_fwd")
     return ws
 
 
@@ -262,24 +364,25 @@ def la_global_bwd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, stream=Non
     """dQ, dK, dV <- gradients of non-causal linear attention for upstream dO; O and den are the
     results of la_global_fwd (den None: recomputed; O is not read and may be None).  fwd_ws
     (optional) is the workspace tensor la_global_fwd returned for the same call."""
-    B, H, N, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_global_bwd_workspace(B, H, N, D, M, t), Q.device)
+    sz = _Sizes(Q, V, features=features)
+    sz.backward(Q, K, V, O, den, dO, dQ, dK, dV, fwd_ws)
+    _fwd_ws_bytes(fwd_ws, la_global_fwd_workspace(*sz.dims, sz.t), "la_global_bwd")
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_global_bwd_workspace(*sz.dims, sz.t), Q.device)
     _check(_lib.la_global_bwd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
-                              _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M, float(eps), t,
+                              _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), *sz.dims, float(eps), sz.t,
                               wp, wb, _stream(stream)), "la_global_bwd")
     return ws
 
 
 def la_global_fwd_bnhd(Q, K, V, O, eps=1e-6, ws=None, stream=None, den=None, features=False):
     """la_global_fwd on token-major tensors: Q, K [B,N,H,D], V, O [B,N,H,M]; den stays [B,H,N]."""
-    B, N, H, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_global_fwd_workspace(B, H, N, D, M, t), Q.device)
-    _check(_lib.la_global_fwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), B, H, N, D, M,
-                                   float(eps), t, wp, wb, _stream(stream)), "la_global_fwd_bnhd")
+    sz = _Sizes(Q, V, token_major=True, features=features)
+    sz.forward(Q, K, V, O, den)
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_global_fwd_workspace(*sz.dims, sz.t), Q.device)
+    _check(_lib.la_global_fwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), *sz.dims,
+                                   float(eps), sz.t, wp, wb, _stream(stream)), "la_global_fwd_bnhd")
     return ws
 
 
@@ -287,32 +390,50 @@ def la_global_bwd_bnhd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, strea
                        features=False):
     """la_global_bwd on token-major tensors ([B,N,H,.]; den [B,H,N]); fwd_ws from
     la_global_fwd_bnhd."""
-    B, N, H, D = Q.shape
-    M = V.shape[-1]
-    t = _dtype_code(Q, features)
-    ws, wp, wb = _ws(ws, la_global_bwd_workspace(B, H, N, D, M, t), Q.device)
+    sz = _Sizes(Q, V, token_major=True, features=features)
+    sz.backward(Q, K, V, O, den, dO, dQ, dK, dV, fwd_ws)
+    _fwd_ws_bytes(fwd_ws, la_global_fwd_workspace(*sz.dims, sz.t), "la_global_bwd_bnhd")
+    _bytes("ws", ws, sz.dev)
+    ws, wp, wb = _ws(ws, la_global_bwd_workspace(*sz.dims, sz.t), Q.device)
     _check(_lib.la_global_bwd_bnhd(_ptr(Q), _ptr(K), _ptr(V), _ptr(O), _ptr(den), _ptr(fwd_ws),
-                                   _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), B, H, N, D, M,
-                                   float(eps), t, wp, wb, _stream(stream)), "la_global_bwd_bnhd")
+                                   _ptr(dO), _ptr(dQ), _ptr(dK), _ptr(dV), *sz.dims,
+                                   float(eps), sz.t, wp, wb, _stream(stream)), "la_global_bwd_bnhd")
     return ws
+
+
+def _step_checks(q, k, v, S, z, out, lead, features):
+    """Shapes of the decode calls: q, k [*lead, B, H, D], v, out [*lead, B, H, M]."""
+    if not isinstance(q, torch.Tensor) or not isinstance(v, torch.Tensor):
+        raise TypeError("q and v must be torch.Tensors")
+    if q.dim() != 3 + lead or v.dim() != 3 + lead:
+        raise ValueError(f"q and v must have {3 + lead} dimensions")
+    t = _dtype_code(q, features)
+    B, H, D = q.shape[lead:]
+    M = v.shape[-1]
+    dev = q.device
+    _like("k", k, q.shape, q.dtype, dev)
+    _like("v", v, tuple(q.shape[:-1]) + (M,), q.dtype, dev)
+    _like("out", out, tuple(q.shape[:-1]) + (M,), q.dtype, dev)
+    _like("S", S, (B, H, D, M), torch.float32, dev)
+    _like("z", z, (B, H, D), torch.float32, dev)
+    return t, B, H, D, M
 
 
 def la_recurrent_step(q, k, v, S, z, out, eps=1e-6, stream=None, features=False):
     """One decode step for q, k [B,H,D], v [B,H,M]: S [B,H,D,M], z [B,H,D] (fp32) are updated
     in place, out [B,H,M] receives the attention output of the new token."""
-    B, H, D = q.shape
-    M = v.shape[-1]
+    t, B, H, D, M = _step_checks(q, k, v, S, z, out, 0, features)
     _check(_lib.la_recurrent_step(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(z), _ptr(out), B, H, D,
-                                  M, float(eps), _dtype_code(q, features), _stream(stream)),
+                                  M, float(eps), t, _stream(stream)),
            "la_recurrent_step")
 
 
 def la_recurrent_steps(q, k, v, S, z, out, eps=1e-6, stream=None, features=False):
     """T decode steps in one launch: q, k [T,B,H,D], v, out [T,B,H,M]; S, z updated in place."""
-    T, B, H, D = q.shape
-    M = v.shape[-1]
+    t, B, H, D, M = _step_checks(q, k, v, S, z, out, 1, features)
+    T = q.shape[0]
     _check(_lib.la_recurrent_steps(_ptr(q), _ptr(k), _ptr(v), _ptr(S), _ptr(z), _ptr(out), T, B, H,
-                                   D, M, float(eps), _dtype_code(q, features), _stream(stream)),
+                                   D, M, float(eps), t, _stream(stream)),
            "la_recurrent_steps")
 
 
@@ -320,17 +441,54 @@ def la_kernel_name(kernel_id: int) -> str:
     return _lib.la_kernel_name(int(kernel_id)).decode()
 
 
+class Profile:
+    """Owner of one la_profile object of the library (HIP events around selected launches made by
+    the thread that calls begin())."""
+
+    def __init__(self):
+        self._h = _lib.la_profile_create()
+        if not self._h:
+            raise MemoryError("la_profile_create failed")
+
+    def begin(self, mask: int = (1 << LA_K_COUNT) - 1) -> None:
+        _check(_lib.la_profile_begin(self._h, int(mask)), "la_profile_begin")
+
+    def end(self) -> dict:
+        """Wait for the recorded events; {kernel name: (total ms, launches)} for kernels that ran."""
+        ms = (ctypes.c_float * LA_K_COUNT)()
+        n = (ctypes.c_int * LA_K_COUNT)()
+        _check(_lib.la_profile_end(self._h, ms, n), "la_profile_end")
+        return {la_kernel_name(k): (float(ms[k]), int(n[k])) for k in range(LA_K_COUNT) if n[k] > 0}
+
+    def close(self) -> None:
+        if self._h:
+            _lib.la_profile_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+_default_profile = None
+
+
 def la_profile_begin(mask: int = (1 << LA_K_COUNT) - 1) -> None:
-    """Bracket every launch of the kernels selected by `mask` with HIP events."""
-    _check(_lib.la_profile_begin(int(mask)), "la_profile_begin")
+    """Bracket every launch (made by this thread) of the kernels selected by `mask` with HIP
+    events, using one Profile object kept by this module."""
+    global _default_profile
+    if _default_profile is None:
+        _default_profile = Profile()
+    _default_profile.begin(mask)
 
 
 def la_profile_end() -> dict:
-    """Wait for the recorded events; {kernel name: (total ms, launches)} for kernels that ran."""
-    ms = (ctypes.c_float * LA_K_COUNT)()
-    n = (ctypes.c_int * LA_K_COUNT)()
-    _check(_lib.la_profile_end(ms, n), "la_profile_end")
-    return {la_kernel_name(k): (float(ms[k]), int(n[k])) for k in range(LA_K_COUNT) if n[k] > 0}
+    """{kernel name: (total ms, launches)} since la_profile_begin."""
+    if _default_profile is None:
+        raise RuntimeError("la_profile_end without la_profile_begin")
+    return _default_profile.end()
 
 
 def raw():

@@ -5,8 +5,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
-#include <atomic>
 #include <mutex>
+#include <new>
 #include <vector>
 
 #include "../../include/la.h"
@@ -136,39 +136,46 @@ int scratch_on_current_device(void **out) {
 }
 
 // ---- optional profiling hook: HIP events around selected launches ----------------------------
+// The state lives in an object the caller owns (la_profile_create); la_profile_begin attaches it
+// to the calling thread, and only launches made by that thread are bracketed.  No process-wide
+// state, no lock.
 struct ProfRec {
     int kid;
     hipEvent_t a, b;
 };
-std::atomic<unsigned> g_prof_mask{0};
-std::mutex g_prof_mu;
-std::vector<ProfRec> g_prof_recs;
-std::vector<hipEvent_t> g_prof_pool;
-constexpr size_t kProfMaxRecs = 8192;
+}  // namespace
 
-hipEvent_t prof_event() {          // caller holds g_prof_mu
-    if (!g_prof_pool.empty()) {
-        hipEvent_t e = g_prof_pool.back();
-        g_prof_pool.pop_back();
+struct la_profile {
+    unsigned mask = 0;
+    std::vector<ProfRec> recs;
+    std::vector<hipEvent_t> pool;
+    hipEvent_t event() {
+        if (!pool.empty()) {
+            hipEvent_t e = pool.back();
+            pool.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
         return e;
     }
-    hipEvent_t e = nullptr;
-    if (hipEventCreate(&e) != hipSuccess) return nullptr;
-    return e;
-}
+};
 
-// Brackets one launch when its kernel is selected; otherwise a single relaxed load.
+namespace {
+thread_local la_profile *t_profile = nullptr;
+constexpr size_t kProfMaxRecs = 8192;
+
+// Brackets one launch when its kernel is selected; otherwise one thread-local load.
 struct ProfScope {
     hipEvent_t stop = nullptr;
     hipStream_t s;
     ProfScope(int kid, hipStream_t stream) : s(stream) {
-        if ((g_prof_mask.load(std::memory_order_relaxed) & (1u << kid)) == 0) return;
-        std::lock_guard<std::mutex> lk(g_prof_mu);
-        if (g_prof_recs.size() >= kProfMaxRecs) return;
-        hipEvent_t a = prof_event(), b = prof_event();
+        la_profile *p = t_profile;
+        if (p == nullptr || (p->mask & (1u << kid)) == 0 || p->recs.size() >= kProfMaxRecs) return;
+        hipEvent_t a = p->event(), b = p->event();
         if (a == nullptr || b == nullptr) return;
         if (hipEventRecord(a, s) != hipSuccess) return;
-        g_prof_recs.push_back({kid, a, b});
+        p->recs.push_back({kid, a, b});
         stop = b;
     }
     ~ProfScope() {
@@ -261,9 +268,9 @@ size_t la_causal_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
-    size_t bytes = 2 * align256(rows * sizeof(float));                      // rden, delta
-    if (p.nseg > 1) bytes += 2 * states_bytes(BH, p, D, M);                 // S and R states
-    bytes += align256(rows * M * esize(t)) + align256(rows * sizeof(float)); // O, den if recomputed
+    size_t bytes = 3 * align256(rows * sizeof(float));      // 1/den, delta, and den if it is recomputed
+    if (p.nseg > 1) bytes += 2 * states_bytes(BH, p, D, M); // S and R states
+    (void)t;
     return bytes;
 }
 
@@ -278,8 +285,9 @@ size_t la_global_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
-    size_t bytes = 2 * states_bytes(BH, p, D, M);                           // the two grand totals
-    bytes += align256(rows * M * esize(t)) + align256(rows * sizeof(float)); // O, den if recomputed
+    size_t bytes = 2 * states_bytes(BH, p, D, M);           // the two grand totals
+    bytes += align256(rows * sizeof(float));                // den if it is recomputed
+    (void)t;
     return bytes;
 }
 
@@ -342,10 +350,10 @@ int la_causal_fwd_noalloc(const void *Q, const void *K, const void *V, void *O, 
                           static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, nullptr, H, 0);
 }
 
-int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float *S0,
-                        const float *z0, void *O, float *den, float *S1, float *z1,
-                        int B, int H, int N, int D, int M, float eps, la_dtype t,
-                        void *ws, size_t ws_bytes, void *stream) {
+static int causal_fwd_state_impl(const void *Q, const void *K, const void *V, const float *S0,
+                                 const float *z0, void *O, float *den, float *S1, float *z1,
+                                 int B, int H, int N, int D, int M, float eps, la_dtype t,
+                                 void *ws, size_t ws_bytes, void *stream, int tok_heads) {
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
     if ((S0 == nullptr) != (z0 == nullptr) || (S1 == nullptr) != (z1 == nullptr)) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
@@ -364,7 +372,23 @@ int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float
                         {S0, (size_t)BH * D * M * 4}, {z0, (size_t)BH * D * 4}};
     if (aliased(outs, ins)) return LA_ERR_ALIAS;
     return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
-                          static_cast<hipStream_t>(stream), S0, z0, S1, z1);
+                          static_cast<hipStream_t>(stream), S0, z0, S1, z1, H, tok_heads);
+}
+
+int la_causal_fwd_state(const void *Q, const void *K, const void *V, const float *S0,
+                        const float *z0, void *O, float *den, float *S1, float *z1,
+                        int B, int H, int N, int D, int M, float eps, la_dtype t,
+                        void *ws, size_t ws_bytes, void *stream) {
+    return causal_fwd_state_impl(Q, K, V, S0, z0, O, den, S1, z1, B, H, N, D, M, eps, t, ws,
+                                 ws_bytes, stream, 0);
+}
+
+int la_causal_fwd_state_bnhd(const void *Q, const void *K, const void *V, const float *S0,
+                             const float *z0, void *O, float *den, float *S1, float *z1,
+                             int B, int H, int N, int D, int M, float eps, la_dtype t,
+                             void *ws, size_t ws_bytes, void *stream) {
+    return causal_fwd_state_impl(Q, K, V, S0, z0, O, den, S1, z1, B, H, N, D, M, eps, t, ws,
+                                 ws_bytes, stream, H > 1 ? H : 0);
 }
 
 static int causal_bwd_impl(const void *Q, const void *K, const void *V, const float *S0,
@@ -416,10 +440,9 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     const bool have_states = p.nseg > 1 && (fwd_ws != nullptr || recompute_fwd);
     if (p.nseg > 1 && fwd_ws != nullptr && !recompute_fwd)
         stS = const_cast<float *>(static_cast<const float *>(fwd_ws));
-    if (recompute_fwd) {                       // recompute the forward's denominators
-        void *Otmp = cv.take(rows * M * esize(t));
+    if (recompute_fwd) {                       // recompute the forward's denominators (no output)
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
-        const int fs = run_causal_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s, S0, z0,
+        const int fs = run_causal_fwd(Q, K, V, nullptr, dentmp, BH, N, D, M, eps, t, p, stS, s, S0, z0,
                                       nullptr, nullptr, H, tok_heads);
         if (fs != LA_OK) return fs;
         den = dentmp;
@@ -493,6 +516,15 @@ int la_causal_bwd_state(const void *Q, const void *K, const void *V, const float
                            N, D, M, eps, t, ws, ws_bytes, stream);
 }
 
+int la_causal_bwd_state_bnhd(const void *Q, const void *K, const void *V, const float *S0,
+                             const float *z0, const void *O, const float *den, const void *fwd_ws,
+                             const void *dO, const float *dS1, const float *dz1, void *dQ, void *dK,
+                             void *dV, float *dS0, float *dz0, int B, int H, int N, int D, int M,
+                             float eps, la_dtype t, void *ws, size_t ws_bytes, void *stream) {
+    return causal_bwd_impl(Q, K, V, S0, z0, O, den, fwd_ws, dO, dS1, dz1, dQ, dK, dV, dS0, dz0, B, H,
+                           N, D, M, eps, t, ws, ws_bytes, stream, H > 1 ? H : 0);
+}
+
 static int global_fwd_impl(const void *Q, const void *K, const void *V, void *O, float *den,
                            int B, int H, int N, int D, int M, float eps, la_dtype t,
                            void *ws, size_t ws_bytes, void *stream, int tok_heads) {
@@ -558,10 +590,9 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
     float *stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
     float *stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
     const int nblocks = (int)(BH * p.nseg);
-    if (den == nullptr) {                      // recompute the forward's denominators;
-        void *Otmp = cv.take(rows * M * esize(t));     // also leaves the K, V total in slot 0 of stS
-        float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
-        const int fs = run_global_fwd(Q, K, V, Otmp, dentmp, BH, N, D, M, eps, t, p, stS, s, H,
+    if (den == nullptr) {                      // recompute the forward's denominators (no output);
+        float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));   // also leaves the K, V sums in stS
+        const int fs = run_global_fwd(Q, K, V, nullptr, dentmp, BH, N, D, M, eps, t, p, stS, s, H,
                                       tok_heads);
         if (fs != LA_OK) return fs;
         den = dentmp;
@@ -670,26 +701,41 @@ const char *la_kernel_name(int kernel_id) {
     return kernel_id >= 0 && kernel_id < LA_K_COUNT ? names[kernel_id] : "unknown";
 }
 
-int la_profile_begin(unsigned mask) {
-    std::lock_guard<std::mutex> lk(g_prof_mu);
-    for (const ProfRec &r : g_prof_recs) {
-        g_prof_pool.push_back(r.a);
-        g_prof_pool.push_back(r.b);
+la_profile *la_profile_create(void) { return new (std::nothrow) la_profile(); }
+
+void la_profile_destroy(la_profile *p) {
+    if (p == nullptr) return;
+    if (t_profile == p) t_profile = nullptr;
+    for (const ProfRec &r : p->recs) {
+        (void)hipEventDestroy(r.a);
+        (void)hipEventDestroy(r.b);
     }
-    g_prof_recs.clear();
-    g_prof_mask.store(mask & ((1u << LA_K_COUNT) - 1u), std::memory_order_relaxed);
+    for (hipEvent_t e : p->pool) (void)hipEventDestroy(e);
+    delete p;
+}
+
+int la_profile_begin(la_profile *p, unsigned mask) {
+    if (p == nullptr) return LA_ERR_NULL;
+    for (const ProfRec &r : p->recs) {
+        p->pool.push_back(r.a);
+        p->pool.push_back(r.b);
+    }
+    p->recs.clear();
+    p->mask = mask & ((1u << LA_K_COUNT) - 1u);
+    t_profile = p;
     return LA_OK;
 }
 
-int la_profile_end(float *ms_total, int *launches) {
-    std::lock_guard<std::mutex> lk(g_prof_mu);
-    g_prof_mask.store(0, std::memory_order_relaxed);
+int la_profile_end(la_profile *p, float *ms_total, int *launches) {
+    if (p == nullptr) return LA_ERR_NULL;
+    if (t_profile == p) t_profile = nullptr;
+    p->mask = 0;
     int status = LA_OK;
     if (ms_total != nullptr)
         for (int k = 0; k < LA_K_COUNT; ++k) ms_total[k] = 0.f;
     if (launches != nullptr)
         for (int k = 0; k < LA_K_COUNT; ++k) launches[k] = 0;
-    for (const ProfRec &r : g_prof_recs) {
+    for (const ProfRec &r : p->recs) {
         float ms = 0.f;
         if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) {
             status = LA_ERR_HIP;
@@ -697,10 +743,10 @@ int la_profile_end(float *ms_total, int *launches) {
             if (ms_total != nullptr) ms_total[r.kid] += ms;
             if (launches != nullptr) launches[r.kid] += 1;
         }
-        g_prof_pool.push_back(r.a);
-        g_prof_pool.push_back(r.b);
+        p->pool.push_back(r.a);
+        p->pool.push_back(r.b);
     }
-    g_prof_recs.clear();
+    p->recs.clear();
     return status;
 }
 

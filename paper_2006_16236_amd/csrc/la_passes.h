@@ -76,7 +76,8 @@ struct PassArgs {
     const void *Q, *K, *V, *G;   // raw tensors, [BH, N, D] / [BH, N, M]
     const float *rden;           // [BH, N] 1/den_i             (reverse passes; written by the dQ pass)
     const float *delta;          // [BH, N] -(dO_i.O_i)/den_i   (reverse passes; written by the dQ pass)
-    void *out;                   // [BH, N, DZ]  (reverse_pass_kernel: dV)
+    void *out;                   // [BH, N, DZ]  (reverse_pass_kernel: dV; kFwd, kGlobal: may be null,
+                                 // the pass then only writes the denominators)
     void *out2;                  // reverse_pass_kernel only: dK [BH, N, D]
     float *den;                  // [BH, N] or null             (kFwd, kGlobal)
     const float *den_in;         // kDq: the forward's denominators [BH, N]
@@ -736,7 +737,9 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         }
         // uniform chunk base + one lane offset; the 16 stores differ by constants only
         T *lane_out = outs + (size_t)t0 * tso + (4 * g * tso + c);
-        if (nvalid == kChunk) {
+        if ((PASS == kFwd || PASS == kGlobal) && out_tensor == nullptr) {
+            // a forward that is run for its denominators only (uniform branch)
+        } else if (nvalid == kChunk) {
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll

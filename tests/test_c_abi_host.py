@@ -202,6 +202,55 @@ def test_binding_refuses_host_tensors(lib):
         b.la_causal_fwd(x.double(), x, x, x)
 
 
+def test_binding_checks_every_tensor_against_the_sizes(lib):
+    """The C ABI cannot see tensor sizes, so the binding must: a tensor of the wrong shape,
+    element type or device is refused before any call (host tensors suffice to show it: the
+    shape and dtype checks come first)."""
+    import torch
+    from paper_2006_16236_amd import binding as b
+    B, H, N, D, M = 2, 3, 20, 64, 32
+    Q, K = torch.zeros(B, H, N, D), torch.zeros(B, H, N, D)
+    V, O, dO = torch.zeros(B, H, N, M), torch.zeros(B, H, N, M), torch.zeros(B, H, N, M)
+    den = torch.zeros(B, H, N)
+    dQ, dK, dV = torch.zeros_like(Q), torch.zeros_like(K), torch.zeros_like(V)
+
+    def refused(fn, *args, match, **kw):
+        with pytest.raises(ValueError, match=match):
+            fn(*args, **kw)
+
+    refused(b.la_causal_fwd, Q, K[:, :, :-1].contiguous(), V, O, match="K: shape")          # shorter K
+    refused(b.la_causal_fwd, Q, K, V[..., :16].contiguous(), O, match="O: shape")           # V, O disagree
+    refused(b.la_causal_fwd, Q, K, V, O[:, :1].contiguous(), match="O: shape")
+    refused(b.la_causal_fwd, Q, K.bfloat16(), V, O, match="K: dtype")                       # fp32 Q, bf16 K
+    refused(b.la_causal_fwd, Q, K, V, O, den.double(), match="den: dtype")                  # fp64 den
+    refused(b.la_causal_fwd, Q, K, V, O, den[:, :, :-1].contiguous(), match="den: shape")
+    refused(b.la_causal_fwd, Q, K, V.transpose(1, 2).contiguous().transpose(1, 2), O, match="V must be contiguous")
+    refused(b.la_causal_fwd_noalloc, Q, K, V[:, :, 1:].contiguous(), O, match="V: shape")
+    refused(b.la_global_fwd, Q, K, V, O, den=den.half(), match="den: dtype")
+    refused(b.la_causal_bwd, Q, K, V, None, den, dO.bfloat16(), dQ, dK, dV, match="dO: dtype")   # autocast dO
+    refused(b.la_causal_bwd, Q, K, V, None, den, dO, dQ, dK[:, :, :4].contiguous(), dV, match="dK: shape")
+    refused(b.la_causal_bwd, Q, K, V, None, den, dO, dQ, dK, dQ, match="dV: shape")
+    refused(b.la_global_bwd, Q, K, V, O[..., :8].contiguous(), den, dO, dQ, dK, dV, match="O: shape")
+    refused(b.la_causal_bwd, Q, K, V, None, den, dO, dQ, dK, dV, fwd_ws=[1, 2], match="fwd_ws")
+    # token-major: Q is [B, N, H, D]; den stays [B, H, N]
+    Qt, Vt = Q.transpose(1, 2).contiguous(), V.transpose(1, 2).contiguous()
+    refused(b.la_causal_fwd_bnhd, Qt, Qt, Vt, Vt.clone(), torch.zeros(B, N, H), match="den: shape")
+    refused(b.la_global_fwd_bnhd, Qt, K, Vt, Vt.clone(), match="K: shape")
+    # state tensors are fp32 [B,H,D,M] / [B,H,D]
+    S, z = torch.zeros(B, H, D, M), torch.zeros(B, H, D)
+    refused(b.la_causal_fwd_state, Q, K, V, O, den, S.double(), z, match="S0: dtype")
+    refused(b.la_causal_fwd_state, Q, K, V, O, den, S, z, S, z[:, :, :-1].contiguous(), match="z1: shape")
+    refused(b.la_causal_bwd_state, Q, K, V, None, den, dO, dQ, dK, dV, dS1=S.transpose(2, 3).contiguous(),
+            dz1=z, match="dS1: shape")
+    q, k, v, out = torch.zeros(B, H, D), torch.zeros(B, H, D), torch.zeros(B, H, M), torch.zeros(B, H, M)
+    refused(b.la_recurrent_step, q, k, v, S.half(), z, out, match="S: dtype")
+    refused(b.la_recurrent_step, q, k[:, :-1].contiguous(), v, S, z, out, match="k: shape")
+    refused(b.la_recurrent_steps, q[None], k[None], v[None], S, z, out, match="out: shape")
+    # everything consistent: the only objection left is that these are host tensors
+    refused(b.la_causal_bwd, Q, K, V, None, den, dO, dQ, dK, dV, match="device tensors")
+    refused(b.la_recurrent_step, q, k, v, S, z, out, match="device tensors")
+
+
 def test_header_is_plain_c_and_links_against_the_library(lib, tmp_path):
     """include/la.h compiles as C99 and as C++11 with pedantic warnings as errors, and a plain C
     program that calls the host-only entry points links against the shared library and runs."""

@@ -600,6 +600,63 @@ def test_token_major_layout(la, oracle, B, H, N, D, M, bf16, sched, reuse):
         assert np.array_equal(a, b)
 
 
+@pytest.mark.parametrize("B,H,N,D,M,sched", [(2, 3, 333, 64, 64, "default"), (1, 4, 1000, 32, 64, "many_segments"),
+                                             (2, 2, 100, 64, 32, "folded_totals"), (3, 2, 16, 32, 32, "one_segment")])
+def test_token_major_layout_with_state(la, oracle, B, H, N, D, M, sched):
+    """la_causal_fwd_state_bnhd / la_causal_bwd_state_bnhd: state in and out on [B, N, H, .]
+    tensors, against the oracle and bit for bit against the [B, H, N, .] entry points."""
+    Q, K, V, G, S0, z0, dS1, dz1 = _state_case(9900 + N, B, H, N, D, M)
+    eps = 1e-6
+    tq, tk, tv, tg = (_token_major(x, False) for x in (Q, K, V, G))
+    s0, zz0, ds1, dzz1 = (to_dev(x) for x in (S0, z0, dS1, dz1))
+    with schedule(**SCHEDULES[sched]):
+        O = torch.full_like(tv, float("nan"))
+        den = torch.full((B, H, N), float("nan"), dtype=torch.float32, device=DEV)
+        S1 = torch.full((B, H, D, M), float("nan"), device=DEV)
+        z1 = torch.full((B, H, D), float("nan"), device=DEV)
+        ws = la.la_causal_fwd_state(tq, tk, tv, O, den, s0, zz0, S1, z1, eps, token_major=True)
+        gq, gk, gv = (torch.full_like(x, float("nan")) for x in (tq, tk, tv))
+        ds0 = torch.full((B, H, D, M), float("nan"), device=DEV)
+        dzz0 = torch.full((B, H, D), float("nan"), device=DEV)
+        la.la_causal_bwd_state(tq, tk, tv, None, den, tg, gq, gk, gv, s0, zz0, ds1, dzz1, ds0, dzz0, eps,
+                               fwd_ws=ws, token_major=True)
+        torch.cuda.synchronize()
+        # the same through the [B, H, N, .] entry points
+        hq, hk, hv = (to_dev(x) for x in (Q, K, V))
+        O2 = torch.empty_like(hv)
+        den2 = torch.empty(B, H, N, device=DEV)
+        S12, z12 = torch.empty_like(S1), torch.empty_like(z1)
+        la.la_causal_fwd_state(hq, hk, hv, O2, den2, s0, zz0, S12, z12, eps)
+        g2 = _gpu_bwd_state(la, Q, K, V, G, S0, z0, dS1, dz1, eps)
+    tol = tol_for(N)
+    ref_O, ref_den, ref_S1, ref_z1 = oracle.causal_fwd_state(Q, K, V, S0, z0, eps)
+    assert rel_err(_head_major(O), ref_O) <= tol and rel_err(den.cpu().numpy(), ref_den) <= tol
+    assert rel_err(S1.cpu().numpy(), ref_S1) <= tol and rel_err(z1.cpu().numpy(), ref_z1) <= tol
+    ref = oracle.causal_bwd_state(Q, K, V, G, S0, z0, dS1, dz1, eps)
+    got = [_head_major(gq), _head_major(gk), _head_major(gv), ds0.cpu().numpy(), dzz0.cpu().numpy()]
+    assert max(grad_errs(got[:3], ref[:3])) <= tol
+    assert rel_err(got[3], ref[3]) <= tol and rel_err(got[4], ref[4]) <= tol
+    assert np.array_equal(_head_major(O), to_host(O2)) and torch.equal(den, den2)
+    assert torch.equal(S1, S12) and torch.equal(z1, z12)
+    for a, b in zip(got, g2):
+        assert np.array_equal(a, b)
+
+
+def test_backward_workspace_holds_no_token_sized_matrix(la, oracle):
+    """The constant-memory backward (section 3.3.1): besides the segment states its workspace is
+    three fp32 scalars per token, also when the denominators are recomputed (the forward is then
+    run for its denominators only)."""
+    B, H, N, D, M = 2, 4, 700, 64, 64
+    Q, K, V, G = wl.random_case(5151, B, H, N, D, M)
+    with schedule(**SCHEDULES["one_segment"]):
+        need = la.la_causal_bwd_workspace(B, H, N, D, M)
+        assert need <= 3 * (B * H * N * 4 + 256)
+        got = run_bwd(la, Q, K, V, G, 1e-6, reuse_fwd=False)
+    assert la.la_global_bwd_workspace(B, H, N, D, M) <= \
+        2 * la.la_global_fwd_workspace(B, H, N, D, M) + B * H * N * 4 + 256
+    assert max(grad_errs(got, oracle.causal_bwd_linear(Q, K, V, G, 1e-6))) <= tol_for(N)
+
+
 @pytest.mark.parametrize("B,H,N,D,M,bf16,sched", [
     (2, 3, 333, 64, 64, False, "default"),
     (1, 8, 1000, 64, 32, False, "many_segments"),
