@@ -32,6 +32,24 @@ def rel_err(got, ref, floor=0.0):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), floor, 1e-300))
 
 
+def err_report(got, ref):
+    """Three views of the same difference (ref: fp64 oracle):
+    max_norm     max|d| / max|ref|                          (the gate of the benchmark spec)
+    elementwise  max over elements of |d| / (|ref| + 1e-3 max|ref|): every element against its
+                 own size, floored so that exact zeros do not divide by nothing.  The causal
+                 output shrinks like 1/sqrt(i) along a long sequence; this view keeps the late
+                 tokens honest where the max-norm only sees the early ones
+    rms          sqrt(mean d^2) / sqrt(mean ref^2)"""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape and np.all(np.isfinite(got))
+    d = np.abs(got - ref)
+    top = max(float(np.abs(ref).max()), 1e-300)
+    return {"max_norm": float(d.max() / top),
+            "elementwise": float((d / (np.abs(ref) + 1e-3 * top)).max()),
+            "rms": float(np.sqrt(np.mean(d * d)) / max(np.sqrt(np.mean(ref * ref)), 1e-300))}
+
+
 def grad_errs(got, ref):
     """Errors of (dQ, dK, dV).  Each tensor is scaled by its own max|ref|, but never by less
     than 1e-3 of the largest of the three: for N = 1 (and for constant V) the exact dQ, dK
