@@ -11,6 +11,11 @@ throughput in Mtokens/s (a token = all 8 heads), the roofline fraction of the
 dominant kernel (HIP events around its launches inside the timed region) and the
 fp64 CPU oracle timed on this machine's host cores on a bounded sample.
 
+`--workload NAME` runs another workload instead of the metric's (same output format, its own
+metric name; for per-kernel profiles of the other kernel families): headline_bf16, global,
+global_bf16, cfg2, cfg3, cfg3_bf16 (forward + backward), decode_B64, decode_B4096 (one
+la_recurrent_step per step), decode_B64_multi (one la_recurrent_steps launch of 3072 steps).
+
 `--table PATH` additionally times the other workloads (sequence-length sweep, the
 MNIST/CIFAR-shaped configs, bf16, the non-causal pair and the decode loop) and writes
 them to PATH as JSON; it is a reporting aid and prints no extra stdout line.
@@ -31,16 +36,36 @@ HBM_PEAK_GBS = 8000.0            # MI355X HBM3E, published
 MFMA_F32_PEAK_TFLOPS = 157.3     # MI355X dense fp32 matrix, published
 
 
-# HBM bytes per launch at the metric's workload, measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# and scaled by a copy kernel of known size (factors 2.000 / 1.000); the runs and their commands are
-# in profiles/hbm_traffic_and_pipe_counters_N65536_B2_H8_D64_f32.md.  Read + written, in bytes.
-MEASURED_TRAFFIC_BYTES = {
-    "causal_pass_fwd": (839.6 + 273.7) * 1e6,
-    "pass_dq": (1095.7 + 296.5) * 1e6,
-    "reverse_pass_dv_dk": (1101.7 + 536.9) * 1e6,
-    "segment_state_kv": (532.8 + 33.8) * 1e6,
-    "scan_states": (34.5 + 25.6) * 1e6,
-}
+# HBM bytes per launch at the metric's workload, measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE and scaled by a copy kernel of known size: read from the tracked summary of that
+# run (the table in profiles/), so that the figure on the bench line cannot drift from it.
+TRAFFIC_SUMMARY = os.path.join(ROOT, "profiles", "hbm_traffic_and_pipe_counters_N65536_B2_H8_D64_f32.md")
+TRAFFIC_ROW = {"causal_pass_fwd": "causal_pass_kernel<0", "pass_dq": "dq_causal_kernel",
+               "reverse_pass_dv_dk": "reverse_pass_kernel", "segment_state_kv": "segment_state_kernel",
+               "scan_states": "scan_states_kernel"}
+
+
+def measured_traffic_bytes(path: str = TRAFFIC_SUMMARY) -> dict:
+    """{bench kernel name: bytes read + written per launch} from the traffic table of the
+    profile summary (columns: kernel | FETCH_SIZE KiB | WRITE_SIZE KiB | read MB (scaled) |
+    written MB (scaled) | ...); {} if the file or the table is missing."""
+    out = {}
+    try:
+        with open(path) as f:
+            lines = f.read().splitlines()
+    except OSError:
+        return out
+    for line in lines:
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 5:
+            continue
+        for name, key in TRAFFIC_ROW.items():
+            if key in cells[0] and name not in out:
+                try:
+                    out[name] = (float(cells[3]) + float(cells[4])) * 1e6
+                except ValueError:
+                    pass
+    return out
 
 
 def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
@@ -52,7 +77,12 @@ def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
         "pass_dq": e * (3 * D + 2 * M) + 12,            # dO V K Q, den -> dQ, 1/den, delta
         "reverse_pass_dv_dk": e * (3 * D + 3 * M) + 8,  # Q K V dO, 1/den, delta -> dV, dK
         "segment_state_kv": e * (D + M),                # K V
-        "global_readout": e * (D + M),                  # Q -> O
+        "global_readout": e * (D + M) + 4,              # Q -> O, den
+        "pass_dq_global": e * (2 * D + M) + 4,          # Q dO, den -> dQ (non-causal)
+        "global_bwd_readouts": e * (3 * D + 2 * M),     # K -> dV;  V K -> dK
+        "recurrent_step": 2 * 4 * D * (M + 1) + e * (2 * D + 2 * M),   # S, z read and written; q k v out
+        "recurrent_steps": e * (2 * D + 2 * M),         # per step of a multi-step launch: q k v out
+                                                        # (the state stays in registers)
     }.get(name, 0.0)
 
 
@@ -61,7 +91,8 @@ def kernel_flops(name: str, D: int, M: int) -> float:
     (2*D*(M+1) each, ones column included) that the pass performs."""
     full = 4.0 * D * (M + 1)
     return {"causal_pass_fwd": full, "pass_dq": 1.5 * full, "reverse_pass_dv_dk": 1.5 * full,
-            "segment_state_kv": full / 2, "global_readout": full / 2}.get(name, 0.0)
+            "segment_state_kv": full / 2, "global_readout": full / 2, "pass_dq_global": full / 2,
+            "global_bwd_readouts": full, "recurrent_step": full, "recurrent_steps": full}.get(name, 0.0)
 
 
 class FwdBwd:
@@ -133,7 +164,7 @@ def profile_kernels(la, fn, steps, torch, mask=None):
     return {k: (ms / n, n // steps) for k, (ms, n) in prof.items()}   # avg ms per launch, launches/step
 
 
-def cpu_baseline(w, host, sample_tokens):
+def cpu_baseline(w, host, sample_tokens, causal=True):
     """The oracle as it stands (fp64, OpenMP over the (b, h) slabs), forward + backward, on
     the first `sample_tokens` tokens of every slab of the same workload."""
     import numpy as np
@@ -141,9 +172,11 @@ def cpu_baseline(w, host, sample_tokens):
     from oracle import la_oracle
     Q, K, V, G = (np.ascontiguousarray(x[:, :, :sample_tokens], dtype=np.float64) for x in host)
     threads = min(la_oracle.max_threads(), w.B * w.H)
+    fwd = la_oracle.causal_fwd_prefix if causal else la_oracle.global_fwd_linear
+    bwd = la_oracle.causal_bwd_linear if causal else la_oracle.global_bwd_linear
     t0 = time.perf_counter()
-    la_oracle.causal_fwd_prefix(Q, K, V, w.eps)
-    la_oracle.causal_bwd_linear(Q, K, V, G, w.eps)
+    fwd(Q, K, V, w.eps)
+    bwd(Q, K, V, G, w.eps)
     dt = time.perf_counter() - t0
     # one thread on one (batch, head) sequence, first 16384 tokens: the per-core rate
     n1 = min(sample_tokens, 16384)
@@ -151,8 +184,8 @@ def cpu_baseline(w, host, sample_tokens):
     nmax = la_oracle.max_threads()
     la_oracle.set_threads(1)
     t1 = time.perf_counter()
-    la_oracle.causal_fwd_prefix(*one[:3], w.eps)
-    la_oracle.causal_bwd_linear(*one, w.eps)
+    fwd(*one[:3], w.eps)
+    bwd(*one, w.eps)
     dt1 = time.perf_counter() - t1
     la_oracle.set_threads(nmax)
     model = "unknown"
@@ -171,62 +204,182 @@ def cpu_baseline(w, host, sample_tokens):
                       f"over sequences ({nmax} threads available, {threads} busy)"}
 
 
-def run_headline(args):
+class GlobalFwdBwd(FwdBwd):
+    """The same buffers, stepping the non-causal pair (la_global_fwd + la_global_bwd)."""
+
+    def __init__(self, w, bf16=False):
+        super().__init__(w, bf16)
+        la, torch = self.la, self.torch
+        code = la.LA_BF16 if bf16 else la.LA_F32
+        self.ws_f = torch.empty(la.la_global_fwd_workspace(w.B, w.H, w.N, w.D, w.M, code),
+                                dtype=torch.uint8, device="cuda:0")
+        self.ws_b = torch.empty(la.la_global_bwd_workspace(w.B, w.H, w.N, w.D, w.M, code),
+                                dtype=torch.uint8, device="cuda:0")
+
+    def step(self):
+        la, w = self.la, self.w
+        la.la_global_fwd(self.Q, self.K, self.V, self.O, w.eps, ws=self.ws_f, den=self.den)
+        la.la_global_bwd(self.Q, self.K, self.V, self.O, self.den, self.G, self.dQ, self.dK, self.dV,
+                         w.eps, ws=self.ws_b, fwd_ws=self.ws_f)
+
+
+class Decode:
+    """Recurrent decode (eq. 16-20): B sequences, one token per head per step; `multi` > 0:
+    one la_recurrent_steps launch of that many steps."""
+
+    def __init__(self, d, B, multi=0):
+        import torch
+
+        import paper_2006_16236_amd as la
+        self.la, self.d, self.B, self.multi, self.t = la, d, B, multi, 0
+        T = multi if multi else 8
+        g = torch.Generator(device="cuda:0").manual_seed(d.seed)
+        self.q = torch.randn(T, B, d.H, d.D, device="cuda:0", generator=g)
+        self.k = torch.randn(T, B, d.H, d.D, device="cuda:0", generator=g)
+        self.v = torch.randn(T, B, d.H, d.M, device="cuda:0", generator=g)
+        self.S = torch.zeros(B, d.H, d.D, d.M, device="cuda:0")
+        self.z = torch.zeros(B, d.H, d.D, device="cuda:0")
+        self.out = torch.empty(T if multi else 1, B, d.H, d.M, device="cuda:0")
+
+    def step(self):
+        la, d = self.la, self.d
+        if self.multi:
+            la.la_recurrent_steps(self.q, self.k, self.v, self.S, self.z, self.out, d.eps)
+        else:
+            t = self.t = (self.t + 1) % 8
+            la.la_recurrent_step(self.q[t], self.k[t], self.v[t], self.S, self.z, self.out[0], d.eps)
+
+
+WORKLOADS = ("headline", "headline_bf16", "global", "global_bf16", "cfg2", "cfg3", "cfg3_bf16",
+             "decode_B64", "decode_B4096", "decode_B64_multi")
+
+
+def make_workload(name):
+    """-> (object with .step(), description dict).  tokens: tokens per step (a token = all H
+    heads); path_bytes: compulsory HBM bytes per token-head of one step (the tensors that must be
+    read and written once), None where a step is not one pass over tensors."""
+    import workloads as wl
+    if name.startswith("decode"):
+        d = wl.CFG5
+        B = 4096 if "4096" in name else d.B
+        multi = d.T if name.endswith("_multi") else 0
+        obj = Decode(d, B, multi)
+        steps_per = multi if multi else 1
+        return obj, {"metric": "recurrent decode Mtokens/s (H=8,D=M=64)", "tokens": B * steps_per,
+                     "H": d.H, "D": d.D, "M": d.M, "e": 4, "dtype": "f32", "host": None,
+                     "path_bytes": kernel_bytes("recurrent_steps" if multi else "recurrent_step", d.D, d.M, 4),
+                     "w": None,
+                     "config": {"workload": name, "B": B, "H": d.H, "D": d.D, "M": d.M, "eps": d.eps,
+                                "step": f"la_recurrent_steps, T={multi}" if multi else "la_recurrent_step",
+                                "seed": d.seed},
+                     "rename": {"recurrent_step": "recurrent_steps"} if multi else {}}
+    bf16 = name.endswith("_bf16")
+    base = name[:-5] if bf16 else name
+    w = {"headline": wl.HEADLINE, "global": wl.HEADLINE, "cfg2": wl.CFG2, "cfg3": wl.CFG3}[base]
+    glob = base == "global"
+    obj = GlobalFwdBwd(w, bf16) if glob else FwdBwd(w, bf16)
+    e = 2 if bf16 else 4
+    metric = ("non-causal" if glob else "causal") + f" linear-attn fwd+bwd Mtokens/s (H={w.H},D={w.D},M={w.M},N={w.N})"
+    if name == "headline":
+        metric = "causal linear-attn fwd+bwd Mtokens/s (H=8,D=M=64,N=2^16)"
+    return obj, {"metric": metric, "tokens": w.B * w.N, "H": w.H, "D": w.D, "M": w.M, "e": e,
+                 "dtype": "bf16" if bf16 else "f32", "host": obj.host, "w": w,
+                 "path_bytes": e * (6 * w.D + 6 * w.M),
+                 "config": {"workload": w.name + ("_bf16" if bf16 else "") + ("_noncausal" if glob else ""),
+                            "B": w.B, "H": w.H, "N": w.N, "D": w.D, "M": w.M, "eps": w.eps,
+                            "step": "la_global_fwd + la_global_bwd" if glob else "la_causal_fwd + la_causal_bwd",
+                            "seed": w.seed},
+                 # the non-causal dQ kernel reads fewer tensors than the causal one
+                 "rename": {"pass_dq": "pass_dq_global"} if glob else {}}
+
+
+def run_workload(args):
+    import statistics
+
     import torch
 
     import paper_2006_16236_amd as la
-    import workloads as wl
 
-    w = wl.HEADLINE
-    fb = FwdBwd(w)
+    obj, info = make_workload(args.workload)
+    step = obj.step
+    # the first --warmup steps, on clocks as they are after a pause: timed, reported beside the
+    # settled figure, not part of it
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    unsettled = (time.perf_counter() - t0) / max(args.warmup, 1)
     # clocks settle only after ~50 ms of back-to-back work (see TABLE_WARMUP): when the caller
     # asks for a shorter warm-up, run the difference as well, untimed, and say so in the output
     settle = max(0, SETTLE_STEPS - args.warmup)
-    for _ in range(args.warmup + settle):
-        fb.step()
+    for _ in range(settle):
+        step()
     # untimed look at every kernel, to find the dominant one
-    prof_all = profile_kernels(la, fb.step, 3, torch)
+    prof_all = profile_kernels(la, step, 3, torch)
     per_step = {k: ms * n for k, (ms, n) in prof_all.items()}
     dominant = max(per_step, key=per_step.get)
     kid = [la.la_kernel_name(i) for i in range(la.binding.LA_K_COUNT)].index(dominant)
 
-    # the timed region: exactly `steps` steps, events only around the dominant kernel
+    # the timed region: exactly `steps` steps between two synchronisations (wall clock: the
+    # mean), HIP events on the launch stream at up to 20 evenly spaced step borders (their
+    # differences give a median), events inside the library only around the dominant kernel
+    groups = max(1, min(args.steps, 20))
+    border = [round(i * args.steps / groups) for i in range(groups + 1)]
+    marks = [torch.cuda.Event(enable_timing=True) for _ in border]
     torch.cuda.synchronize()
     la.la_profile_begin(1 << kid)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        fb.step()
+    nxt = 0
+    for i in range(args.steps):
+        if i == border[nxt]:
+            marks[nxt].record()
+            nxt += 1
+        step()
+    marks[nxt].record()
     torch.cuda.synchronize()
     sec = (time.perf_counter() - t0) / args.steps
     dom_ms, dom_n = la.la_profile_end()[dominant]
     dom_ms /= dom_n
+    per_group = [marks[i].elapsed_time(marks[i + 1]) / (border[i + 1] - border[i]) for i in range(groups)]
+    median_ms = statistics.median(per_group)
 
-    tokens = w.B * w.N
-    th = tokens * w.H
+    D, M, e, H = info["D"], info["M"], info["e"], info["H"]
+    tokens = info["tokens"]
+    th = tokens * H
     value = tokens / sec / 1e6
-    ach_gbs = kernel_bytes(dominant, w.D, w.M, 4) * th / (dom_ms * 1e-3) / 1e9
-    ach_tf = kernel_flops(dominant, w.D, w.M) * th / (dom_ms * 1e-3) / 1e12
-    hbm_ceiling = HBM_PEAK_GBS * 1e9 / (w.H * 4 * (6 * w.D + 6 * w.M)) / 1e6
+    kname = info["rename"].get(dominant, dominant)
+    launches_per_step = prof_all[dominant][1]
+    th_per_launch = th / launches_per_step if args.workload.startswith("decode") else th
+    if args.workload.endswith("_multi"):
+        th_per_launch = th
+    ach_gbs = kernel_bytes(kname, D, M, e) * th_per_launch / (dom_ms * 1e-3) / 1e9
+    ach_tf = kernel_flops(kname, D, M) * th_per_launch / (dom_ms * 1e-3) / 1e12
+    hbm_ceiling = HBM_PEAK_GBS * 1e9 / (H * info["path_bytes"]) / 1e6
+    traffic = measured_traffic_bytes().get(dominant) if args.workload == "headline" else None
     out = {
-        "metric": "causal linear-attn fwd+bwd Mtokens/s (H=8,D=M=64,N=2^16)",
+        "metric": info["metric"],
         "value": round(value, 3), "unit": "Mtokens/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "settle_steps": settle, "ms_per_step": round(sec * 1e3, 4),
+        "ms_per_step_median": round(median_ms, 4),
+        "unsettled_ms_per_step": round(unsettled * 1e3, 4),
         "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "D": w.D, "M": w.M,
-                   "eps": w.eps, "step": "la_causal_fwd + la_causal_bwd", "seed": w.seed},
+        "scaling": "weak", "vs_baseline": None, "dtype": info["dtype"], "data": "synthetic",
+        "config": info["config"],
         "roofline": {"bound": "hbm", "kernel": dominant, "achieved": round(ach_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(ach_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant), "avg_kernel_ms": round(dom_ms, 4),
+                     "traffic": traffic, "avg_kernel_ms": round(dom_ms, 4),
                      "mfma_f32_tflops_algorithmic": round(ach_tf, 2),
                      "mfma_f32_frac": round(ach_tf / MFMA_F32_PEAK_TFLOPS, 4)},
         "path_frac_of_hbm_roofline": round(value / hbm_ceiling, 4),
         "path_hbm_ceiling_mtok_s": round(hbm_ceiling, 1),
         "kernels_ms_per_step": {k: round(v, 4) for k, v in sorted(per_step.items(), key=lambda kv: -kv[1])},
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, fb.host, args.cpu_sample_tokens)
-    return out, fb
+    if not args.no_cpu_baseline and info["w"] is not None:
+        w = info["w"]
+        out["cpu_baseline"] = cpu_baseline(w, info["host"], min(args.cpu_sample_tokens, w.N),
+                                           causal="global" not in args.workload)
+    return out, obj
 
 
 def run_table(args):
@@ -361,6 +514,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-tokens", type=int, default=65536)
+    ap.add_argument("--workload", choices=WORKLOADS, default="headline",
+                    help="which workload to step (default: the metric's)")
     ap.add_argument("--table", metavar="PATH", default=None,
                     help="also time the other workloads and write them to PATH (JSON)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -382,8 +537,8 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    out, fb = run_headline(args)
-    del fb
+    out, obj = run_workload(args)
+    del obj
     if args.table:
         run_table(args)
     print(json.dumps(out), flush=True)

@@ -167,28 +167,36 @@ def la_global_bwd_workspace(B, H, N, D, M, dtype_code=LA_F32) -> int:
 # them before the call (ValueError / TypeError, nothing is launched).
 
 def _like(name, t, shape, dtype, device, optional=False):
+    """`t` must be a contiguous tensor of exactly this shape, element type and device.  The
+    accepting path is one expression (these checks run on every call, decode steps included)."""
     if t is None:
         if optional:
             return
         raise ValueError(f"{name} is required")
-    if not isinstance(t, torch.Tensor):
-        raise TypeError(f"{name} must be a torch.Tensor")
+    try:
+        if t.shape == shape and t.dtype is dtype and t.device == device and t.is_contiguous():
+            return
+    except AttributeError:
+        raise TypeError(f"{name} must be a torch.Tensor") from None
     if tuple(t.shape) != tuple(shape):
         raise ValueError(f"{name}: shape {tuple(t.shape)}, expected {tuple(shape)}")
     if t.dtype != dtype:
         raise ValueError(f"{name}: dtype {t.dtype}, expected {dtype}")
     if t.device != device:
         raise ValueError(f"{name}: device {t.device}, expected {device}")
-    if not t.is_contiguous():
-        raise ValueError(f"{name} must be contiguous")
+    raise ValueError(f"{name} must be contiguous")
 
 
 def _bytes(name, t, device):
     """A workspace: any contiguous tensor on the same device (its size is passed along)."""
     if t is None:
         return
-    if not isinstance(t, torch.Tensor) or t.device != device or not t.is_contiguous():
-        raise ValueError(f"{name} must be a contiguous tensor on {device}")
+    try:
+        if t.device == device and t.is_contiguous():
+            return
+    except AttributeError:
+        pass
+    raise ValueError(f"{name} must be a contiguous tensor on {device}")
 
 
 class _Sizes:
@@ -196,34 +204,69 @@ class _Sizes:
     token_major); `features` selects the element-type code."""
 
     def __init__(self, Q, V, token_major=False, features=False):
-        if not isinstance(Q, torch.Tensor) or not isinstance(V, torch.Tensor):
-            raise TypeError("Q and V must be torch.Tensors")
-        if Q.dim() != 4 or V.dim() != 4:
+        try:
+            qs, vs = Q.shape, V.shape
+        except AttributeError:
+            raise TypeError("Q and V must be torch.Tensors") from None
+        if len(qs) != 4 or len(vs) != 4:
             raise ValueError("Q and V must have four dimensions")
         self.t = _dtype_code(Q, features)
         if token_major:
-            self.B, self.N, self.H, self.D = Q.shape
+            B, N, H, D = qs
         else:
-            self.B, self.H, self.N, self.D = Q.shape
-        self.M = V.shape[-1]
-        self.qk = tuple(Q.shape)
-        self.v = tuple(Q.shape[:-1]) + (self.M,)
-        self.rows = (self.B, self.H, self.N)              # den: always [B, H, N]
-        self.S, self.z = (self.B, self.H, self.D, self.M), (self.B, self.H, self.D)
+            B, H, N, D = qs
+        M = vs[3]
+        self.B, self.H, self.N, self.D, self.M = B, H, N, D, M
+        self.qk = qs
+        self.v = (qs[0], qs[1], qs[2], M)
+        self.rows = (B, H, N)                             # den: always [B, H, N]
         self.dtype, self.dev = Q.dtype, Q.device
-        self.dims = (self.B, self.H, self.N, self.D, self.M)
+        self.dims = (B, H, N, D, M)
+
+    @property
+    def S(self):
+        return (self.B, self.H, self.D, self.M)
+
+    @property
+    def z(self):
+        return (self.B, self.H, self.D)
 
     def inputs(self, Q, K, V):
-        _like("Q", Q, self.qk, self.dtype, self.dev)
+        if not Q.is_contiguous():
+            raise ValueError("Q must be contiguous")
         _like("K", K, self.qk, self.dtype, self.dev)
         _like("V", V, self.v, self.dtype, self.dev)
 
     def forward(self, Q, K, V, O, den):
+        try:    # the accepting path in one expression; the named checks below find what is wrong
+            qk, vv, dt, dev = self.qk, self.v, self.dtype, self.dev
+            if (Q.is_contiguous() and K.shape == qk and K.dtype is dt and K.device == dev and K.is_contiguous()
+                    and V.shape == vv and V.dtype is dt and V.device == dev and V.is_contiguous()
+                    and O.shape == vv and O.dtype is dt and O.device == dev and O.is_contiguous()
+                    and (den is None or (den.shape == self.rows and den.dtype is torch.float32
+                                         and den.device == dev and den.is_contiguous()))):
+                return
+        except AttributeError:
+            pass
         self.inputs(Q, K, V)
         _like("O", O, self.v, self.dtype, self.dev)
         _like("den", den, self.rows, torch.float32, self.dev, optional=True)
 
     def backward(self, Q, K, V, O, den, dO, dQ, dK, dV, fwd_ws):
+        try:
+            qk, vv, dt, dev = self.qk, self.v, self.dtype, self.dev
+            if (O is None and fwd_ws is not None and den is not None
+                    and Q.is_contiguous() and K.shape == qk and K.dtype is dt and K.device == dev and K.is_contiguous()
+                    and V.shape == vv and V.dtype is dt and V.device == dev and V.is_contiguous()
+                    and dO.shape == vv and dO.dtype is dt and dO.device == dev and dO.is_contiguous()
+                    and dQ.shape == qk and dQ.dtype is dt and dQ.device == dev and dQ.is_contiguous()
+                    and dK.shape == qk and dK.dtype is dt and dK.device == dev and dK.is_contiguous()
+                    and dV.shape == vv and dV.dtype is dt and dV.device == dev and dV.is_contiguous()
+                    and den.shape == self.rows and den.dtype is torch.float32 and den.device == dev
+                    and den.is_contiguous() and fwd_ws.device == dev and fwd_ws.is_contiguous()):
+                return
+        except AttributeError:
+            pass
         self.inputs(Q, K, V)
         _like("O", O, self.v, self.dtype, self.dev, optional=True)
         _like("den", den, self.rows, torch.float32, self.dev, optional=True)
@@ -403,17 +446,31 @@ def la_global_bwd_bnhd(Q, K, V, O, den, dO, dQ, dK, dV, eps=1e-6, ws=None, strea
 
 def _step_checks(q, k, v, S, z, out, lead, features):
     """Shapes of the decode calls: q, k [*lead, B, H, D], v, out [*lead, B, H, M]."""
-    if not isinstance(q, torch.Tensor) or not isinstance(v, torch.Tensor):
-        raise TypeError("q and v must be torch.Tensors")
-    if q.dim() != 3 + lead or v.dim() != 3 + lead:
+    try:
+        qs, vs = q.shape, v.shape
+    except AttributeError:
+        raise TypeError("q and v must be torch.Tensors") from None
+    if len(qs) != 3 + lead or len(vs) != 3 + lead:
         raise ValueError(f"q and v must have {3 + lead} dimensions")
     t = _dtype_code(q, features)
-    B, H, D = q.shape[lead:]
-    M = v.shape[-1]
-    dev = q.device
-    _like("k", k, q.shape, q.dtype, dev)
-    _like("v", v, tuple(q.shape[:-1]) + (M,), q.dtype, dev)
-    _like("out", out, tuple(q.shape[:-1]) + (M,), q.dtype, dev)
+    B, H, D = qs[lead:]
+    M = vs[-1]
+    dev, dt = q.device, q.dtype
+    vshape = tuple(qs[:-1]) + (M,)
+    try:        # the accepting path: one expression, no calls (this runs before every decode step)
+        if (q.is_contiguous() and k.shape == qs and k.dtype is dt and k.device == dev and k.is_contiguous()
+                and v.shape == vshape and v.dtype is dt and v.device == dev and v.is_contiguous()
+                and out.shape == vshape and out.dtype is dt and out.device == dev and out.is_contiguous()
+                and S.shape == (B, H, D, M) and S.dtype is torch.float32 and S.device == dev and S.is_contiguous()
+                and z.shape == (B, H, D) and z.dtype is torch.float32 and z.device == dev and z.is_contiguous()):
+            return t, B, H, D, M
+    except AttributeError:
+        pass
+    if not q.is_contiguous():
+        raise ValueError("q must be contiguous")
+    _like("k", k, qs, dt, dev)
+    _like("v", v, vshape, dt, dev)
+    _like("out", out, vshape, dt, dev)
     _like("S", S, (B, H, D, M), torch.float32, dev)
     _like("z", z, (B, H, D), torch.float32, dev)
     return t, B, H, D, M

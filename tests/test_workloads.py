@@ -35,3 +35,18 @@ def test_bf16_rounding_matches_library():
     bits = wl.bf16_bits(r)
     assert np.array_equal(bits, t.view(torch.int16).numpy().view(np.uint16))
     assert np.array_equal(wl.bf16_bits_to_f32(bits), r)
+
+
+def test_bench_traffic_figures_come_from_the_tracked_profile_summary():
+    """bench.py's roofline.traffic is read from the table in profiles/ (no literal to go
+    stale), and the measured bytes of every pass kernel equal the tensors it must read and
+    write once within a few percent."""
+    import bench
+    t = bench.measured_traffic_bytes()
+    w = wl.HEADLINE
+    th = w.B * w.H * w.N
+    for k in ("causal_pass_fwd", "pass_dq", "reverse_pass_dv_dk", "segment_state_kv"):
+        assert k in t, k
+        alg = bench.kernel_bytes(k, w.D, w.M, 4) * th
+        assert 0.98 * alg <= t[k] <= 1.08 * alg, (k, t[k], alg)
+    assert bench.measured_traffic_bytes("/nonexistent/file.md") == {}
