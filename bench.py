@@ -98,7 +98,9 @@ def kernel_flops(name: str, D: int, M: int) -> float:
 class FwdBwd:
     """Device buffers and the step function for one workload."""
 
-    def __init__(self, w, bf16=False, token_major=False):
+    def __init__(self, w, bf16=False, token_major=False, group=0):
+        """group > 0: the (batch, head) sequences are processed `group` at a time (forward and
+        backward of one group, then the next): a schedule experiment, see --groups."""
         import torch
 
         import paper_2006_16236_amd as la
@@ -123,9 +125,28 @@ class FwdBwd:
         nb = la.la_causal_bwd_workspace(w.B, w.H, w.N, w.D, w.M, code)
         self.ws_f = torch.empty(max(nf, 16), dtype=torch.uint8, device=dev)
         self.ws_b = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
+        self.groups = None
+        if group > 0 and not token_major:
+            BH = w.B * w.H
+            flat = [x.view(BH, *x.shape[2:]) for x in (self.Q, self.K, self.V, self.G, self.O, self.den,
+                                                       self.dQ, self.dK, self.dV)]
+            self.groups = []
+            for i in range(0, BH, group):
+                n = min(group, BH - i)
+                views = [x[i:i + n].unsqueeze(0) for x in flat]      # [1, n, N, .]: contiguous slices
+                wf = torch.empty(max(la.la_causal_fwd_workspace(1, n, w.N, w.D, w.M, code), 16),
+                                 dtype=torch.uint8, device=dev)
+                wb = torch.empty(max(la.la_causal_bwd_workspace(1, n, w.N, w.D, w.M, code), 16),
+                                 dtype=torch.uint8, device=dev)
+                self.groups.append((views, wf, wb))
 
     def step(self):
         la, w = self.la, self.w
+        if self.groups is not None:
+            for (Q, K, V, G, O, den, dQ, dK, dV), wf, wb in self.groups:
+                la.la_causal_fwd(Q, K, V, O, den, w.eps, ws=wf)
+                la.la_causal_bwd(Q, K, V, O, den, G, dQ, dK, dV, w.eps, ws=wb, fwd_ws=wf)
+            return
         fwd = la.la_causal_fwd_bnhd if self.token_major else la.la_causal_fwd
         bwd = la.la_causal_bwd_bnhd if self.token_major else la.la_causal_bwd
         fwd(self.Q, self.K, self.V, self.O, self.den, w.eps, ws=self.ws_f)
@@ -254,7 +275,7 @@ WORKLOADS = ("headline", "headline_bf16", "global", "global_bf16", "cfg2", "cfg3
              "decode_B64", "decode_B4096", "decode_B64_multi")
 
 
-def make_workload(name):
+def make_workload(name, group=0):
     """-> (object with .step(), description dict).  tokens: tokens per step (a token = all H
     heads); path_bytes: compulsory HBM bytes per token-head of one step (the tensors that must be
     read and written once), None where a step is not one pass over tensors."""
@@ -277,7 +298,7 @@ def make_workload(name):
     base = name[:-5] if bf16 else name
     w = {"headline": wl.HEADLINE, "global": wl.HEADLINE, "cfg2": wl.CFG2, "cfg3": wl.CFG3}[base]
     glob = base == "global"
-    obj = GlobalFwdBwd(w, bf16) if glob else FwdBwd(w, bf16)
+    obj = GlobalFwdBwd(w, bf16) if glob else FwdBwd(w, bf16, group=group)
     e = 2 if bf16 else 4
     metric = ("non-causal" if glob else "causal") + f" linear-attn fwd+bwd Mtokens/s (H={w.H},D={w.D},M={w.M},N={w.N})"
     if name == "headline":
@@ -300,7 +321,9 @@ def run_workload(args):
 
     import paper_2006_16236_amd as la
 
-    obj, info = make_workload(args.workload)
+    obj, info = make_workload(args.workload, args.groups)
+    if args.groups:
+        info["config"]["sequences_per_group"] = args.groups
     step = obj.step
     # the first --warmup steps, on clocks as they are after a pause: timed, reported beside the
     # settled figure, not part of it
@@ -516,6 +539,10 @@ def main():
     ap.add_argument("--cpu-sample-tokens", type=int, default=65536)
     ap.add_argument("--workload", choices=WORKLOADS, default="headline",
                     help="which workload to step (default: the metric's)")
+    ap.add_argument("--groups", type=int, default=0, metavar="G",
+                    help="schedule experiment (causal workloads): process the B*H sequences G at a time, "
+                         "forward and backward of one group before the next, so that a group's tensors "
+                         "could stay in the 256 MB memory-side cache between its kernels")
     ap.add_argument("--table", metavar="PATH", default=None,
                     help="also time the other workloads and write them to PATH (JSON)")
     ap.add_argument("--copy-calibration", action="store_true",

@@ -17,3 +17,13 @@ def test_native_client_forward_backward(N):
     r = subprocess.run([CLIENT, str(N)], capture_output=True, text=True, timeout=120)
     print(r.stdout, r.stderr)
     assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
+
+
+def test_operand_split_is_exact_on_the_gpu():
+    """tests/split_exact.hip (built by __graft_entry__.build()) runs the kernels' own split3 /
+    split2 device functions on 4M values: x = h + m + l exactly, parts shrinking by 2^-8."""
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "split_exact")
+    assert os.path.exists(exe), "build first: python -c 'import __graft_entry__ as g; g.build()'"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    print(r.stdout, r.stderr)
+    assert r.returncode == 0, (r.returncode, r.stdout, r.stderr)
