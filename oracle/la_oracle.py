@@ -256,3 +256,66 @@ def causal_bwd_state(Q, K, V, G, S0=None, Z0=None, dS1=None, dZ1=None, eps=1e-6)
                                    ctypes.c_int(BH), ctypes.c_int(N), ctypes.c_int(D),
                                    ctypes.c_int(M), ctypes.c_double(eps))
     return dQ, dK, dV, dS0, dZ0
+
+
+# ---- degree-2 polynomial kernel (section 3.2) -------------------------------------------------
+# sim(q, k) = (q . k)^2 has the finite feature map phi(x) = vec(x x^T): d raw dimensions give
+# C = d^2 features, phi(q) . phi(k) = sum_ij q_i q_j k_i k_j = (q . k)^2, and the cost of the
+# linear form becomes O(N d^2 M).  The functions below are that definition written out: map the
+# raw vectors, run the functions above with the identity feature map on the mapped values, and
+# carry the gradients back to the raw vectors by the chain rule of x -> x x^T.
+
+def poly2_features(X):
+    """[..., d] -> [..., d*d]: feature d*i + j = x_i x_j."""
+    X = np.asarray(X, dtype=np.float64)
+    return (X[..., :, None] * X[..., None, :]).reshape(X.shape[:-1] + (X.shape[-1] ** 2,))
+
+
+def poly2_chain(X, dF):
+    """Gradient with respect to the features [..., d*d] -> gradient with respect to x [..., d]:
+    d(x_i x_j)/dx_k = delta_ik x_j + delta_jk x_i, so dx_k = sum_j (dF[k, j] + dF[j, k]) x_j."""
+    X = np.asarray(X, dtype=np.float64)
+    d = X.shape[-1]
+    G = np.asarray(dF, dtype=np.float64).reshape(X.shape[:-1] + (d, d))
+    return np.einsum("...kj,...j->...k", G + np.swapaxes(G, -1, -2), X)
+
+
+class _identity_map:
+    """Run the C functions with Q, K taken as feature values (and put the switch back)."""
+
+    def __enter__(self):
+        set_feature_map(1)
+
+    def __exit__(self, *exc):
+        set_feature_map(0)
+
+
+def causal_fwd_poly2(Q, K, V, eps=1e-6, return_den=False):
+    """eq. 10-12 with phi(x) = vec(x x^T)."""
+    with _identity_map():
+        return causal_fwd_prefix(poly2_features(Q), poly2_features(K), V, eps, return_den)
+
+
+def causal_bwd_poly2(Q, K, V, G, eps=1e-6):
+    """Gradients of the above for the raw Q, K and for V."""
+    with _identity_map():
+        dFq, dFk, dV = causal_bwd_linear(poly2_features(Q), poly2_features(K), V, G, eps)
+    return poly2_chain(Q, dFq), poly2_chain(K, dFk), dV
+
+
+def global_fwd_poly2(Q, K, V, eps=1e-6):
+    """eq. 5-6 with phi(x) = vec(x x^T)."""
+    with _identity_map():
+        return global_fwd_linear(poly2_features(Q), poly2_features(K), V, eps)
+
+
+def global_bwd_poly2(Q, K, V, G, eps=1e-6):
+    with _identity_map():
+        dFq, dFk, dV = global_bwd_linear(poly2_features(Q), poly2_features(K), V, G, eps)
+    return poly2_chain(Q, dFq), poly2_chain(K, dFk), dV
+
+
+def recurrent_step_poly2(q, k, v, S, z, eps=1e-6):
+    """eq. 16-20 with phi(x) = vec(x x^T); S [..., d*d, M], z [..., d*d] updated in place."""
+    with _identity_map():
+        return recurrent_step(poly2_features(q), poly2_features(k), v, S, z, eps)

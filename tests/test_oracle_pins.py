@@ -560,3 +560,70 @@ def test_identity_map_equals_elu_map_on_shifted_positive_inputs(oracle):
     np.testing.assert_allclose(ogot, oref, rtol=1e-13)
     for a, b in zip(got, ref):
         np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-15)
+
+
+# ---- degree-2 polynomial kernel (section 3.2): the written-out (q . k)^2 attention ----------------
+
+def _poly2_attention_torch(Q, K, V, eps, causal):
+    """The definition with the kernel itself, no feature map: sim(q, k) = (q . k)^2 (torch fp64)."""
+    A = (Q @ K.transpose(-1, -2)) ** 2
+    if causal:
+        A = torch.tril(A)
+    return (A @ V) / (A.sum(-1, keepdim=True) + eps)
+
+
+@pytest.mark.parametrize("causal", [True, False])
+def test_poly2_map_is_the_squared_dot_product_kernel(oracle, causal):
+    rng = np.random.default_rng(77)
+    B, H, N, d, M = 2, 2, 37, 8, 5
+    Q, K = rng.standard_normal((B, H, N, d)), rng.standard_normal((B, H, N, d))
+    V, G = rng.standard_normal((B, H, N, M)), rng.standard_normal((B, H, N, M))
+    eps = 1e-3
+    # the feature map reproduces the kernel: phi(q) . phi(k) = (q . k)^2
+    fq, fk = oracle.poly2_features(Q), oracle.poly2_features(K)
+    assert fq.shape == (B, H, N, d * d)
+    np.testing.assert_allclose(np.einsum("bhic,bhjc->bhij", fq, fk), np.einsum("bhid,bhjd->bhij", Q, K) ** 2,
+                               rtol=1e-12, atol=1e-12)
+    assert fq[0, 0, 3, 8 * 2 + 5] == Q[0, 0, 3, 2] * Q[0, 0, 3, 5]          # feature d*i + j = x_i x_j
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    ref = _poly2_attention_torch(tq, tk, tv, eps, causal)
+    ref.backward(torch.tensor(G))
+    if causal:
+        O = oracle.causal_fwd_poly2(Q, K, V, eps)
+        dQ, dK, dV = oracle.causal_bwd_poly2(Q, K, V, G, eps)
+    else:
+        O = oracle.global_fwd_poly2(Q, K, V, eps)
+        dQ, dK, dV = oracle.global_bwd_poly2(Q, K, V, G, eps)
+    np.testing.assert_allclose(O, ref.detach().numpy(), rtol=1e-9, atol=1e-11)
+    for got, t in ((dQ, tq), (dK, tk), (dV, tv)):
+        np.testing.assert_allclose(got, t.grad.numpy(), rtol=1e-8, atol=1e-10)
+    # the switch is put back: the default map is elu + 1 again
+    assert oracle.phi(-1.0) == pytest.approx(np.exp(-1.0))
+
+
+def test_poly2_gradients_against_finite_differences_and_recurrence(oracle):
+    rng = np.random.default_rng(78)
+    N, d, M = 9, 8, 3
+    Q, K = rng.standard_normal((1, 1, N, d)), rng.standard_normal((1, 1, N, d))
+    V, G = rng.standard_normal((1, 1, N, M)), rng.standard_normal((1, 1, N, M))
+    eps = 1e-2
+    dQ, dK, dV = oracle.causal_bwd_poly2(Q, K, V, G, eps)
+    loss = lambda q, k, v: float((oracle.causal_fwd_poly2(q, k, v, eps) * G).sum())
+    h = 1e-6
+    for X, dX, which in ((Q, dQ, 0), (K, dK, 1), (V, dV, 2)):
+        for idx in [(0, 0, 0, 0), (0, 0, 4, min(2, X.shape[-1] - 1)), (0, 0, N - 1, X.shape[-1] - 1)]:
+            args = [Q.copy(), K.copy(), V.copy()]
+            args[which][idx] += h
+            up = loss(*args)
+            args[which][idx] -= 2 * h
+            fd = (up - loss(*args)) / (2 * h)
+            assert fd == pytest.approx(dX[idx], rel=1e-5, abs=1e-8)
+    # stepping the recurrence (eq. 16-20 on the mapped vectors) reproduces the parallel form
+    S, z = np.zeros((1, 1, d * d, M)), np.zeros((1, 1, d * d))
+    O = oracle.causal_fwd_poly2(Q, K, V, eps)
+    for i in range(N):
+        out = oracle.recurrent_step_poly2(Q[:, :, i], K[:, :, i], V[:, :, i], S, z, eps)
+        np.testing.assert_allclose(out, O[:, :, i], rtol=1e-12, atol=1e-14)
+    # the chain rule helper alone: d/dx of sum(W * vec(x x^T)) = (W + W^T) x
+    x, W = rng.standard_normal(d), rng.standard_normal((d, d))
+    np.testing.assert_allclose(oracle.poly2_chain(x, W.reshape(-1)), (W + W.T) @ x, rtol=1e-12)
