@@ -98,9 +98,11 @@ def kernel_flops(name: str, D: int, M: int) -> float:
 class FwdBwd:
     """Device buffers and the step function for one workload."""
 
-    def __init__(self, w, bf16=False, token_major=False, group=0):
+    def __init__(self, w, bf16=False, token_major=False, group=0, poly2=False):
         """group > 0: the (batch, head) sequences are processed `group` at a time (forward and
-        backward of one group, then the next): a schedule experiment, see --groups."""
+        backward of one group, then the next): a schedule experiment, see --groups.
+        poly2: Q and K hold 8 raw values per token and the library applies the degree-2
+        polynomial map (section 3.2) to 64 features; eps 0.5."""
         import torch
 
         import paper_2006_16236_amd as la
@@ -110,6 +112,11 @@ class FwdBwd:
         host = wl.qkvg(w)
         if bf16:
             host = [wl.round_to_bf16(x) for x in host]
+        self.feat = False
+        self.eps = w.eps
+        if poly2:       # the first 8 of the 64 columns of Q and K are the raw vectors
+            host = [host[0][..., :8].copy(), host[1][..., :8].copy(), host[2], host[3]]
+            self.feat, self.eps = "poly2", 0.5
         self.host = host
         dt = torch.bfloat16 if bf16 else torch.float32
         self.Q, self.K, self.V, self.G = (torch.from_numpy(x).to(dev).to(dt) for x in host)
@@ -120,9 +127,10 @@ class FwdBwd:
         self.O = torch.empty_like(self.V)
         self.den = torch.empty(w.B, w.H, w.N, dtype=torch.float32, device=dev)
         self.dQ, self.dK, self.dV = (torch.empty_like(x) for x in (self.Q, self.K, self.V))
-        code = la.LA_BF16 if bf16 else la.LA_F32
-        nf = la.la_causal_fwd_workspace(w.B, w.H, w.N, w.D, w.M, code)
-        nb = la.la_causal_bwd_workspace(w.B, w.H, w.N, w.D, w.M, code)
+        code = la.LA_F32_POLY2 if poly2 else la.LA_BF16 if bf16 else la.LA_F32
+        Dq = 8 if poly2 else w.D
+        nf = la.la_causal_fwd_workspace(w.B, w.H, w.N, Dq, w.M, code)
+        nb = la.la_causal_bwd_workspace(w.B, w.H, w.N, Dq, w.M, code)
         self.ws_f = torch.empty(max(nf, 16), dtype=torch.uint8, device=dev)
         self.ws_b = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
         self.groups = None
@@ -149,13 +157,13 @@ class FwdBwd:
             return
         fwd = la.la_causal_fwd_bnhd if self.token_major else la.la_causal_fwd
         bwd = la.la_causal_bwd_bnhd if self.token_major else la.la_causal_bwd
-        fwd(self.Q, self.K, self.V, self.O, self.den, w.eps, ws=self.ws_f)
+        fwd(self.Q, self.K, self.V, self.O, self.den, self.eps, ws=self.ws_f, features=self.feat)
         bwd(self.Q, self.K, self.V, self.O, self.den, self.G, self.dQ, self.dK,
-            self.dV, w.eps, ws=self.ws_b, fwd_ws=self.ws_f)
+            self.dV, self.eps, ws=self.ws_b, fwd_ws=self.ws_f, features=self.feat)
 
     def fwd_only(self):
         fwd = self.la.la_causal_fwd_bnhd if self.token_major else self.la.la_causal_fwd
-        fwd(self.Q, self.K, self.V, self.O, self.den, self.w.eps, ws=self.ws_f)
+        fwd(self.Q, self.K, self.V, self.O, self.den, self.eps, ws=self.ws_f, features=self.feat)
 
 
 # The GPU needs some tens of milliseconds of back-to-back work to settle its clocks: the first
@@ -271,7 +279,7 @@ class Decode:
             la.la_recurrent_step(self.q[t], self.k[t], self.v[t], self.S, self.z, self.out[0], d.eps)
 
 
-WORKLOADS = ("headline", "headline_bf16", "global", "global_bf16", "cfg2", "cfg3", "cfg3_bf16",
+WORKLOADS = ("headline", "headline_bf16", "headline_poly2", "global", "global_bf16", "cfg2", "cfg3", "cfg3_bf16",
              "decode_B64", "decode_B4096", "decode_B64_multi")
 
 
@@ -295,19 +303,25 @@ def make_workload(name, group=0):
                                 "seed": d.seed},
                      "rename": {"recurrent_step": "recurrent_steps"} if multi else {}}
     bf16 = name.endswith("_bf16")
-    base = name[:-5] if bf16 else name
+    poly2 = name.endswith("_poly2")
+    base = name[:-5] if bf16 else name[:-6] if poly2 else name
     w = {"headline": wl.HEADLINE, "global": wl.HEADLINE, "cfg2": wl.CFG2, "cfg3": wl.CFG3}[base]
     glob = base == "global"
-    obj = GlobalFwdBwd(w, bf16) if glob else FwdBwd(w, bf16, group=group)
+    obj = GlobalFwdBwd(w, bf16) if glob else FwdBwd(w, bf16, group=group, poly2=poly2)
     e = 2 if bf16 else 4
     metric = ("non-causal" if glob else "causal") + f" linear-attn fwd+bwd Mtokens/s (H={w.H},D={w.D},M={w.M},N={w.N})"
     if name == "headline":
         metric = "causal linear-attn fwd+bwd Mtokens/s (H=8,D=M=64,N=2^16)"
-    return obj, {"metric": metric, "tokens": w.B * w.N, "H": w.H, "D": w.D, "M": w.M, "e": e,
-                 "dtype": "bf16" if bf16 else "f32", "host": obj.host, "w": w,
-                 "path_bytes": e * (6 * w.D + 6 * w.M),
-                 "config": {"workload": w.name + ("_bf16" if bf16 else "") + ("_noncausal" if glob else ""),
-                            "B": w.B, "H": w.H, "N": w.N, "D": w.D, "M": w.M, "eps": w.eps,
+    if poly2:
+        metric = "causal linear-attn fwd+bwd Mtokens/s, degree-2 polynomial map of 8 raw dims (H=8,C=M=64,N=2^16)"
+    # D: elements per token of Q, K (sizes the bytes); C: feature width (sizes the flops)
+    return obj, {"metric": metric, "tokens": w.B * w.N, "H": w.H, "D": 8 if poly2 else w.D, "C": w.D, "M": w.M, "e": e,
+                 "dtype": "bf16" if bf16 else "f32", "host": obj.host, "w": None if poly2 else w,
+                 # (polynomial map: Q, K and their gradients are 8 wide, 4 of the 12 tensors)
+                 "path_bytes": e * (6 * w.M + 4 * 8) if poly2 else e * (6 * w.D + 6 * w.M),
+                 "config": {"workload": w.name + ("_bf16" if bf16 else "") + ("_noncausal" if glob else "")
+                            + ("_poly2_map_of_8_raw_dims" if poly2 else ""),
+                            "B": w.B, "H": w.H, "N": w.N, "D": 8 if poly2 else w.D, "M": w.M, "eps": obj.eps,
                             "step": "la_global_fwd + la_global_bwd" if glob else "la_causal_fwd + la_causal_bwd",
                             "seed": w.seed},
                  # the non-causal dQ kernel reads fewer tensors than the causal one
@@ -377,7 +391,7 @@ def run_workload(args):
     if args.workload.endswith("_multi"):
         th_per_launch = th
     ach_gbs = kernel_bytes(kname, D, M, e) * th_per_launch / (dom_ms * 1e-3) / 1e9
-    ach_tf = kernel_flops(kname, D, M) * th_per_launch / (dom_ms * 1e-3) / 1e12
+    ach_tf = kernel_flops(kname, info.get("C", D), M) * th_per_launch / (dom_ms * 1e-3) / 1e12
     hbm_ceiling = HBM_PEAK_GBS * 1e9 / (H * info["path_bytes"]) / 1e6
     traffic = measured_traffic_bytes().get(dominant) if args.workload == "headline" else None
     out = {

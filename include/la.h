@@ -25,8 +25,21 @@
  *              inputs): Q and K (q and k of the decode calls) then hold the
  *              feature values, no map is applied, and dQ, dK are gradients
  *              with respect to those features.  The feature width is D.
+ *              With t = LA_F32_POLY2 the feature map is that of the polynomial
+ *              kernel of degree 2 (section 3.2), sim(q, k) = (q . k)^2:
+ *              phi(x) = vec(x x^T), feature D*i + j = x_i x_j.  Q and K (q, k of the
+ *              decode calls) hold the RAW vectors, D = 8 values per token (fp32),
+ *              the kernels build the C = D^2 = 64 features as they load a tile
+ *              (a call reads 32 bytes of Q per token and head, not 256), and dQ, dK
+ *              are gradients with respect to the raw vectors, [.., 8] like Q and K.
+ *              Everything sized by the feature width is sized by C: the decode
+ *              state S [B,H,C,M], z [B,H,C] and the states of the _state entry
+ *              points.  The features are signed, so den is not bounded away from
+ *              zero by construction: pass an eps that suits the data.  All entry
+ *              points take this code.
  *   Sizes      B, H, N >= 1.  N needs no alignment.  D and M must each be 32 or
- *              64 (LA_ERR_UNSUPPORTED otherwise).  B*H*N*max(D,M) < 2^40.
+ *              64 (LA_ERR_UNSUPPORTED otherwise; LA_F32_POLY2: D = 8, M 32 or 64).
+ *              B*H*N*max(D,M) < 2^40.
  *   eps        den_i = phi(Q_i) . Z_i + eps, added once to the finished dot
  *              product; eps >= 0.  With eps = 0 a denominator can still be exactly
  *              0 in fp32: phi(x) = exp(x) underflows to 0 for x below about -87, and
@@ -73,14 +86,15 @@ typedef enum {
     LA_F32 = 0,
     LA_BF16 = 1,
     LA_F32_FEATURES = 2,      /* fp32, Q and K hold feature values already  */
-    LA_BF16_FEATURES = 3      /* bf16, Q and K hold feature values already  */
+    LA_BF16_FEATURES = 3,     /* bf16, Q and K hold feature values already  */
+    LA_F32_POLY2 = 4          /* fp32, degree-2 polynomial kernel: phi(x) = vec(x x^T)  */
 } la_dtype;
 
 typedef enum {
     LA_OK = 0,
     LA_ERR_NULL = -1,         /* a required pointer is NULL                         */
     LA_ERR_SHAPE = -2,        /* B, H or N < 1, eps < 0 or not finite, size overflow */
-    LA_ERR_UNSUPPORTED = -3,  /* D or M not in {32, 64}, unknown dtype              */
+    LA_ERR_UNSUPPORTED = -3,  /* D or M not in {32, 64} (LA_F32_POLY2: D != 8), unknown dtype */
     LA_ERR_WORKSPACE = -4,    /* ws is NULL or ws_bytes is smaller than the query   */
     LA_ERR_HIP = -5,          /* a HIP call or kernel launch failed                 */
     LA_ERR_ALIGN = -6,        /* a tensor pointer is not 16-byte aligned            */

@@ -14,7 +14,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libla_hip.so")
 
-LA_F32, LA_BF16, LA_F32_FEATURES, LA_BF16_FEATURES = 0, 1, 2, 3
+LA_F32, LA_BF16, LA_F32_FEATURES, LA_BF16_FEATURES, LA_F32_POLY2 = 0, 1, 2, 3, 4
 LA_OK, LA_ERR_NULL, LA_ERR_SHAPE, LA_ERR_UNSUPPORTED = 0, -1, -2, -3
 LA_ERR_WORKSPACE, LA_ERR_HIP, LA_ERR_ALIGN, LA_ERR_ALIAS, LA_ERR_SCRATCH = -4, -5, -6, -7, -8
 LA_NOALLOC_SCRATCH_BYTES = 40 << 20
@@ -108,9 +108,14 @@ def la_version() -> int:
     return int(_lib.la_version())
 
 
-def _dtype_code(t: torch.Tensor, features: bool = False) -> int:
+def _dtype_code(t: torch.Tensor, features=False) -> int:
     """features=True: Q and K hold feature values of a map the caller applied (no elu + 1 inside,
-    gradients with respect to the features)."""
+    gradients with respect to the features).  features="poly2": Q and K hold raw 8-vectors and
+    the library applies the degree-2 polynomial map vec(x x^T) (fp32 only)."""
+    if features == "poly2":
+        if t.dtype != torch.float32:
+            raise TypeError(f"the polynomial map takes float32 tensors, not {t.dtype}")
+        return LA_F32_POLY2
     if t.dtype == torch.float32:
         return LA_F32_FEATURES if features else LA_F32
     if t.dtype == torch.bfloat16:
@@ -222,14 +227,15 @@ class _Sizes:
         self.rows = (B, H, N)                             # den: always [B, H, N]
         self.dtype, self.dev = Q.dtype, Q.device
         self.dims = (B, H, N, D, M)
+        self.C = D * D if self.t == LA_F32_POLY2 else D       # feature width (sizes the states)
 
     @property
     def S(self):
-        return (self.B, self.H, self.D, self.M)
+        return (self.B, self.H, self.C, self.M)
 
     @property
     def z(self):
-        return (self.B, self.H, self.D)
+        return (self.B, self.H, self.C)
 
     def inputs(self, Q, K, V):
         if not Q.is_contiguous():
@@ -455,14 +461,15 @@ def _step_checks(q, k, v, S, z, out, lead, features):
     t = _dtype_code(q, features)
     B, H, D = qs[lead:]
     M = vs[-1]
+    C = D * D if t == LA_F32_POLY2 else D          # feature width (sizes the state)
     dev, dt = q.device, q.dtype
     vshape = tuple(qs[:-1]) + (M,)
     try:        # the accepting path: one expression, no calls (this runs before every decode step)
         if (q.is_contiguous() and k.shape == qs and k.dtype is dt and k.device == dev and k.is_contiguous()
                 and v.shape == vshape and v.dtype is dt and v.device == dev and v.is_contiguous()
                 and out.shape == vshape and out.dtype is dt and out.device == dev and out.is_contiguous()
-                and S.shape == (B, H, D, M) and S.dtype is torch.float32 and S.device == dev and S.is_contiguous()
-                and z.shape == (B, H, D) and z.dtype is torch.float32 and z.device == dev and z.is_contiguous()):
+                and S.shape == (B, H, C, M) and S.dtype is torch.float32 and S.device == dev and S.is_contiguous()
+                and z.shape == (B, H, C) and z.dtype is torch.float32 and z.device == dev and z.is_contiguous()):
             return t, B, H, D, M
     except AttributeError:
         pass
@@ -471,8 +478,8 @@ def _step_checks(q, k, v, S, z, out, lead, features):
     _like("k", k, qs, dt, dev)
     _like("v", v, vshape, dt, dev)
     _like("out", out, vshape, dt, dev)
-    _like("S", S, (B, H, D, M), torch.float32, dev)
-    _like("z", z, (B, H, D), torch.float32, dev)
+    _like("S", S, (B, H, C, M), torch.float32, dev)
+    _like("z", z, (B, H, C), torch.float32, dev)
     return t, B, H, D, M
 
 

@@ -60,10 +60,18 @@ size_t states_bytes(long BH, const Plan &p, int D, int M) {
     return align256((size_t)BH * p.nseg * la::state_stride(D, M) * sizeof(float));
 }
 
+// Feature width C of Q and K inside the kernels: D itself, or D^2 for the degree-2 polynomial
+// map (section 3.2), whose Q and K hold D = 8 raw values per token.
+int feat_width(int D, la_dtype t) { return t == LA_F32_POLY2 ? D * D : D; }
+
 int check_dims(int B, int H, int N, int D, int M, float eps, la_dtype t) {
-    if (t != LA_F32 && t != LA_BF16 && t != LA_F32_FEATURES && t != LA_BF16_FEATURES)
+    if (t != LA_F32 && t != LA_BF16 && t != LA_F32_FEATURES && t != LA_BF16_FEATURES && t != LA_F32_POLY2)
         return LA_ERR_UNSUPPORTED;
-    if (!((D == 32 || D == 64) && (M == 32 || M == 64))) return LA_ERR_UNSUPPORTED;
+    if (t == LA_F32_POLY2) {
+        if (!(D == 8 && (M == 32 || M == 64))) return LA_ERR_UNSUPPORTED;
+    } else if (!((D == 32 || D == 64) && (M == 32 || M == 64))) {
+        return LA_ERR_UNSUPPORTED;
+    }
     if (B < 1 || H < 1 || N < 1) return LA_ERR_SHAPE;
     if (!(eps >= 0.0f) || !isfinite(eps)) return LA_ERR_SHAPE;
     const double elems = (double)B * H * (double)N * (D > M ? D : M);
@@ -258,34 +266,38 @@ int la_version(void) { return kVersion; }
 
 size_t la_causal_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const int C = feat_width(D, t);
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
-    return p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+    return p.nseg > 1 ? states_bytes(BH, p, C, M) : 0;
 }
 
 size_t la_causal_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const int C = feat_width(D, t);
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
     size_t bytes = 3 * align256(rows * sizeof(float));      // 1/den, delta, and den if it is recomputed
-    if (p.nseg > 1) bytes += 2 * states_bytes(BH, p, D, M); // S and R states
+    if (p.nseg > 1) bytes += 2 * states_bytes(BH, p, C, M); // S and R states
     (void)t;
     return bytes;
 }
 
 size_t la_global_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const int C = feat_width(D, t);
     const long BH = (long)B * H;
-    return states_bytes(BH, make_plan(BH, N), D, M);
+    return states_bytes(BH, make_plan(BH, N), C, M);
 }
 
 size_t la_global_bwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
+    const int C = feat_width(D, t);
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
-    size_t bytes = 2 * states_bytes(BH, p, D, M);           // the two grand totals
+    size_t bytes = 2 * states_bytes(BH, p, C, M);           // the two grand totals
     bytes += align256(rows * sizeof(float));                // den if it is recomputed
     (void)t;
     return bytes;
@@ -297,17 +309,18 @@ static int causal_fwd_impl(const void *Q, const void *K, const void *V, void *O,
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws))
         return LA_ERR_ALIGN;
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
-    const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+    const size_t need = p.nseg > 1 ? states_bytes(BH, p, C, M) : 0;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return LA_ERR_WORKSPACE;
     const size_t rows = (size_t)BH * N, e = esize(t);
     const Span outs[] = {{O, rows * M * e}, {den, rows * 4}, {ws, need}};
     const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e}};
     if (aliased(outs, ins)) return LA_ERR_ALIAS;
-    return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
+    return run_causal_fwd(Q, K, V, O, den, BH, N, C, M, eps, t, p, static_cast<float *>(ws),
                           static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, nullptr, H,
                           tok_heads);
 }
@@ -330,10 +343,11 @@ int la_causal_fwd_noalloc(const void *Q, const void *K, const void *V, void *O, 
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O)) return LA_ERR_ALIGN;
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
-    const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+    const size_t need = p.nseg > 1 ? states_bytes(BH, p, C, M) : 0;
     if (need > kScratchBytes) return LA_ERR_SCRATCH;
     const size_t rows = (size_t)BH * N, e = esize(t);
     const Span outs[] = {{O, rows * M * e}, {den, rows * 4}};
@@ -346,7 +360,7 @@ int la_causal_fwd_noalloc(const void *Q, const void *K, const void *V, void *O, 
         const int ss = scratch_on_current_device(&states);
         if (ss != LA_OK) return ss;
     }
-    return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(states),
+    return run_causal_fwd(Q, K, V, O, den, BH, N, C, M, eps, t, p, static_cast<float *>(states),
                           static_cast<hipStream_t>(stream), nullptr, nullptr, nullptr, nullptr, H, 0);
 }
 
@@ -358,20 +372,21 @@ static int causal_fwd_state_impl(const void *Q, const void *K, const void *V, co
     if ((S0 == nullptr) != (z0 == nullptr) || (S1 == nullptr) != (z1 == nullptr)) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws) ||
         misaligned(S0) || misaligned(z0) || misaligned(S1) || misaligned(z1))
         return LA_ERR_ALIGN;
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
-    const size_t need = p.nseg > 1 ? states_bytes(BH, p, D, M) : 0;
+    const size_t need = p.nseg > 1 ? states_bytes(BH, p, C, M) : 0;
     if (need > 0 && (ws == nullptr || ws_bytes < need)) return LA_ERR_WORKSPACE;
     const size_t rows = (size_t)BH * N, e = esize(t);
     const Span outs[] = {{O, rows * M * e}, {den, rows * 4}, {ws, need},
-                         {S1, (size_t)BH * D * M * 4}, {z1, (size_t)BH * D * 4}};
+                         {S1, (size_t)BH * C * M * 4}, {z1, (size_t)BH * C * 4}};
     const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e},
-                        {S0, (size_t)BH * D * M * 4}, {z0, (size_t)BH * D * 4}};
+                        {S0, (size_t)BH * C * M * 4}, {z0, (size_t)BH * C * 4}};
     if (aliased(outs, ins)) return LA_ERR_ALIAS;
-    return run_causal_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
+    return run_causal_fwd(Q, K, V, O, den, BH, N, C, M, eps, t, p, static_cast<float *>(ws),
                           static_cast<hipStream_t>(stream), S0, z0, S1, z1, H, tok_heads);
 }
 
@@ -405,6 +420,7 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
         return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) ||
         misaligned(dK) || misaligned(dV) || misaligned(O) || misaligned(den) || misaligned(ws) ||
         misaligned(fwd_ws) || misaligned(S0) || misaligned(z0) || misaligned(dS1) ||
@@ -418,12 +434,12 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     const Plan p = make_plan(BH, N);
     const size_t rows = (size_t)BH * N;
     {
-        const size_t e = esize(t), sb = (size_t)BH * D * M * 4, zb = (size_t)BH * D * 4;
+        const size_t e = esize(t), sb = (size_t)BH * C * M * 4, zb = (size_t)BH * C * 4;
         const Span outs[] = {{dQ, rows * D * e}, {dK, rows * D * e}, {dV, rows * M * e},
                              {ws, need}, {dS0, sb}, {dz0, zb}};
         const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e},
                             {dO, rows * M * e}, {den, rows * 4}, {S0, sb}, {z0, zb}, {dS1, sb},
-                            {dz1, zb}, {fwd_ws, p.nseg > 1 ? states_bytes(BH, p, D, M) : 0}};
+                            {dz1, zb}, {fwd_ws, p.nseg > 1 ? states_bytes(BH, p, C, M) : 0}};
         if (aliased(outs, ins)) return LA_ERR_ALIAS;
     }
     Carver cv{static_cast<char *>(ws), 0};
@@ -431,8 +447,8 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     float *delta = static_cast<float *>(cv.take(rows * sizeof(float)));
     float *stS = nullptr, *stR = nullptr;
     if (p.nseg > 1) {
-        stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
-        stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
+        stS = static_cast<float *>(cv.take(states_bytes(BH, p, C, M)));
+        stR = static_cast<float *>(cv.take(states_bytes(BH, p, C, M)));
     }
     (void)O;                                   // not read: delta is rebuilt from the state
     const bool recompute_fwd = (den == nullptr);
@@ -442,7 +458,7 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
         stS = const_cast<float *>(static_cast<const float *>(fwd_ws));
     if (recompute_fwd) {                       // recompute the forward's denominators (no output)
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));
-        const int fs = run_causal_fwd(Q, K, V, nullptr, dentmp, BH, N, D, M, eps, t, p, stS, s, S0, z0,
+        const int fs = run_causal_fwd(Q, K, V, nullptr, dentmp, BH, N, C, M, eps, t, p, stS, s, S0, z0,
                                       nullptr, nullptr, H, tok_heads);
         if (fs != LA_OK) return fs;
         den = dentmp;
@@ -454,9 +470,9 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
         sa.Y = K; sa.Z = V; sa.state = stS;
         sa.skip_seg = p.nseg - 1;
         sa.heads = H; sa.tok_heads = tok_heads;
-        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(C, M, (int)t, sa, nblocks, s)); }
         if (!p.fold)
-            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanForward, s, S0, z0, D * M)); }
+            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(C, M), la::kScanForward, s, S0, z0, C * M)); }
     }
     // The two kernels of the backward run two waves per workgroup, so half as many workgroups
     // fill the machine: they take the forward's segments in pairs.  The prefix states (laid out
@@ -478,15 +494,15 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
     // the caller's state: the scan has added it to the prefix states already, if there was one
     const bool scanned = p.nseg > 1 && !p.fold;
     a.init_S = scanned ? nullptr : S0; a.init_z = scanned ? nullptr : z0;
-    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(true, D, M, (int)t, a, nblocks_b, s)); }
+    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(true, C, M, (int)t, a, nblocks_b, s)); }
     const bool scanned_b = pb.nseg > 1 && !p.fold;
     if (scanned_b)
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(D, M), la::kScanReverse, s, dS1, dz1, D * M)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(C, M), la::kScanReverse, s, dS1, dz1, C * M)); }
     a.out = dV; a.out2 = dK; a.state = pb.nseg > 1 ? stR : nullptr;
     a.state_nseg = 0; a.state_step = 0;      // stR is laid out for this very cut
     a.init_S = scanned_b ? nullptr : dS1; a.init_z = scanned_b ? nullptr : dz1;
     a.final_S = dS0; a.final_z = dz0;
-    { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(D, M, (int)t, a, nblocks_b, s)); }
+    { ProfScope ps(LA_K_REV, s); LA_TRY(la::launch_pass_reverse(C, M, (int)t, a, nblocks_b, s)); }
     return LA_OK;
 }
 
@@ -531,17 +547,18 @@ static int global_fwd_impl(const void *Q, const void *K, const void *V, void *O,
     if (Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || misaligned(ws) ||
         misaligned(den))
         return LA_ERR_ALIGN;
     const long BH = (long)B * H;
     const Plan p = make_plan(BH, N);
-    if (ws == nullptr || ws_bytes < states_bytes(BH, p, D, M)) return LA_ERR_WORKSPACE;
+    if (ws == nullptr || ws_bytes < states_bytes(BH, p, C, M)) return LA_ERR_WORKSPACE;
     const size_t rows = (size_t)BH * N, e = esize(t);
-    const Span outs[] = {{O, rows * M * e}, {den, rows * 4}, {ws, states_bytes(BH, p, D, M)}};
+    const Span outs[] = {{O, rows * M * e}, {den, rows * 4}, {ws, states_bytes(BH, p, C, M)}};
     const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e}};
     if (aliased(outs, ins)) return LA_ERR_ALIAS;
-    return run_global_fwd(Q, K, V, O, den, BH, N, D, M, eps, t, p, static_cast<float *>(ws),
+    return run_global_fwd(Q, K, V, O, den, BH, N, C, M, eps, t, p, static_cast<float *>(ws),
                           static_cast<hipStream_t>(stream), H, tok_heads);
 }
 
@@ -567,6 +584,7 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
         return LA_ERR_NULL;
     const int st = check_dims(B, H, N, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(dO) || misaligned(dQ) ||
         misaligned(dK) || misaligned(dV) || misaligned(O) || misaligned(den) || misaligned(ws) ||
         misaligned(fwd_ws))
@@ -583,16 +601,16 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
         const size_t e = esize(t);
         const Span outs[] = {{dQ, rows * D * e}, {dK, rows * D * e}, {dV, rows * M * e}, {ws, need}};
         const Span ins[] = {{Q, rows * D * e}, {K, rows * D * e}, {V, rows * M * e},
-                            {dO, rows * M * e}, {den, rows * 4}, {fwd_ws, states_bytes(BH, p, D, M)}};
+                            {dO, rows * M * e}, {den, rows * 4}, {fwd_ws, states_bytes(BH, p, C, M)}};
         if (aliased(outs, ins)) return LA_ERR_ALIAS;
     }
     Carver cv{static_cast<char *>(ws), 0};
-    float *stS = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
-    float *stR = static_cast<float *>(cv.take(states_bytes(BH, p, D, M)));
+    float *stS = static_cast<float *>(cv.take(states_bytes(BH, p, C, M)));
+    float *stR = static_cast<float *>(cv.take(states_bytes(BH, p, C, M)));
     const int nblocks = (int)(BH * p.nseg);
     if (den == nullptr) {                      // recompute the forward's denominators (no output);
         float *dentmp = static_cast<float *>(cv.take(rows * sizeof(float)));   // also leaves the K, V sums in stS
-        const int fs = run_global_fwd(Q, K, V, nullptr, dentmp, BH, N, D, M, eps, t, p, stS, s, H,
+        const int fs = run_global_fwd(Q, K, V, nullptr, dentmp, BH, N, C, M, eps, t, p, stS, s, H,
                                       tok_heads);
         if (fs != LA_OK) return fs;
         den = dentmp;
@@ -603,9 +621,9 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
         sa.heads = H; sa.tok_heads = tok_heads;
         sa.N = N; sa.nseg = p.nseg; sa.chunks_per_seg = p.cps; sa.skip_seg = -1;
         sa.Y = K; sa.Z = V; sa.state = stS;
-        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(D, M, (int)t, sa, nblocks, s)); }
+        { ProfScope ps(LA_K_SEG_KV, s); LA_TRY(la::launch_segment_state(C, M, (int)t, sa, nblocks, s)); }
         if (p.nseg > 1 && !p.fold)
-            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+            { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stS, (int)BH, p.nseg, la::state_stride(C, M), la::kScanTotal, s)); }
     }
     // dQ against the K, V total; on the way the per-segment Q, dO sums.  A kernel with two
     // waves per workgroup: it takes the segments in pairs (see the causal backward).
@@ -619,17 +637,17 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
     a.Q = Q; a.K = K; a.V = V; a.G = dO; a.den_in = den; a.totals = stR;
     a.N = N; a.nseg = pb.nseg; a.chunks_per_seg = pb.cps; a.eps = eps;
     a.out = dQ; a.state = stS; a.state_nseg = p.nseg; a.fold = p.fold;
-    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(false, D, M, (int)t, a, (int)(BH * pb.nseg), s)); }
+    { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(false, C, M, (int)t, a, (int)(BH * pb.nseg), s)); }
     if (pb.nseg > 1 && !p.fold)
-        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(D, M), la::kScanTotal, s)); }
+        { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(C, M), la::kScanTotal, s)); }
     // dV and dK against the Q, dO total
     a.totals = nullptr; a.nseg = p.nseg; a.chunks_per_seg = p.cps;
     a.state = stR; a.state_nseg = pb.nseg;
     ProfScope ps(LA_K_GLOBAL_BWD, s);
     a.out = dV;
-    LA_TRY(la::launch_pass_global_bwd(1, D, M, (int)t, a, nblocks, s));
+    LA_TRY(la::launch_pass_global_bwd(1, C, M, (int)t, a, nblocks, s));
     a.out = dK;
-    LA_TRY(la::launch_pass_global_bwd(2, D, M, (int)t, a, nblocks, s));
+    LA_TRY(la::launch_pass_global_bwd(2, C, M, (int)t, a, nblocks, s));
     return LA_OK;
 }
 
@@ -656,18 +674,19 @@ int la_recurrent_step(const void *q, const void *k, const void *v, float *S, flo
         return LA_ERR_NULL;
     const int st = check_dims(B, H, 1, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(S) || misaligned(z) ||
         misaligned(out))
         return LA_ERR_ALIGN;
     {
         const size_t bh = (size_t)B * H, e = esize(t);
-        const Span outs[] = {{out, bh * M * e}, {S, bh * D * M * 4}, {z, bh * D * 4}};
+        const Span outs[] = {{out, bh * M * e}, {S, bh * C * M * 4}, {z, bh * C * 4}};
         const Span ins[] = {{q, bh * D * e}, {k, bh * D * e}, {v, bh * M * e}};
         if (aliased(outs, ins)) return LA_ERR_ALIAS;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     ProfScope ps(LA_K_STEP, s);
-    LA_TRY(la::launch_recurrent_step(q, k, v, S, z, out, (int)((long)B * H), D, M, eps, (int)t, s));
+    LA_TRY(la::launch_recurrent_step(q, k, v, S, z, out, (int)((long)B * H), C, M, eps, (int)t, s));
     return LA_OK;
 }
 
@@ -678,19 +697,20 @@ int la_recurrent_steps(const void *q, const void *k, const void *v, float *S, fl
         return LA_ERR_NULL;
     const int st = check_dims(B, H, T, D, M, eps, t);
     if (st != LA_OK) return st;
+    const int C = feat_width(D, t);
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(S) || misaligned(z) ||
         misaligned(out))
         return LA_ERR_ALIGN;
     {
         const size_t bh = (size_t)B * H, e = esize(t);
-        const Span outs[] = {{out, (size_t)T * bh * M * e}, {S, bh * D * M * 4}, {z, bh * D * 4}};
+        const Span outs[] = {{out, (size_t)T * bh * M * e}, {S, bh * C * M * 4}, {z, bh * C * 4}};
         const Span ins[] = {{q, (size_t)T * bh * D * e}, {k, (size_t)T * bh * D * e},
                             {v, (size_t)T * bh * M * e}};
         if (aliased(outs, ins)) return LA_ERR_ALIAS;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     ProfScope ps(LA_K_STEP, s);
-    LA_TRY(la::launch_recurrent_steps(q, k, v, S, z, out, T, (int)((long)B * H), D, M, eps, (int)t, s));
+    LA_TRY(la::launch_recurrent_steps(q, k, v, S, z, out, T, (int)((long)B * H), C, M, eps, (int)t, s));
     return LA_OK;
 }
 

@@ -40,11 +40,22 @@ struct bf16_t { uint16_t bits; };
 // the element type; for them the tag changes nothing.)
 struct feat_f32 { float v; };
 struct feat_bf16 { uint16_t bits; };
+// fp32 tensors with the feature map of the degree-2 polynomial kernel (section 3.2),
+// phi(x) = vec(x x^T): Q and K hold kPolyRaw = 8 raw values per token, a tile of phi(Q) or phi(K)
+// has 64 features (feature 8i + j = x_i x_j) and is built in the staging registers when it is
+// fetched (stage_load_poly2); inside the kernels it is a tile of given features like any other.
+// Gradients go back to the raw vectors (poly2_chain).
+struct poly2_f32 { float v; };
+constexpr int kPolyRaw = 8;
 
 template <typename T>
 constexpr bool is_bf16 = std::is_same<T, bf16_t>::value || std::is_same<T, feat_bf16>::value;
 template <typename T>
-constexpr bool is_feat = std::is_same<T, feat_f32>::value || std::is_same<T, feat_bf16>::value;
+constexpr bool is_poly = std::is_same<T, poly2_f32>::value;
+template <typename T>
+constexpr bool is_feat = std::is_same<T, feat_f32>::value || std::is_same<T, feat_bf16>::value || is_poly<T>;
+// elements per token of a Q or K tensor (and of dQ, dK) whose feature width is F
+template <typename T> __host__ __device__ constexpr int qk_width(int F) { return is_poly<T> ? kPolyRaw : F; }
 
 // feature value of a raw element of Q or K: eq. 7, or the element itself when the caller has
 // applied the map; and the slope of the map recovered from the feature value
@@ -61,6 +72,7 @@ __device__ __forceinline__ float to_f32(float x) { return x; }
 __device__ __forceinline__ float to_f32(bf16_t x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
 __device__ __forceinline__ float to_f32(feat_f32 x) { return x.v; }
 __device__ __forceinline__ float to_f32(feat_bf16 x) { return __uint_as_float(((uint32_t)x.bits) << 16); }
+__device__ __forceinline__ float to_f32(poly2_f32 x) { return x.v; }
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {      // round to nearest even
     return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f));     // v_cvt_pk_bf16_f32
@@ -84,6 +96,9 @@ template <> __device__ __forceinline__ void store_elem<bf16_t>(bf16_t *p, float 
     p->bits = f32_to_bf16_bits(v);
 }
 template <> __device__ __forceinline__ void store_elem<feat_f32>(feat_f32 *p, float v) { p->v = v; }
+template <> __device__ __forceinline__ void store_elem<poly2_f32>(poly2_f32 *p, float v) {
+    store_elem(reinterpret_cast<float *>(p), v);
+}
 template <> __device__ __forceinline__ void store_elem<feat_bf16>(feat_bf16 *p, float v) {
     p->bits = f32_to_bf16_bits(v);
 }
@@ -107,6 +122,9 @@ __device__ __forceinline__ f32x4 load4(const feat_f32 *p) {
 }
 __device__ __forceinline__ f32x4 load4(const feat_bf16 *p) {
     return load4(reinterpret_cast<const bf16_t *>(p));
+}
+__device__ __forceinline__ f32x4 load4(const poly2_f32 *p) {
+    return load4(reinterpret_cast<const float *>(p));
 }
 
 // ---- wave-level helpers ---------------------------------------------------------------------
@@ -352,6 +370,39 @@ __device__ __forceinline__ void stage_load(const T *base, int ts, int nvalid, in
     }
 }
 
+// A 16 x 64 tile of phi(Q) or phi(K) for the degree-2 polynomial map: `base` points at the 8
+// raw values of the tile's first token, rows are `ts` elements apart.  The lane that stages
+// features col .. col + 3 of a row (col = 4 * (lane % 16), the same assignment as stage_load<64>)
+// needs x_i with i = col / 8 and x_j for j = col % 8 .. + 3: one scalar and one 16-byte load.
+template <bool kFull, typename T>
+__device__ __forceinline__ void stage_load_poly2(const T *base, int ts, int nvalid, int lane, f32x4 (&st)[4]) {
+    const int i = (lane & 15) >> 1, j0 = 4 * (lane & 1);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int row = kFull ? stage_row<64>(lane, k) : min(stage_row<64>(lane, k), nvalid - 1);
+        const T *p = base + (size_t)row * ts;
+        st[k] = to_f32(p[i]) * load4(p + j0);
+    }
+}
+// fetch of a Q or K tile: the plain tile, or the expanded one
+template <int F, bool kFull, typename T>
+__device__ __forceinline__ void stage_load_qk(const T *base, int ts, int nvalid, int lane, f32x4 (&st)[F / 16]) {
+    if constexpr (is_poly<T>) {
+        static_assert(F == 64, "the degree-2 map of 8 raw values has 64 features");
+        stage_load_poly2<kFull>(base, ts, nvalid, lane, st);
+    } else {
+        stage_load<F, kFull>(base, ts, nvalid, lane, st);
+    }
+}
+// the 8 raw values of token min(lane / 4, nvalid - 1) of the tile (for poly2_chain)
+template <typename T>
+__device__ __forceinline__ void load_raw8(const T *base, int ts, int nvalid, int lane, float (&x)[kPolyRaw]) {
+    const T *p = base + (size_t)min(lane >> 2, nvalid - 1) * ts;
+    const f32x4 a = load4(p), b = load4(p + 4);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) x[j] = a[j], x[4 + j] = b[j];
+}
+
 // per-token fp32 scalars (1/den) of the rows a lane stages
 template <int F, bool kFull>
 __device__ __forceinline__ void stage_rows(const float *base, int nvalid, int lane, float (&sc)[F / 16]) {
@@ -404,6 +455,40 @@ __device__ __forceinline__ void lds_feature_lane(const float *tile, int c, int g
 #pragma unroll
         for (int ft = 0; ft < F / 16; ++ft) x[ft][s] = p[16 * ft];
     }
+}
+
+// Chain rule of x -> vec(x x^T) for one 16-token tile.  `out` is the gradient for the 64
+// features in the accumulator layout (lane (c, g), register r of out[zt]: token 4g + r, feature
+// 16zt + c); d(x_i x_j)/dx_k = delta_ik x_j + delta_jk x_i gives
+//   dx_k = sum_j (dphi[8k + j] + dphi[8j + k]) x_j.
+// The tile goes through `scratch` (16 rows of tile_stride(64) floats, private to the calling
+// wave, which both writes and reads it: LDS operations of one wave execute in order); lane
+// (t = lane / 4, p = lane % 4) returns dx[t][2p] and dx[t][2p + 1]; `x` holds the raw vector of
+// token t (load_raw8).
+__device__ __forceinline__ void poly2_chain(float *scratch, const f32x4 (&out)[4], const float (&x)[kPolyRaw],
+                                            int lane, float &g0, float &g1) {
+    const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int zt = 0; zt < 4; ++zt)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) scratch[(4 * g + r) * tile_stride(64) + 16 * zt + c] = out[zt][r];
+    __builtin_amdgcn_wave_barrier();
+    const float *row = scratch + (lane >> 2) * tile_stride(64);
+    const int k0 = 2 * (lane & 3);
+    float acc[2] = {0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+        const int k = k0 + kk;
+        const f32x4 a = *reinterpret_cast<const f32x4 *>(row + 8 * k);
+        const f32x4 b = *reinterpret_cast<const f32x4 *>(row + 8 * k + 4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            acc[kk] = fmaf(a[j] + row[8 * j + k], x[j], acc[kk]);
+            acc[kk] = fmaf(b[j] + row[8 * (j + 4) + k], x[j + 4], acc[kk]);
+        }
+    }
+    __builtin_amdgcn_wave_barrier();     // the next tile's writes stay behind these reads
+    g0 = acc[0], g1 = acc[1];
 }
 
 }  // namespace la

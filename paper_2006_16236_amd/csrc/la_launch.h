@@ -9,7 +9,8 @@
 namespace la {
 
 // dtype: the la_dtype of the public header (0 fp32, 1 bf16, 2 / 3 the same with Q, K holding
-// feature values already)
+// feature values already, 4 fp32 with the degree-2 polynomial map: D is then the FEATURE width
+// 64, Q and K hold 8 raw values per token)
 hipError_t launch_pass_fwd(bool global, int D, int M, int dtype, const PassArgs &a, int nblocks,
                            hipStream_t s);
 // dQ, 1/den, delta and (a.totals) the per-segment Q, dO sums; causal or against the global sums
@@ -56,6 +57,20 @@ hipError_t launch_recurrent_steps(const void *q, const void *k, const void *v, f
         else if ((D) == 64 && (M) == 32) { constexpr int kD = 64, kM = 32; __VA_ARGS__; } \
         else if ((D) == 64 && (M) == 64) { constexpr int kD = 64, kM = 64; __VA_ARGS__; } \
         else return hipErrorInvalidValue;                                      \
+    } while (0)
+
+// every supported (D, M, element type): the four head sizes for the first four types; the
+// degree-2 polynomial map has 64 features (D = 64 here) and either M
+#define LA_DISPATCH(D, M, dtype, ...)                                          \
+    do {                                                                       \
+        if ((dtype) == 4) {                                                    \
+            using TT = poly2_f32;                                              \
+            if ((D) == 64 && (M) == 32) { constexpr int kD = 64, kM = 32; __VA_ARGS__; }      \
+            else if ((D) == 64 && (M) == 64) { constexpr int kD = 64, kM = 64; __VA_ARGS__; } \
+            else return hipErrorInvalidValue;                                  \
+        } else {                                                               \
+            LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, __VA_ARGS__));           \
+        }                                                                      \
     } while (0)
 
 }  // namespace la

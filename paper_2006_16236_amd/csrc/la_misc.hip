@@ -92,6 +92,13 @@ hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hip
     return hipGetLastError();
 }
 
+// feature d of one token's q or k: eq. 7 of element d, the element itself when the caller has
+// applied the map, or x_i x_j with 8i + j = d for the degree-2 polynomial map (section 3.2)
+template <typename T> __device__ __forceinline__ float feature_of(const T *row, int d) {
+    if constexpr (is_poly<T>) return to_f32(row[d >> 3]) * to_f32(row[d & 7]);
+    else return feature<T>(to_f32(row[d]));
+}
+
 // ---- recurrent decode step (eq. 16-20) -------------------------------------------------------
 // One workgroup of four waves per head.  Every lane owns four adjacent columns of
 // S; M/4 lanes cover a row, a wave covers 256/M rows per iteration.  The rank-1
@@ -111,7 +118,8 @@ __global__ __launch_bounds__(256) void recurrent_step_kernel(const T *q, const T
 
     const int bh = blockIdx.x, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int col4 = (lane % LPR) * 4, rsub = lane / LPR;
-    const T *qh = q + (size_t)bh * D, *kh = k + (size_t)bh * D;
+    constexpr int W = qk_width<T>(D);          // elements per token of q and k
+    const T *qh = q + (size_t)bh * W, *kh = k + (size_t)bh * W;
     float *Sh = S + (size_t)bh * D * M, *zh = z + (size_t)bh * D;
 
     const f32x4 v4 = load4(v + (size_t)bh * M + col4);
@@ -120,8 +128,8 @@ __global__ __launch_bounds__(256) void recurrent_step_kernel(const T *q, const T
 #pragma unroll
     for (int it = 0; it < D / RPI; ++it) {
         const int d = it * RPI + wave * RPW + rsub;
-        const float kd = feature<T>(to_f32(kh[d]));
-        const float qd = feature<T>(to_f32(qh[d]));
+        const float kd = feature_of<T>(kh, d);
+        const float qd = feature_of<T>(qh, d);
         f32x4 s4 = *reinterpret_cast<f32x4 *>(Sh + (size_t)d * M + col4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -180,13 +188,19 @@ __global__ __launch_bounds__(256) void recurrent_steps_kernel(const T *q, const 
         s4[it] = *reinterpret_cast<const f32x4 *>(Sh + (size_t)d * M + col4);
         zr[it] = zh[d];
     }
+    constexpr int W = qk_width<T>(D);          // elements per token of q and k
     auto fetch = [&](int t, float (&kq)[2][NIT], f32x4 &v4) {
-        const T *qh = q + ((size_t)t * BH + bh) * D, *kh = k + ((size_t)t * BH + bh) * D;
+        const T *qh = q + ((size_t)t * BH + bh) * W, *kh = k + ((size_t)t * BH + bh) * W;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int d = it * RPI + wave * RPW + rsub;
-            kq[0][it] = to_f32(kh[d]);
-            kq[1][it] = to_f32(qh[d]);
+            if constexpr (is_poly<T>) {      // the feature itself (x_i x_j): nothing is left to map
+                kq[0][it] = feature_of<T>(kh, d);
+                kq[1][it] = feature_of<T>(qh, d);
+            } else {
+                kq[0][it] = to_f32(kh[d]);
+                kq[1][it] = to_f32(qh[d]);
+            }
         }
         v4 = load4(v + ((size_t)t * BH + bh) * M + col4);
     };
@@ -247,21 +261,21 @@ __global__ __launch_bounds__(256) void recurrent_steps_kernel(const T *q, const 
 hipError_t launch_recurrent_steps(const void *q, const void *k, const void *v, float *S, float *z,
                                   void *out, int steps, int BH, int D, int M, float eps, int dtype,
                                   hipStream_t s) {
-    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+    LA_DISPATCH(D, M, dtype, {
         recurrent_steps_kernel<kD, kM, TT><<<BH, 256, 0, s>>>((const TT *)q, (const TT *)k,
                                                              (const TT *)v, S, z, (TT *)out, eps,
                                                              steps, (size_t)BH);
-    }));
+    });
     return hipGetLastError();
 }
 
 hipError_t launch_recurrent_step(const void *q, const void *k, const void *v, float *S, float *z,
                                  void *out, int BH, int D, int M, float eps, int dtype,
                                  hipStream_t s) {
-    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+    LA_DISPATCH(D, M, dtype, {
         recurrent_step_kernel<kD, kM, TT><<<BH, 256, 0, s>>>((const TT *)q, (const TT *)k,
                                                             (const TT *)v, S, z, (TT *)out, eps);
-    }));
+    });
     return hipGetLastError();
 }
 

@@ -5,7 +5,7 @@ namespace la {
 
 hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &a, int nblocks,
                           hipStream_t s) {
-    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+    LA_DISPATCH(D, M, dtype, {
         if (a.tok_heads > 1) {
             if (!causal) dq_pass_kernel<kD, kM, TT, false, true><<<nblocks, 2 * kWave, 0, s>>>(a);
             else if constexpr (is_bf16<TT>) dq_pass_kernel<kD, kM, TT, true, true><<<nblocks, 2 * kWave, 0, s>>>(a);
@@ -15,7 +15,7 @@ hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &
             else if constexpr (is_bf16<TT>) dq_pass_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
             else dq_causal_kernel<kD, kM, TT><<<nblocks, 2 * kWave, 0, s>>>(a);
         }
-    }));
+    });
     return hipGetLastError();
 }
 

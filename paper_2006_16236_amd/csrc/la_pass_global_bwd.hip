@@ -6,7 +6,7 @@ namespace la {
 
 hipError_t launch_pass_global_bwd(int which, int D, int M, int dtype, const PassArgs &a,
                                   int nblocks, hipStream_t s) {
-    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+    LA_DISPATCH(D, M, dtype, {
         if (a.tok_heads > 1) {
             if (which == 1) causal_pass_kernel<kGlobalDv, kD, kM, TT, true><<<nblocks, kWave, 0, s>>>(a);
             else causal_pass_kernel<kGlobalDk, kD, kM, TT, true><<<nblocks, kWave, 0, s>>>(a);
@@ -14,7 +14,7 @@ hipError_t launch_pass_global_bwd(int which, int D, int M, int dtype, const Pass
             if (which == 1) causal_pass_kernel<kGlobalDv, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
             else causal_pass_kernel<kGlobalDk, kD, kM, TT><<<nblocks, kWave, 0, s>>>(a);
         }
-    }));
+    });
     return hipGetLastError();
 }
 

@@ -6,10 +6,10 @@ namespace la {
 
 hipError_t launch_pass_reverse(int D, int M, int dtype, const PassArgs &a, int nblocks,
                                hipStream_t s) {
-    LA_DISPATCH_DM(D, M, LA_DISPATCH_T(dtype, {
+    LA_DISPATCH(D, M, dtype, {
         if (a.tok_heads > 1) reverse_pass_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
         else reverse_pass_kernel<kD, kM, TT><<<nblocks, 2 * kWave, 0, s>>>(a);
-    }));
+    });
     return hipGetLastError();
 }
 

@@ -209,25 +209,31 @@ struct PassStager {
     static_assert(PASS == kFwd || PASS == kGlobal || PASS == kGlobalDv || PASS == kGlobalDk,
                   "the other passes have stagers of their own");
     static constexpr int DX = Tr::DX, DZ = Tr::DZ, XT = DX / 16, ZT = DZ / 16;
+    // X is phi(Q) (kFwd, kGlobal) or phi(K) (kGlobalDv): a Q / K tensor (qk_width elements per
+    // token, expanded on fetch for the polynomial map); otherwise it is V
+    static constexpr bool kXqk = (Tr::BP == kFwd || Tr::BP == kDv);
     const T *Xs, *Ys, *Zs, *Rs;
     float *lds_x, *lds_y, *lds_z, *lds_r;
     int N, lane;
-    int tsx, tsz;                       // token strides of the DX-wide and DZ-wide tensors
+    int tsx, tsy, tsz, tsr;             // token strides of X, of K as Y, of V as Z, of K under the output
     f32x4 sx[XT], sy[XT], sz[ZT], sr[ZT];
     float onex[XT], onez[ZT];
     float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
+    float xraw[kPolyRaw], n_xraw[kPolyRaw];   // polynomial map, kGlobalDk: raw K of token lane / 4
 
     __device__ __forceinline__ PassStager(const PassArgs &a, int bh, int lane_, float *lx,
                                           float *ly, float *lz, float *lr)
-        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_),
-          tsx(tok_stride<kStrided>(a.tok_heads, DX)), tsz(tok_stride<kStrided>(a.tok_heads, DZ)) {
+        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_) {
         constexpr int BP = Tr::BP;
-        const size_t bx = seq_base<kStrided>(a.N, a.heads, bh, DX);
-        const size_t bz = seq_base<kStrided>(a.N, a.heads, bh, DZ);
-        Xs = static_cast<const T *>(BP == kFwd ? a.Q : BP == kDv ? a.K : a.V) + bx;
-        Ys = static_cast<const T *>(a.K) + bx;      // kFwd
-        Zs = static_cast<const T *>(a.V) + bz;      // kFwd
-        Rs = static_cast<const T *>(a.K) + bz;      // kGlobalDk
+        constexpr int wx = kXqk ? qk_width<T>(DX) : DX, wy = qk_width<T>(DX), wr = qk_width<T>(DZ);
+        tsx = tok_stride<kStrided>(a.tok_heads, wx);
+        tsy = tok_stride<kStrided>(a.tok_heads, wy);
+        tsz = tok_stride<kStrided>(a.tok_heads, DZ);
+        tsr = tok_stride<kStrided>(a.tok_heads, wr);
+        Xs = static_cast<const T *>(BP == kFwd ? a.Q : BP == kDv ? a.K : a.V) + seq_base<kStrided>(a.N, a.heads, bh, wx);
+        Ys = static_cast<const T *>(a.K) + seq_base<kStrided>(a.N, a.heads, bh, wy);      // kFwd
+        Zs = static_cast<const T *>(a.V) + seq_base<kStrided>(a.N, a.heads, bh, DZ);      // kFwd
+        Rs = static_cast<const T *>(a.K) + seq_base<kStrided>(a.N, a.heads, bh, wr);      // kGlobalDk
         dl1 = 0.f;
 #pragma unroll
         for (int s = 0; s < 4; ++s) dl4[s] = 0.f;
@@ -235,18 +241,24 @@ struct PassStager {
         for (int i = 0; i < XT; ++i) onex[i] = 1.0f;
 #pragma unroll
         for (int i = 0; i < ZT; ++i) onez[i] = 1.0f;
+#pragma unroll
+        for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j] = 0.f;
     }
 
     static constexpr int kDepth = 1;
 
     template <bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        stage_load<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx);
+        if constexpr (kXqk) stage_load_qk<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx);
+        else stage_load<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx);
         if constexpr (Tr::kHasYZ) {
-            stage_load<DX, kFull>(Ys + (size_t)t0 * tsx, tsx, nvalid, lane, sy);
+            stage_load_qk<DX, kFull>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
             stage_load<DZ, kFull>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
         }
-        if constexpr (Tr::kHasRaw) stage_load<DZ, kFull>(Rs + (size_t)t0 * tsz, tsz, nvalid, lane, sr);
+        if constexpr (Tr::kHasRaw) {
+            if constexpr (is_poly<T>) load_raw8(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, n_xraw);
+            else stage_load<DZ, kFull>(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, sr);
+        }
     }
 
     template <int SLOT>
@@ -264,7 +276,14 @@ struct PassStager {
             park_tile<DX, Tr::kMapY, kFull, is_feat<T>>(lds_y, sy, onex, nvalid, lane);
             park_tile<DZ, Tr::kMapZ, kFull, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
         }
-        if constexpr (Tr::kHasRaw) park_tile<DZ, kMapDphi, kFull, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
+        if constexpr (Tr::kHasRaw) {
+            if constexpr (is_poly<T>) {       // lds_r serves as the scratch of poly2_chain instead
+#pragma unroll
+                for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j];
+            } else {
+                park_tile<DZ, kMapDphi, kFull, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
+            }
+        }
     }
 
     template <int SLOT>
@@ -291,13 +310,20 @@ struct ReverseStager {
     float scd[DT], scb[kDepth][MT];
     float n_dl4[kDepth][4];
     float dl1, dl4[4];
+    float xraw[kPolyRaw], n_xraw[kDepth][kPolyRaw];   // polynomial map, role 1: raw K of token lane / 4
 
     __device__ __forceinline__ ReverseStager(const PassArgs &a, int bh, int lane_, float *la,
                                              float *la2, float *lb)
         : lds_a(la), lds_a2(la2), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4),
-          tsd(tok_stride<kStrided>(a.tok_heads, D)), tsm(tok_stride<kStrided>(a.tok_heads, M)) {
+          tsd(tok_stride<kStrided>(a.tok_heads, qk_width<T>(D))), tsm(tok_stride<kStrided>(a.tok_heads, M)) {
         const size_t rowbase = (size_t)bh * a.N;
-        As = static_cast<const T *>(ROLE == 0 ? a.Q : a.K) + seq_base<kStrided>(a.N, a.heads, bh, D);
+        As = static_cast<const T *>(ROLE == 0 ? a.Q : a.K) + seq_base<kStrided>(a.N, a.heads, bh, qk_width<T>(D));
+#pragma unroll
+        for (int j = 0; j < kPolyRaw; ++j) {
+            xraw[j] = 0.f;
+#pragma unroll
+            for (int k = 0; k < kDepth; ++k) n_xraw[k][j] = 0.f;
+        }
         Bs = static_cast<const T *>(ROLE == 0 ? a.G : a.V) + seq_base<kStrided>(a.N, a.heads, bh, M);
         rden = a.rden + rowbase;
         delta = a.delta + rowbase;
@@ -317,10 +343,11 @@ struct ReverseStager {
 
     template <int SLOT, bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        stage_load<D, kFull>(As + (size_t)t0 * tsd, tsd, nvalid, lane, sa[SLOT]);
+        stage_load_qk<D, kFull>(As + (size_t)t0 * tsd, tsd, nvalid, lane, sa[SLOT]);
         stage_load<M, kFull>(Bs + (size_t)t0 * tsm, tsm, nvalid, lane, sb[SLOT]);
         if constexpr (ROLE == 0) stage_rows<M, kFull>(rden + t0, nvalid, lane, scb[SLOT]);
         else rows4<kFull>(delta + t0, nvalid, g, n_dl4[SLOT]);
+        if constexpr (ROLE == 1 && is_poly<T>) load_raw8(As + (size_t)t0 * tsd, tsd, nvalid, lane, n_xraw[SLOT]);
     }
 
     template <int SLOT>
@@ -337,7 +364,8 @@ struct ReverseStager {
         if constexpr (ROLE == 0) {
             park_tile<M, kMapScale, kFull, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         } else {
-            park_tile<D, kMapDphi, kFull, is_feat<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
+            // (polynomial map: there is no phi' tile; lds_a2 is the scratch of poly2_chain)
+            if constexpr (!is_poly<T>) park_tile<D, kMapDphi, kFull, is_feat<T>>(lds_a2, sa[SLOT], scd, nvalid, lane);
             park_tile<M, kMapId, kFull, is_feat<T>>(lds_b, sb[SLOT], scb[SLOT], nvalid, lane);
         }
     }
@@ -348,6 +376,10 @@ struct ReverseStager {
         else park_impl<SLOT, false>(nvalid);
 #pragma unroll
         for (int s = 0; s < 4; ++s) dl4[s] = n_dl4[SLOT][s];
+        if constexpr (ROLE == 1 && is_poly<T>) {
+#pragma unroll
+            for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[SLOT][j];
+        }
     }
 };
 
@@ -367,7 +399,10 @@ template <int PASS, int D, int M, typename T, int kStateMode = kOwnState, typena
 __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const float *lds_x,
                                          const float *lds_y, const float *lds_z,
                                          const float *lds_r, void *out_tensor, const int bh,
-                                         const int seg, const int lane, float *lds_u = nullptr) {
+                                         const int seg, const int lane, float *lds_u = nullptr,
+                                         float *lds_scratch = nullptr) {
+    // lds_scratch: polynomial map, passes that end in a gradient for Q or K: one tile
+    // (16 x tile_stride(64) floats) private to the calling wave, for poly2_chain
     using Tr = PassTraits<PASS, D, M>;
     constexpr bool kXisD = Tr::kXisD;
     constexpr int DX = Tr::DX, DZ = Tr::DZ;
@@ -396,8 +431,12 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     const int count = ch_end - ch_begin;
     const size_t rowbase = (size_t)bh * a.N;
     constexpr bool kStrided = Stager::kStridedLayout;
-    const int tso = tok_stride<kStrided>(a.tok_heads, DZ);
-    T *outs = static_cast<T *>(out_tensor) + seq_base<kStrided>(a.N, a.heads, bh, DZ);
+    // width of the output tensor: DZ, or the raw width when the output is a gradient for Q or K
+    // of the polynomial map
+    constexpr bool kRawGrad = is_poly<T> && (Tr::BP == kDq || Tr::BP == kDk);
+    constexpr int WO = kRawGrad ? qk_width<T>(DZ) : DZ;
+    const int tso = tok_stride<kStrided>(a.tok_heads, WO);
+    T *outs = static_cast<T *>(out_tensor) + seq_base<kStrided>(a.N, a.heads, bh, WO);
 
     // ---- carried state --------------------------------------------------------------------
     f32x4 U[XT][ZT];
@@ -727,7 +766,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                 a.delta_out[rowbase + t0 + 4 * g + c] = dsel;
                 a.rden_out[rowbase + t0 + 4 * g + c] = rsel;
             }
-        } else if constexpr (kHasRaw) {
+        } else if constexpr (kHasRaw && !is_poly<T>) {
             float dp[ZT][4];             // phi' of the raw K under the output
             lds_feature_lane<DZ>(lds_r, c, g, dp);
 #pragma unroll
@@ -737,7 +776,16 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         }
         // uniform chunk base + one lane offset; the 16 stores differ by constants only
         T *lane_out = outs + (size_t)t0 * tso + (4 * g * tso + c);
-        if ((PASS == kFwd || PASS == kGlobal) && out_tensor == nullptr) {
+        if constexpr (kRawGrad) {
+            // `out` is the gradient for the 64 features: back to the 8 raw values of each token
+            float g0, g1;
+            poly2_chain(lds_scratch, out, stg.xraw, lane, g0, g1);
+            if ((lane >> 2) < nvalid) {
+                T *p = outs + (size_t)(t0 + (lane >> 2)) * tso + 2 * (lane & 3);
+                store_elem(p, g0);
+                store_elem(p + 1, g1);
+            }
+        } else if ((PASS == kFwd || PASS == kGlobal) && out_tensor == nullptr) {
             // a forward that is run for its denominators only (uniform branch)
         } else if (nvalid == kChunk) {
 #pragma unroll
@@ -878,7 +926,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
     const int lane = threadIdx.x;
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     PassStager<PASS, D, M, T, kStrided> stg(a, bh, lane, lds_x, lds_y, lds_z, lds_r);
-    run_pass<PASS, D, M, T>(a, stg, lds_x, lds_y, lds_z, lds_r, a.out, bh, seg, lane);
+    run_pass<PASS, D, M, T>(a, stg, lds_x, lds_y, lds_z, lds_r, a.out, bh, seg, lane, nullptr, lds_r);
 }
 
 // Both reverse passes of the backward (eq. 14 and eq. 15) on one fetch of Q, K, V, dO:
@@ -904,7 +952,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     } else {
         ReverseStager<1, D, M, T, kStrided> stg(a, bh, lane, lds_fk, lds_dk, lds_v);
         run_pass<kDk, D, M, T, kBorrowState>(a, stg, lds_v, lds_g, lds_fq, lds_dk, a.out2, bh, seg,
-                                             lane, lds_R);
+                                             lane, lds_R, lds_dk);
     }
 }
 
@@ -927,13 +975,22 @@ struct DqStager {
     float n_den4[4];
     float dl1, dl4[4];                  // unused by this pass (interface of run_pass)
     float rd4[4];                       // 1/den of tokens 4g + s of the parked chunk, 0 past the end
+    // polynomial map, role 0 (the wave that finishes dQ): raw Q of token lane / 4
+    const T *Qraw;
+    int tsq;
+    float xraw[kPolyRaw], n_xraw[kPolyRaw];
+    static constexpr int W = ROLE == 0 ? F : qk_width<T>(F);    // elements per token of this role's tensors
 
     __device__ __forceinline__ DqStager(const PassArgs &a, int bh, int lane_, float *la,
                                         float *lb)
-        : lds_a(la), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4), ts(tok_stride<kStrided>(a.tok_heads, F)) {
+        : lds_a(la), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4), ts(tok_stride<kStrided>(a.tok_heads, W)) {
         const size_t rowbase = (size_t)bh * a.N;
-        As = static_cast<const T *>(ROLE == 0 ? a.G : a.Q) + seq_base<kStrided>(a.N, a.heads, bh, F);
-        Bs = static_cast<const T *>(ROLE == 0 ? a.V : a.K) + seq_base<kStrided>(a.N, a.heads, bh, F);
+        As = static_cast<const T *>(ROLE == 0 ? a.G : a.Q) + seq_base<kStrided>(a.N, a.heads, bh, W);
+        Bs = static_cast<const T *>(ROLE == 0 ? a.V : a.K) + seq_base<kStrided>(a.N, a.heads, bh, W);
+        tsq = tok_stride<kStrided>(a.tok_heads, qk_width<T>(D));
+        Qraw = static_cast<const T *>(a.Q) + seq_base<kStrided>(a.N, a.heads, bh, qk_width<T>(D));
+#pragma unroll
+        for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j] = 0.f;
         den = a.den_in + rowbase;
         dl1 = 0.f;
 #pragma unroll
@@ -944,8 +1001,14 @@ struct DqStager {
 
     template <bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        stage_load<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa);
-        if constexpr (kCausal) stage_load<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb);
+        if constexpr (ROLE == 1) {
+            stage_load_qk<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa);
+            if constexpr (kCausal) stage_load_qk<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb);
+        } else {
+            stage_load<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa);
+            if constexpr (kCausal) stage_load<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb);
+            if constexpr (is_poly<T>) load_raw8(Qraw + (size_t)t0 * tsq, tsq, nvalid, lane, n_xraw);
+        }
         if constexpr (ROLE == 0) {
             stage_rows<F, kFull>(den + t0, nvalid, lane, sca);      // den of the staged rows
 #pragma unroll
@@ -972,6 +1035,10 @@ struct DqStager {
 #pragma unroll
             for (int s = 0; s < 4; ++s)
                 rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
+            if constexpr (is_poly<T>) {
+#pragma unroll
+                for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j];
+            }
         } else {
             park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_a, sa, one, nvalid, lane);
             if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_b, sb, one, nvalid, lane);
@@ -1144,6 +1211,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     __shared__ float lds_fk[kCausal ? tile_floats(D) : 4];        // phi(K)
     __shared__ float lds_fq[tile_floats(D)];                      // phi(Q)
     __shared__ float lds_S[kCausal ? M * (D + 4) : 4];            // S before the current chunk, as [m][d]
+    __shared__ float lds_chain[is_poly<T> ? tile_floats(D) : 4];  // polynomial map: scratch of poly2_chain
     const int lane = threadIdx.x & (kWave - 1);
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
@@ -1154,7 +1222,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
                                                  seg, lane, lds_S);
         else
             run_pass<kGlobalDq, D, M, T>(a, stg, lds_g, nullptr, nullptr, lds_fq, a.out, bh, seg,
-                                         lane);
+                                         lane, nullptr, lds_chain);
     } else {
         DqStager<1, D, M, T, kCausal, kStrided> stg(a, bh, lane, lds_fq, lds_fk);
         run_dq_sums<D, M, T, kCausal>(a, stg, lds_fk, lds_v, lds_fq, lds_g, lds_S, bh, seg, lane);
@@ -1187,6 +1255,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     __shared__ float lds_fk[2][tile_floats(D)];      // phi(K)
     __shared__ float lds_fq[2][tile_floats(D)];      // phi(Q)
     __shared__ __attribute__((aligned(16))) float lds_a0[DT][kWave][4];   // A0, in wave 1's register layout
+    __shared__ float lds_chain[is_poly<T> ? tile_floats(D) : 4];          // polynomial map: scratch of poly2_chain
     const int lane = threadIdx.x & (kWave - 1), c = lane & 15, g = lane >> 4;
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
@@ -1203,13 +1272,17 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 
     if (role == 0) {
         // ---- chunk wave: brings Q and K --------------------------------------------------------
-        const int ts = tok_stride<kStrided>(a.tok_heads, D);
-        const T *Qs = static_cast<const T *>(a.Q) + seq_base<kStrided>(a.N, a.heads, bh, D);
-        const T *Ks = static_cast<const T *>(a.K) + seq_base<kStrided>(a.N, a.heads, bh, D);
-        T *outs = static_cast<T *>(a.out) + seq_base<kStrided>(a.N, a.heads, bh, D);
+        constexpr int W = qk_width<T>(D);          // elements per token of Q, K and dQ
+        const int ts = tok_stride<kStrided>(a.tok_heads, W);
+        const T *Qs = static_cast<const T *>(a.Q) + seq_base<kStrided>(a.N, a.heads, bh, W);
+        const T *Ks = static_cast<const T *>(a.K) + seq_base<kStrided>(a.N, a.heads, bh, W);
+        T *outs = static_cast<T *>(a.out) + seq_base<kStrided>(a.N, a.heads, bh, W);
         const float *den = a.den_in + rowbase;
         f32x4 sq[DT], sk[DT];
         float one[DT], nden[4], rd4[4];
+        float xraw[kPolyRaw], n_xraw[kPolyRaw];    // polynomial map: raw Q of token lane / 4
+#pragma unroll
+        for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j] = 0.f;
         float ecp[DT];     // z[16zt + c] before the chunk, as four per-lane partial sums (lanes (c, g = 0..3))
         float rho[DT];     // this segment's sum of delta_b phi(Q_b)[16zt + c], same partial form
 #pragma unroll
@@ -1233,12 +1306,13 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             const int t0 = ch * kChunk;
             const int nvalid = min(kChunk, a.N - t0);
             if (nvalid == kChunk) {
-                stage_load<D, true>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
-                stage_load<D, true>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
+                stage_load_qk<D, true>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
+                stage_load_qk<D, true>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
             } else {
-                stage_load<D, false>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
-                stage_load<D, false>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
+                stage_load_qk<D, false>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
+                stage_load_qk<D, false>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
             }
+            if constexpr (is_poly<T>) load_raw8(Qs + (size_t)t0 * ts, ts, nvalid, lane, n_xraw);
 #pragma unroll
             for (int s = 0; s < 4; ++s) nden[s] = den[t0 + min(4 * g + s, nvalid - 1)];
         };
@@ -1253,6 +1327,10 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             }
 #pragma unroll
             for (int s = 0; s < 4; ++s) rd4[s] = 4 * g + s < nvalid ? __builtin_amdgcn_rcpf(nden[s]) : 0.f;
+            if constexpr (is_poly<T>) {
+#pragma unroll
+                for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j];
+            }
         };
 
         if (count > 0) {
@@ -1321,7 +1399,16 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             }
             const int tso = ts;
             T *lane_out = outs + (size_t)t0 * tso + (4 * g * tso + c);
-            if (nvalid == kChunk) {
+            if constexpr (is_poly<T>) {
+                // `out` is the gradient for the 64 features: back to the 8 raw values of each token
+                float g0, g1;
+                poly2_chain(lds_chain, out, xraw, lane, g0, g1);
+                if ((lane >> 2) < nvalid) {
+                    T *p = outs + (size_t)(t0 + (lane >> 2)) * tso + 2 * (lane & 3);
+                    store_elem(p, g0);
+                    store_elem(p + 1, g1);
+                }
+            } else if (nvalid == kChunk) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -1512,8 +1599,8 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     const int nchunks = (a.N + kChunk - 1) / kChunk;
     const int ch_begin = seg * a.chunks_per_seg;
     const int ch_end = min(ch_begin + a.chunks_per_seg, nchunks);
-    const int tsy = tok_stride<kStrided>(a.tok_heads, D), tsz = tok_stride<kStrided>(a.tok_heads, M);
-    const T *Ys = static_cast<const T *>(a.Y) + seq_base<kStrided>(a.N, a.heads, bh, D);
+    const int tsy = tok_stride<kStrided>(a.tok_heads, qk_width<T>(D)), tsz = tok_stride<kStrided>(a.tok_heads, M);
+    const T *Ys = static_cast<const T *>(a.Y) + seq_base<kStrided>(a.N, a.heads, bh, qk_width<T>(D));
     const T *Zs = static_cast<const T *>(a.Z) + seq_base<kStrided>(a.N, a.heads, bh, M);
 
     f32x4 U[XT][ZT];
@@ -1536,10 +1623,10 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
         if (nvalid == kChunk) {
-            stage_load<D, true>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
+            stage_load_qk<D, true>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
             stage_load<M, true>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
         } else {
-            stage_load<D, false>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
+            stage_load_qk<D, false>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
             stage_load<M, false>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
         }
     };

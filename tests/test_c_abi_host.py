@@ -131,12 +131,19 @@ def test_argument_errors_are_reported_before_any_launch(lib):
     assert bws(*args, *tail) == b.LA_ERR_ALIGN
     assert bws(*ok16, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE
 
-    # element type codes: 0..3 are known (fp32, bf16, and the same with Q, K as feature values)
-    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 4, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    # element type codes: 0..4 are known (fp32, bf16, the same with Q, K as feature values, fp32 poly2)
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 5, null, 0, null) == b.LA_ERR_UNSUPPORTED
     assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), -1, null, 0, null) == b.LA_ERR_UNSUPPORTED
     assert fwd(p, p, p, p, null, 1, 1, 4096, 64, 64, f(1e-6), 3, null, 0, null) == b.LA_ERR_WORKSPACE
     assert b.la_causal_bwd_workspace(2, 8, 4096, 64, 64, b.LA_BF16_FEATURES) == \
         b.la_causal_bwd_workspace(2, 8, 4096, 64, 64, b.LA_BF16)
+
+    # the degree-2 polynomial map: 8 raw values per token, nothing else
+    assert fwd(p, p, p, p, null, 1, 1, 16, 64, 64, f(0.5), b.LA_F32_POLY2, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd(p, p, p, p, null, 1, 1, 16, 4, 64, f(0.5), b.LA_F32_POLY2, null, 0, null) == b.LA_ERR_UNSUPPORTED
+    assert fwd(p, p, p, p, null, 1, 1, 4096, 8, 64, f(0.5), b.LA_F32_POLY2, null, 0, null) == b.LA_ERR_WORKSPACE
+    assert b.la_causal_fwd_workspace(1, 1, 4096, 8, 64, b.LA_F32_POLY2) == b.la_causal_fwd_workspace(1, 1, 4096, 64, 64)
+    assert b.la_causal_fwd_workspace(1, 1, 4096, 8, 64) == 0            # D = 8 without the map: unsupported
 
     glob = lib.la_global_fwd
     assert glob(p, p, p, p, null, 1, 1, 16, 64, 64, f(1e-6), 0, null, 0, null) == b.LA_ERR_WORKSPACE

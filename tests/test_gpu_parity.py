@@ -911,3 +911,110 @@ def test_underflowed_keys_give_zero_rows(la):
     O, den = run_fwd(la, Q, K, V, 1e-6)
     assert np.all(O[:, :, :20] == 0.0)
     assert np.all(np.isfinite(O))
+
+
+# ---- fused degree-2 polynomial map (section 3.2): Q, K hold 8 raw values per token ---------------
+
+def _poly2_case(seed, B, H, N, M):
+    rng = np.random.default_rng(seed)
+    Q, K = (rng.standard_normal((B, H, N, 8)).astype(np.float32) for _ in range(2))
+    V, G = (rng.standard_normal((B, H, N, M)).astype(np.float32) for _ in range(2))
+    return Q, K, V, G
+
+
+# (q . k)^2 can be arbitrarily small, and where den is tiny its rounding error in fp32 is amplified
+# by 1/den^2 in the gradients (token 0 of a causal sequence has a single term): a sizeable eps
+# keeps the cases well conditioned
+POLY_EPS = 0.5
+
+
+@pytest.mark.parametrize("sched", list(SCHEDULES))
+@pytest.mark.parametrize("N,M", [(1, 64), (16, 32), (17, 64), (100, 64), (257, 32), (1000, 64)])
+def test_poly2_map_causal_forward_backward(la, oracle, N, M, sched):
+    B, H = 2, 3
+    Q, K, V, G = _poly2_case(7000 + N, B, H, N, M)
+    ref, dref = oracle.causal_fwd_poly2(Q, K, V, POLY_EPS, return_den=True)
+    gref = oracle.causal_bwd_poly2(Q, K, V, G, POLY_EPS)
+    dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+    with schedule(**SCHEDULES[sched]):
+        O = torch.full_like(dv, float("nan"))
+        den = torch.full((B, H, N), float("nan"), device=DEV)
+        ws = la.la_causal_fwd(dq, dk, dv, O, den, POLY_EPS, features="poly2")
+        gq, gk, gv = (torch.full_like(x, float("nan")) for x in (dq, dk, dv))
+        la.la_causal_bwd(dq, dk, dv, None, den, dg, gq, gk, gv, POLY_EPS, fwd_ws=ws, features="poly2")
+        # and without anything kept from the forward
+        rq, rk, rv = (torch.full_like(x, float("nan")) for x in (dq, dk, dv))
+        la.la_causal_bwd(dq, dk, dv, None, None, dg, rq, rk, rv, POLY_EPS, features="poly2")
+        torch.cuda.synchronize()
+    tol = tol_for(N)
+    assert gq.shape == (B, H, N, 8)
+    assert rel_err(to_host(O), ref) <= tol and rel_err(den.cpu().numpy(), dref) <= tol
+    assert max(grad_errs([to_host(x) for x in (gq, gk, gv)], gref)) <= tol
+    assert torch.equal(gq, rq) and torch.equal(gk, rk) and torch.equal(gv, rv)
+
+
+@pytest.mark.parametrize("sched", ["default", "one_segment", "many_segments", "folded_totals"])
+@pytest.mark.parametrize("N,M", [(1, 32), (17, 64), (300, 64), (1000, 32)])
+def test_poly2_map_non_causal_forward_backward(la, oracle, N, M, sched):
+    B, H = 2, 2
+    Q, K, V, G = _poly2_case(7100 + N, B, H, N, M)
+    ref = oracle.global_fwd_poly2(Q, K, V, POLY_EPS)
+    gref = oracle.global_bwd_poly2(Q, K, V, G, POLY_EPS)
+    dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+    with schedule(**SCHEDULES[sched]):
+        O = torch.full_like(dv, float("nan"))
+        den = torch.full((B, H, N), float("nan"), device=DEV)
+        ws = la.la_global_fwd(dq, dk, dv, O, POLY_EPS, den=den, features="poly2")
+        gq, gk, gv = (torch.full_like(x, float("nan")) for x in (dq, dk, dv))
+        la.la_global_bwd(dq, dk, dv, None, den, dg, gq, gk, gv, POLY_EPS, fwd_ws=ws, features="poly2")
+        torch.cuda.synchronize()
+    tol = tol_for(N)
+    assert rel_err(to_host(O), ref) <= tol
+    assert max(grad_errs([to_host(x) for x in (gq, gk, gv)], gref)) <= tol
+
+
+def test_poly2_map_equals_the_feature_interface_and_decode(la, oracle):
+    """The fused map against the same call on host-built features (LA_F32_FEATURES): same
+    products, so the outputs agree to rounding of the features; token-major layout bit for bit;
+    decode step by step and in one launch against the oracle's recurrence."""
+    B, H, N, M = 2, 4, 203, 64
+    Q, K, V, G = _poly2_case(7200, B, H, N, M)
+    dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+    O = torch.empty_like(dv)
+    la.la_causal_fwd(dq, dk, dv, O, None, POLY_EPS, features="poly2")
+    FQ = (dq[..., :, None] * dq[..., None, :]).reshape(B, H, N, 64).contiguous()      # fp32 products,
+    FK = (dk[..., :, None] * dk[..., None, :]).reshape(B, H, N, 64).contiguous()      # as in the kernel
+    O2 = torch.empty_like(dv)
+    la.la_causal_fwd(FQ, FK, dv, O2, None, POLY_EPS, features=True)
+    torch.cuda.synchronize()
+    assert torch.equal(O, O2)
+    # token-major tensors
+    tq, tk, tv, tg = (x.transpose(1, 2).contiguous() for x in (dq, dk, dv, dg))
+    Ot = torch.empty_like(tv); den = torch.empty(B, H, N, device=DEV)
+    ws = la.la_causal_fwd_bnhd(tq, tk, tv, Ot, den, POLY_EPS, features="poly2")
+    gq, gk, gv = (torch.empty_like(x) for x in (tq, tk, tv))
+    la.la_causal_bwd_bnhd(tq, tk, tv, None, den, tg, gq, gk, gv, POLY_EPS, fwd_ws=ws, features="poly2")
+    hq, hk, hv = (torch.empty_like(x) for x in (dq, dk, dv))
+    la.la_causal_bwd(dq, dk, dv, None, den, dg, hq, hk, hv, POLY_EPS, features="poly2")
+    torch.cuda.synchronize()
+    assert torch.equal(Ot.transpose(1, 2), O)
+    for a, b in ((gq, hq), (gk, hk), (gv, hv)):
+        assert torch.equal(a.transpose(1, 2), b)
+    # decode: state sized by the 64 features
+    T = 40
+    q, k, v = (x[:, :, :T].permute(2, 0, 1, 3).contiguous() for x in (dq, dk, dv))
+    S = torch.zeros(B, H, 64, M, device=DEV); z = torch.zeros(B, H, 64, device=DEV)
+    out = torch.empty(T, B, H, M, device=DEV)
+    for t in range(T):
+        la.la_recurrent_step(q[t], k[t], v[t], S, z, out[t], POLY_EPS, features="poly2")
+    S2 = torch.zeros_like(S); z2 = torch.zeros_like(z); out2 = torch.empty_like(out)
+    la.la_recurrent_steps(q, k, v, S2, z2, out2, POLY_EPS, features="poly2")
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2) and torch.equal(S, S2) and torch.equal(z, z2)
+    So, zo = np.zeros((B, H, 64, M)), np.zeros((B, H, 64))
+    qh, kh, vh = (to_host(x) for x in (q, k, v))
+    for t in range(T):
+        ref = oracle.recurrent_step_poly2(qh[t], kh[t], vh[t], So, zo, POLY_EPS)
+        assert rel_err(to_host(out[t]), ref) <= 1e-4
+    assert rel_err(S.cpu().numpy(), So) <= 1e-4 and rel_err(z.cpu().numpy(), zo) <= 1e-4
+    assert rel_err(to_host(out), np.moveaxis(to_host(O[:, :, :T]), 2, 0)) <= 1e-4     # decode == parallel
