@@ -1254,8 +1254,14 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     __shared__ float lds_v[2][tile_floats(M)];       // V
     __shared__ float lds_fk[2][tile_floats(D)];      // phi(K)
     __shared__ float lds_fq[2][tile_floats(D)];      // phi(Q)
-    __shared__ __attribute__((aligned(16))) float lds_a0[DT][kWave][4];   // A0, in wave 1's register layout
-    __shared__ float lds_chain[is_poly<T> ? tile_floats(D) : 4];          // polynomial map: scratch of poly2_chain
+    // A0 in wave 1's register layout, [DT][kWave][4].  With the polynomial map the same memory is
+    // wave 0's scratch for poly2_chain: wave 0 has taken A0 out by then, and wave 1 writes the next
+    // A0 only after the barrier that follows (a separate array would cost the fourth workgroup
+    // per compute unit).
+    constexpr int kA0Floats = DT * kWave * 4;
+    __shared__ __attribute__((aligned(16))) float lds_a0_mem[is_poly<T> && tile_floats(D) > kA0Floats ? tile_floats(D) : kA0Floats];
+    float (*lds_a0)[kWave][4] = reinterpret_cast<float (*)[kWave][4]>(lds_a0_mem);
+    float *lds_chain = lds_a0_mem;
     const int lane = threadIdx.x & (kWave - 1), c = lane & 15, g = lane >> 4;
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
