@@ -1018,3 +1018,42 @@ def test_poly2_map_equals_the_feature_interface_and_decode(la, oracle):
         assert rel_err(to_host(out[t]), ref) <= 1e-4
     assert rel_err(S.cpu().numpy(), So) <= 1e-4 and rel_err(z.cpu().numpy(), zo) <= 1e-4
     assert rel_err(to_host(out), np.moveaxis(to_host(O[:, :, :T]), 2, 0)) <= 1e-4     # decode == parallel
+
+
+@pytest.mark.parametrize("sched", ["default", "many_segments", "folded_totals"])
+def test_poly2_map_sequence_in_two_pieces_through_the_state(la, oracle, sched):
+    """The state interface with the polynomial map: the state is sized by the 64 features, not by
+    the 8 raw values.  Forward in two pieces (the first one's final state starts the second),
+    backward in reverse (the second one's state gradient arrives at the first): outputs and
+    gradients must be those of the uncut sequence."""
+    B, H, N1, N2, M = 2, 2, 130, 275, 64
+    N = N1 + N2
+    Q, K, V, G = _poly2_case(7300, B, H, N, M)
+    ref = oracle.causal_fwd_poly2(Q, K, V, POLY_EPS)
+    gref = oracle.causal_bwd_poly2(Q, K, V, G, POLY_EPS)
+    dev = [to_dev(x) for x in (Q, K, V, G)]
+    a = [x[:, :, :N1].contiguous() for x in dev]
+    b = [x[:, :, N1:].contiguous() for x in dev]
+    S1 = torch.full((B, H, 64, M), float("nan"), device=DEV); z1 = torch.full((B, H, 64), float("nan"), device=DEV)
+    kw = dict(features="poly2")
+    with schedule(**SCHEDULES[sched]):
+        Oa = torch.empty_like(a[2]); dena = torch.empty(B, H, N1, device=DEV)
+        wsa = la.la_causal_fwd_state(a[0], a[1], a[2], Oa, dena, None, None, S1, z1, POLY_EPS, **kw)
+        Ob = torch.empty_like(b[2]); denb = torch.empty(B, H, N2, device=DEV)
+        wsb = la.la_causal_fwd_state(b[0], b[1], b[2], Ob, denb, S1, z1, None, None, POLY_EPS, **kw)
+        gb = [torch.full_like(x, float("nan")) for x in b[:3]]
+        dS = torch.full_like(S1, float("nan")); dz = torch.full_like(z1, float("nan"))
+        la.la_causal_bwd_state(b[0], b[1], b[2], Ob, denb, b[3], gb[0], gb[1], gb[2], S1, z1, None, None,
+                               dS, dz, POLY_EPS, fwd_ws=wsb, **kw)
+        ga = [torch.full_like(x, float("nan")) for x in a[:3]]
+        la.la_causal_bwd_state(a[0], a[1], a[2], None, None, a[3], ga[0], ga[1], ga[2], None, None, dS, dz,
+                               None, None, POLY_EPS, **kw)
+        torch.cuda.synchronize()
+    assert ga[0].shape == (B, H, N1, 8)
+    tol = tol_for(N)
+    assert rel_err(np.concatenate([to_host(Oa), to_host(Ob)], axis=2), ref) <= tol
+    got = [np.concatenate([to_host(x), to_host(y)], axis=2) for x, y in zip(ga, gb)]
+    assert max(grad_errs(got, gref)) <= tol
+    fk = oracle.poly2_features(K[:, :, :N1].astype(np.float64))
+    assert rel_err(S1.cpu().numpy(), np.einsum("bhnd,bhnm->bhdm", fk, V[:, :, :N1].astype(np.float64))) <= tol
+    assert rel_err(z1.cpu().numpy(), fk.sum(2), floor=1.0) <= tol
