@@ -205,3 +205,59 @@ def test_one_very_long_sequence(la, oracle):
     assert rel_err(den.cpu().numpy(), dref) <= tol
     errs = grad_errs([to_host(x) for x in (dQ, dK, dV)], gref)
     assert max(errs) <= tol, errs
+
+
+def test_tensors_beyond_2_to_31_elements(la, oracle):
+    """B = 64, H = 8, N = 2^16 + 77, D = M = 64 in fp32: every tensor holds 2.15e9 elements
+    (8.6 GB), so element offsets pass 2^31 and byte offsets 2^33 (the last sequences sit
+    wholly beyond both).  Inputs are drawn on the device (seeded); the oracle runs on three
+    sampled (batch, head) slabs, the first, one in the middle and the last, over all tokens;
+    the sequences are cut (four segments each by default, 32 scanned segments in the second
+    schedule); token-major tensors must give the same bits."""
+    from gpu_util import schedule
+    B, H, N, D, M = 64, 8, (1 << 16) + 77, 64, 64
+    assert B * H * N * D > (1 << 31)
+    free, _ = torch.cuda.mem_get_info()
+    if free < 200 * (1 << 30):
+        pytest.skip("needs 200 GB of free device memory")
+    gen = torch.Generator(device=DEV).manual_seed(1700)
+    Q, K, V, G = (torch.randn(B, H, N, D, generator=gen, device=DEV) for _ in range(4))
+    slabs = [(0, 0), (31, 5), (63, 7)]
+    host = [np.stack([x[b, h].cpu().numpy() for b, h in slabs])[:, None] for x in (Q, K, V, G)]   # [3,1,N,.]
+    eps = 1e-6
+    ref, dref = oracle.causal_fwd_prefix(*host[:3], eps, return_den=True)
+    gref = oracle.causal_bwd_linear(*host, eps)
+    tol = tol_for(N)
+
+    def run(token_major):
+        fwd = la.la_causal_fwd_bnhd if token_major else la.la_causal_fwd
+        bwd = la.la_causal_bwd_bnhd if token_major else la.la_causal_bwd
+        O = torch.empty_like(V if not token_major else Vt)
+        den = torch.empty(B, H, N, device=DEV)
+        src = (Qt, Kt, Vt, Gt) if token_major else (Q, K, V, G)
+        grads = [torch.empty_like(x) for x in src[:3]]
+        ws = fwd(src[0], src[1], src[2], O, den, eps)
+        bwd(src[0], src[1], src[2], None, den, src[3], grads[0], grads[1], grads[2], eps, fwd_ws=ws)
+        torch.cuda.synchronize()
+        return [O, den] + grads
+
+    def check(out):
+        pick = lambda x: np.stack([x[b, h].cpu().numpy() for b, h in slabs])[:, None]
+        assert rel_err(pick(out[0]), ref) <= tol
+        assert rel_err(pick(out[1]), dref) <= tol
+        errs = grad_errs([pick(x) for x in out[2:]], gref)
+        assert max(errs) <= tol, errs
+
+    first = run(False)
+    check(first)
+    with schedule(target_waves=16384, min_seg_chunks=2, fold_max_segs=8):
+        assert la.la_causal_fwd_workspace(B, H, N, D, M) == B * H * 32 * (D * M + D) * 4
+        second = run(False)
+    check(second)
+    del second
+    # token-major copies of the inputs, one tensor at a time
+    Qt, Kt, Vt, Gt = (x.transpose(1, 2).contiguous() for x in (Q, K, V, G))
+    third = run(True)
+    assert torch.equal(third[1], first[1])
+    for a, b in zip([third[0]] + third[2:], [first[0]] + first[2:]):
+        assert torch.equal(a.transpose(1, 2), b)
