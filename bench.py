@@ -79,7 +79,7 @@ def kernel_bytes(name: str, D: int, M: int, e: int) -> float:
         "segment_state_kv": e * (D + M),                # K V
         "global_readout": e * (D + M) + 4,              # Q -> O, den
         "pass_dq_global": e * (2 * D + M) + 4,          # Q dO, den -> dQ (non-causal)
-        "global_bwd_readouts": e * (3 * D + 2 * M),     # K -> dV;  V K -> dK
+        "global_bwd_readouts": e * (2 * D + 2 * M),     # K V -> dV, dK
         "recurrent_step": 2 * 4 * D * (M + 1) + e * (2 * D + 2 * M),   # S, z read and written; q k v out
         "recurrent_steps": e * (2 * D + 2 * M),         # per step of a multi-step launch: q k v out
                                                         # (the state stays in registers)

@@ -640,14 +640,13 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
     { ProfScope ps(LA_K_DQ, s); LA_TRY(la::launch_pass_dq(false, C, M, (int)t, a, (int)(BH * pb.nseg), s)); }
     if (pb.nseg > 1 && !p.fold)
         { ProfScope ps(LA_K_SCAN, s); LA_TRY(la::launch_scan(stR, (int)BH, pb.nseg, la::state_stride(C, M), la::kScanTotal, s)); }
-    // dV and dK against the Q, dO total
-    a.totals = nullptr; a.nseg = p.nseg; a.chunks_per_seg = p.cps;
+    // dV and dK against the Q, dO total: one kernel, two waves per workgroup over the same
+    // pairs of segments
+    a.totals = nullptr;
     a.state = stR; a.state_nseg = pb.nseg;
     ProfScope ps(LA_K_GLOBAL_BWD, s);
-    a.out = dV;
-    LA_TRY(la::launch_pass_global_bwd(1, C, M, (int)t, a, nblocks, s));
-    a.out = dK;
-    LA_TRY(la::launch_pass_global_bwd(2, C, M, (int)t, a, nblocks, s));
+    a.out = dV; a.out2 = dK;
+    LA_TRY(la::launch_global_dkdv(C, M, (int)t, a, (int)(BH * pb.nseg), s));
     return LA_OK;
 }
 

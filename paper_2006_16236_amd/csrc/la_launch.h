@@ -19,9 +19,8 @@ hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &
 // both reverse passes (dV into a.out, dK into a.out2) on one fetch of the inputs
 hipError_t launch_pass_reverse(int D, int M, int dtype, const PassArgs &a, int nblocks,
                                hipStream_t s);
-// read-out-only gradients of the non-causal form: which = 1 dV, 2 dK (into a.out)
-hipError_t launch_pass_global_bwd(int which, int D, int M, int dtype, const PassArgs &a,
-                                  int nblocks, hipStream_t s);
+// read-out-only gradients of the non-causal form: dV into a.out, dK into a.out2
+hipError_t launch_global_dkdv(int D, int M, int dtype, const PassArgs &a, int nblocks, hipStream_t s);
 hipError_t launch_segment_state(int D, int M, int dtype, const SegArgs &a, int nblocks,
                                 hipStream_t s);
 

@@ -956,6 +956,101 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     }
 }
 
+// Staging of the two read-outs of the non-causal backward that sweep K and V (dV and dK against
+// the grand total of phi(Q)^T dO/den), run side by side by the two waves of one workgroup so
+// that K is fetched once for both.  Wave 0 (the dV role) brings K, parked as phi and, for the
+// chain rule under dK, as phi'; wave 1 (the dK role) brings V.
+template <int ROLE, int D, int M, typename T, bool kStrided = false>
+struct GlobalBwdStager {
+    static constexpr bool kStridedLayout = kStrided;
+    static constexpr int kDepth = 1;
+    static constexpr int F = ROLE == 0 ? D : M, FT = F / 16;
+    const T *Src;                       // role 0: K; role 1: V
+    const T *Kraw;                      // role 1, polynomial map: K again, for the raw vectors
+    float *lds_a, *lds_a2;              // role 0: phi(K), phi'(K); role 1: V, -
+    int N, lane;
+    int ts, tsk;
+    f32x4 st[FT];
+    float one[FT];
+    float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
+    float xraw[kPolyRaw], n_xraw[kPolyRaw];   // polynomial map, role 1: raw K of token lane / 4
+
+    __device__ __forceinline__ GlobalBwdStager(const PassArgs &a, int bh, int lane_, float *la, float *la2)
+        : lds_a(la), lds_a2(la2), N(a.N), lane(lane_) {
+        constexpr int wk = qk_width<T>(D);
+        tsk = tok_stride<kStrided>(a.tok_heads, wk);
+        ts = ROLE == 0 ? tsk : tok_stride<kStrided>(a.tok_heads, M);
+        Kraw = static_cast<const T *>(a.K) + seq_base<kStrided>(a.N, a.heads, bh, wk);
+        Src = ROLE == 0 ? Kraw : static_cast<const T *>(a.V) + seq_base<kStrided>(a.N, a.heads, bh, M);
+        dl1 = 0.f;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) dl4[s] = 0.f;
+#pragma unroll
+        for (int i = 0; i < FT; ++i) one[i] = 1.0f;
+#pragma unroll
+        for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j] = 0.f;
+    }
+
+    template <bool kFull>
+    __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
+        if constexpr (ROLE == 0) {
+            stage_load_qk<D, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st);
+        } else {
+            stage_load<M, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st);
+            if constexpr (is_poly<T>) load_raw8(Kraw + (size_t)t0 * tsk, tsk, nvalid, lane, n_xraw);
+        }
+    }
+    template <int SLOT>
+    __device__ __forceinline__ void fetch(const int ch) {
+        const int t0 = ch * kChunk;
+        const int nvalid = min(kChunk, N - t0);
+        if (nvalid == kChunk) fetch_impl<true>(t0, nvalid);      // uniform branch
+        else fetch_impl<false>(t0, nvalid);
+    }
+
+    template <bool kFull>
+    __device__ __forceinline__ void park_impl(const int nvalid) {
+        if constexpr (ROLE == 0) {
+            park_tile<D, kMapPhi, kFull, is_feat<T>>(lds_a, st, one, nvalid, lane);
+            // (polynomial map: no phi' tile; the dK wave uses that memory as the scratch of poly2_chain)
+            if constexpr (!is_poly<T>) park_tile<D, kMapDphi, kFull, is_feat<T>>(lds_a2, st, one, nvalid, lane);
+        } else {
+            park_tile<M, kMapId, kFull, is_feat<T>>(lds_a, st, one, nvalid, lane);
+        }
+    }
+    template <int SLOT>
+    __device__ __forceinline__ void park(const int nvalid) {
+        if (nvalid == kChunk) park_impl<true>(nvalid);
+        else park_impl<false>(nvalid);
+        if constexpr (ROLE == 1 && is_poly<T>) {
+#pragma unroll
+            for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j];
+        }
+    }
+};
+
+// dV (a.out, wave 0) and dK (a.out2, wave 1) of the non-causal form (eq. 4-6 differentiated) on
+// one sweep over K and V: both are read-outs against the same total, dV_b = phi(K_b) R and
+// dphi(K)_b = R V_b + rho, so the only thing the waves share is the K tile.
+template <int D, int M, typename T, bool kStrided = false>
+__global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) void global_dkdv_kernel(
+    const PassArgs a) {
+    __shared__ float lds_fk[tile_floats(D)];    // phi(K)
+    __shared__ float lds_dk[tile_floats(D)];    // phi'(K) (polynomial map: wave 1's chain-rule scratch)
+    __shared__ float lds_v[tile_floats(M)];     // V
+    const int lane = threadIdx.x & (kWave - 1);
+    const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
+    const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
+    if (role == 0) {
+        GlobalBwdStager<0, D, M, T, kStrided> stg(a, bh, lane, lds_fk, lds_dk);
+        run_pass<kGlobalDv, D, M, T>(a, stg, lds_fk, nullptr, nullptr, nullptr, a.out, bh, seg, lane);
+    } else {
+        GlobalBwdStager<1, D, M, T, kStrided> stg(a, bh, lane, lds_v, nullptr);
+        run_pass<kGlobalDk, D, M, T>(a, stg, lds_v, nullptr, nullptr, lds_dk, a.out2, bh, seg, lane,
+                                     nullptr, lds_dk);
+    }
+}
+
 // Staging of the dQ pass, shared by the two waves of its workgroup.  Wave 0 (the dQ role)
 // brings dO (parked as dO/den, den being the forward's denominator) and V; wave 1 brings Q
 // and K, both parked as phi.  The non-causal pass (kCausal = false) has no in-chunk part and
