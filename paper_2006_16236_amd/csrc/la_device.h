@@ -329,6 +329,11 @@ __device__ __forceinline__ f32x4 mfma16_split_ba(const SplitB<3> &x, const Split
     acc = mfma32_bf16(x.hm(), u.hm(), acc);    // hh + mm
     return acc;
 }
+__device__ __forceinline__ f32x4 mfma16_split_ba(const SplitB<2> &x, const SplitA<2> &u, f32x4 acc) {
+    acc = mfma32_bf16(x.m0(), u.hm(), acc);    // mh
+    acc = mfma32_bf16(x.hh(), u.hm(), acc);    // hh + hm
+    return acc;
+}
 template <int P> __device__ __forceinline__ SplitA<P> split_a(f32x4 x) {
     const float q[4] = {x[0], x[1], x[2], x[3]};
     return split_a<P>(q);

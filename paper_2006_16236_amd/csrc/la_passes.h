@@ -55,6 +55,9 @@
 #ifndef LA_SPLIT_SUMS
 #define LA_SPLIT_SUMS 1          // 0: every fp32 product on the fp32 MFMA (for comparison)
 #endif
+#ifndef LA_GLOBAL_DEPTH
+#define LA_GLOBAL_DEPTH(T) 1     // chunks in flight per wave in the non-causal passes (1 or 2)
+#endif
 #ifndef LA_SLEEP_AFTER_FETCH
 #define LA_SLEEP_AFTER_FETCH 1   // in units of 64 clocks
 #endif
@@ -202,7 +205,7 @@ struct PassTraits {
 
 // Staging of a pass run by one wave on its own (kFwd and the read-out-only passes kGlobal,
 // kGlobalDv, kGlobalDk): the wave fetches and parks all its tiles.
-template <int PASS, int D, int M, typename T, bool kStrided = false>
+template <int PASS, int D, int M, typename T, bool kStrided = false, int kDepth_ = 1>
 struct PassStager {
     static constexpr bool kStridedLayout = kStrided;
     using Tr = PassTraits<PASS, D, M>;
@@ -216,10 +219,11 @@ struct PassStager {
     float *lds_x, *lds_y, *lds_z, *lds_r;
     int N, lane;
     int tsx, tsy, tsz, tsr;             // token strides of X, of K as Y, of V as Z, of K under the output
-    f32x4 sx[XT], sy[XT], sz[ZT], sr[ZT];
+    static constexpr int kDepth = kDepth_;    // chunks in flight = sets of staging registers (1 or 2)
+    f32x4 sx[kDepth][XT], sy[kDepth][XT], sz[kDepth][ZT], sr[kDepth][ZT];
     float onex[XT], onez[ZT];
     float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
-    float xraw[kPolyRaw], n_xraw[kPolyRaw];   // polynomial map, kGlobalDk: raw K of token lane / 4
+    float xraw[kPolyRaw], n_xraw[kDepth][kPolyRaw];   // polynomial map, kGlobalDk: raw K of token lane / 4
 
     __device__ __forceinline__ PassStager(const PassArgs &a, int bh, int lane_, float *lx,
                                           float *ly, float *lz, float *lr)
@@ -242,22 +246,24 @@ struct PassStager {
 #pragma unroll
         for (int i = 0; i < ZT; ++i) onez[i] = 1.0f;
 #pragma unroll
-        for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j] = 0.f;
+        for (int j = 0; j < kPolyRaw; ++j) {
+            xraw[j] = 0.f;
+#pragma unroll
+            for (int k = 0; k < kDepth; ++k) n_xraw[k][j] = 0.f;
+        }
     }
 
-    static constexpr int kDepth = 1;
-
-    template <bool kFull>
+    template <int SLOT, bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        if constexpr (kXqk) stage_load_qk<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx);
-        else stage_load<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx);
+        if constexpr (kXqk) stage_load_qk<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx[SLOT]);
+        else stage_load<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx[SLOT]);
         if constexpr (Tr::kHasYZ) {
-            stage_load_qk<DX, kFull>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
-            stage_load<DZ, kFull>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
+            stage_load_qk<DX, kFull>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy[SLOT]);
+            stage_load<DZ, kFull>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz[SLOT]);
         }
         if constexpr (Tr::kHasRaw) {
-            if constexpr (is_poly<T>) load_raw8(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, n_xraw);
-            else stage_load<DZ, kFull>(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, sr);
+            if constexpr (is_poly<T>) load_raw8(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, n_xraw[SLOT]);
+            else stage_load<DZ, kFull>(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, sr[SLOT]);
         }
     }
 
@@ -265,31 +271,31 @@ struct PassStager {
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        if (nvalid == kChunk) fetch_impl<true>(t0, nvalid);      // uniform branch
-        else fetch_impl<false>(t0, nvalid);
+        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);      // uniform branch
+        else fetch_impl<SLOT, false>(t0, nvalid);
     }
 
-    template <bool kFull>
+    template <int SLOT, bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
-        park_tile<DX, Tr::kMapX, kFull, is_feat<T>>(lds_x, sx, onex, nvalid, lane);
+        park_tile<DX, Tr::kMapX, kFull, is_feat<T>>(lds_x, sx[SLOT], onex, nvalid, lane);
         if constexpr (Tr::kHasYZ) {
-            park_tile<DX, Tr::kMapY, kFull, is_feat<T>>(lds_y, sy, onex, nvalid, lane);
-            park_tile<DZ, Tr::kMapZ, kFull, is_feat<T>>(lds_z, sz, onez, nvalid, lane);
+            park_tile<DX, Tr::kMapY, kFull, is_feat<T>>(lds_y, sy[SLOT], onex, nvalid, lane);
+            park_tile<DZ, Tr::kMapZ, kFull, is_feat<T>>(lds_z, sz[SLOT], onez, nvalid, lane);
         }
         if constexpr (Tr::kHasRaw) {
             if constexpr (is_poly<T>) {       // lds_r serves as the scratch of poly2_chain instead
 #pragma unroll
-                for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j];
+                for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[SLOT][j];
             } else {
-                park_tile<DZ, kMapDphi, kFull, is_feat<T>>(lds_r, sr, onez, nvalid, lane);
+                park_tile<DZ, kMapDphi, kFull, is_feat<T>>(lds_r, sr[SLOT], onez, nvalid, lane);
             }
         }
     }
 
     template <int SLOT>
     __device__ __forceinline__ void park(const int nvalid) {
-        if (nvalid == kChunk) park_impl<true>(nvalid);
-        else park_impl<false>(nvalid);
+        if (nvalid == kChunk) park_impl<SLOT, true>(nvalid);
+        else park_impl<SLOT, false>(nvalid);
     }
 };
 
@@ -491,16 +497,16 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         }
     }
 
-    // Read-out-only passes of fp32 tensors: U never changes, so it is cut into its three bf16
-    // parts once, here, and every chunk's read-out runs on the bf16 pipe (section on split3 in
-    // la_device.h); only the chunk's own operand is split per chunk.
-    constexpr bool kConstState = !kHasYZ && kSplit && !is_bf16<T>;
-    SplitA<3> us[XT][ZT];
+    // Read-out-only passes: U never changes, so it is cut into its bf16 parts (three for fp32
+    // tensors, two for bf16 tensors) once, here, and every chunk's read-out runs on the bf16 pipe
+    // (section on split3 in la_device.h); only the chunk's own operand is split per chunk.
+    constexpr bool kConstState = !kHasYZ && kSplit;
+    SplitA<kParts> us[XT][ZT];
     if constexpr (kConstState) {
 #pragma unroll
         for (int xt = 0; xt < XT; ++xt)
 #pragma unroll
-            for (int zt = 0; zt < ZT; ++zt) us[xt][zt] = split_a<3>(U[xt][zt]);
+            for (int zt = 0; zt < ZT; ++zt) us[xt][zt] = split_a<kParts>(U[xt][zt]);
     }
 
     // Chunks are visited in steps of `dir`; the stager keeps kDepth chunks in flight, each in
@@ -577,7 +583,7 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         } else if constexpr (kConstState) {
 #pragma unroll
             for (int xt = 0; xt < XT; ++xt) {
-                const SplitB<3> xs = split_b<3>(xa[xt]);
+                const SplitB<kParts> xs = split_b<kParts>(xa[xt]);
 #pragma unroll
                 for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16_split_ba(xs, us[xt][zt], out[zt]);
             }
@@ -915,6 +921,13 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
     }
 }
 
+// Chunks a pass of the non-causal entry points keeps in flight per wave (sets of staging
+// registers).  Measured with bf16 tensors, where a tile is half as many bytes and there is
+// register room for a second set: two chunks in flight change nothing (step 0.564 against
+// 0.565 ms), these passes wait for instruction issue, not for their loads; so one set it is.
+template <typename T>
+constexpr int kGlobalDepth = LA_GLOBAL_DEPTH(T);
+
 template <int PASS, int D, int M, typename T, bool kStrided = false>
 __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void causal_pass_kernel(
     const PassArgs a) {
@@ -925,7 +938,7 @@ __global__ __launch_bounds__(kWave) __attribute__((amdgpu_waves_per_eu(2))) void
     __shared__ float lds_r[Tr::kHasRaw ? tile_floats(Tr::DZ) : 4];
     const int lane = threadIdx.x;
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
-    PassStager<PASS, D, M, T, kStrided> stg(a, bh, lane, lds_x, lds_y, lds_z, lds_r);
+    PassStager<PASS, D, M, T, kStrided, PASS >= kGlobal ? kGlobalDepth<T> : 1> stg(a, bh, lane, lds_x, lds_y, lds_z, lds_r);
     run_pass<PASS, D, M, T>(a, stg, lds_x, lds_y, lds_z, lds_r, a.out, bh, seg, lane, nullptr, lds_r);
 }
 
@@ -960,20 +973,20 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 // the grand total of phi(Q)^T dO/den), run side by side by the two waves of one workgroup so
 // that K is fetched once for both.  Wave 0 (the dV role) brings K, parked as phi and, for the
 // chain rule under dK, as phi'; wave 1 (the dK role) brings V.
-template <int ROLE, int D, int M, typename T, bool kStrided = false>
+template <int ROLE, int D, int M, typename T, bool kStrided = false, int kDepth_ = 1>
 struct GlobalBwdStager {
     static constexpr bool kStridedLayout = kStrided;
-    static constexpr int kDepth = 1;
+    static constexpr int kDepth = kDepth_;    // chunks in flight = sets of staging registers (1 or 2)
     static constexpr int F = ROLE == 0 ? D : M, FT = F / 16;
     const T *Src;                       // role 0: K; role 1: V
     const T *Kraw;                      // role 1, polynomial map: K again, for the raw vectors
     float *lds_a, *lds_a2;              // role 0: phi(K), phi'(K); role 1: V, -
     int N, lane;
     int ts, tsk;
-    f32x4 st[FT];
+    f32x4 st[kDepth][FT];
     float one[FT];
     float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
-    float xraw[kPolyRaw], n_xraw[kPolyRaw];   // polynomial map, role 1: raw K of token lane / 4
+    float xraw[kPolyRaw], n_xraw[kDepth][kPolyRaw];   // polynomial map, role 1: raw K of token lane / 4
 
     __device__ __forceinline__ GlobalBwdStager(const PassArgs &a, int bh, int lane_, float *la, float *la2)
         : lds_a(la), lds_a2(la2), N(a.N), lane(lane_) {
@@ -988,43 +1001,47 @@ struct GlobalBwdStager {
 #pragma unroll
         for (int i = 0; i < FT; ++i) one[i] = 1.0f;
 #pragma unroll
-        for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j] = 0.f;
+        for (int j = 0; j < kPolyRaw; ++j) {
+            xraw[j] = 0.f;
+#pragma unroll
+            for (int k = 0; k < kDepth; ++k) n_xraw[k][j] = 0.f;
+        }
     }
 
-    template <bool kFull>
+    template <int SLOT, bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
         if constexpr (ROLE == 0) {
-            stage_load_qk<D, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st);
+            stage_load_qk<D, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st[SLOT]);
         } else {
-            stage_load<M, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st);
-            if constexpr (is_poly<T>) load_raw8(Kraw + (size_t)t0 * tsk, tsk, nvalid, lane, n_xraw);
+            stage_load<M, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st[SLOT]);
+            if constexpr (is_poly<T>) load_raw8(Kraw + (size_t)t0 * tsk, tsk, nvalid, lane, n_xraw[SLOT]);
         }
     }
     template <int SLOT>
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        if (nvalid == kChunk) fetch_impl<true>(t0, nvalid);      // uniform branch
-        else fetch_impl<false>(t0, nvalid);
+        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);      // uniform branch
+        else fetch_impl<SLOT, false>(t0, nvalid);
     }
 
-    template <bool kFull>
+    template <int SLOT, bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
         if constexpr (ROLE == 0) {
-            park_tile<D, kMapPhi, kFull, is_feat<T>>(lds_a, st, one, nvalid, lane);
+            park_tile<D, kMapPhi, kFull, is_feat<T>>(lds_a, st[SLOT], one, nvalid, lane);
             // (polynomial map: no phi' tile; the dK wave uses that memory as the scratch of poly2_chain)
-            if constexpr (!is_poly<T>) park_tile<D, kMapDphi, kFull, is_feat<T>>(lds_a2, st, one, nvalid, lane);
+            if constexpr (!is_poly<T>) park_tile<D, kMapDphi, kFull, is_feat<T>>(lds_a2, st[SLOT], one, nvalid, lane);
         } else {
-            park_tile<M, kMapId, kFull, is_feat<T>>(lds_a, st, one, nvalid, lane);
+            park_tile<M, kMapId, kFull, is_feat<T>>(lds_a, st[SLOT], one, nvalid, lane);
         }
     }
     template <int SLOT>
     __device__ __forceinline__ void park(const int nvalid) {
-        if (nvalid == kChunk) park_impl<true>(nvalid);
-        else park_impl<false>(nvalid);
+        if (nvalid == kChunk) park_impl<SLOT, true>(nvalid);
+        else park_impl<SLOT, false>(nvalid);
         if constexpr (ROLE == 1 && is_poly<T>) {
 #pragma unroll
-            for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j];
+            for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[SLOT][j];
         }
     }
 };
@@ -1042,10 +1059,10 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
-        GlobalBwdStager<0, D, M, T, kStrided> stg(a, bh, lane, lds_fk, lds_dk);
+        GlobalBwdStager<0, D, M, T, kStrided, kGlobalDepth<T>> stg(a, bh, lane, lds_fk, lds_dk);
         run_pass<kGlobalDv, D, M, T>(a, stg, lds_fk, nullptr, nullptr, nullptr, a.out, bh, seg, lane);
     } else {
-        GlobalBwdStager<1, D, M, T, kStrided> stg(a, bh, lane, lds_v, nullptr);
+        GlobalBwdStager<1, D, M, T, kStrided, kGlobalDepth<T>> stg(a, bh, lane, lds_v, nullptr);
         run_pass<kGlobalDk, D, M, T>(a, stg, lds_v, nullptr, nullptr, lds_dk, a.out2, bh, seg, lane,
                                      nullptr, lds_dk);
     }
@@ -1055,25 +1072,25 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 // brings dO (parked as dO/den, den being the forward's denominator) and V; wave 1 brings Q
 // and K, both parked as phi.  The non-causal pass (kCausal = false) has no in-chunk part and
 // no running sum: V and K are not needed.
-template <int ROLE, int D, int M, typename T, bool kCausal, bool kStrided = false>
+template <int ROLE, int D, int M, typename T, bool kCausal, bool kStrided = false, int kDepth_ = 1>
 struct DqStager {
     static constexpr bool kStridedLayout = kStrided;
     static constexpr int F = ROLE == 0 ? M : D;
     static constexpr int FT = F / 16;
-    static constexpr int kDepth = 1;
+    static constexpr int kDepth = kDepth_;    // chunks in flight = sets of staging registers (1 or 2)
     const T *As, *Bs;                   // role 0: dO, V; role 1: Q, K
     const float *den;
     float *lds_a, *lds_b;               // role 0: dO/den, V; role 1: phi(Q), phi(K)
     int N, lane, g, ts;                 // ts: token stride of this role's tensors
-    f32x4 sa[FT], sb[FT];
-    float sca[FT], one[FT];
-    float n_den4[4];
+    f32x4 sa[kDepth][FT], sb[kDepth][FT];
+    float sca[kDepth][FT], one[FT];
+    float n_den4[kDepth][4];
     float dl1, dl4[4];                  // unused by this pass (interface of run_pass)
     float rd4[4];                       // 1/den of tokens 4g + s of the parked chunk, 0 past the end
     // polynomial map, role 0 (the wave that finishes dQ): raw Q of token lane / 4
     const T *Qraw;
     int tsq;
-    float xraw[kPolyRaw], n_xraw[kPolyRaw];
+    float xraw[kPolyRaw], n_xraw[kDepth][kPolyRaw];
     static constexpr int W = ROLE == 0 ? F : qk_width<T>(F);    // elements per token of this role's tensors
 
     __device__ __forceinline__ DqStager(const PassArgs &a, int bh, int lane_, float *la,
@@ -1085,30 +1102,42 @@ struct DqStager {
         tsq = tok_stride<kStrided>(a.tok_heads, qk_width<T>(D));
         Qraw = static_cast<const T *>(a.Q) + seq_base<kStrided>(a.N, a.heads, bh, qk_width<T>(D));
 #pragma unroll
-        for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j] = 0.f;
+        for (int j = 0; j < kPolyRaw; ++j) {
+            xraw[j] = 0.f;
+#pragma unroll
+            for (int k = 0; k < kDepth; ++k) n_xraw[k][j] = 0.f;
+        }
         den = a.den_in + rowbase;
         dl1 = 0.f;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) dl4[s] = rd4[s] = 0.f, n_den4[s] = 1.f;
+        for (int s = 0; s < 4; ++s) {
+            dl4[s] = rd4[s] = 0.f;
 #pragma unroll
-        for (int i = 0; i < FT; ++i) sca[i] = one[i] = 1.0f;
+            for (int k = 0; k < kDepth; ++k) n_den4[k][s] = 1.f;
+        }
+#pragma unroll
+        for (int i = 0; i < FT; ++i) {
+            one[i] = 1.0f;
+#pragma unroll
+            for (int k = 0; k < kDepth; ++k) sca[k][i] = 1.0f;
+        }
     }
 
-    template <bool kFull>
+    template <int SLOT, bool kFull>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
         if constexpr (ROLE == 1) {
-            stage_load_qk<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa);
-            if constexpr (kCausal) stage_load_qk<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb);
+            stage_load_qk<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa[SLOT]);
+            if constexpr (kCausal) stage_load_qk<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb[SLOT]);
         } else {
-            stage_load<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa);
-            if constexpr (kCausal) stage_load<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb);
-            if constexpr (is_poly<T>) load_raw8(Qraw + (size_t)t0 * tsq, tsq, nvalid, lane, n_xraw);
+            stage_load<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa[SLOT]);
+            if constexpr (kCausal) stage_load<F, kFull>(Bs + (size_t)t0 * ts, ts, nvalid, lane, sb[SLOT]);
+            if constexpr (is_poly<T>) load_raw8(Qraw + (size_t)t0 * tsq, tsq, nvalid, lane, n_xraw[SLOT]);
         }
         if constexpr (ROLE == 0) {
-            stage_rows<F, kFull>(den + t0, nvalid, lane, sca);      // den of the staged rows
+            stage_rows<F, kFull>(den + t0, nvalid, lane, sca[SLOT]);      // den of the staged rows
 #pragma unroll
             for (int s = 0; s < 4; ++s)                             // den of tokens 4g + s
-                n_den4[s] = den[t0 + (kFull ? 4 * g + s : min(4 * g + s, nvalid - 1))];
+                n_den4[SLOT][s] = den[t0 + (kFull ? 4 * g + s : min(4 * g + s, nvalid - 1))];
         }
     }
 
@@ -1116,34 +1145,34 @@ struct DqStager {
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        if (nvalid == kChunk) fetch_impl<true>(t0, nvalid);
-        else fetch_impl<false>(t0, nvalid);
+        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);
+        else fetch_impl<SLOT, false>(t0, nvalid);
     }
 
-    template <bool kFull>
+    template <int SLOT, bool kFull>
     __device__ __forceinline__ void park_impl(const int nvalid) {
         if constexpr (ROLE == 0) {
 #pragma unroll
-            for (int i = 0; i < FT; ++i) sca[i] = __builtin_amdgcn_rcpf(sca[i]);
-            park_tile<F, kMapScale, kFull, is_feat<T>>(lds_a, sa, sca, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapId, kFull, is_feat<T>>(lds_b, sb, one, nvalid, lane);
+            for (int i = 0; i < FT; ++i) sca[SLOT][i] = __builtin_amdgcn_rcpf(sca[SLOT][i]);
+            park_tile<F, kMapScale, kFull, is_feat<T>>(lds_a, sa[SLOT], sca[SLOT], nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapId, kFull, is_feat<T>>(lds_b, sb[SLOT], one, nvalid, lane);
 #pragma unroll
             for (int s = 0; s < 4; ++s)
-                rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[s]) : 0.f;
+                rd4[s] = (kFull || 4 * g + s < nvalid) ? __builtin_amdgcn_rcpf(n_den4[SLOT][s]) : 0.f;
             if constexpr (is_poly<T>) {
 #pragma unroll
-                for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[j];
+                for (int j = 0; j < kPolyRaw; ++j) xraw[j] = n_xraw[SLOT][j];
             }
         } else {
-            park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_a, sa, one, nvalid, lane);
-            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_b, sb, one, nvalid, lane);
+            park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_a, sa[SLOT], one, nvalid, lane);
+            if constexpr (kCausal) park_tile<F, kMapPhi, kFull, is_feat<T>>(lds_b, sb[SLOT], one, nvalid, lane);
         }
     }
 
     template <int SLOT>
     __device__ __forceinline__ void park(const int nvalid) {
-        if (nvalid == kChunk) park_impl<true>(nvalid);
-        else park_impl<false>(nvalid);
+        if (nvalid == kChunk) park_impl<SLOT, true>(nvalid);
+        else park_impl<SLOT, false>(nvalid);
     }
 };
 
@@ -1192,12 +1221,18 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
         }
     }
 
+    // kDepth chunks in flight, each in its own set of staging registers (as in run_pass)
+    constexpr int kDepth = Stager::kDepth;
     if (ch_begin < ch_end) stg.template fetch<0>(ch_begin);
-    for (int ch = ch_begin; ch < ch_end; ++ch) {
+    if constexpr (kDepth == 2) {
+        if (ch_begin + 1 < ch_end) stg.template fetch<1>(ch_begin + 1);
+    }
+    auto step = [&](auto slot_tag, const int ch) {
+        constexpr int kSlot = decltype(slot_tag)::value;
         const int nvalid = min(kChunk, a.N - ch * kChunk);
         __syncthreads();
-        stg.template park<0>(nvalid);
-        if (ch + 1 < ch_end) stg.template fetch<0>(ch + 1);
+        stg.template park<kSlot>(nvalid);
+        if (ch + kDepth < ch_end) stg.template fetch<kSlot>(ch + kDepth);
         if constexpr (kCausal) {
             // S as it stands before this chunk, element (d, m) at lds_u[m][d] (row stride D + 4)
 #pragma unroll
@@ -1277,6 +1312,12 @@ __device__ __forceinline__ void run_dq_sums(const PassArgs &a, Stager &stg, cons
                             R[xt][zt] = mfma16(qf[xt][s], gf[zt][s], R[xt][zt]);
             }
         }
+    };
+    for (int ch = ch_begin; ch < ch_end; ch += kDepth) {
+        step(std::integral_constant<int, 0>{}, ch);
+        if constexpr (kDepth == 2) {
+            if (ch + 1 < ch_end) step(std::integral_constant<int, 1>{}, ch + 1);
+        }
     }
     if (want) {
         float *st = a.totals + ((size_t)bh * a.nseg + seg) * state_stride(D, M);
@@ -1311,7 +1352,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
-        DqStager<0, D, M, T, kCausal, kStrided> stg(a, bh, lane, lds_g, lds_v);
+        DqStager<0, D, M, T, kCausal, kStrided, kCausal ? 1 : kGlobalDepth<T>> stg(a, bh, lane, lds_g, lds_v);
         if constexpr (kCausal)
             run_pass<kDq, D, M, T, kBorrowState>(a, stg, lds_g, lds_v, lds_fk, lds_fq, a.out, bh,
                                                  seg, lane, lds_S);
@@ -1319,7 +1360,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             run_pass<kGlobalDq, D, M, T>(a, stg, lds_g, nullptr, nullptr, lds_fq, a.out, bh, seg,
                                          lane, nullptr, lds_chain);
     } else {
-        DqStager<1, D, M, T, kCausal, kStrided> stg(a, bh, lane, lds_fq, lds_fk);
+        DqStager<1, D, M, T, kCausal, kStrided, kCausal ? 1 : kGlobalDepth<T>> stg(a, bh, lane, lds_fq, lds_fk);
         run_dq_sums<D, M, T, kCausal>(a, stg, lds_fk, lds_v, lds_fq, lds_g, lds_S, bh, seg, lane);
     }
 }
