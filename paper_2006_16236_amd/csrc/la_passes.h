@@ -58,6 +58,23 @@
 #ifndef LA_GLOBAL_DEPTH
 #define LA_GLOBAL_DEPTH(T) 1     // chunks in flight per wave in the non-causal passes (1 or 2)
 #endif
+// Issue priority (s_setprio, 0..3) of the two waves of the two-wave kernels.  Measured: in the
+// reverse kernel the dK wave, which borrows the state through LDS every chunk, is the one the
+// chunk waits for; letting it issue first takes 3.5 % off the kernel (0.358 -> 0.346 ms).  In the
+// dQ kernel neither choice helps (state wave first: 0.328 against 0.323 ms), nor in the two-wave
+// kernels of the non-causal backward and of bf16 tensors (tried, within noise; not kept).
+#ifndef LA_PRIO_DQ_CHUNK_WAVE
+#define LA_PRIO_DQ_CHUNK_WAVE 0
+#endif
+#ifndef LA_PRIO_DQ_STATE_WAVE
+#define LA_PRIO_DQ_STATE_WAVE 0
+#endif
+#ifndef LA_PRIO_REV_DV_WAVE
+#define LA_PRIO_REV_DV_WAVE 0
+#endif
+#ifndef LA_PRIO_REV_DK_WAVE
+#define LA_PRIO_REV_DK_WAVE 3
+#endif
 #ifndef LA_SLEEP_AFTER_FETCH
 #define LA_SLEEP_AFTER_FETCH 1   // in units of 64 clocks
 #endif
@@ -959,10 +976,12 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (role == 0) {
+        __builtin_amdgcn_s_setprio(LA_PRIO_REV_DV_WAVE);
         ReverseStager<0, D, M, T, kStrided> stg(a, bh, lane, lds_fq, nullptr, lds_g);
         run_pass<kDv, D, M, T, kPublishState>(a, stg, lds_fk, lds_fq, lds_g, nullptr, a.out, bh, seg,
                                               lane, lds_R);
     } else {
+        __builtin_amdgcn_s_setprio(LA_PRIO_REV_DK_WAVE);
         ReverseStager<1, D, M, T, kStrided> stg(a, bh, lane, lds_fk, lds_dk, lds_v);
         run_pass<kDk, D, M, T, kBorrowState>(a, stg, lds_v, lds_g, lds_fq, lds_dk, a.out2, bh, seg,
                                              lane, lds_R, lds_dk);
@@ -1414,6 +1433,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 
     if (role == 0) {
         // ---- chunk wave: brings Q and K --------------------------------------------------------
+        __builtin_amdgcn_s_setprio(LA_PRIO_DQ_CHUNK_WAVE);
         constexpr int W = qk_width<T>(D);          // elements per token of Q, K and dQ
         const int ts = tok_stride<kStrided>(a.tok_heads, W);
         const T *Qs = static_cast<const T *>(a.Q) + seq_base<kStrided>(a.N, a.heads, bh, W);
@@ -1586,6 +1606,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         }
     } else {
         // ---- state wave: brings dO (parked as dO/den) and V --------------------------------------
+        __builtin_amdgcn_s_setprio(LA_PRIO_DQ_STATE_WAVE);
         const int ts = tok_stride<kStrided>(a.tok_heads, M);
         const T *Gs = static_cast<const T *>(a.G) + seq_base<kStrided>(a.N, a.heads, bh, M);
         const T *Vs = static_cast<const T *>(a.V) + seq_base<kStrided>(a.N, a.heads, bh, M);
