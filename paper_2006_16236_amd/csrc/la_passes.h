@@ -62,7 +62,7 @@
 // reverse kernel the dK wave, which borrows the state through LDS every chunk, is the one the
 // chunk waits for; letting it issue first takes 3.5 % off the kernel timed between events
 // (0.358 -> 0.346 ms) and 0.5-1 % off the whole step (1.016 -> 1.011 ms, a second box 1.040 ->
-// 1.027 ms: back to back the kernels overlap at their ends, which hides part of it).  In the
+// 1.027 ms, wall clock over back-to-back steps).  In the
 // dQ kernel neither choice helps (state wave first: 0.328 against 0.323 ms), nor in the two-wave
 // kernels of the non-causal backward and of bf16 tensors (tried, within noise; not kept).
 #ifndef LA_PRIO_DQ_CHUNK_WAVE
