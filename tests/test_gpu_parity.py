@@ -790,6 +790,50 @@ def test_degree_two_polynomial_kernel_through_the_feature_interface(la, oracle_f
     assert max(grad_errs([to_host(x) for x in (hq, hk, hv)], o.global_bwd_linear(FQ, FK, V, G, eps))) <= tol
 
 
+def test_random_fourier_features_through_the_feature_interface(la, oracle_features):
+    """Random Fourier features (the paper's conclusion names them as a feature map to explore):
+    phi(x) = sqrt(1/R) [cos(Wx), sin(Wx)] with R = 32 Gaussian directions, so that
+    phi(q) . phi(k) = mean_r cos(w_r . (q - k)), the Monte Carlo estimate of the RBF kernel
+    exp(-|q - k|^2 / 2).  The map needs a projection, which the caller applies; the 64 signed
+    features go through the feature interface.  The oracle on these features must equal
+    attention with that similarity written out, which in turn is the RBF kernel up to the
+    Monte Carlo error; the GPU must equal the oracle, forward and backward, causal and not."""
+    o = oracle_features
+    rng = np.random.default_rng(1357)
+    B, H, N, d, R, M = 2, 2, 300, 16, 32, 64
+    xq, xk = (0.1 * rng.standard_normal((B, H, N, d)) for _ in range(2))
+    W = rng.standard_normal((R, d))
+    V, G = (rng.standard_normal((B, H, N, M)).astype(np.float32) for _ in range(2))
+    feat = lambda x: (np.concatenate([np.cos(x @ W.T), np.sin(x @ W.T)], axis=-1) / np.sqrt(R)).astype(np.float32)
+    FQ, FK = feat(xq), feat(xk)
+    eps = 1e-6
+    diff = xq[:, :, :, None, :] - xk[:, :, None, :, :]
+    A_def = np.cos(diff @ W.T).mean(-1)                     # the similarity, written out
+    A = np.einsum("bhic,bhjc->bhij", FQ.astype(np.float64), FK.astype(np.float64))
+    np.testing.assert_allclose(A, A_def, rtol=0, atol=5e-7)
+    rbf = np.exp(-0.5 * (diff ** 2).sum(-1))
+    assert np.abs(A_def - rbf).max() < 0.3 and np.abs(A_def - rbf).mean() < 0.04 and A.min() > 0.3
+    Ac = np.tril(A)
+    ref_c = (Ac @ V) / (Ac.sum(-1, keepdims=True) + eps)
+    ref_g = (A @ V) / (A.sum(-1, keepdims=True) + eps)
+    np.testing.assert_allclose(o.causal_fwd_prefix(FQ, FK, V, eps), ref_c, rtol=1e-9, atol=1e-11)
+    np.testing.assert_allclose(o.global_fwd_linear(FQ, FK, V, eps), ref_g, rtol=1e-9, atol=1e-11)
+    dq, dk, dv, dg = (to_dev(x) for x in (FQ, FK, V, G))
+    O = torch.empty_like(dv); den = torch.empty(B, H, N, device=DEV)
+    ws = la.la_causal_fwd(dq, dk, dv, O, den, eps, features=True)
+    gq, gk, gv = (torch.empty_like(x) for x in (dq, dk, dv))
+    la.la_causal_bwd(dq, dk, dv, None, den, dg, gq, gk, gv, eps, fwd_ws=ws, features=True)
+    Og = torch.empty_like(dv); deng = torch.empty(B, H, N, device=DEV)
+    wsg = la.la_global_fwd(dq, dk, dv, Og, eps, den=deng, features=True)
+    hq, hk, hv = (torch.empty_like(x) for x in (dq, dk, dv))
+    la.la_global_bwd(dq, dk, dv, None, deng, dg, hq, hk, hv, eps, fwd_ws=wsg, features=True)
+    torch.cuda.synchronize()
+    tol = tol_for(N)
+    assert rel_err(to_host(O), ref_c) <= tol and rel_err(to_host(Og), ref_g) <= tol
+    assert max(grad_errs([to_host(x) for x in (gq, gk, gv)], o.causal_bwd_linear(FQ, FK, V, G, eps))) <= tol
+    assert max(grad_errs([to_host(x) for x in (hq, hk, hv)], o.global_bwd_linear(FQ, FK, V, G, eps))) <= tol
+
+
 def test_caller_supplied_features_decode_and_bf16(la, oracle_features):
     o = oracle_features
     B, H, T, D, M = 3, 2, 25, 64, 64
