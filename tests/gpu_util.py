@@ -69,10 +69,10 @@ def to_host(t):
 
 
 @contextlib.contextmanager
-def schedule(target_waves=None, min_seg_chunks=None, fold_max_segs=None):
+def schedule(target_waves=None, min_seg_chunks=None, fold_max_segs=None, bwd_seg_group=None):
     """Force the segment schedule of the library through its environment knobs."""
     keys = {"LA_TARGET_WAVES": target_waves, "LA_MIN_SEG_CHUNKS": min_seg_chunks,
-            "LA_FOLD_MAX_SEGS": fold_max_segs}
+            "LA_FOLD_MAX_SEGS": fold_max_segs, "LA_BWD_SEG_GROUP": bwd_seg_group}
     old = {k: os.environ.get(k) for k in keys}
     try:
         for k, v in keys.items():

@@ -396,6 +396,33 @@ def test_forward_with_state_in_and_out(la, oracle, sched):
     assert rel_err(zb.cpu().numpy(), fk.sum(2)) <= 1e-4
 
 
+@pytest.mark.parametrize("group", [1, 2])
+@pytest.mark.parametrize("D,M", [(32, 32), (64, 64), (64, 32)])
+@pytest.mark.parametrize("cut", ["scanned", "folded"])
+def test_backward_takes_segments_singly_or_in_pairs(la, oracle, D, M, group, cut):
+    """The backward's workgroups take the forward's segments one by one (the default at
+    D = M = 32) or in pairs (the default otherwise): both groupings, for either head size, on
+    scanned and on folded segment totals, causal and non-causal, against the oracle."""
+    B, H, N = 2, 2, 1000
+    Q, K, V, G = wl.random_case(990 + D + M, B, H, N, D, M)
+    ref = oracle.causal_bwd_linear(Q, K, V, G, 1e-6)
+    gref = oracle.global_bwd_linear(Q, K, V, G, 1e-6)
+    dq, dk, dv, dg = (to_dev(x) for x in (Q, K, V, G))
+    kw = dict(target_waves=1 << 20, min_seg_chunks=3) if cut == "scanned" else dict(target_waves=24, min_seg_chunks=1, fold_max_segs=64)
+    with schedule(bwd_seg_group=group, **kw):
+        O = torch.empty_like(dv); den = torch.empty(B, H, N, device=DEV)
+        ws = la.la_causal_fwd(dq, dk, dv, O, den, 1e-6)
+        got = [torch.full_like(x, float("nan")) for x in (dq, dk, dv)]
+        la.la_causal_bwd(dq, dk, dv, None, den, dg, got[0], got[1], got[2], 1e-6, fwd_ws=ws)
+        Og = torch.empty_like(dv); deng = torch.empty(B, H, N, device=DEV)
+        wsg = la.la_global_fwd(dq, dk, dv, Og, 1e-6, den=deng)
+        ggot = [torch.full_like(x, float("nan")) for x in (dq, dk, dv)]
+        la.la_global_bwd(dq, dk, dv, None, deng, dg, ggot[0], ggot[1], ggot[2], 1e-6, fwd_ws=wsg)
+        torch.cuda.synchronize()
+    assert max(grad_errs([to_host(x) for x in got], ref)) <= tol_for(N)
+    assert max(grad_errs([to_host(x) for x in ggot], gref)) <= tol_for(N)
+
+
 def _state_case(seed, B, H, N, D, M):
     """Inputs plus a non-zero initial state and a non-zero gradient arriving at the final state
     (the state is that of P imaginary earlier tokens: positive z0, S0 of matching size)."""
