@@ -7,12 +7,10 @@ hipError_t launch_pass_dq(bool causal, int D, int M, int dtype, const PassArgs &
                           hipStream_t s) {
     LA_DISPATCH(D, M, dtype, {
         if (a.tok_heads > 1) {
-            if (!causal) dq_pass_kernel<kD, kM, TT, false, true><<<nblocks, 2 * kWave, 0, s>>>(a);
-            else if constexpr (is_bf16<TT>) dq_pass_kernel<kD, kM, TT, true, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+            if (!causal) dq_pass_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
             else dq_causal_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
         } else {
-            if (!causal) dq_pass_kernel<kD, kM, TT, false><<<nblocks, 2 * kWave, 0, s>>>(a);
-            else if constexpr (is_bf16<TT>) dq_pass_kernel<kD, kM, TT, true><<<nblocks, 2 * kWave, 0, s>>>(a);
+            if (!causal) dq_pass_kernel<kD, kM, TT><<<nblocks, 2 * kWave, 0, s>>>(a);
             else dq_causal_kernel<kD, kM, TT><<<nblocks, 2 * kWave, 0, s>>>(a);
         }
     });
