@@ -348,6 +348,25 @@ __device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB<2> &b, f32
     return mfma32_bf16(cat_parts(mk, mk), b.hm(), acc);                 // mask (h + m)
 }
 
+// An operand quad whose values are exact in bf16 (V of a bf16 tensor, widened to fp32 when the
+// tile was parked): it has no second part, so the product against a two-part operand is the two
+// halves of one instruction, (h + m) * v, where the general two-part product takes two.
+struct ExactBf16 {
+    u32x2_t v;
+};
+__device__ __forceinline__ ExactBf16 exact_bf16(const float (&x)[4]) {
+    return ExactBf16{__builtin_bit_cast(u32x2_t, pack_bf16x4(x))};
+}
+__device__ __forceinline__ f32x4 mfma16_split(const ExactBf16 &a, const SplitB<2> &b, f32x4 acc) {
+    return mfma32_bf16(cat_parts(a.v, a.v), b.hm(), acc);
+}
+__device__ __forceinline__ f32x4 mfma16_split(const SplitA<2> &a, const ExactBf16 &b, f32x4 acc) {
+    return mfma32_bf16(a.hm(), cat_parts(b.v, b.v), acc);
+}
+__device__ __forceinline__ f32x4 mfma16_split_ba(const ExactBf16 &x, const SplitA<2> &u, f32x4 acc) {
+    return mfma32_bf16(cat_parts(x.v, x.v), u.hm(), acc);
+}
+
 // ---- tiles ------------------------------------------------------------------------------------
 // A tile is 16 consecutive tokens x F features of one [N, F] slab, F in {32, 64}.
 //

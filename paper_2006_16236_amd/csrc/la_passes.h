@@ -591,6 +591,9 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         for (int zt = 0; zt < ZT; ++zt) out[zt] = f32x4{0.f, 0.f, 0.f, 0.f};
         bf16x4_t xp[XT];                 // X packed (bf16 path)
         Split2 x2[XT];                   // X in two parts (bf16 tensors, backward passes)
+        // bf16 tensors, the dK passes: X is V itself, exact in bf16, and needs no second part
+        constexpr bool kExactX = is_bf16<T> && Tr::BP == kDk;
+        ExactBf16 xe[XT];
         if constexpr (kBf) {
 #pragma unroll
             for (int xt = 0; xt < XT; ++xt) {
@@ -602,18 +605,31 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
         } else if constexpr (kConstState) {
 #pragma unroll
             for (int xt = 0; xt < XT; ++xt) {
-                const SplitB<kParts> xs = split_b<kParts>(xa[xt]);
+                if constexpr (kExactX) {
+                    xe[xt] = exact_bf16(xa[xt]);
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16_split_ba(xs, us[xt][zt], out[zt]);
+                    for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16_split_ba(xe[xt], us[xt][zt], out[zt]);
+                } else {
+                    const SplitB<kParts> xs = split_b<kParts>(xa[xt]);
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt) out[zt] = mfma16_split_ba(xs, us[xt][zt], out[zt]);
+                }
             }
         } else if constexpr (kSplitState) {
 #pragma unroll
             for (int xt = 0; xt < XT; ++xt) {
-                x2[xt] = split2(xa[xt]);
-                const SplitA<2> xs = as_a(x2[xt]);
+                if constexpr (kExactX) {
+                    xe[xt] = exact_bf16(xa[xt]);
 #pragma unroll
-                for (int zt = 0; zt < ZT; ++zt)
-                    out[zt] = mfma16_split(xs, split_b<2>(U[xt][zt]), out[zt]);
+                    for (int zt = 0; zt < ZT; ++zt)
+                        out[zt] = mfma16_split(xe[xt], split_b<2>(U[xt][zt]), out[zt]);
+                } else {
+                    x2[xt] = split2(xa[xt]);
+                    const SplitA<2> xs = as_a(x2[xt]);
+#pragma unroll
+                    for (int zt = 0; zt < ZT; ++zt)
+                        out[zt] = mfma16_split(xs, split_b<2>(U[xt][zt]), out[zt]);
+                }
             }
         } else {
 #pragma unroll
@@ -656,8 +672,13 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
             if constexpr (kSplitState) {
 #pragma unroll
                 for (int xt = 0; xt < XT; xt += 2) {
-                    w0 = mfma16_split(split_a<2>(ya[xt]), as_b(x2[xt]), w0);
-                    w1 = mfma16_split(split_a<2>(ya[xt + 1]), as_b(x2[xt + 1]), w1);
+                    if constexpr (kExactX) {
+                        w0 = mfma16_split(split_a<2>(ya[xt]), xe[xt], w0);
+                        w1 = mfma16_split(split_a<2>(ya[xt + 1]), xe[xt + 1], w1);
+                    } else {
+                        w0 = mfma16_split(split_a<2>(ya[xt]), as_b(x2[xt]), w0);
+                        w1 = mfma16_split(split_a<2>(ya[xt + 1]), as_b(x2[xt + 1]), w1);
+                    }
                 }
             } else if constexpr (kBf) {       // 16-bit operands: den is good to 2^-16
 #pragma unroll
@@ -1426,11 +1447,11 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             lds_token_lane<M>(lds_g[buf], c, g, xa);
             lds_token_lane<M>(lds_v[buf], c, g, ya);
             f32x4 w0 = zero4, w1 = zero4;
-            if constexpr (is_bf16<T>) {
+            if constexpr (is_bf16<T>) {       // V of a bf16 tensor is exact in bf16
 #pragma unroll
                 for (int xt = 0; xt < MT; xt += 2) {
-                    w0 = mfma16_split(split_a<2>(ya[xt]), split_b<2>(xa[xt]), w0);
-                    w1 = mfma16_split(split_a<2>(ya[xt + 1]), split_b<2>(xa[xt + 1]), w1);
+                    w0 = mfma16_split(exact_bf16(ya[xt]), split_b<2>(xa[xt]), w0);
+                    w1 = mfma16_split(exact_bf16(ya[xt + 1]), split_b<2>(xa[xt + 1]), w1);
                 }
             } else {
 #pragma unroll
@@ -1630,9 +1651,15 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
                 for (int zt = 0; zt < DT; ++zt) zs[zt] = split_b<kParts>(zf[zt]);
 #pragma unroll
                 for (int xt = 0; xt < MT; ++xt) {
-                    const SplitA<kParts> ys = split_a<kParts>(yf[xt]);
+                    if constexpr (is_bf16<T>) {
+                        const ExactBf16 ys = exact_bf16(yf[xt]);
 #pragma unroll
-                    for (int zt = 0; zt < DT; ++zt) U[xt][zt] = mfma16_split(ys, zs[zt], U[xt][zt]);
+                        for (int zt = 0; zt < DT; ++zt) U[xt][zt] = mfma16_split(ys, zs[zt], U[xt][zt]);
+                    } else {
+                        const SplitA<kParts> ys = split_a<kParts>(yf[xt]);
+#pragma unroll
+                        for (int zt = 0; zt < DT; ++zt) U[xt][zt] = mfma16_split(ys, zs[zt], U[xt][zt]);
+                    }
                 }
             }
             // this segment's phi(Q)^T dO/den (eq. 14-15 restricted to the segment)
@@ -1750,9 +1777,15 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
             for (int xt = 0; xt < XT; ++xt) ys[xt] = split_a<kParts>(yf[xt]);
 #pragma unroll
             for (int zt = 0; zt < ZT; ++zt) {
-                const SplitB<kParts> zs = split_b<kParts>(zf[zt]);
+                if constexpr (is_bf16<T>) {     // V of a bf16 tensor is exact in bf16
+                    const ExactBf16 zs = exact_bf16(zf[zt]);
 #pragma unroll
-                for (int xt = 0; xt < XT; ++xt) U[xt][zt] = mfma16_split(ys[xt], zs, U[xt][zt]);
+                    for (int xt = 0; xt < XT; ++xt) U[xt][zt] = mfma16_split(ys[xt], zs, U[xt][zt]);
+                } else {
+                    const SplitB<kParts> zs = split_b<kParts>(zf[zt]);
+#pragma unroll
+                    for (int xt = 0; xt < XT; ++xt) U[xt][zt] = mfma16_split(ys[xt], zs, U[xt][zt]);
+                }
             }
         } else {
 #pragma unroll
