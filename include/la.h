@@ -59,6 +59,10 @@
  *              the argument checks.
  *   Determinism No floating-point atomics: the same call on the same inputs
  *              gives bit-identical results.
+ *   Non-finite Inf or NaN in the inputs gives unspecified results, with one
+ *              guarantee: the causal forward's outputs and denominators before
+ *              token t do not depend on what Q, K, V hold from token t on,
+ *              finite or not (the causal mask of eq. 8).
  *   Threads    No global mutable state (la_causal_fwd_noalloc's built-in scratch
  *              array aside); calls from several host threads are safe as long as
  *              they do not share output or workspace buffers.

@@ -165,14 +165,22 @@ __device__ __forceinline__ void state_slots(const PassArgs &a, const int seg, co
     }
 }
 
-enum Map { kMapId = 0, kMapPhi = 1, kMapDphi = 2, kMapScale = 3, kMapOne = 4 };
+enum Map { kMapId = 0, kMapPhi = 1, kMapDphi = 2, kMapScale = 3, kMapOne = 4, kMapFinite = 5 };
 
+// kMapFinite: the value itself, with +-Inf and NaN replaced by finite values (one instruction:
+// the median of (v, -big, big), which returns the smallest operand when one is a NaN; big is the
+// largest finite bf16, so that it survives the operand packing of every element type).  It is
+// the map of V in the causal forward: the in-chunk term adds mask(scores)_ab V_b over the whole
+// 16-token tile, masked entries being exact zeros, and 0 * Inf would carry a non-finite value of
+// token b back to the tokens before it.  The scores need no such care: they are masked by a
+// select on the product's result.
 template <int MAP>
 __device__ __forceinline__ float map_value(float v, float scale) {
     if constexpr (MAP == kMapPhi) return phi(v);
     if constexpr (MAP == kMapDphi) return dphi(v);
     if constexpr (MAP == kMapScale) return v * scale;
     if constexpr (MAP == kMapOne) return 1.0f;
+    if constexpr (MAP == kMapFinite) return __builtin_amdgcn_fmed3f(v, -3.3895314e38f, 3.3895314e38f);
     return v;
 }
 
@@ -219,7 +227,7 @@ struct PassTraits {
     static constexpr bool kHasYZ = (PASS < kGlobal);                  // false: read-out only
     static constexpr int kMapX = (BP == kDq) ? kMapScale : (BP == kDk) ? kMapId : kMapPhi;
     static constexpr int kMapY = (PASS == kDq) ? kMapId : (PASS == kDk) ? kMapScale : kMapPhi;
-    static constexpr int kMapZ = (PASS == kFwd) ? kMapId : (PASS == kDv) ? kMapScale : kMapPhi;
+    static constexpr int kMapZ = (PASS == kFwd) ? kMapFinite : (PASS == kDv) ? kMapScale : kMapPhi;
 };
 
 // Staging of a pass run by one wave on its own (kFwd and the read-out-only passes kGlobal,

@@ -933,23 +933,32 @@ def test_bitwise_determinism_and_slab_independence(la):
     assert np.array_equal(O3, O1[perm])
 
 
-def test_causality_huge_future_does_not_leak(la):
-    """Outputs before token t are bit-identical whatever finite values follow it: the mask
-    is a select on the scores, so even 1e30-sized future values contribute an exact zero.
-    (Non-finite inputs are outside the contract: 0 * inf inside a 16-token tile is NaN.)"""
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("future", ["huge", "inf", "nan"])
+def test_causality_future_does_not_leak(la, future, bf16):
+    """Outputs before token t are bit-identical whatever follows it, finite or not: the mask is a
+    select on the scores, so 1e30-sized (or NaN) scores of future tokens contribute an exact
+    zero, and V is made finite when its tile is parked, so that the zero is not multiplied by an
+    Inf or a NaN of a later token of the same 16-token tile."""
     B, H, N, D, M = 1, 2, 200, 64, 64
-    Q, K, V = wl.random_case(801, B, H, N, D, M)[:3]
+    Q, K, V = maybe_bf16(wl.random_case(801, B, H, N, D, M)[:3], bf16)
     t = 77                                     # inside a chunk: 77 = 4*16 + 13
-    O, _ = run_fwd(la, Q, K, V, 1e-6)
+    dev = [to_dev(x, bf16) for x in (Q, K, V)]
+    O = torch.empty_like(dev[2]); den = torch.empty(B, H, N, device=DEV)
+    la.la_causal_fwd(dev[0], dev[1], dev[2], O, den, 1e-6)
     Q2, K2, V2 = Q.copy(), K.copy(), V.copy()
-    V2[:, :, t:] = 1e30
-    Q2[:, :, t:] = -3.0
-    K2[:, :, t:] = 50.0
-    dq, dk, dv = (to_dev(x) for x in (Q2, K2, V2))
-    O2 = torch.empty_like(dv)
-    la.la_causal_fwd(dq, dk, dv, O2, None, 1e-6)
+    if future == "huge":
+        V2[:, :, t:] = 1e30; Q2[:, :, t:] = -3.0; K2[:, :, t:] = 50.0
+    elif future == "inf":
+        V2[:, :, t:] = np.inf; V2[:, :, t + 1::2] = -np.inf; Q2[:, :, t:] = np.inf; K2[:, :, t:] = np.inf
+    else:
+        V2[:, :, t:] = np.nan; Q2[:, :, t:] = np.nan; K2[:, :, t:] = np.nan
+    dq, dk, dv = (to_dev(x, bf16) for x in (Q2, K2, V2))
+    O2 = torch.empty_like(dv); den2 = torch.empty_like(den)
+    la.la_causal_fwd(dq, dk, dv, O2, den2, 1e-6)
     torch.cuda.synchronize()
-    assert np.array_equal(to_host(O2)[:, :, :t], O[:, :, :t])
+    assert torch.equal(O2[:, :, :t], O[:, :, :t]) and torch.equal(den2[:, :, :t], den[:, :, :t])
+    assert bool(torch.isfinite(O2[:, :, :t].float()).all())
 
 
 def test_outputs_stay_inside_their_buffers(la):
