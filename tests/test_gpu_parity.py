@@ -1137,3 +1137,43 @@ def test_poly2_map_sequence_in_two_pieces_through_the_state(la, oracle, sched):
     fk = oracle.poly2_features(K[:, :, :N1].astype(np.float64))
     assert rel_err(S1.cpu().numpy(), np.einsum("bhnd,bhnm->bhdm", fk, V[:, :, :N1].astype(np.float64))) <= tol
     assert rel_err(z1.cpu().numpy(), fk.sum(2), floor=1.0) <= tol
+
+
+def test_two_host_threads_on_their_own_streams(la):
+    """The header's thread-safety claim: calls from several host threads are safe as long as
+    they share no output or workspace buffer.  Two threads, each with its own stream and
+    buffers, run forward + backward + decode steps repeatedly at the same time; every result
+    must be bit for bit what the same calls give one after the other."""
+    import threading
+    cases = [wl.random_case(1800 + i, 2, 3, 700 + 37 * i, 64, 64) for i in range(2)]
+
+    def work(i, stream, rounds, out):
+        Q, K, V, G = (to_dev(x) for x in cases[i])
+        B, H, N = Q.shape[:3]
+        with torch.cuda.stream(stream):
+            for _ in range(rounds):
+                O = torch.empty_like(V); den = torch.empty(B, H, N, device=DEV)
+                ws = la.la_causal_fwd(Q, K, V, O, den, 1e-6)
+                g = [torch.empty_like(x) for x in (Q, K, V)]
+                la.la_causal_bwd(Q, K, V, None, den, G, g[0], g[1], g[2], 1e-6, fwd_ws=ws)
+                S = torch.zeros(B, H, 64, 64, device=DEV); z = torch.zeros(B, H, 64, device=DEV)
+                o = torch.empty(B, H, 64, device=DEV)
+                for t in range(8):
+                    la.la_recurrent_step(Q[:, :, t].contiguous(), K[:, :, t].contiguous(),
+                                         V[:, :, t].contiguous(), S, z, o, 1e-6)
+            stream.synchronize()
+        out[i] = [O, den] + g + [S, z, o]
+
+    serial, parallel = {}, {}
+    for i in range(2):
+        work(i, torch.cuda.Stream(), 1, serial)
+    threads = [threading.Thread(target=work, args=(i, torch.cuda.Stream(), 20, parallel)) for i in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    for i in range(2):
+        assert len(parallel[i]) == len(serial[i])
+        for a, b in zip(parallel[i], serial[i]):
+            assert torch.equal(a, b)
