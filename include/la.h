@@ -255,6 +255,9 @@ int la_causal_bwd_bnhd(const void *Q, const void *K, const void *V, const void *
  *   O_i = phi(Q_i)^T (sum_j phi(K_j) V_j^T) / (phi(Q_i) . sum_j phi(K_j) + eps).
  * Arguments as la_causal_fwd; den [B,H,N] fp32 out (the denominators, eps
  * included) or NULL.  ws: la_global_fwd_workspace() bytes (never 0).
+ * Sequences shorter than N in one batch: give the K rows of the padded tokens
+ * the value -inf (phi(-inf) = 0 and phi'(-inf) = 0 exactly, so they drop out of
+ * both sums) and, in the backward, the dO rows of the padded queries zeros.
  */
 int la_global_fwd(const void *Q, const void *K, const void *V, void *O, float *den,
                   int B, int H, int N, int D, int M, float eps, la_dtype t,

@@ -1177,3 +1177,30 @@ def test_two_host_threads_on_their_own_streams(la):
         assert len(parallel[i]) == len(serial[i])
         for a, b in zip(parallel[i], serial[i]):
             assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("sched", ["default", "many_segments", "folded_totals"])
+def test_padded_keys_are_masked_by_minus_infinity(la, oracle, sched, bf16):
+    """Sequences of different lengths in one batch of the non-causal calls: the padded tail of a
+    sequence is taken out of the sums of eq. 5-6 by K = -inf there (phi(-inf) = 0 and phi' = 0,
+    exactly), with a zero upstream gradient on the padded queries.  Every sequence must then
+    equal the oracle on the sequence cut to its own length, forward and backward, and the padded
+    rows of dK and dV must be exact zeros."""
+    B, H, N, D, M = 3, 2, 700, 64, 64
+    lengths = [700, 517, 130]
+    Q, K, V, G = wl.random_case(1900, B, H, N, D, M)
+    for b, n in enumerate(lengths):
+        K[b, :, n:] = -np.inf
+        G[b, :, n:] = 0.0
+    Q, K, V, G = maybe_bf16([Q, K, V, G], bf16)
+    with schedule(**SCHEDULES[sched]):
+        O, den, grads = run_global(la, Q, K, V, G, 1e-6, bf16=bf16)
+    tol = tol_for(N, bf16)
+    for b, n in enumerate(lengths):
+        cut = [x[b:b + 1, :, :n] for x in (Q, K, V, G)]
+        assert rel_err(O[b:b + 1, :, :n], oracle.global_fwd_linear(*cut[:3], 1e-6)) <= tol
+        ref = oracle.global_bwd_linear(*cut, 1e-6)
+        assert max(grad_errs([g[b:b + 1, :, :n] for g in grads], ref)) <= tol
+        assert np.all(grads[0][b, :, n:] == 0) and np.all(grads[1][b, :, n:] == 0) and np.all(grads[2][b, :, n:] == 0)
+    assert np.all(np.isfinite(O)) and all(np.all(np.isfinite(g)) for g in grads)
