@@ -66,18 +66,20 @@
  *   Threads    No global mutable state (la_causal_fwd_noalloc's built-in scratch
  *              array aside); calls from several host threads are safe as long as
  *              they do not share output or workspace buffers.
- *   Tuning     Four environment variables, read at every call, override the
- *              segment schedule (for tests and experiments): LA_TARGET_WAVES
+ *   Tuning     Five environment variables, read at every call, override the
+ *              schedule (for tests and experiments): LA_TARGET_WAVES
  *              (default 2048: wavefronts wanted in flight), LA_MIN_SEG_CHUNKS
  *              (default 2: shortest segment, in 16-token chunks),
  *              LA_FOLD_MAX_SEGS (default 8: up to this many segments per
  *              sequence the passes add up the segment totals themselves and no
- *              scan kernel runs) and LA_BWD_SEG_GROUP (1 or 2: how many of the
+ *              scan kernel runs), LA_BWD_SEG_GROUP (1 or 2: how many of the
  *              forward's segments a workgroup of the backward takes; default 1
- *              for 32 x 32 heads, else 2).  Sequences are not cut at all once
- *              B*H reaches half of LA_TARGET_WAVES.  The workspace query, a
- *              forward and the backward that is handed its workspace must see
- *              the same values.
+ *              for 32 x 32 heads, else 2) and LA_STREAM_LOADS (0 or 1: plain or
+ *              non-temporal loads of the tensors; default by size: non-temporal
+ *              once Q, K, V, dO together pass 192 MB).  Sequences are not cut at
+ *              all once B*H reaches half of LA_TARGET_WAVES.  The workspace
+ *              query, a forward and the backward that is handed its workspace
+ *              must see the same values of the first three.
  */
 #ifndef LA_H_
 #define LA_H_

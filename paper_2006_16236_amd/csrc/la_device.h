@@ -103,6 +103,10 @@ template <> __device__ __forceinline__ void store_elem<feat_bf16>(feat_bf16 *p, 
     p->bits = f32_to_bf16_bits(v);
 }
 
+// four consecutive floats of a state (written by the kernel before, read once per workgroup:
+// a plain load, so that it is found in the cache)
+__device__ __forceinline__ f32x4 load4_state(const float *p) { return *reinterpret_cast<const f32x4 *>(p); }
+
 // four consecutive elements, 16-byte (fp32) or 8-byte (bf16) aligned
 __device__ __forceinline__ f32x4 load4(const float *p) {
     if constexpr (LA_NT_LOADS != 0) return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
@@ -117,6 +121,33 @@ __device__ __forceinline__ f32x4 load4(const bf16_t *p) {
     r[3] = __uint_as_float(u.y & 0xffff0000u);
     return r;
 }
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+// What one fetch leaves in a lane's staging registers: the four elements as they are in memory.
+// bf16 elements are widened when the tile is parked, not at the load: widening there would make
+// the wave wait for the data right behind the fetch, a whole chunk before it is needed.
+template <typename T> struct Staged { using type = f32x4; };
+template <> struct Staged<bf16_t> { using type = u32x2_t; };
+template <> struct Staged<feat_bf16> { using type = u32x2_t; };
+template <typename T> using staged_t = typename Staged<T>::type;
+__device__ __forceinline__ f32x4 widen(f32x4 v) { return v; }
+__device__ __forceinline__ f32x4 widen(u32x2_t u) {
+    f32x4 r;
+    r[0] = __uint_as_float(u[0] << 16);
+    r[1] = __uint_as_float(u[0] & 0xffff0000u);
+    r[2] = __uint_as_float(u[1] << 16);
+    r[3] = __uint_as_float(u[1] & 0xffff0000u);
+    return r;
+}
+// kNt: non-temporal (the tensors of a call that streams more than the caches hold) or plain
+template <bool kNt> __device__ __forceinline__ u32x2_t load4_staged(const bf16_t *p) {
+    if constexpr (kNt && LA_NT_LOADS != 0) return __builtin_nontemporal_load(reinterpret_cast<const u32x2_t *>(p));
+    else return *reinterpret_cast<const u32x2_t *>(p);
+}
+template <bool kNt> __device__ __forceinline__ u32x2_t load4_staged(const feat_bf16 *p) {
+    return load4_staged<kNt>(reinterpret_cast<const bf16_t *>(p));
+}
 __device__ __forceinline__ f32x4 load4(const feat_f32 *p) {
     return load4(reinterpret_cast<const float *>(p));
 }
@@ -125,6 +156,16 @@ __device__ __forceinline__ f32x4 load4(const feat_bf16 *p) {
 }
 __device__ __forceinline__ f32x4 load4(const poly2_f32 *p) {
     return load4(reinterpret_cast<const float *>(p));
+}
+template <bool kNt> __device__ __forceinline__ f32x4 load4_staged(const float *p) {
+    if constexpr (kNt) return load4(p);
+    else return *reinterpret_cast<const f32x4 *>(p);
+}
+template <bool kNt> __device__ __forceinline__ f32x4 load4_staged(const feat_f32 *p) {
+    return load4_staged<kNt>(reinterpret_cast<const float *>(p));
+}
+template <bool kNt> __device__ __forceinline__ f32x4 load4_staged(const poly2_f32 *p) {
+    return load4_staged<kNt>(reinterpret_cast<const float *>(p));
 }
 
 // ---- wave-level helpers ---------------------------------------------------------------------
@@ -185,8 +226,6 @@ __device__ __forceinline__ f32x4 mfma16_bf16(bf16x4_t a, bf16x4_t b, f32x4 acc) 
 // are the 16 of a 16x16x16 tile twice, with any pair of parts on the two halves.  Lane (c, g)
 // supplies the same four values per operand as for four mfma16 calls; three instructions of 16
 // cycles replace four of 32, and they leave the vector pipe free.
-typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 struct Split3 {
     u32x2_t h, m, l;        // four bf16 each, element j in the low / high half of word j / 2
@@ -380,19 +419,21 @@ template <int F> __device__ __forceinline__ int stage_col(int lane, int i) { ret
 // kFull: all 16 rows exist (the common case): no clamping.  `ts` is the distance between
 // consecutive tokens in elements: F when the sequence is contiguous ([B, H, N, F] tensors, the
 // tile is then one run of 16 * F elements), H * F for [B, N, H, F] tensors.
-template <int F, bool kFull, typename T>
-__device__ __forceinline__ void stage_load(const T *base, int ts, int nvalid, int lane, f32x4 (&st)[F / 16]) {
+// kNt: the call streams its tensors (see PassArgs::stream)
+template <int F, bool kFull, bool kNt, typename T>
+__device__ __forceinline__ void stage_load(const T *base, int ts, int nvalid, int lane, staged_t<T> (&st)[F / 16]) {
     const T *lane_base = base + (size_t)stage_row<F>(lane, 0) * ts + stage_col<F>(lane, 0);
 #pragma unroll
     for (int i = 0; i < F / 16; ++i) {
         if constexpr (kFull) {
-            st[i] = load4(lane_base + (size_t)(i * (256 / F)) * ts);
+            st[i] = load4_staged<kNt>(lane_base + (size_t)(i * (256 / F)) * ts);
         } else {
             const int row = min(stage_row<F>(lane, i), nvalid - 1);
-            st[i] = load4(base + (size_t)row * ts + stage_col<F>(lane, i));
+            st[i] = load4_staged<kNt>(base + (size_t)row * ts + stage_col<F>(lane, i));
         }
     }
 }
+
 
 // A 16 x 64 tile of phi(Q) or phi(K) for the degree-2 polynomial map: `base` points at the 8
 // raw values of the tile's first token, rows are `ts` elements apart.  The lane that stages
@@ -409,13 +450,13 @@ __device__ __forceinline__ void stage_load_poly2(const T *base, int ts, int nval
     }
 }
 // fetch of a Q or K tile: the plain tile, or the expanded one
-template <int F, bool kFull, typename T>
-__device__ __forceinline__ void stage_load_qk(const T *base, int ts, int nvalid, int lane, f32x4 (&st)[F / 16]) {
+template <int F, bool kFull, bool kNt, typename T>
+__device__ __forceinline__ void stage_load_qk(const T *base, int ts, int nvalid, int lane, staged_t<T> (&st)[F / 16]) {
     if constexpr (is_poly<T>) {
         static_assert(F == 64, "the degree-2 map of 8 raw values has 64 features");
         stage_load_poly2<kFull>(base, ts, nvalid, lane, st);
     } else {
-        stage_load<F, kFull>(base, ts, nvalid, lane, st);
+        stage_load<F, kFull, kNt>(base, ts, nvalid, lane, st);
     }
 }
 // the 8 raw values of token min(lane / 4, nvalid - 1) of the tile (for poly2_chain)

@@ -189,37 +189,36 @@ __global__ __launch_bounds__(256) void recurrent_steps_kernel(const T *q, const 
         zr[it] = zh[d];
     }
     constexpr int W = qk_width<T>(D);          // elements per token of q and k
-    auto fetch = [&](int t, float (&kq)[2][NIT], f32x4 &v4) {
-        const T *qh = q + ((size_t)t * BH + bh) * W, *kh = k + ((size_t)t * BH + bh) * W;
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) {
-            const int d = it * RPI + wave * RPW + rsub;
-            if constexpr (is_poly<T>) {      // the feature itself (x_i x_j): nothing is left to map
-                kq[0][it] = feature_of<T>(kh, d);
-                kq[1][it] = feature_of<T>(qh, d);
-            } else {
-                kq[0][it] = to_f32(kh[d]);
-                kq[1][it] = to_f32(qh[d]);
-            }
-        }
+    // The wave sweeps NR rows of S per step, and every lane of a row needs that row's feature of
+    // k and of q.  The feature map is evaluated once per row and wave, not once per lane: lane
+    // j < NR fetches and maps k's element of row j of the sweep, lane NR + j the same of q (the
+    // lanes above 2 NR repeat them, unused), and the lanes of a row pick the values up with a
+    // shuffle.  The values are those every lane computed for itself before, bit for bit.
+    constexpr int NR = NIT * RPW;
+    static_assert(2 * NR <= kWave, "one lane per row and operand");
+    const int j = lane % NR;
+    const bool mine_is_q = ((lane / NR) & 1) != 0;
+    const int dj = (j / RPW) * RPI + wave * RPW + (j % RPW);
+    auto fetch = [&](int t, float &x, f32x4 &v4) {
+        const T *row = (mine_is_q ? q : k) + ((size_t)t * BH + bh) * W;
+        if constexpr (is_poly<T>) x = feature_of<T>(row, dj);   // the feature itself (x_i x_j): nothing is left to map
+        else x = to_f32(row[dj]);
         v4 = load4(v + ((size_t)t * BH + bh) * M + col4);
     };
-    float kq_next[2][NIT];
+    float x_next;
     f32x4 v_next;
-    fetch(0, kq_next, v_next);
+    fetch(0, x_next, v_next);
     for (int t = 0; t < steps; ++t) {
-        float kq[2][NIT];
+        const float f = feature<T>(x_next);
         const f32x4 v4 = v_next;
-#pragma unroll
-        for (int it = 0; it < NIT; ++it) { kq[0][it] = kq_next[0][it]; kq[1][it] = kq_next[1][it]; }
-        if (t + 1 < steps) fetch(t + 1, kq_next, v_next);
+        if (t + 1 < steps) fetch(t + 1, x_next, v_next);
 
         f32x4 acc = {0.f, 0.f, 0.f, 0.f};
         float dpart = 0.f;
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            const float kd = feature<T>(kq[0][it]);
-            const float qd = feature<T>(kq[1][it]);
+            const float kd = __shfl(f, it * RPW + rsub);
+            const float qd = __shfl(f, NR + it * RPW + rsub);
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 s4[it][e] = fmaf(kd, v4[e], s4[it][e]);

@@ -129,6 +129,10 @@ struct PassArgs {
     // tok_heads = H = heads: [B, N, H, F], consecutive tokens of a sequence H * F elements
     // apart (kernels with kStrided = true).
     int heads, tok_heads;
+    // 1: the call moves more tensor bytes than the last-level cache holds, so the tiles are
+    // fetched with non-temporal loads (every element is touched once per kernel and need not
+    // stay); 0: a later kernel of the same step finds them in the cache (small shapes).
+    int stream;
 };
 
 // element offset of token 0 of sequence bh in a tensor of row width F, and the distance
@@ -198,17 +202,18 @@ constexpr bool bf16_products = is_bf16<T> && (PASS == kFwd || PASS == kGlobal);
 // of the sequence.  The parked values stay fp32 for every element type: a pass that multiplies
 // on the bf16 MFMA rounds them when it packs its operands.
 // kFeat (the caller has applied the feature map): phi becomes the identity, phi' becomes 1.
-template <int F, int MAP_, bool kFull, bool kFeat>
-__device__ __forceinline__ void park_tile(float *tile, const f32x4 (&st)[F / 16],
+template <int F, int MAP_, bool kFull, bool kFeat, typename ST>
+__device__ __forceinline__ void park_tile(float *tile, const ST (&st)[F / 16],
                                           const float (&scale)[F / 16], int nvalid, int lane) {
     constexpr int MAP = !kFeat ? MAP_ : MAP_ == kMapPhi ? kMapId : MAP_ == kMapDphi ? kMapOne : MAP_;
 #pragma unroll
     for (int i = 0; i < F / 16; ++i) {
         const int row = stage_row<F>(lane, i);
+        const f32x4 w = widen(st[i]);
         f32x4 v;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            const float m = map_value<MAP>(st[i][r], scale[i]);
+            const float m = map_value<MAP>(w[r], scale[i]);
             v[r] = (kFull || row < nvalid) ? m : 0.0f;
         }
         lds_store4(tile + row * tile_stride(F) + stage_col<F>(lane, i), v);
@@ -245,16 +250,17 @@ struct PassStager {
     const T *Xs, *Ys, *Zs, *Rs;
     float *lds_x, *lds_y, *lds_z, *lds_r;
     int N, lane;
+    bool nt;                            // non-temporal fetches (PassArgs::stream)
     int tsx, tsy, tsz, tsr;             // token strides of X, of K as Y, of V as Z, of K under the output
     static constexpr int kDepth = kDepth_;    // chunks in flight = sets of staging registers (1 or 2)
-    f32x4 sx[kDepth][XT], sy[kDepth][XT], sz[kDepth][ZT], sr[kDepth][ZT];
+    staged_t<T> sx[kDepth][XT], sy[kDepth][XT], sz[kDepth][ZT], sr[kDepth][ZT];
     float onex[XT], onez[ZT];
     float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
     float xraw[kPolyRaw], n_xraw[kDepth][kPolyRaw];   // polynomial map, kGlobalDk: raw K of token lane / 4
 
     __device__ __forceinline__ PassStager(const PassArgs &a, int bh, int lane_, float *lx,
                                           float *ly, float *lz, float *lr)
-        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_) {
+        : lds_x(lx), lds_y(ly), lds_z(lz), lds_r(lr), N(a.N), lane(lane_), nt(a.stream != 0) {
         constexpr int BP = Tr::BP;
         constexpr int wx = kXqk ? qk_width<T>(DX) : DX, wy = qk_width<T>(DX), wr = qk_width<T>(DZ);
         tsx = tok_stride<kStrided>(a.tok_heads, wx);
@@ -280,17 +286,17 @@ struct PassStager {
         }
     }
 
-    template <int SLOT, bool kFull>
+    template <int SLOT, bool kFull, bool kNt>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        if constexpr (kXqk) stage_load_qk<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx[SLOT]);
-        else stage_load<DX, kFull>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx[SLOT]);
+        if constexpr (kXqk) stage_load_qk<DX, kFull, kNt>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx[SLOT]);
+        else stage_load<DX, kFull, kNt>(Xs + (size_t)t0 * tsx, tsx, nvalid, lane, sx[SLOT]);
         if constexpr (Tr::kHasYZ) {
-            stage_load_qk<DX, kFull>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy[SLOT]);
-            stage_load<DZ, kFull>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz[SLOT]);
+            stage_load_qk<DX, kFull, kNt>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy[SLOT]);
+            stage_load<DZ, kFull, kNt>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz[SLOT]);
         }
         if constexpr (Tr::kHasRaw) {
             if constexpr (is_poly<T>) load_raw8(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, n_xraw[SLOT]);
-            else stage_load<DZ, kFull>(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, sr[SLOT]);
+            else stage_load<DZ, kFull, kNt>(Rs + (size_t)t0 * tsr, tsr, nvalid, lane, sr[SLOT]);
         }
     }
 
@@ -298,8 +304,13 @@ struct PassStager {
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);      // uniform branch
-        else fetch_impl<SLOT, false>(t0, nvalid);
+        if (nt) {                            // uniform branches
+            if (nvalid == kChunk) fetch_impl<SLOT, true, true>(t0, nvalid);
+            else fetch_impl<SLOT, false, true>(t0, nvalid);
+        } else {
+            if (nvalid == kChunk) fetch_impl<SLOT, true, false>(t0, nvalid);
+            else fetch_impl<SLOT, false, false>(t0, nvalid);
+        }
     }
 
     template <int SLOT, bool kFull>
@@ -338,8 +349,9 @@ struct ReverseStager {
     const float *rden, *delta;
     float *lds_a, *lds_a2, *lds_b;      // role 0: phi(Q), -, dO/den; role 1: phi(K), phi'(K), V
     int N, lane, g;
+    bool nt;                            // non-temporal fetches (PassArgs::stream)
     int tsd, tsm;                       // token strides of the D-wide and M-wide tensors
-    f32x4 sa[kDepth][DT], sb[kDepth][MT];
+    staged_t<T> sa[kDepth][DT], sb[kDepth][MT];
     float scd[DT], scb[kDepth][MT];
     float n_dl4[kDepth][4];
     float dl1, dl4[4];
@@ -347,7 +359,7 @@ struct ReverseStager {
 
     __device__ __forceinline__ ReverseStager(const PassArgs &a, int bh, int lane_, float *la,
                                              float *la2, float *lb)
-        : lds_a(la), lds_a2(la2), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4),
+        : lds_a(la), lds_a2(la2), lds_b(lb), N(a.N), lane(lane_), g(lane_ >> 4), nt(a.stream != 0),
           tsd(tok_stride<kStrided>(a.tok_heads, qk_width<T>(D))), tsm(tok_stride<kStrided>(a.tok_heads, M)) {
         const size_t rowbase = (size_t)bh * a.N;
         As = static_cast<const T *>(ROLE == 0 ? a.Q : a.K) + seq_base<kStrided>(a.N, a.heads, bh, qk_width<T>(D));
@@ -374,10 +386,10 @@ struct ReverseStager {
         }
     }
 
-    template <int SLOT, bool kFull>
+    template <int SLOT, bool kFull, bool kNt>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
-        stage_load_qk<D, kFull>(As + (size_t)t0 * tsd, tsd, nvalid, lane, sa[SLOT]);
-        stage_load<M, kFull>(Bs + (size_t)t0 * tsm, tsm, nvalid, lane, sb[SLOT]);
+        stage_load_qk<D, kFull, kNt>(As + (size_t)t0 * tsd, tsd, nvalid, lane, sa[SLOT]);
+        stage_load<M, kFull, kNt>(Bs + (size_t)t0 * tsm, tsm, nvalid, lane, sb[SLOT]);
         if constexpr (ROLE == 0) stage_rows<M, kFull>(rden + t0, nvalid, lane, scb[SLOT]);
         else rows4<kFull>(delta + t0, nvalid, g, n_dl4[SLOT]);
         if constexpr (ROLE == 1 && is_poly<T>) load_raw8(As + (size_t)t0 * tsd, tsd, nvalid, lane, n_xraw[SLOT]);
@@ -387,8 +399,13 @@ struct ReverseStager {
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);
-        else fetch_impl<SLOT, false>(t0, nvalid);
+        if (nt) {                            // uniform branches
+            if (nvalid == kChunk) fetch_impl<SLOT, true, true>(t0, nvalid);
+            else fetch_impl<SLOT, false, true>(t0, nvalid);
+        } else {
+            if (nvalid == kChunk) fetch_impl<SLOT, true, false>(t0, nvalid);
+            else fetch_impl<SLOT, false, false>(t0, nvalid);
+        }
     }
 
     template <int SLOT, bool kFull>
@@ -500,12 +517,12 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     for (int r = 0; r < 4; ++r)
                         U[xt][zt][r] += sm[(16 * xt + 4 * g + r) * M + 16 * zt + c];
                 } else {                      // U[m][d] = S[d][m], m = 16xt + 4g + r, d = 16zt + c
-                    U[xt][zt] += load4(sm + (16 * zt + c) * M + 16 * xt + 4 * g);
+                    U[xt][zt] += load4_state(sm + (16 * zt + c) * M + 16 * xt + 4 * g);
                 }
             }
         if constexpr (PASS == kFwd || PASS == kGlobal) {
 #pragma unroll
-            for (int xt = 0; xt < XT; ++xt) zg[xt] += load4(sv + 16 * xt + 4 * g);
+            for (int xt = 0; xt < XT; ++xt) zg[xt] += load4_state(sv + 16 * xt + 4 * g);
         }
         if constexpr (Tr::BP == kDq || Tr::BP == kDk) {
 #pragma unroll
@@ -1032,14 +1049,15 @@ struct GlobalBwdStager {
     const T *Kraw;                      // role 1, polynomial map: K again, for the raw vectors
     float *lds_a, *lds_a2;              // role 0: phi(K), phi'(K); role 1: V, -
     int N, lane;
+    bool nt;                            // non-temporal fetches (PassArgs::stream)
     int ts, tsk;
-    f32x4 st[kDepth][FT];
+    staged_t<T> st[kDepth][FT];
     float one[FT];
     float dl1, dl4[4];                  // unused by these passes (interface of run_pass)
     float xraw[kPolyRaw], n_xraw[kDepth][kPolyRaw];   // polynomial map, role 1: raw K of token lane / 4
 
     __device__ __forceinline__ GlobalBwdStager(const PassArgs &a, int bh, int lane_, float *la, float *la2)
-        : lds_a(la), lds_a2(la2), N(a.N), lane(lane_) {
+        : lds_a(la), lds_a2(la2), N(a.N), lane(lane_), nt(a.stream != 0) {
         constexpr int wk = qk_width<T>(D);
         tsk = tok_stride<kStrided>(a.tok_heads, wk);
         ts = ROLE == 0 ? tsk : tok_stride<kStrided>(a.tok_heads, M);
@@ -1058,12 +1076,12 @@ struct GlobalBwdStager {
         }
     }
 
-    template <int SLOT, bool kFull>
+    template <int SLOT, bool kFull, bool kNt>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
         if constexpr (ROLE == 0) {
-            stage_load_qk<D, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st[SLOT]);
+            stage_load_qk<D, kFull, kNt>(Src + (size_t)t0 * ts, ts, nvalid, lane, st[SLOT]);
         } else {
-            stage_load<M, kFull>(Src + (size_t)t0 * ts, ts, nvalid, lane, st[SLOT]);
+            stage_load<M, kFull, kNt>(Src + (size_t)t0 * ts, ts, nvalid, lane, st[SLOT]);
             if constexpr (is_poly<T>) load_raw8(Kraw + (size_t)t0 * tsk, tsk, nvalid, lane, n_xraw[SLOT]);
         }
     }
@@ -1071,8 +1089,13 @@ struct GlobalBwdStager {
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);      // uniform branch
-        else fetch_impl<SLOT, false>(t0, nvalid);
+        if (nt) {                            // uniform branches
+            if (nvalid == kChunk) fetch_impl<SLOT, true, true>(t0, nvalid);
+            else fetch_impl<SLOT, false, true>(t0, nvalid);
+        } else {
+            if (nvalid == kChunk) fetch_impl<SLOT, true, false>(t0, nvalid);
+            else fetch_impl<SLOT, false, false>(t0, nvalid);
+        }
     }
 
     template <int SLOT, bool kFull>
@@ -1131,7 +1154,8 @@ struct DqStager {
     const float *den;
     float *lds_a;                       // role 0: dO/den; role 1: phi(Q)
     int N, lane, g, ts;                 // ts: token stride of this role's tensor
-    f32x4 sa[kDepth][FT];
+    bool nt;                            // non-temporal fetches (PassArgs::stream)
+    staged_t<T> sa[kDepth][FT];
     float sca[kDepth][FT], one[FT];
     float n_den4[kDepth][4];
     float dl1, dl4[4];                  // unused by this pass (interface of run_pass)
@@ -1143,7 +1167,8 @@ struct DqStager {
     static constexpr int W = ROLE == 0 ? F : qk_width<T>(F);    // elements per token of this role's tensor
 
     __device__ __forceinline__ DqStager(const PassArgs &a, int bh, int lane_, float *la)
-        : lds_a(la), N(a.N), lane(lane_), g(lane_ >> 4), ts(tok_stride<kStrided>(a.tok_heads, W)) {
+        : lds_a(la), N(a.N), lane(lane_), g(lane_ >> 4), ts(tok_stride<kStrided>(a.tok_heads, W)),
+          nt(a.stream != 0) {
         const size_t rowbase = (size_t)bh * a.N;
         As = static_cast<const T *>(ROLE == 0 ? a.G : a.Q) + seq_base<kStrided>(a.N, a.heads, bh, W);
         tsq = tok_stride<kStrided>(a.tok_heads, qk_width<T>(D));
@@ -1170,12 +1195,12 @@ struct DqStager {
         }
     }
 
-    template <int SLOT, bool kFull>
+    template <int SLOT, bool kFull, bool kNt>
     __device__ __forceinline__ void fetch_impl(const int t0, const int nvalid) {
         if constexpr (ROLE == 1) {
-            stage_load_qk<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa[SLOT]);
+            stage_load_qk<F, kFull, kNt>(As + (size_t)t0 * ts, ts, nvalid, lane, sa[SLOT]);
         } else {
-            stage_load<F, kFull>(As + (size_t)t0 * ts, ts, nvalid, lane, sa[SLOT]);
+            stage_load<F, kFull, kNt>(As + (size_t)t0 * ts, ts, nvalid, lane, sa[SLOT]);
             if constexpr (is_poly<T>) load_raw8(Qraw + (size_t)t0 * tsq, tsq, nvalid, lane, n_xraw[SLOT]);
             stage_rows<F, kFull>(den + t0, nvalid, lane, sca[SLOT]);      // den of the staged rows
 #pragma unroll
@@ -1188,8 +1213,13 @@ struct DqStager {
     __device__ __forceinline__ void fetch(const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, N - t0);
-        if (nvalid == kChunk) fetch_impl<SLOT, true>(t0, nvalid);
-        else fetch_impl<SLOT, false>(t0, nvalid);
+        if (nt) {                            // uniform branches
+            if (nvalid == kChunk) fetch_impl<SLOT, true, true>(t0, nvalid);
+            else fetch_impl<SLOT, false, true>(t0, nvalid);
+        } else {
+            if (nvalid == kChunk) fetch_impl<SLOT, true, false>(t0, nvalid);
+            else fetch_impl<SLOT, false, false>(t0, nvalid);
+        }
     }
 
     template <int SLOT, bool kFull>
@@ -1362,6 +1392,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
     float *lds_chain = lds_a0_mem;
     const int lane = threadIdx.x & (kWave - 1), c = lane & 15, g = lane >> 4;
     const int role = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform
+    const bool nt = a.stream != 0;                                       // non-temporal fetches
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
     const int ch_begin = seg * a.chunks_per_seg;
@@ -1383,7 +1414,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         const T *Ks = static_cast<const T *>(a.K) + seq_base<kStrided>(a.N, a.heads, bh, W);
         T *outs = static_cast<T *>(a.out) + seq_base<kStrided>(a.N, a.heads, bh, W);
         const float *den = a.den_in + rowbase;
-        f32x4 sq[DT], sk[DT];
+        staged_t<T> sq[DT], sk[DT];
         float one[DT], nden[4], rd4[4];
         float xraw[kPolyRaw], n_xraw[kPolyRaw];    // polynomial map: raw Q of token lane / 4
 #pragma unroll
@@ -1407,15 +1438,20 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         const u32x2_t mk = {((4 * g + 0) <= c ? 0x3f80u : 0u) | ((4 * g + 1) <= c ? 0x3f800000u : 0u),
                             ((4 * g + 2) <= c ? 0x3f80u : 0u) | ((4 * g + 3) <= c ? 0x3f800000u : 0u)};
 
+        auto fetch_tiles = [&](auto full_tag, auto nt_tag, const int t0, const int nvalid) {
+            constexpr bool kFull = decltype(full_tag)::value, kNt = decltype(nt_tag)::value;
+            stage_load_qk<D, kFull, kNt>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
+            stage_load_qk<D, kFull, kNt>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
+        };
         auto fetch = [&](const int ch) {
             const int t0 = ch * kChunk;
             const int nvalid = min(kChunk, a.N - t0);
-            if (nvalid == kChunk) {
-                stage_load_qk<D, true>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
-                stage_load_qk<D, true>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
+            if (nt) {                        // uniform branches
+                if (nvalid == kChunk) fetch_tiles(std::true_type{}, std::true_type{}, t0, nvalid);
+                else fetch_tiles(std::false_type{}, std::true_type{}, t0, nvalid);
             } else {
-                stage_load_qk<D, false>(Qs + (size_t)t0 * ts, ts, nvalid, lane, sq);
-                stage_load_qk<D, false>(Ks + (size_t)t0 * ts, ts, nvalid, lane, sk);
+                if (nvalid == kChunk) fetch_tiles(std::true_type{}, std::false_type{}, t0, nvalid);
+                else fetch_tiles(std::false_type{}, std::false_type{}, t0, nvalid);
             }
             if constexpr (is_poly<T>) load_raw8(Qs + (size_t)t0 * ts, ts, nvalid, lane, n_xraw);
 #pragma unroll
@@ -1563,7 +1599,7 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
         const T *Vs = static_cast<const T *>(a.V) + seq_base<kStrided>(a.N, a.heads, bh, M);
         const float *den = a.den_in + rowbase;
         const bool want = a.totals != nullptr;         // uniform
-        f32x4 sg[MT], sv[MT];
+        staged_t<T> sg[MT], sv[MT];
         float sca[MT], one[MT];
         f32x4 U[MT][DT];      // S^T: element (m = 16xt + 4g + r, d = 16zt + c)
         f32x4 R[DT][MT];      // this segment's phi(Q)^T dO/den: element (d = 16xt + 4g + r, m = 16zt + c)
@@ -1577,21 +1613,25 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
 #pragma unroll
             for (int xt = 0; xt < MT; ++xt)
 #pragma unroll
-                for (int zt = 0; zt < DT; ++zt) U[xt][zt] += load4(sm + (16 * zt + c) * M + 16 * xt + 4 * g);
+                for (int zt = 0; zt < DT; ++zt) U[xt][zt] += load4_state(sm + (16 * zt + c) * M + 16 * xt + 4 * g);
         };
         if (a.init_S != nullptr) add_state(a.init_S + (size_t)bh * D * M);
         for (int j = slot_lo; j < slot_hi; ++j) add_state(slots + (size_t)j * state_stride(D, M));
+        auto fetch_tiles = [&](auto full_tag, auto nt_tag, const int t0, const int nvalid) {
+            constexpr bool kFull = decltype(full_tag)::value, kNt = decltype(nt_tag)::value;
+            stage_load<M, kFull, kNt>(Gs + (size_t)t0 * ts, ts, nvalid, lane, sg);
+            stage_load<M, kFull, kNt>(Vs + (size_t)t0 * ts, ts, nvalid, lane, sv);
+            stage_rows<M, kFull>(den + t0, nvalid, lane, sca);
+        };
         auto fetch = [&](const int ch) {
             const int t0 = ch * kChunk;
             const int nvalid = min(kChunk, a.N - t0);
-            if (nvalid == kChunk) {
-                stage_load<M, true>(Gs + (size_t)t0 * ts, ts, nvalid, lane, sg);
-                stage_load<M, true>(Vs + (size_t)t0 * ts, ts, nvalid, lane, sv);
-                stage_rows<M, true>(den + t0, nvalid, lane, sca);
+            if (nt) {                        // uniform branches
+                if (nvalid == kChunk) fetch_tiles(std::true_type{}, std::true_type{}, t0, nvalid);
+                else fetch_tiles(std::false_type{}, std::true_type{}, t0, nvalid);
             } else {
-                stage_load<M, false>(Gs + (size_t)t0 * ts, ts, nvalid, lane, sg);
-                stage_load<M, false>(Vs + (size_t)t0 * ts, ts, nvalid, lane, sv);
-                stage_rows<M, false>(den + t0, nvalid, lane, sca);
+                if (nvalid == kChunk) fetch_tiles(std::true_type{}, std::false_type{}, t0, nvalid);
+                else fetch_tiles(std::false_type{}, std::false_type{}, t0, nvalid);
             }
         };
         auto park = [&](const int ch, const int buf) {
@@ -1710,6 +1750,7 @@ struct SegArgs {
     int N, nseg, chunks_per_seg;
     int skip_seg;         // segment whose total nobody reads (-1: none)
     int heads, tok_heads; // layout of K and V, as in PassArgs
+    int stream;           // as in PassArgs
 };
 
 template <int D, int M, typename T, bool kStrided = false>
@@ -1723,6 +1764,7 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
     __shared__ float lds_y[tile_floats(D)];
     __shared__ float lds_z[tile_floats(M)];
     const int lane = threadIdx.x, c = lane & 15, g = lane >> 4;
+    const bool nt = a.stream != 0;        // non-temporal fetches
     const int seg = blockIdx.x % a.nseg, bh = blockIdx.x / a.nseg;
     if (seg == a.skip_seg) return;
     const int nchunks = (a.N + kChunk - 1) / kChunk;
@@ -1741,22 +1783,27 @@ __global__ __launch_bounds__(kWave) void segment_state_kernel(const SegArgs a) {
         for (int zt = 0; zt < ZT; ++zt) U[xt][zt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
 
-    f32x4 sy[XT], sz[ZT];
+    staged_t<T> sy[XT], sz[ZT];
     float oney[XT], onez[ZT];
 #pragma unroll
     for (int i = 0; i < XT; ++i) oney[i] = 1.0f;
 #pragma unroll
     for (int i = 0; i < ZT; ++i) onez[i] = 1.0f;
 
+    auto fetch_tiles = [&](auto full_tag, auto nt_tag, const int t0, const int nvalid) {
+        constexpr bool kFull = decltype(full_tag)::value, kNt = decltype(nt_tag)::value;
+        stage_load_qk<D, kFull, kNt>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
+        stage_load<M, kFull, kNt>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
+    };
     auto fetch = [&](const int ch) {
         const int t0 = ch * kChunk;
         const int nvalid = min(kChunk, a.N - t0);
-        if (nvalid == kChunk) {
-            stage_load_qk<D, true>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
-            stage_load<M, true>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
+        if (nt) {                            // uniform branches
+            if (nvalid == kChunk) fetch_tiles(std::true_type{}, std::true_type{}, t0, nvalid);
+            else fetch_tiles(std::false_type{}, std::true_type{}, t0, nvalid);
         } else {
-            stage_load_qk<D, false>(Ys + (size_t)t0 * tsy, tsy, nvalid, lane, sy);
-            stage_load<M, false>(Zs + (size_t)t0 * tsz, tsz, nvalid, lane, sz);
+            if (nvalid == kChunk) fetch_tiles(std::true_type{}, std::false_type{}, t0, nvalid);
+            else fetch_tiles(std::false_type{}, std::false_type{}, t0, nvalid);
         }
     };
 
