@@ -63,23 +63,24 @@
  *              guarantee: the causal forward's outputs and denominators before
  *              token t do not depend on what Q, K, V hold from token t on,
  *              finite or not (the causal mask of eq. 8).
- *   Threads    No global mutable state (la_causal_fwd_noalloc's built-in scratch
- *              array aside); calls from several host threads are safe as long as
- *              they do not share output or workspace buffers.
- *   Tuning     Five environment variables, read at every call, override the
- *              schedule (for tests and experiments): LA_TARGET_WAVES
- *              (default 2048: wavefronts wanted in flight), LA_MIN_SEG_CHUNKS
- *              (default 2: shortest segment, in 16-token chunks),
- *              LA_FOLD_MAX_SEGS (default 8: up to this many segments per
- *              sequence the passes add up the segment totals themselves and no
- *              scan kernel runs), LA_BWD_SEG_GROUP (1 or 2: how many of the
- *              forward's segments a workgroup of the backward takes; default 1
- *              for 32 x 32 heads, else 2) and LA_STREAM_LOADS (0 or 1: plain or
- *              non-temporal loads of the tensors; default by size: non-temporal
- *              once Q, K, V, dO together pass 192 MB).  Sequences are not cut at
- *              all once B*H reaches half of LA_TARGET_WAVES.  The workspace
- *              query, a forward and the backward that is handed its workspace
- *              must see the same values of the first three.
+ *   Threads    No global mutable state apart from the tuning values below and
+ *              la_causal_fwd_noalloc's built-in scratch array; calls from
+ *              several host threads are safe as long as they do not share
+ *              output or workspace buffers.
+ *   Tuning     Five environment variables override the schedule (for tests and
+ *              experiments): LA_TARGET_WAVES (default 2048: wavefronts wanted
+ *              in flight), LA_MIN_SEG_CHUNKS (default 2: shortest segment, in
+ *              16-token chunks), LA_FOLD_MAX_SEGS (default 8: up to this many
+ *              segments per sequence the passes add up the segment totals
+ *              themselves and no scan kernel runs), LA_BWD_SEG_GROUP (1 or 2:
+ *              how many of the forward's segments a workgroup of the backward
+ *              takes; default 1 for 32 x 32 heads, else 2) and LA_STREAM_LOADS
+ *              (1: non-temporal instead of plain loads of the tensors).
+ *              Sequences are not cut at all once B*H reaches half of
+ *              LA_TARGET_WAVES.  The environment is read once per process, by
+ *              the first workspace query or entry point, so a query and the
+ *              calls that use its workspace see the same values;
+ *              la_tuning_reload() reads it again.
  */
 #ifndef LA_H_
 #define LA_H_
@@ -115,6 +116,14 @@ const char *la_status_string(int status);
 
 /* Library version, major * 10000 + minor * 100 + patch. */
 int la_version(void);
+
+/*
+ * Reads the tuning variables of the environment again (see "Tuning" above).
+ * For tests and experiments that change them inside a process.  Not to be
+ * called while another thread is inside an entry point or between a workspace
+ * query and the calls that rely on it.
+ */
+void la_tuning_reload(void);
 
 /*
  * Workspace queries.  Host-only, no GPU call.  Return the number of bytes the

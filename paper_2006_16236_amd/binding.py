@@ -25,7 +25,7 @@ EXPORTS = ("la_status_string", "la_version", "la_causal_fwd_workspace", "la_caus
            "la_causal_fwd_state_bnhd", "la_causal_bwd_state_bnhd", "la_profile_create", "la_profile_destroy",
            "la_global_fwd", "la_global_bwd", "la_global_fwd_bnhd", "la_global_bwd_bnhd",
            "la_recurrent_step", "la_recurrent_steps", "la_causal_fwd_noalloc", "la_kernel_name", "la_profile_begin",
-           "la_profile_end")
+           "la_profile_end", "la_tuning_reload")
 LA_K_COUNT = 8
 
 
@@ -49,6 +49,8 @@ def _load() -> ctypes.CDLL:
     lib.la_status_string.restype = ctypes.c_char_p
     lib.la_status_string.argtypes = [i]
     lib.la_version.restype = i
+    lib.la_tuning_reload.restype = None
+    lib.la_tuning_reload.argtypes = []
     for name in ("la_causal_fwd_workspace", "la_causal_bwd_workspace", "la_global_fwd_workspace",
                  "la_global_bwd_workspace"):
         fn = getattr(lib, name)
@@ -106,6 +108,11 @@ def status_string(status: int) -> str:
 
 def la_version() -> int:
     return int(_lib.la_version())
+
+
+def la_tuning_reload() -> None:
+    """Have the library read its LA_* tuning variables from the environment again."""
+    _lib.la_tuning_reload()
 
 
 def _dtype_code(t: torch.Tensor, features=False) -> int:

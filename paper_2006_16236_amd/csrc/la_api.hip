@@ -14,7 +14,7 @@
 
 namespace {
 
-constexpr int kVersion = 400;   // 0.4.0
+constexpr int kVersion = 401;   // 0.4.1
 
 // ---- schedule ---------------------------------------------------------------------------------
 // One wavefront (forward) or one two-wave workgroup (backward) walks one segment of one
@@ -34,9 +34,45 @@ int env_int(const char *name, int dflt) {
     return v > 0 && v < (1 << 24) ? (int)v : dflt;
 }
 
+// The schedule's knobs.  The environment is read once, at the first call that needs a value (and
+// again only on la_tuning_reload): a workspace query and the calls that use the workspace then see
+// the same values, and no entry point calls getenv while another thread changes the environment.
+struct Tuning {
+    int target_waves;   // LA_TARGET_WAVES
+    int min_chunks;     // LA_MIN_SEG_CHUNKS
+    int fold_max;       // LA_FOLD_MAX_SEGS
+    int bwd_group;      // LA_BWD_SEG_GROUP, 0 = by head size
+    int stream;         // LA_STREAM_LOADS: 0, 1, or -1 = by tensor size
+};
+
+std::mutex g_tuning_mu;
+Tuning g_tuning;
+bool g_tuning_read = false;
+
+Tuning read_tuning() {
+    Tuning t;
+    t.target_waves = env_int("LA_TARGET_WAVES", 2048);
+    t.min_chunks = env_int("LA_MIN_SEG_CHUNKS", 2);
+    t.fold_max = env_int("LA_FOLD_MAX_SEGS", 8);
+    t.bwd_group = env_int("LA_BWD_SEG_GROUP", 0);
+    const char *s = getenv("LA_STREAM_LOADS");
+    t.stream = (s != nullptr && (s[0] == '0' || s[0] == '1') && s[1] == '\0') ? s[0] - '0' : -1;
+    return t;
+}
+
+Tuning tuning() {
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    if (!g_tuning_read) {
+        g_tuning = read_tuning();
+        g_tuning_read = true;
+    }
+    return g_tuning;
+}
+
 Plan make_plan(long BH, int N) {
-    const int target_waves = env_int("LA_TARGET_WAVES", 2048);
-    const int min_chunks = env_int("LA_MIN_SEG_CHUNKS", 2);
+    const Tuning tn = tuning();
+    const int target_waves = tn.target_waves;
+    const int min_chunks = tn.min_chunks;
     Plan p;
     p.nchunks = (N + la::kChunk - 1) / la::kChunk;
     long want = (target_waves + BH - 1) / BH;
@@ -48,7 +84,7 @@ Plan make_plan(long BH, int N) {
     if (2 * BH >= target_waves) nseg = 1;
     p.cps = (int)((p.nchunks + nseg - 1) / nseg);
     p.nseg = (p.nchunks + p.cps - 1) / p.cps;
-    p.fold = p.nseg > 1 && p.nseg <= env_int("LA_FOLD_MAX_SEGS", 8);
+    p.fold = p.nseg > 1 && p.nseg <= tn.fold_max;
     return p;
 }
 
@@ -57,21 +93,20 @@ Plan make_plan(long BH, int N) {
 // two waves fill a SIMD, half as many workgroups fill the machine, and taking the segments in
 // pairs is 10 % faster.  At D = M = 32 four waves fit a SIMD and the finer cut wins.
 int backward_group(int C, int M) {
-    const int dflt = (C == 32 && M == 32) ? 1 : 2;
-    const int g = env_int("LA_BWD_SEG_GROUP", dflt);
+    const int g = tuning().bwd_group;
+    if (g == 0) return (C == 32 && M == 32) ? 1 : 2;
     return g == 1 ? 1 : 2;
 }
 
 // Whether a call fetches its tiles with non-temporal loads.  A step sweeps Q, K, V (and dO) several
 // times, one kernel after the other.  Where those tensors fit the last-level cache (256 MB) the
-// later sweeps find them there if the loads are plain (measured: MNIST / CIFAR shapes 12 % and 8 %
-// faster); where they do not, non-temporal loads are the faster ones (N = 65536: 1.2 %, the
-// segment sums alone 20 %).  The measure is the four tensors the backward reads twice.
-int stream_loads(size_t rows, int D, int M, size_t esize) {
-    const int forced = env_int("LA_STREAM_LOADS", -1);
-    if (forced == 0 || forced == 1) return forced;
-    const size_t four = rows * (size_t)(2 * D + 2 * M) * esize;
-    return four > ((size_t)192 << 20) ? 1 : 0;
+// later sweeps find them there if the loads are plain (measured: MNIST / CIFAR shapes 2 % and 9 %
+// faster than with non-temporal loads); where they do not, the two kinds are equally fast for fp32
+// tensors and plain loads 1.5 % faster for bf16 ones (N = 65536).  So plain loads are the default
+// and LA_STREAM_LOADS=1 is there for measuring.  (The outputs are always stored non-temporally and
+// the segment states always loaded plain.)
+int stream_loads() {
+    return tuning().stream == 1 ? 1 : 0;
 }
 
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -226,7 +261,7 @@ int run_causal_fwd(const void *Q, const void *K, const void *V, void *O, float *
                    hipStream_t s, const float *S0 = nullptr, const float *z0 = nullptr,
                    float *S1 = nullptr, float *z1 = nullptr, int heads = 0, int tok_heads = 0) {
     const int nblocks = (int)(BH * p.nseg);
-    const int nt_loads = stream_loads((size_t)BH * N, D, M, esize(t));
+    const int nt_loads = stream_loads();
     if (p.nseg > 1) {
         la::SegArgs sa{};
         sa.stream = nt_loads;
@@ -254,7 +289,7 @@ int run_global_fwd(const void *Q, const void *K, const void *V, void *O, float *
                    int N, int D, int M, float eps, la_dtype t, const Plan &p, float *states,
                    hipStream_t s, int heads = 0, int tok_heads = 0) {
     const int nblocks = (int)(BH * p.nseg);
-    const int nt_loads = stream_loads((size_t)BH * N, D, M, esize(t));
+    const int nt_loads = stream_loads();
     la::SegArgs sa{};
     sa.stream = nt_loads;
     sa.heads = heads; sa.tok_heads = tok_heads;
@@ -291,6 +326,13 @@ const char *la_status_string(int status) {
 }
 
 int la_version(void) { return kVersion; }
+
+void la_tuning_reload(void) {
+    const Tuning t = read_tuning();
+    std::lock_guard<std::mutex> lock(g_tuning_mu);
+    g_tuning = t;
+    g_tuning_read = true;
+}
 
 size_t la_causal_fwd_workspace(int B, int H, int N, int D, int M, la_dtype t) {
     if (check_dims(B, H, N, D, M, 0.0f, t) != LA_OK) return 0;
@@ -470,7 +512,7 @@ static int causal_bwd_impl(const void *Q, const void *K, const void *V, const fl
                             {dz1, zb}, {fwd_ws, p.nseg > 1 ? states_bytes(BH, p, C, M) : 0}};
         if (aliased(outs, ins)) return LA_ERR_ALIAS;
     }
-    const int nt_loads = stream_loads(rows, C, M, esize(t));
+    const int nt_loads = stream_loads();
     Carver cv{static_cast<char *>(ws), 0};
     float *rden = static_cast<float *>(cv.take(rows * sizeof(float)));
     float *delta = static_cast<float *>(cv.take(rows * sizeof(float)));
@@ -637,7 +679,7 @@ static int global_bwd_impl(const void *Q, const void *K, const void *V, const vo
                             {dO, rows * M * e}, {den, rows * 4}, {fwd_ws, states_bytes(BH, p, C, M)}};
         if (aliased(outs, ins)) return LA_ERR_ALIAS;
     }
-    const int nt_loads = stream_loads(rows, C, M, esize(t));
+    const int nt_loads = stream_loads();
     Carver cv{static_cast<char *>(ws), 0};
     float *stS = static_cast<float *>(cv.take(states_bytes(BH, p, C, M)));
     float *stR = static_cast<float *>(cv.take(states_bytes(BH, p, C, M)));

@@ -129,9 +129,9 @@ struct PassArgs {
     // tok_heads = H = heads: [B, N, H, F], consecutive tokens of a sequence H * F elements
     // apart (kernels with kStrided = true).
     int heads, tok_heads;
-    // 1: the call moves more tensor bytes than the last-level cache holds, so the tiles are
-    // fetched with non-temporal loads (every element is touched once per kernel and need not
-    // stay); 0: a later kernel of the same step finds them in the cache (small shapes).
+    // 1: the tiles are fetched with non-temporal loads (every element is touched once per kernel
+    // and need not stay in the caches); 0, the host's default: plain loads, so that a later kernel
+    // of the same step finds in the last-level cache what fits there.
     int stream;
 };
 

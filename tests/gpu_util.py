@@ -6,6 +6,7 @@ import os
 import numpy as np
 import torch
 
+import paper_2006_16236_amd as la
 import workloads as wl
 
 DEV = "cuda:0"
@@ -69,10 +70,13 @@ def to_host(t):
 
 
 @contextlib.contextmanager
-def schedule(target_waves=None, min_seg_chunks=None, fold_max_segs=None, bwd_seg_group=None):
-    """Force the segment schedule of the library through its environment knobs."""
+def schedule(target_waves=None, min_seg_chunks=None, fold_max_segs=None, bwd_seg_group=None,
+             stream_loads=None):
+    """Force the segment schedule (and the kind of loads) of the library through its environment
+    knobs."""
     keys = {"LA_TARGET_WAVES": target_waves, "LA_MIN_SEG_CHUNKS": min_seg_chunks,
-            "LA_FOLD_MAX_SEGS": fold_max_segs, "LA_BWD_SEG_GROUP": bwd_seg_group}
+            "LA_FOLD_MAX_SEGS": fold_max_segs, "LA_BWD_SEG_GROUP": bwd_seg_group,
+            "LA_STREAM_LOADS": stream_loads}
     old = {k: os.environ.get(k) for k in keys}
     try:
         for k, v in keys.items():
@@ -80,6 +84,7 @@ def schedule(target_waves=None, min_seg_chunks=None, fold_max_segs=None, bwd_seg
                 os.environ.pop(k, None)
             else:
                 os.environ[k] = str(v)
+        la.la_tuning_reload()
         yield
     finally:
         for k, v in old.items():
@@ -87,6 +92,7 @@ def schedule(target_waves=None, min_seg_chunks=None, fold_max_segs=None, bwd_seg
                 os.environ.pop(k, None)
             else:
                 os.environ[k] = v
+        la.la_tuning_reload()
 
 
 SCHEDULES = {

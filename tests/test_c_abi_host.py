@@ -192,11 +192,19 @@ def test_aliasing_is_refused(lib):
 
 def test_schedule_knobs_change_the_workspace(lib, monkeypatch):
     from paper_2006_16236_amd import binding as b
-    monkeypatch.setenv("LA_TARGET_WAVES", "1")
-    assert b.la_causal_fwd_workspace(1, 1, 4096, 64, 64) == 0
-    monkeypatch.setenv("LA_TARGET_WAVES", str(1 << 20))
-    monkeypatch.setenv("LA_MIN_SEG_CHUNKS", "1")
-    assert b.la_causal_fwd_workspace(1, 1, 4096, 64, 64) == 256 * (64 * 64 + 64) * 4
+    try:
+        monkeypatch.setenv("LA_TARGET_WAVES", "1")
+        b.la_tuning_reload()
+        assert b.la_causal_fwd_workspace(1, 1, 4096, 64, 64) == 0
+        monkeypatch.setenv("LA_TARGET_WAVES", str(1 << 20))
+        monkeypatch.setenv("LA_MIN_SEG_CHUNKS", "1")
+        # the environment is read once: without a reload the query still answers for the old values
+        assert b.la_causal_fwd_workspace(1, 1, 4096, 64, 64) == 0
+        b.la_tuning_reload()
+        assert b.la_causal_fwd_workspace(1, 1, 4096, 64, 64) == 256 * (64 * 64 + 64) * 4
+    finally:
+        monkeypatch.undo()
+        b.la_tuning_reload()
 
 
 def test_binding_refuses_host_tensors(lib):

@@ -423,6 +423,34 @@ def test_backward_takes_segments_singly_or_in_pairs(la, oracle, D, M, group, cut
     assert max(grad_errs([to_host(x) for x in ggot], gref)) <= tol_for(N)
 
 
+@pytest.mark.parametrize("bf16", [False, True])
+@pytest.mark.parametrize("D,M", [(32, 32), (64, 64)])
+def test_non_temporal_loads_change_no_bit(la, oracle, D, M, bf16):
+    """LA_STREAM_LOADS=1 makes every kernel fetch its tiles with non-temporal loads (plain loads
+    are the default): the same values arrive, so causal and non-causal forward and backward must
+    come out bit for bit the same, and equal to the oracle's within the gate; ragged length,
+    several segments per sequence."""
+    B, H, N = 2, 2, 1000
+    host = maybe_bf16(wl.random_case(7100 + D, B, H, N, D, M, scale=0.5 if bf16 else 1.0), bf16)
+    Q, K, V, G = host
+    ref_o = oracle.causal_fwd_prefix(Q, K, V, 1e-6)
+    ref_g = oracle.causal_bwd_linear(Q, K, V, G, 1e-6)
+    gref = oracle.global_bwd_linear(Q, K, V, G, 1e-6)
+    res = []
+    for nt in (0, 1):
+        with schedule(target_waves=1 << 20, min_seg_chunks=3, stream_loads=nt):
+            O, den = run_fwd(la, Q, K, V, 1e-6, bf16=bf16)
+            grads = run_bwd(la, Q, K, V, G, 1e-6, bf16=bf16)
+            Og, deng, ggrads = run_global(la, Q, K, V, G, 1e-6, bf16=bf16)
+        res.append([O, den, *grads, Og, deng, *ggrads])
+    for a, b in zip(*res):
+        assert np.array_equal(a, b)
+    O, den, gq, gk, gv, Og, deng, hq, hk, hv = res[1]
+    assert rel_err(O, ref_o) <= tol_for(N, bf16)
+    assert max(grad_errs((gq, gk, gv), ref_g)) <= tol_for(N, bf16)
+    assert max(grad_errs((hq, hk, hv), gref)) <= tol_for(N, bf16)
+
+
 def _state_case(seed, B, H, N, D, M):
     """Inputs plus a non-zero initial state and a non-zero gradient arriving at the final state
     (the state is that of P imaginary earlier tokens: positive z0, S0 of matching size)."""
