@@ -270,12 +270,14 @@ __device__ __forceinline__ bf16x8_t cat_parts(u32x2_t lo, u32x2_t hi) {
 }
 // The operand pairs of the two sides of a product, built once per operand quad and reused over
 // the other side's tiles.  Each side keeps its parts in one run of registers and the instructions
-// take overlapping windows of it.
-//   P = 3 (fp32 accuracy): side A holds [l h m] (windows l|h and h|m), side B holds [h m h l]
-//         (windows h|m, m|h and h|l): lh + hl, hh + mm, hm + mh are the six products.
+// take windows of it.  (The compiler gives every window registers of its own, so each part that
+// sits in two windows costs a copy: the layouts below have one such part per run.)
+//   P = 3 (fp32 accuracy): both sides hold [l h m] (windows l|h and h|m): A(l|h) B(h|m) is
+//         lh + hm, A(h|m) B(l|h) is hl + mh, A(h|m) B(h|m) is hh + mm: the six products.
 //   P = 2 (x ~ h + m, 16 significant bits, for bf16 tensors whose results are rounded to 8):
 //         side A holds [h m], side B holds [h h m 0] (windows h|h, h|m, m|0): hh + mh and hm
-//         are the three products, two instructions.
+//         are the three products, two instructions.  (Measured: [h m h] with windows h|m and
+//         m|h, which adds the product mm, makes the bf16 dV + dK kernel 3 % slower.)
 typedef unsigned u32x6_t __attribute__((ext_vector_type(6)));
 typedef unsigned u32x8_t __attribute__((ext_vector_type(8)));
 template <int P> struct SplitA;
@@ -290,10 +292,9 @@ template <> struct SplitA<3> {
     LA_WINDOW(hm, v, 2)
 };
 template <> struct SplitB<3> {
-    u32x8_t v;
-    LA_WINDOW(hm, v, 0)
-    LA_WINDOW(mh, v, 2)
-    LA_WINDOW(hl, v, 4)
+    u32x6_t v;
+    LA_WINDOW(lh, v, 0)
+    LA_WINDOW(hm, v, 2)
 };
 template <> struct SplitA<2> {
     u32x4_t v;
@@ -339,7 +340,7 @@ template <int P> __device__ __forceinline__ SplitA<P> split_a(const float (&x)[4
 template <int P> __device__ __forceinline__ SplitB<P> split_b(const float (&x)[4]) {
     if constexpr (P == 3) {
         const Split3 s = split3(x);
-        return SplitB<3>{u32x8_t{s.h[0], s.h[1], s.m[0], s.m[1], s.h[0], s.h[1], s.l[0], s.l[1]}};
+        return SplitB<3>{u32x6_t{s.l[0], s.l[1], s.h[0], s.h[1], s.m[0], s.m[1]}};
     } else {
         return as_b(split2(x));
     }
@@ -353,8 +354,8 @@ __device__ __forceinline__ f32x4 mfma32_bf16(bf16x8_t a, bf16x8_t b, f32x4 acc) 
 }
 // acc + sum over the four contraction steps of a * b: the small terms first
 __device__ __forceinline__ f32x4 mfma16_split(const SplitA<3> &a, const SplitB<3> &b, f32x4 acc) {
-    acc = mfma32_bf16(a.lh(), b.hl(), acc);    // lh + hl
-    acc = mfma32_bf16(a.hm(), b.mh(), acc);    // hm + mh
+    acc = mfma32_bf16(a.lh(), b.hm(), acc);    // lh + hm
+    acc = mfma32_bf16(a.hm(), b.lh(), acc);    // hl + mh
     acc = mfma32_bf16(a.hm(), b.hm(), acc);    // hh + mm
     return acc;
 }
@@ -364,10 +365,10 @@ __device__ __forceinline__ f32x4 mfma16_split(const SplitA<2> &a, const SplitB<2
     return acc;
 }
 // the same product with the sides exchanged: `x` (kept in side-B form) is the first operand of
-// the MFMA, `u` (kept in the narrower side-A form) the second
+// the MFMA, `u` (kept in side-A form) the second
 __device__ __forceinline__ f32x4 mfma16_split_ba(const SplitB<3> &x, const SplitA<3> &u, f32x4 acc) {
-    acc = mfma32_bf16(x.hl(), u.lh(), acc);    // hl + lh
-    acc = mfma32_bf16(x.mh(), u.hm(), acc);    // mh + hm
+    acc = mfma32_bf16(x.lh(), u.hm(), acc);    // lh + hm
+    acc = mfma32_bf16(x.hm(), u.lh(), acc);    // hl + mh
     acc = mfma32_bf16(x.hm(), u.hm(), acc);    // hh + mm
     return acc;
 }
@@ -382,8 +383,8 @@ template <int P> __device__ __forceinline__ SplitA<P> split_a(f32x4 x) {
 }
 // acc + mask * b for a mask of zeros and ones (exact in bf16), four bf16 per lane in `mk`
 __device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB<3> &b, f32x4 acc) {
-    acc = mfma32_bf16(cat_parts(mk, mk), b.hl(), acc);                  // mask (h + l)
-    acc = mfma32_bf16(cat_parts(mk, u32x2_t{0u, 0u}), b.mh(), acc);     // mask m
+    acc = mfma32_bf16(cat_parts(mk, mk), b.lh(), acc);                  // mask (l + h)
+    acc = mfma32_bf16(cat_parts(u32x2_t{0u, 0u}, mk), b.hm(), acc);     // mask m
     return acc;
 }
 __device__ __forceinline__ f32x4 mfma16_mask(u32x2_t mk, const SplitB<2> &b, f32x4 acc) {
