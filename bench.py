@@ -62,7 +62,7 @@ def measured_traffic_bytes(path: str = TRAFFIC_SUMMARY) -> dict:
         for name, key in TRAFFIC_ROW.items():
             if key in cells[0] and name not in out:
                 try:
-                    out[name] = (float(cells[3]) + float(cells[4])) * 1e6
+                    out[name] = float(round((float(cells[3]) + float(cells[4])) * 1e6))
                 except ValueError:
                     pass
     return out
