@@ -649,11 +649,13 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     for (int zt = 0; zt < ZT; ++zt)
                         out[zt] = mfma16_split(xe[xt], split_b<2>(U[xt][zt]), out[zt]);
                 } else {
+                    // the state quads, cut anew every chunk, take the narrow form (the wide one
+                    // costs four register copies per quad), the tile quad the wide one
                     x2[xt] = split2(xa[xt]);
-                    const SplitA<2> xs = as_a(x2[xt]);
+                    const SplitB<2> xs = as_b(x2[xt]);
 #pragma unroll
                     for (int zt = 0; zt < ZT; ++zt)
-                        out[zt] = mfma16_split(xs, split_b<2>(U[xt][zt]), out[zt]);
+                        out[zt] = mfma16_split_ba(xs, split_a<2>(U[xt][zt]), out[zt]);
                 }
             }
         } else {
@@ -1667,9 +1669,10 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
             if constexpr (is_bf16<T>) {
 #pragma unroll
                 for (int xt = 0; xt < MT; ++xt) {
-                    const SplitA<2> xs = split_a<2>(xa[xt]);
+                    // the state quads take the narrow form (see run_pass), the tile quad the wide one
+                    const SplitB<2> xs = split_b<2>(xa[xt]);
 #pragma unroll
-                    for (int zt = 0; zt < DT; ++zt) out[zt] = mfma16_split(xs, split_b<2>(U[xt][zt]), out[zt]);
+                    for (int zt = 0; zt < DT; ++zt) out[zt] = mfma16_split_ba(xs, split_a<2>(U[xt][zt]), out[zt]);
                 }
             } else {
 #pragma unroll
