@@ -654,8 +654,15 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     x2[xt] = split2(xa[xt]);
                     const SplitB<2> xs = as_b(x2[xt]);
 #pragma unroll
-                    for (int zt = 0; zt < ZT; ++zt)
-                        out[zt] = mfma16_split_ba(xs, split_a<2>(U[xt][zt]), out[zt]);
+                    for (int zt = 0; zt < ZT; ++zt) {
+                        // The cut overwrites its input, and U must live on: a wave that has
+                        // just published U cuts the copy in LDS (one 16-byte read per quad)
+                        // instead of four register copies.
+                        f32x4 uq = U[xt][zt];
+                        if constexpr (kStateMode == kPublishState)
+                            uq = *reinterpret_cast<const f32x4 *>(lds_u + (16 * zt + c) * (DX + 4) + 16 * xt + 4 * g);
+                        out[zt] = mfma16_split_ba(xs, split_a<2>(uq), out[zt]);
+                    }
                 }
             }
         } else {
