@@ -323,6 +323,29 @@ __device__ __forceinline__ Split2 split2(const float (&x)[4]) {
     return s;
 }
 
+// N quads cut into two parts stage by stage (all first roundings, then all remainders, then the
+// second roundings), so that an instruction and the one that needs its result are several
+// instructions apart (a remainder right behind its rounding costs idle cycles).
+template <int N>
+__device__ __forceinline__ void split2_batch(const f32x4 (&q)[N], Split2 (&s)[N]) {
+    float r[N][4];
+#pragma unroll
+    for (int n = 0; n < N; ++n)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) s[n].h[j] = round_pair(q[n][2 * j], q[n][2 * j + 1]);
+#pragma unroll
+    for (int n = 0; n < N; ++n)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            r[n][2 * j] = minus_low(s[n].h[j], q[n][2 * j]);
+            r[n][2 * j + 1] = minus_high(s[n].h[j], q[n][2 * j + 1]);
+        }
+#pragma unroll
+    for (int n = 0; n < N; ++n)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) s[n].m[j] = round_pair(r[n][2 * j], r[n][2 * j + 1]);
+}
+
 __device__ __forceinline__ SplitA<2> as_a(const Split2 &s) {
     return SplitA<2>{u32x4_t{s.h[0], s.h[1], s.m[0], s.m[1]}};
 }

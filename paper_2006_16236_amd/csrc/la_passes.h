@@ -657,7 +657,9 @@ __device__ __forceinline__ void run_pass(const PassArgs &a, Stager &stg, const f
                     for (int zt = 0; zt < ZT; ++zt) {
                         // The cut overwrites its input, and U must live on: a wave that has
                         // just published U cuts the copy in LDS (one 16-byte read per quad)
-                        // instead of four register copies.
+                        // instead of four register copies.  (Cutting the four quads of a row
+                        // stage by stage, as the dQ kernel does, costs this kernel 24 registers
+                        // and 2 % of its time.)
                         f32x4 uq = U[xt][zt];
                         if constexpr (kStateMode == kPublishState)
                             uq = *reinterpret_cast<const f32x4 *>(lds_u + (16 * zt + c) * (DX + 4) + 16 * xt + 4 * g);
@@ -1678,8 +1680,10 @@ __global__ __launch_bounds__(2 * kWave) __attribute__((amdgpu_waves_per_eu(2))) 
                 for (int xt = 0; xt < MT; ++xt) {
                     // the state quads take the narrow form (see run_pass), the tile quad the wide one
                     const SplitB<2> xs = split_b<2>(xa[xt]);
+                    Split2 us[DT];
+                    split2_batch(U[xt], us);
 #pragma unroll
-                    for (int zt = 0; zt < DT; ++zt) out[zt] = mfma16_split_ba(xs, split_a<2>(U[xt][zt]), out[zt]);
+                    for (int zt = 0; zt < DT; ++zt) out[zt] = mfma16_split_ba(xs, as_a(us[zt]), out[zt]);
                 }
             } else {
 #pragma unroll
