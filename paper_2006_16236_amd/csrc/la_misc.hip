@@ -5,21 +5,22 @@
 namespace la {
 
 // ---- scan over the segment states of each sequence ------------------------------------------
-// state: [BH, nseg, stride].  A workgroup takes 256 / PARTS consecutive elements of one
-// sequence; its PARTS groups of threads split the nseg slots into PARTS consecutive runs.
+// state: [BH, nseg, stride], stride a multiple of 4.  A thread owns four consecutive elements
+// (16-byte loads and stores); a workgroup takes 4 * 256 / PARTS consecutive elements of one
+// sequence, and its PARTS groups of threads split the nseg slots into PARTS consecutive runs.
 // Each group first sums its run (all loads independent), the run totals are exchanged through
 // LDS, then the group walks its run again (now from cache) and writes the exclusive prefix.
 // Slots are visited in scan order: ascending for the prefix, descending for the suffix.
 // Fixed order: deterministic.  PARTS grows with nseg (1 for a handful of slots: every thread
-// then has an element of its own and no thread idles).
+// then has elements of its own and no thread idles).
 template <int PARTS>
 __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg, int stride,
                                                           int mode, const float *init_S,
                                                           const float *init_z, int DM) {
-    constexpr int EPW = 256 / PARTS;          // elements per workgroup
-    __shared__ float part_total[PARTS][EPW];
+    constexpr int EPW = 256 / PARTS;          // threads (quads of elements) per run
+    __shared__ f32x4 part_total[PARTS][EPW];
     const int el = threadIdx.x % EPW, part = threadIdx.x / EPW;
-    const int e = blockIdx.x * EPW + el;
+    const int e = 4 * (blockIdx.x * EPW + el);
     const bool live = e < stride;
     float *p = state + (size_t)blockIdx.y * nseg * stride + (live ? e : 0);
     const bool reverse = mode == kScanReverse;
@@ -27,47 +28,46 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg
     const int k0 = min(part * per, nseg), k1 = min(k0 + per, nseg);
     // the last slot in scan order holds no total (nobody reads past it): never read it
     const int klast = mode == kScanTotal ? nseg : nseg - 1;
+    const f32x4 zero4 = {0.f, 0.f, 0.f, 0.f};
+    auto slot = [&](const int k) { return reinterpret_cast<f32x4 *>(p + (size_t)(reverse ? nseg - 1 - k : k) * stride); };
 
     // eight independent loads in flight per thread (a plain loop waits for each in turn)
     constexpr int kBlock = 8;
     const int kread = min(k1, klast);
-    float total = 0.f;
+    f32x4 total = zero4;
     for (int kb = k0; kb < kread; kb += kBlock) {
-        float t[kBlock];
+        f32x4 t[kBlock];
 #pragma unroll
-        for (int j = 0; j < kBlock; ++j) {
-            const int k = min(kb + j, kread - 1);
-            t[j] = p[(size_t)(reverse ? nseg - 1 - k : k) * stride];
-        }
+        for (int j = 0; j < kBlock; ++j) t[j] = *slot(min(kb + j, kread - 1));
 #pragma unroll
-        for (int j = 0; j < kBlock; ++j) total += kb + j < kread ? t[j] : 0.f;
+        for (int j = 0; j < kBlock; ++j) total += kb + j < kread ? t[j] : zero4;
     }
     // the scan starts from the caller's initial state when there is one (forward prefix only)
-    float acc = 0.f;
+    f32x4 acc = zero4;
     if (init_S != nullptr && live)
-        acc = e < DM ? init_S[(size_t)blockIdx.y * DM + e]
-                     : init_z[(size_t)blockIdx.y * (stride - DM) + (e - DM)];
+        acc = e < DM ? *reinterpret_cast<const f32x4 *>(init_S + (size_t)blockIdx.y * DM + e)
+                     : *reinterpret_cast<const f32x4 *>(init_z + (size_t)blockIdx.y * (stride - DM) + (e - DM));
     if constexpr (PARTS > 1) {
         part_total[part][el] = total;
         __syncthreads();
         for (int q = 0; q < part; ++q) acc += part_total[q][el];
     }
     if (mode == kScanTotal) {
-        if (part == PARTS - 1 && live) p[0] = acc + total;
+        if (part == PARTS - 1 && live) *reinterpret_cast<f32x4 *>(p) = acc + total;
         return;
     }
     for (int kb = k0; kb < k1; kb += kBlock) {
-        float t[kBlock];
+        f32x4 t[kBlock];
 #pragma unroll
         for (int j = 0; j < kBlock; ++j) {
             const int k = min(kb + j, k1 - 1);
-            t[j] = k < klast ? p[(size_t)(reverse ? nseg - 1 - k : k) * stride] : 0.f;
+            t[j] = k < klast ? *slot(k) : zero4;
         }
 #pragma unroll
         for (int j = 0; j < kBlock; ++j) {
             const int k = kb + j;
             if (k < k1) {
-                if (live) p[(size_t)(reverse ? nseg - 1 - k : k) * stride] = acc;
+                if (live) *slot(k) = acc;
                 acc += t[j];
             }
         }
@@ -76,17 +76,18 @@ __global__ __launch_bounds__(256) void scan_states_kernel(float *state, int nseg
 
 hipError_t launch_scan(float *state, int BH, int nseg, int stride, int mode, hipStream_t s,
                        const float *init_S, const float *init_z, int DM) {
+    const int quads = (stride + 3) / 4;
     if (nseg <= 4) {
-        dim3 grid((stride + 255) / 256, BH);
+        dim3 grid((quads + 255) / 256, BH);
         scan_states_kernel<1><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
     } else if (nseg <= 16) {
-        dim3 grid((stride + 127) / 128, BH);
+        dim3 grid((quads + 127) / 128, BH);
         scan_states_kernel<2><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
     } else if (nseg <= 32) {
-        dim3 grid((stride + 63) / 64, BH);
+        dim3 grid((quads + 63) / 64, BH);
         scan_states_kernel<4><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
     } else {
-        dim3 grid((stride + 31) / 32, BH);
+        dim3 grid((quads + 31) / 32, BH);
         scan_states_kernel<8><<<grid, 256, 0, s>>>(state, nseg, stride, mode, init_S, init_z, DM);
     }
     return hipGetLastError();
